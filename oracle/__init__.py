@@ -1,0 +1,7 @@
+"""CPU oracle (test infrastructure only).
+
+`oracle.reference` wraps the plain fp64 C routines of `dense_oracle.c`;
+`oracle.planner` is the reference group planner in pure Python integers.
+Only the tests, the smoke check and the benchmark's CPU-baseline leg may import
+this package; the GPU library never does, and this package never imports it.
+"""

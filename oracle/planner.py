@@ -1,0 +1,137 @@
+"""Reference group planner (test infrastructure only; pure Python integers).
+
+The allocator of the paper decides, per task, the batch shape and which services
+share a GPU (Sec. 3.1: BS = requests of one service form a batch, MT = several
+services run together, MF = a request may bring several frames).  On one GPU that
+decision becomes: how many rows each service's batch has, where those rows sit in
+a packed buffer, and which output tiles one launch has to produce.  This module
+states those rules in the most literal form; the C++ planner of the library must
+reproduce every integer.
+
+Rules
+-----
+batch accounting   M_g = sum of rows(r) over the requests r of service g; a request's
+                   first row is the running sum of the rows before it (Sec. 3.1 BS/MF;
+                   Sec. 4.1, inter-request count = floor(BS / MF)).
+offsets            row_off[g] = sum_{h<g} M_h,  x_off[g] = sum_{h<g} M_h*K_h,
+                   y_off[g] = sum_{h<g} M_h*N_h              (each of length G+1)
+tile class         the first class c with M_g <= max_M[c]
+canonical tiles    for g ascending, m0 = 0, BM, 2BM, ... < M_g, n0 = 0, BN, ... < N_g:
+                   (g, m0, n0, rows=min(BM, M_g-m0), cols=min(BN, N_g-n0), c)
+visit order        see `schedule_tiles`.
+"""
+
+INT32_MAX = 2**31 - 1
+
+
+def batch_rows(request_rows_per_service):
+    """M_g and per-request first rows from lists of per-request row counts."""
+    M, first = [], []
+    for reqs in request_rows_per_service:
+        acc, starts = 0, []
+        for r in reqs:
+            if r < 0:
+                raise ValueError("negative row count")
+            starts.append(acc)
+            acc += r
+        M.append(acc)
+        first.append(starts)
+    return M, first
+
+
+def dp_group_count(rate_required, rate_of_one_group):
+    """Sec. 4.1, Eq. "DP group count" = ceil(required rate / rate of one group), integers."""
+    if rate_required < 0 or rate_of_one_group <= 0:
+        raise ValueError("bad rates")
+    return -(-rate_required // rate_of_one_group)
+
+
+def inter_request_count(batch_size, max_inter_frame_count):
+    """Sec. 4.1, Eq. "inter request count" = floor(BS / max inter-frame count)."""
+    if batch_size < 0 or max_inter_frame_count <= 0:
+        raise ValueError("bad counts")
+    return batch_size // max_inter_frame_count
+
+
+def pick_class(M, classes):
+    for c, (max_M, _bm, _bn) in enumerate(classes):
+        if M <= max_M:
+            return c
+    raise ValueError("no tile class admits M=%d" % M)
+
+
+def plan_groups(groups, classes):
+    """groups: list of (M, K, N); classes: list of (max_M, BM, BN) with increasing max_M.
+
+    Returns (row_off, x_off, y_off, tiles) with tiles a list of 6-tuples.
+    """
+    prev = -1
+    for max_M, bm, bn in classes:
+        if bm <= 0 or bn <= 0 or max_M <= prev:
+            raise ValueError("bad tile class table")
+        prev = max_M
+    row_off, x_off, y_off, tiles = [0], [0], [0], []
+    for g, (M, K, N) in enumerate(groups):
+        if M < 0 or K <= 0 or N <= 0:
+            raise ValueError("bad group shape")
+        row_off.append(row_off[-1] + M)
+        x_off.append(x_off[-1] + M * K)
+        y_off.append(y_off[-1] + M * N)
+        if M == 0:
+            continue
+        c = pick_class(M, classes)
+        _, bm, bn = classes[c]
+        for m0 in range(0, M, bm):
+            for n0 in range(0, N, bn):
+                tiles.append((g, m0, n0, min(bm, M - m0), min(bn, N - n0), c))
+    return row_off, x_off, y_off, tiles
+
+
+def schedule_tiles(groups, classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
+    """Visit order of the persistent workgroups.
+
+    Workgroup b of a launch of W = n_workgroups visits slots b, b+W, b+2W, ... and the
+    hardware places workgroup b on compute die b mod n_xcd.  The order is built in two
+    steps.
+
+    1. Locality sequence: classes by descending BM*BN (ties: lower class first); inside a
+       class the groups by descending K (ties: lower group first); inside a group the
+       tile grid TM x TN is cut into panels of panel_m x panel_n tiles, panels taken with
+       the n-panel index outermost, and inside a panel the m index runs fastest.
+    2. Slot of the l-th tile of that sequence: j = l div W, w = l mod W, die x = w div (W/X),
+       i = w mod (W/X), slot = j*W + i*X + x.  So the W/X tiles that run together on
+       one die are consecutive in the locality sequence.
+
+    Returns a list of length ceil(T/W)*W holding tile indices, -1 for idle slots.
+    """
+    W, X = n_workgroups, n_xcd
+    if W <= 0 or X <= 0 or W % X != 0 or panel_m <= 0 or panel_n <= 0:
+        raise ValueError("bad schedule parameters")
+    T = len(tiles)
+    # index ranges of each group's tiles in the canonical table
+    first = {}
+    for t, tile in enumerate(tiles):
+        first.setdefault(tile[0], t)
+    seq = []
+    class_order = sorted(range(len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
+    for c in class_order:
+        members = sorted({t[0] for t in tiles if t[5] == c}, key=lambda g: (-groups[g][1], g))
+        _, bm, bn = classes[c]
+        for g in members:
+            M, _K, N = groups[g]
+            TM, TN = -(-M // bm), -(-N // bn)
+            base = first[g]
+            for pn in range(0, TN, panel_n):
+                for pm in range(0, TM, panel_m):
+                    for tn in range(pn, min(pn + panel_n, TN)):
+                        for tm in range(pm, min(pm + panel_m, TM)):
+                            seq.append(base + tm * TN + tn)
+    assert len(seq) == T
+    n_slots = -(-T // W) * W
+    order = [-1] * n_slots
+    per = W // X
+    for l, t in enumerate(seq):
+        j, w = divmod(l, W)
+        x, i = divmod(w, per)
+        order[j * W + i * X + x] = t
+    return order

@@ -1,0 +1,126 @@
+"""Pins for the reference planner: invariants of the tiling rule, closed-form counts
+for the decode and prefill mixes, and the worked numbers the paper prints for the
+batch-accounting equations of Sec. 4.1 (tests/golden/paper_worked_numbers.txt)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import planner as P
+
+CLASSES = [(64, 64, 32), (P.INT32_MAX, 256, 256)]
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_worked_numbers.txt")
+
+
+def coverage(groups, tiles):
+    cov = [np.zeros((M, N), dtype=np.int32) for M, _K, N in groups]
+    for g, m0, n0, rows, cols, _c in tiles:
+        cov[g][m0:m0 + rows, n0:n0 + cols] += 1
+    return cov
+
+
+@pytest.mark.parametrize("groups", [
+    [(4, 256, 512), (16, 256, 512)],
+    [(1, 8, 10)],
+    [(0, 8, 8), (65, 16, 257), (64, 32, 33), (0, 4, 4)],
+    [(197, 768, 2304), (6304, 768, 3072), (255, 8, 256), (256, 8, 256), (257, 8, 255)],
+])
+def test_tiles_partition_every_output_exactly_once(groups):
+    row_off, x_off, y_off, tiles = P.plan_groups(groups, CLASSES)
+    assert row_off[0] == x_off[0] == y_off[0] == 0
+    assert row_off[-1] == sum(g[0] for g in groups)
+    assert x_off[-1] == sum(g[0] * g[1] for g in groups)
+    assert y_off[-1] == sum(g[0] * g[2] for g in groups)
+    assert all(b >= a for a, b in zip(row_off, row_off[1:]))
+    for cov in coverage(groups, tiles):
+        assert np.all(cov == 1)
+    keys = [(t[0], t[1], t[2]) for t in tiles]
+    assert keys == sorted(keys) and len(set(keys)) == len(keys)       # canonical, strictly increasing
+    assert all(t[3] >= 1 and t[4] >= 1 for t in tiles)
+    expect = 0
+    for M, _K, N in groups:
+        if M:
+            _, bm, bn = CLASSES[P.pick_class(M, CLASSES)]
+            expect += -(-M // bm) * -(-N // bn)
+    assert len(tiles) == expect
+
+
+def test_class_choice_and_empty_groups():
+    assert P.pick_class(1, CLASSES) == 0 and P.pick_class(64, CLASSES) == 0 and P.pick_class(65, CLASSES) == 1
+    _, _, _, tiles = P.plan_groups([(0, 4, 4)], CLASSES)
+    assert tiles == []
+    assert P.plan_groups([], CLASSES) == ([0], [0], [0], [])
+    with pytest.raises(ValueError):
+        P.plan_groups([(1, 0, 4)], CLASSES)
+    with pytest.raises(ValueError):
+        P.plan_groups([(1, 4, 4)], [(64, 64, 32), (64, 256, 256)])
+    with pytest.raises(ValueError):
+        P.plan_groups([(100, 4, 4)], [(64, 64, 32)])
+
+
+def test_closed_form_counts_decode_and_prefill():
+    # decode mix: 4 services, M <= 64, gate/up phase seen as N = 11008 hidden columns
+    dec = [(m, 4096, 11008) for m in (1, 8, 32, 64)]
+    _, _, _, t = P.plan_groups(dec, CLASSES)
+    assert len(t) == 4 * (11008 // 32)
+    # prefill mix: rows 4692 and 3500; gate/up phase with 128 hidden columns per tile
+    pre = [(4692, 5120, 13824), (3500, 5120, 13824)]
+    _, _, _, t = P.plan_groups(pre, [(64, 64, 32), (P.INT32_MAX, 256, 128)])
+    assert len(t) == (19 + 14) * 108
+    row_off, x_off, y_off, t = P.plan_groups([(4692, 13824, 5120), (3500, 13824, 5120)], CLASSES)
+    assert len(t) == (19 + 14) * 20 and row_off == [0, 4692, 8192]
+    assert x_off[-1] == 8192 * 13824 and y_off[-1] == 8192 * 5120
+    last = t[19 * 20 - 1]
+    assert last == (0, 18 * 256, 19 * 256, 4692 - 18 * 256, 256, 1)
+
+
+@pytest.mark.parametrize("W,X", [(256, 8), (8, 8), (16, 1), (24, 4)])
+def test_schedule_is_a_permutation_with_idle_padding(W, X):
+    groups = [(700, 64, 900), (3, 128, 100), (300, 256, 300), (64, 32, 64)]
+    _, _, _, tiles = P.plan_groups(groups, CLASSES)
+    order = P.schedule_tiles(groups, CLASSES, tiles, W, X, 8, 4)
+    assert len(order) % W == 0 and len(order) - len(tiles) < W
+    used = [t for t in order if t >= 0]
+    assert sorted(used) == list(range(len(tiles)))
+    # big-tile classes come first in slot rounds, and within them the larger K
+    first_round = [tiles[t] for t in order[:W] if t >= 0]
+    assert all(t[5] == 1 for t in first_round) or len(tiles) < W
+
+
+def test_schedule_keeps_a_die_on_one_panel():
+    # one group whose grid is a whole number of 8x4 panels: the 32 tiles that run together on one
+    # die (slots congruent mod 8 within a round of 256) are exactly one panel
+    groups = [(16 * 256, 64, 16 * 256)]
+    _, _, _, tiles = P.plan_groups(groups, CLASSES)
+    order = P.schedule_tiles(groups, CLASSES, tiles, 256, 8, 8, 4)
+    assert len(order) == 256
+    for x in range(8):
+        mine = [tiles[order[s]] for s in range(x, 256, 8)]
+        ms = sorted({t[1] // 256 for t in mine})
+        ns = sorted({t[2] // 256 for t in mine})
+        assert len(ms) == 8 and len(ns) == 4 and ms[-1] - ms[0] == 7 and ns[-1] - ns[0] == 3
+
+
+def test_batch_rows_accounting():
+    M, first = P.batch_rows([[197] * 3, [], [5, 0, 7]])
+    assert M == [591, 0, 12] and first == [[0, 197, 394], [], [0, 5, 5]]
+
+
+def test_paper_worked_numbers():
+    seen = 0
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, args, expect, _cite = [f.strip() for f in line.split(";", 3)]
+        a = [int(v) for v in args.split()]
+        if name == "dp_group_count":
+            assert P.dp_group_count(*a) == int(expect)
+        elif name == "inter_request_count":
+            assert P.inter_request_count(*a) == int(expect)
+        elif name == "satisfied_frames":
+            assert a[0] * a[1] // a[2] == int(expect)
+        else:
+            raise AssertionError(name)
+        seen += 1
+    assert seen >= 6
