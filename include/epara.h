@@ -1,0 +1,200 @@
+/*
+ * libepara -- grouped dense forward for co-located inference services on one MI355X.
+ *
+ *     Y_g = act_g( s_g * X_g W_g + b_g )          for g = 0 .. G-1, in ONE launch
+ *
+ * Vocabulary follows the paper (Sec. 3.1, "Task-Categorized Parallelism Allocator"):
+ * a *service* is a deployed model, a *request* brings one or more rows (frames,
+ * tokens), a *task* is a (request, service) pair.  Batching (BS) makes the rows of one
+ * service's requests one ragged batch X_g [M_g, K_g]; multi-task (MT) lets several
+ * services with different weights share the GPU -- here they share a kernel launch;
+ * multi-frame (MF) only changes how many rows a request contributes.  The paper states
+ * no layer arithmetic: the formula is the ordinary affine layer plus activation.
+ * A *group* is one (service, layer) product.
+ *
+ * Conventions
+ *   - plain C ABI; every entry point returns an epara_status (0 = EPARA_OK) unless noted;
+ *     nothing aborts on bad input.
+ *   - "h_" / "d_" prefixes say whether a pointer is host or device memory.
+ *   - the caller owns every buffer and the stream; the library allocates no device memory,
+ *     never synchronises and keeps no mutable global state.  Launch functions only
+ *     enqueue work on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *   - X_g and Y_g are dense row-major ([M,K] and [M,N]); device pointers must be 16-byte
+ *     aligned and K*sizeof(element) must be a multiple of 16 for bf16/fp8 inputs.
+ *   - weights: logical W_g is [K,N] row-major.  fp32 kernels read that layout directly;
+ *     bf16 / fp8 kernels read the tile-packed layout written by epara_pack_weights
+ *     (done once when a service is placed on the GPU, ahead of its requests -- the paper
+ *     pre-places models because loading costs far more than one task, Sec. 3.3).
+ */
+#ifndef EPARA_H
+#define EPARA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EPARA_OK = 0,
+    EPARA_ERR_NULL = 1,      /* a required pointer is NULL */
+    EPARA_ERR_SHAPE = 2,     /* negative/zero dimension, bad class table, tile outside its group, bad grid */
+    EPARA_ERR_DTYPE = 3,     /* unsupported dtype / activation combination */
+    EPARA_ERR_CAPACITY = 4,  /* an output array is too small (the needed size is still written) */
+    EPARA_ERR_ALIGN = 5,     /* pointer or row pitch not 16-byte aligned */
+    EPARA_ERR_HIP = 6        /* the HIP runtime refused the launch */
+} epara_status;
+
+typedef enum { EPARA_F32 = 0, EPARA_BF16 = 1, EPARA_FP8_E4M3 = 2 } epara_dtype;
+
+/* EPARA_ACT_SWIGLU: the group has two weight matrices and computes
+ * SiLU(s * X W) * (s2 * X W2); no bias. */
+typedef enum {
+    EPARA_ACT_NONE = 0, EPARA_ACT_RELU = 1, EPARA_ACT_GELU_ERF = 2,
+    EPARA_ACT_GELU_TANH = 3, EPARA_ACT_SILU = 4, EPARA_ACT_SWIGLU = 5
+} epara_act;
+
+/* Sec. 3.1 "Task categories": latency- vs frequency-sensitive.  Metadata only: it never
+ * changes a group's arithmetic. */
+typedef enum { EPARA_CAT_LATENCY = 0, EPARA_CAT_FREQUENCY = 1 } epara_category;
+
+typedef struct { int32_t M, K, N; int32_t act; int32_t has_bias; int32_t category; } epara_group_desc;
+
+/* A group with M <= max_M (first such class wins) is cut into BM x BN output tiles. */
+typedef struct { int32_t max_M; int32_t BM, BN; } epara_tile_class;
+
+/* One output tile: rows [m0, m0+rows) x columns [n0, n0+cols) of group `group`. 24 bytes. */
+typedef struct { int32_t group, m0, n0, rows, cols, cls; } epara_tile;
+
+/* Per-group kernel arguments; the same bytes are used on the host (validation) and on the
+ * device (the kernels read d_args[g]).  72 bytes. */
+typedef struct {
+    const void*  X;            /* device, [M,K] row-major, input dtype */
+    const void*  W;            /* device, weights (layout: see above) */
+    const void*  W2;           /* device, second weight matrix (EPARA_ACT_SWIGLU), else NULL */
+    const float* bias;         /* device, fp32 [N], or NULL */
+    void*        Y;            /* device, [M,N] row-major, output dtype */
+    int32_t M, K, N;
+    int32_t act;               /* epara_act */
+    float scale;               /* s = s_x * s_w   (fp8 per-tensor scales; 1 otherwise) */
+    float scale2;              /* s2 = s_x * s_w2 (EPARA_ACT_SWIGLU) */
+    float out_inv_scale;       /* fp8 output: stored code = sat(RNE(y * out_inv_scale)); else 1 */
+    int32_t reserved;
+} epara_group_args;
+
+/* Everything one launch needs.  h_* copies let the library validate shapes before it
+ * enqueues anything; d_* copies are what the kernel reads. */
+typedef struct {
+    const epara_group_args* h_args;   /* host,   G entries */
+    const epara_group_args* d_args;   /* device, G entries (same bytes) */
+    const epara_tile*       h_tiles;  /* host,   n_tiles entries, canonical order */
+    const epara_tile*       d_tiles;  /* device, same bytes */
+    const int32_t*          d_order;  /* device, n_slots entries from epara_schedule_tiles */
+    int64_t n_tiles;
+    int64_t n_slots;
+    int32_t n_workgroups;             /* the value the order was built for; becomes the grid size */
+    int32_t G;
+} epara_launch;
+
+/* SwiGLU FFN of one service: Y = (SiLU(X Wgate) * (X Wup)) Wdown, H = the hidden
+ * activations [M, d_ff] (caller-provided scratch, written then read). */
+typedef struct {
+    const void* X; const void* Wgate; const void* Wup; const void* Wdown;
+    void* H; void* Y;
+    int32_t M, d_model, d_ff;
+    float s_x, s_wgate, s_wup, s_h, s_wdown;   /* per-tensor fp8 scales; ignored (1) otherwise */
+} epara_ffn_desc;
+
+/* ---- host side: batch accounting and planning (integers only, deterministic) ---------- */
+
+/* Batch accounting (Sec. 3.1 BS / MF; Sec. 4.1): service g owns requests
+ * request_off[g] .. request_off[g+1]-1, request r contributes request_rows[r] rows.
+ * Writes M[g] = sum of its requests' rows and first_row[r] = rows of the same service
+ * before request r.  ERR_SHAPE on a negative count, a decreasing offset or an M beyond int32. */
+int32_t epara_batch_rows(const int32_t* request_rows, const int64_t* request_off, int32_t G,
+                         int32_t* M, int64_t* first_row);
+
+/* Sec. 4.1, Eq. "DP group count" = ceil(required rate / rate of one group); -1 on bad input. */
+int64_t epara_dp_group_count(int64_t rate_required, int64_t rate_of_one_group);
+/* Sec. 4.1, Eq. "inter request count" = floor(BS / max inter-frame count); -1 on bad input. */
+int64_t epara_inter_request_count(int64_t batch_size, int64_t max_inter_frame_count);
+
+/* Group planning: the single-GPU part of the allocator's "parallel mode per task" decision.
+ *   row_off[g] = sum_{h<g} M_h ; x_off[g] = sum_{h<g} M_h K_h ; y_off[g] = sum_{h<g} M_h N_h
+ *   (each G+1 entries; x_off / y_off are element offsets for callers that pack groups
+ *   back to back), tile class of g = first class with M_g <= max_M, and the canonical tile
+ *   table: g ascending, then m0, then n0, rows = min(BM, M_g - m0), cols = min(BN, N_g - n0).
+ * M_g = 0 and G = 0 are legal (no tiles).  tiles may be NULL to query *n_tiles only.
+ * Errors: NULL groups (G > 0) / classes / n_tiles -> ERR_NULL; M < 0, K <= 0, N <= 0, G < 0,
+ * BM or BN <= 0, max_M not strictly increasing, or a group no class admits -> ERR_SHAPE;
+ * tiles_cap < needed -> ERR_CAPACITY with *n_tiles written. row_off/x_off/y_off may be NULL. */
+int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
+                          const epara_tile_class* classes, int32_t n_classes,
+                          int64_t* row_off, int64_t* x_off, int64_t* y_off,
+                          epara_tile* tiles, int64_t tiles_cap, int64_t* n_tiles);
+
+/* Visit order of the persistent workgroups.  Workgroup b of n_workgroups visits slots
+ * b, b + n_workgroups, ...; order[slot] is a tile index or -1 (idle).
+ *   1. locality sequence: classes by descending BM*BN (ties: lower class), inside a class
+ *      groups by descending K (ties: lower group), inside a group panels of
+ *      panel_m x panel_n tiles, n-panel outermost, m fastest inside a panel;
+ *   2. the l-th tile of that sequence goes to slot j*W + i*X + x with j = l div W,
+ *      w = l mod W, x = w div (W/X), i = w mod (W/X)   (W = n_workgroups, X = n_xcd),
+ *      so the W/X workgroups of one compute die (workgroup b runs on die b mod X) work on
+ *      neighbouring tiles and share operands in that die's L2.
+ * *n_slots = ceil(n_tiles / W) * W.  order may be NULL to query.  W must be a positive
+ * multiple of X.  Errors as above. */
+int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
+                             const epara_tile_class* classes, int32_t n_classes,
+                             const epara_tile* tiles, int64_t n_tiles,
+                             int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
+                             int32_t* order, int64_t order_cap, int64_t* n_slots);
+
+/* The tile classes the kernels implement for an input dtype (gated = EPARA_ACT_SWIGLU
+ * launches, whose BN counts hidden columns).  Writes up to cap classes, *n_classes = count. */
+int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated,
+                             epara_tile_class* classes, int32_t cap, int32_t* n_classes);
+
+/* Fills the two phases' group arguments of a SwiGLU FFN from per-service descriptors:
+ * up_args[g]   : X -> H, W = Wgate, W2 = Wup, act = SWIGLU, K = d_model, N = d_ff
+ * down_args[g] : H -> Y, W = Wdown, act = NONE, K = d_ff, N = d_model
+ * with the fp8 scale products filled in (all 1 for other dtypes).  Host only. */
+int32_t epara_ffn_swiglu_args(const epara_ffn_desc* ffn, int32_t G, int32_t in_dtype,
+                              epara_group_args* up_args, epara_group_args* down_args);
+
+/* ---- device side -------------------------------------------------------------------- */
+
+/* Bytes of the packed form of a [K,N] weight matrix (fp32: K*N*4, unchanged layout). */
+int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype);
+
+/* Packs d_W ([K,N] row-major, `dtype`) into d_packed for the bf16 / fp8 kernels:
+ * 1 KiB fragments of 16 columns x (64 bytes of K), fragment (nb, ks) at
+ * ((nb * ceil(K/KF) + ks) * 1024) bytes, KF = 32 (bf16) or 64 (fp8); inside a fragment the
+ * 16-byte chunk (q*16 + r) holds W[ks*KF + q*KF/4 ... +KF/4-1][nb*16 + r]; zero padded.
+ * fp32: plain copy.  Enqueues one kernel. */
+int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
+                           void* d_packed, int64_t packed_bytes, void* stream);
+
+/* Y_g = act_g(s_g X_g W_g + b_g) for all groups of the launch, in one persistent kernel
+ * that walks the device tile table in the scheduled order; bias, activation, SwiGLU gating
+ * and the output cast are fused in the epilogue.  Accumulation is fp32 in a fixed order
+ * (bit-reproducible, independent of n_workgroups).
+ * in_dtype / out_dtype: F32 -> F32; BF16 -> BF16; FP8_E4M3 -> BF16 or FP8_E4M3.
+ * n_tiles = 0 enqueues nothing.  Validates h_args / h_tiles first: ERR_NULL, ERR_SHAPE,
+ * ERR_DTYPE, ERR_ALIGN as described at the top; ERR_HIP if the launch fails. */
+int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int32_t out_dtype,
+                              void* stream);
+
+/* Y_g = (SiLU(X_g Wgate_g) * (X_g Wup_g)) Wdown_g for all services: phase `up` (gated
+ * launch writing H in h_dtype) then phase `down` (reading H), enqueued back to back on
+ * `stream`.  in_dtype BF16: h_dtype = out_dtype = BF16.  in_dtype FP8_E4M3: h_dtype =
+ * FP8_E4M3 (codes sat(RNE(h / s_h))), out_dtype = BF16. */
+int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
+                                 int32_t in_dtype, int32_t h_dtype, int32_t out_dtype, void* stream);
+
+const char* epara_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPARA_H */

@@ -1,0 +1,187 @@
+"""ctypes binding of libepara: the same entry points as include/epara.h, argument marshalling only.
+
+Structured numpy dtypes mirror the C structs byte for byte; device memory is passed as integer
+addresses (e.g. torch.Tensor.data_ptr()).  A non-zero status raises EparaError.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+# ---- enums (include/epara.h) -------------------------------------------------------------
+EPARA_OK, EPARA_ERR_NULL, EPARA_ERR_SHAPE, EPARA_ERR_DTYPE, EPARA_ERR_CAPACITY, EPARA_ERR_ALIGN, EPARA_ERR_HIP = range(7)
+EPARA_F32, EPARA_BF16, EPARA_FP8_E4M3 = 0, 1, 2
+EPARA_ACT_NONE, EPARA_ACT_RELU, EPARA_ACT_GELU_ERF, EPARA_ACT_GELU_TANH, EPARA_ACT_SILU, EPARA_ACT_SWIGLU = range(6)
+EPARA_CAT_LATENCY, EPARA_CAT_FREQUENCY = 0, 1
+
+ACT_BY_NAME = {"none": EPARA_ACT_NONE, "relu": EPARA_ACT_RELU, "gelu_erf": EPARA_ACT_GELU_ERF,
+               "gelu_tanh": EPARA_ACT_GELU_TANH, "silu": EPARA_ACT_SILU, "swiglu": EPARA_ACT_SWIGLU}
+DTYPE_BY_NAME = {"f32": EPARA_F32, "bf16": EPARA_BF16, "fp8": EPARA_FP8_E4M3}
+DTYPE_BYTES = {EPARA_F32: 4, EPARA_BF16: 2, EPARA_FP8_E4M3: 1}
+
+# ---- struct layouts ----------------------------------------------------------------------
+GROUP_DESC = np.dtype([("M", "<i4"), ("K", "<i4"), ("N", "<i4"), ("act", "<i4"), ("has_bias", "<i4"), ("category", "<i4")])
+TILE_CLASS = np.dtype([("max_M", "<i4"), ("BM", "<i4"), ("BN", "<i4")])
+TILE = np.dtype([("group", "<i4"), ("m0", "<i4"), ("n0", "<i4"), ("rows", "<i4"), ("cols", "<i4"), ("cls", "<i4")])
+GROUP_ARGS = np.dtype([("X", "<u8"), ("W", "<u8"), ("W2", "<u8"), ("bias", "<u8"), ("Y", "<u8"),
+                       ("M", "<i4"), ("K", "<i4"), ("N", "<i4"), ("act", "<i4"),
+                       ("scale", "<f4"), ("scale2", "<f4"), ("out_inv_scale", "<f4"), ("reserved", "<i4")])
+FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "<u8"), ("H", "<u8"), ("Y", "<u8"),
+                     ("M", "<i4"), ("d_model", "<i4"), ("d_ff", "<i4"),
+                     ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
+assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24
+assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
+
+
+class Launch(ctypes.Structure):
+    """struct epara_launch."""
+    _fields_ = [("h_args", ctypes.c_void_p), ("d_args", ctypes.c_void_p),
+                ("h_tiles", ctypes.c_void_p), ("d_tiles", ctypes.c_void_p), ("d_order", ctypes.c_void_p),
+                ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
+                ("n_workgroups", ctypes.c_int32), ("G", ctypes.c_int32)]
+
+
+assert ctypes.sizeof(Launch) == 64
+
+
+class EparaError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, epara_status_string(status)))
+
+
+_lib = None
+
+
+def library_path():
+    return _build.LIB
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise RuntimeError("libepara.so is not built (%s); run `python -m paper_2511_00603_amd.build`" % path)
+        L = ctypes.CDLL(path)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.epara_status_string.argtypes = [i32]
+        L.epara_status_string.restype = ctypes.c_char_p
+        L.epara_batch_rows.argtypes = [vp, vp, i32, vp, vp]
+        L.epara_dp_group_count.argtypes = [i64, i64]
+        L.epara_dp_group_count.restype = i64
+        L.epara_inter_request_count.argtypes = [i64, i64]
+        L.epara_inter_request_count.restype = i64
+        L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
+        L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
+        L.epara_kernel_classes.argtypes = [i32, i32, vp, i32, vp]
+        L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
+        L.epara_packed_weight_bytes.argtypes = [i32, i32, i32]
+        L.epara_packed_weight_bytes.restype = i64
+        L.epara_pack_weights.argtypes = [vp, i32, i32, i32, vp, i64, vp]
+        L.epara_grouped_forward.argtypes = [vp, i32, i32, vp]
+        L.epara_grouped_ffn_swiglu.argtypes = [vp, vp, i32, i32, i32, vp]
+        for name in ("epara_batch_rows", "epara_plan_groups", "epara_schedule_tiles", "epara_kernel_classes",
+                     "epara_ffn_swiglu_args", "epara_pack_weights", "epara_grouped_forward", "epara_grouped_ffn_swiglu"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    """Address of a numpy array's buffer (None -> NULL)."""
+    return None if a is None else a.ctypes.data
+
+
+def _check(status, where):
+    if status != EPARA_OK:
+        raise EparaError(status, where)
+
+
+def epara_status_string(status):
+    return lib().epara_status_string(int(status)).decode()
+
+
+def epara_batch_rows(request_rows, request_off):
+    """-> (M int32[G], first_row int64[R])."""
+    request_rows = np.ascontiguousarray(request_rows, dtype=np.int32)
+    request_off = np.ascontiguousarray(request_off, dtype=np.int64)
+    G = len(request_off) - 1
+    M = np.zeros(max(G, 0), dtype=np.int32)
+    first = np.zeros(len(request_rows), dtype=np.int64)
+    _check(lib().epara_batch_rows(_ptr(request_rows), _ptr(request_off), G, _ptr(M), _ptr(first)), "epara_batch_rows")
+    return M, first
+
+
+def epara_dp_group_count(rate_required, rate_of_one_group):
+    return int(lib().epara_dp_group_count(int(rate_required), int(rate_of_one_group)))
+
+
+def epara_inter_request_count(batch_size, max_inter_frame_count):
+    return int(lib().epara_inter_request_count(int(batch_size), int(max_inter_frame_count)))
+
+
+def epara_plan_groups(groups, classes):
+    """groups: GROUP_DESC array, classes: TILE_CLASS array -> (row_off, x_off, y_off, tiles)."""
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
+    G = len(groups)
+    n = np.zeros(1, dtype=np.int64)
+    row_off, x_off, y_off = (np.zeros(G + 1, dtype=np.int64) for _ in range(3))
+    _check(lib().epara_plan_groups(_ptr(groups), G, _ptr(classes), len(classes), _ptr(row_off), _ptr(x_off),
+                                   _ptr(y_off), None, 0, _ptr(n)), "epara_plan_groups")
+    tiles = np.zeros(int(n[0]), dtype=TILE)
+    _check(lib().epara_plan_groups(_ptr(groups), G, _ptr(classes), len(classes), _ptr(row_off), _ptr(x_off),
+                                   _ptr(y_off), _ptr(tiles), len(tiles), _ptr(n)), "epara_plan_groups")
+    return row_off, x_off, y_off, tiles
+
+
+def epara_schedule_tiles(groups, classes, tiles, n_workgroups, n_xcd=8, panel_m=8, panel_n=4):
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
+    tiles = np.ascontiguousarray(tiles, dtype=TILE)
+    n = np.zeros(1, dtype=np.int64)
+    args = (_ptr(groups), len(groups), _ptr(classes), len(classes), _ptr(tiles), len(tiles),
+            int(n_workgroups), int(n_xcd), int(panel_m), int(panel_n))
+    _check(lib().epara_schedule_tiles(*args, None, 0, _ptr(n)), "epara_schedule_tiles")
+    order = np.zeros(int(n[0]), dtype=np.int32)
+    _check(lib().epara_schedule_tiles(*args, _ptr(order), len(order), _ptr(n)), "epara_schedule_tiles")
+    return order
+
+
+def epara_kernel_classes(in_dtype, gated):
+    n = np.zeros(1, dtype=np.int32)
+    classes = np.zeros(4, dtype=TILE_CLASS)
+    _check(lib().epara_kernel_classes(int(in_dtype), int(bool(gated)), _ptr(classes), len(classes), _ptr(n)),
+           "epara_kernel_classes")
+    return classes[: int(n[0])].copy()
+
+
+def epara_ffn_swiglu_args(ffn, in_dtype):
+    ffn = np.ascontiguousarray(ffn, dtype=FFN_DESC)
+    up = np.zeros(len(ffn), dtype=GROUP_ARGS)
+    down = np.zeros(len(ffn), dtype=GROUP_ARGS)
+    _check(lib().epara_ffn_swiglu_args(_ptr(ffn), len(ffn), int(in_dtype), _ptr(up), _ptr(down)), "epara_ffn_swiglu_args")
+    return up, down
+
+
+def epara_packed_weight_bytes(K, N, dtype):
+    return int(lib().epara_packed_weight_bytes(int(K), int(N), int(dtype)))
+
+
+def epara_pack_weights(d_W, K, N, dtype, d_packed, packed_bytes, stream=0):
+    _check(lib().epara_pack_weights(int(d_W), int(K), int(N), int(dtype), int(d_packed), int(packed_bytes),
+                                    int(stream) or None), "epara_pack_weights")
+
+
+def epara_grouped_forward(launch, in_dtype, out_dtype, stream=0):
+    _check(lib().epara_grouped_forward(ctypes.addressof(launch), int(in_dtype), int(out_dtype), int(stream) or None),
+           "epara_grouped_forward")
+
+
+def epara_grouped_ffn_swiglu(up, down, in_dtype, h_dtype, out_dtype, stream=0):
+    _check(lib().epara_grouped_ffn_swiglu(ctypes.addressof(up), ctypes.addressof(down), int(in_dtype), int(h_dtype),
+                                          int(out_dtype), int(stream) or None), "epara_grouped_ffn_swiglu")

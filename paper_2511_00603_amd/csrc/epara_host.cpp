@@ -1,0 +1,271 @@
+// Host half of libepara: batch accounting, group planning, visit order, argument helpers.
+// Integer-only and deterministic; nothing here touches the GPU.
+//
+// The planner is the single-GPU part of the allocator of Sec. 3.1: the batching (BS) and
+// multi-frame (MF) operators fix how many rows each service's batch has, multi-task (MT)
+// puts several services into one launch, and the tile class picked per group is the
+// "parallel mode" that group runs in.
+#include "epara.h"
+
+#include <algorithm>
+#include <climits>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int32_t check_classes(const epara_tile_class* classes, int32_t n_classes)
+{
+    if (!classes) return EPARA_ERR_NULL;
+    if (n_classes <= 0) return EPARA_ERR_SHAPE;
+    for (int32_t c = 0; c < n_classes; ++c) {
+        if (classes[c].BM <= 0 || classes[c].BN <= 0) return EPARA_ERR_SHAPE;
+        if (c > 0 && classes[c].max_M <= classes[c - 1].max_M) return EPARA_ERR_SHAPE;
+    }
+    return EPARA_OK;
+}
+
+int32_t class_of(int32_t M, const epara_tile_class* classes, int32_t n_classes)
+{
+    for (int32_t c = 0; c < n_classes; ++c)
+        if (M <= classes[c].max_M) return c;
+    return -1;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* epara_status_string(int32_t status)
+{
+    switch (status) {
+    case EPARA_OK:           return "ok";
+    case EPARA_ERR_NULL:     return "required pointer is NULL";
+    case EPARA_ERR_SHAPE:    return "bad shape, class table, tile or grid";
+    case EPARA_ERR_DTYPE:    return "unsupported dtype or activation";
+    case EPARA_ERR_CAPACITY: return "output array too small";
+    case EPARA_ERR_ALIGN:    return "pointer or row pitch not 16-byte aligned";
+    case EPARA_ERR_HIP:      return "HIP runtime error";
+    default:                 return "unknown status";
+    }
+}
+
+int32_t epara_batch_rows(const int32_t* request_rows, const int64_t* request_off, int32_t G,
+                         int32_t* M, int64_t* first_row)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (G == 0) return EPARA_OK;
+    if (!request_off || !M) return EPARA_ERR_NULL;
+    if (request_off[0] < 0) return EPARA_ERR_SHAPE;
+    for (int32_t g = 0; g < G; ++g) {
+        const int64_t lo = request_off[g], hi = request_off[g + 1];
+        if (hi < lo) return EPARA_ERR_SHAPE;
+        if (hi > lo && !request_rows) return EPARA_ERR_NULL;
+        int64_t acc = 0;
+        for (int64_t r = lo; r < hi; ++r) {
+            if (request_rows[r] < 0) return EPARA_ERR_SHAPE;
+            if (first_row) first_row[r] = acc;
+            acc += request_rows[r];
+            if (acc > INT32_MAX) return EPARA_ERR_SHAPE;
+        }
+        M[g] = static_cast<int32_t>(acc);
+    }
+    return EPARA_OK;
+}
+
+int64_t epara_dp_group_count(int64_t rate_required, int64_t rate_of_one_group)
+{
+    if (rate_required < 0 || rate_of_one_group <= 0) return -1;
+    return ceil_div(rate_required, rate_of_one_group);
+}
+
+int64_t epara_inter_request_count(int64_t batch_size, int64_t max_inter_frame_count)
+{
+    if (batch_size < 0 || max_inter_frame_count <= 0) return -1;
+    return batch_size / max_inter_frame_count;
+}
+
+int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
+                          const epara_tile_class* classes, int32_t n_classes,
+                          int64_t* row_off, int64_t* x_off, int64_t* y_off,
+                          epara_tile* tiles, int64_t tiles_cap, int64_t* n_tiles)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (!n_tiles || (G > 0 && !groups)) return EPARA_ERR_NULL;
+    if (int32_t st = check_classes(classes, n_classes)) return st;
+
+    // pass 1: validate and count, so that nothing is written on a shape error
+    int64_t need = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_group_desc& d = groups[g];
+        if (d.M < 0 || d.K <= 0 || d.N <= 0) return EPARA_ERR_SHAPE;
+        if (d.M == 0) continue;
+        const int32_t c = class_of(d.M, classes, n_classes);
+        if (c < 0) return EPARA_ERR_SHAPE;
+        need += ceil_div(d.M, classes[c].BM) * ceil_div(d.N, classes[c].BN);
+    }
+    *n_tiles = need;
+
+    int64_t rows = 0, xs = 0, ys = 0;
+    for (int32_t g = 0; g <= G; ++g) {
+        if (row_off) row_off[g] = rows;
+        if (x_off) x_off[g] = xs;
+        if (y_off) y_off[g] = ys;
+        if (g == G) break;
+        rows += groups[g].M;
+        xs += static_cast<int64_t>(groups[g].M) * groups[g].K;
+        ys += static_cast<int64_t>(groups[g].M) * groups[g].N;
+    }
+    if (!tiles) return EPARA_OK;
+    if (tiles_cap < need) return EPARA_ERR_CAPACITY;
+
+    epara_tile* out = tiles;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_group_desc& d = groups[g];
+        if (d.M == 0) continue;
+        const int32_t c = class_of(d.M, classes, n_classes);
+        const int32_t BM = classes[c].BM, BN = classes[c].BN;
+        for (int64_t m0 = 0; m0 < d.M; m0 += BM)
+            for (int64_t n0 = 0; n0 < d.N; n0 += BN) {
+                out->group = g;
+                out->m0 = static_cast<int32_t>(m0);
+                out->n0 = static_cast<int32_t>(n0);
+                out->rows = static_cast<int32_t>(std::min<int64_t>(BM, d.M - m0));
+                out->cols = static_cast<int32_t>(std::min<int64_t>(BN, d.N - n0));
+                out->cls = c;
+                ++out;
+            }
+    }
+    return EPARA_OK;
+}
+
+int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
+                             const epara_tile_class* classes, int32_t n_classes,
+                             const epara_tile* tiles, int64_t n_tiles,
+                             int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
+                             int32_t* order, int64_t order_cap, int64_t* n_slots)
+{
+    if (G < 0 || n_tiles < 0) return EPARA_ERR_SHAPE;
+    if (!n_slots || (G > 0 && !groups) || (n_tiles > 0 && !tiles)) return EPARA_ERR_NULL;
+    if (int32_t st = check_classes(classes, n_classes)) return st;
+    if (n_workgroups <= 0 || n_xcd <= 0 || n_workgroups % n_xcd != 0 || panel_m <= 0 || panel_n <= 0)
+        return EPARA_ERR_SHAPE;
+    if (n_tiles > INT32_MAX) return EPARA_ERR_SHAPE;
+
+    const int64_t W = n_workgroups, X = n_xcd, per_die = W / X;
+    const int64_t slots = ceil_div(n_tiles, W) * W;
+    *n_slots = slots;
+    if (!order) return EPARA_OK;
+    if (order_cap < slots) return EPARA_ERR_CAPACITY;
+
+    // where each group's tiles start in the canonical table, and which class it was cut with
+    std::vector<int64_t> first(G, -1);
+    std::vector<int32_t> cls(G, -1);
+    for (int64_t t = 0; t < n_tiles; ++t) {
+        const epara_tile& tl = tiles[t];
+        if (tl.group < 0 || tl.group >= G || tl.cls < 0 || tl.cls >= n_classes) return EPARA_ERR_SHAPE;
+        if (first[tl.group] < 0) { first[tl.group] = t; cls[tl.group] = tl.cls; }
+        else if (cls[tl.group] != tl.cls) return EPARA_ERR_SHAPE;
+    }
+    // every group's tile count must be what the grid rule gives, or the table is not canonical
+    {
+        int64_t expect = 0;
+        for (int32_t g = 0; g < G; ++g)
+            if (first[g] >= 0) {
+                if (first[g] != expect) return EPARA_ERR_SHAPE;
+                expect += ceil_div(groups[g].M, classes[cls[g]].BM) * ceil_div(groups[g].N, classes[cls[g]].BN);
+            }
+        if (expect != n_tiles) return EPARA_ERR_SHAPE;
+    }
+
+    std::vector<int32_t> class_order(n_classes);
+    for (int32_t c = 0; c < n_classes; ++c) class_order[c] = c;
+    std::stable_sort(class_order.begin(), class_order.end(), [&](int32_t a, int32_t b) {
+        return static_cast<int64_t>(classes[a].BM) * classes[a].BN > static_cast<int64_t>(classes[b].BM) * classes[b].BN;
+    });
+
+    std::fill(order, order + slots, -1);
+    int64_t l = 0;
+    auto place = [&](int64_t tile) {
+        const int64_t j = l / W, w = l % W, x = w / per_die, i = w % per_die;
+        order[j * W + i * X + x] = static_cast<int32_t>(tile);
+        ++l;
+    };
+    std::vector<int32_t> members;
+    for (int32_t c : class_order) {
+        members.clear();
+        for (int32_t g = 0; g < G; ++g)
+            if (cls[g] == c) members.push_back(g);
+        std::stable_sort(members.begin(), members.end(),
+                         [&](int32_t a, int32_t b) { return groups[a].K > groups[b].K; });
+        const int64_t BM = classes[c].BM, BN = classes[c].BN;
+        for (int32_t g : members) {
+            const int64_t TM = ceil_div(groups[g].M, BM), TN = ceil_div(groups[g].N, BN);
+            for (int64_t pn = 0; pn < TN; pn += panel_n)
+                for (int64_t pm = 0; pm < TM; pm += panel_m)
+                    for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
+                        for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm)
+                            place(first[g] + tm * TN + tn);
+        }
+    }
+    return l == n_tiles ? EPARA_OK : EPARA_ERR_SHAPE;
+}
+
+int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated,
+                             epara_tile_class* classes, int32_t cap, int32_t* n_classes)
+{
+    if (!n_classes) return EPARA_ERR_NULL;
+    epara_tile_class table[2];
+    int32_t n = 0;
+    if (in_dtype == EPARA_F32) {
+        if (gated) return EPARA_ERR_DTYPE;
+        table[n++] = {INT32_MAX, 64, 64};
+    } else if (in_dtype == EPARA_BF16 || in_dtype == EPARA_FP8_E4M3) {
+        table[n++] = {64, 64, 32};                       // weight-streaming class, whole batch per tile
+        table[n++] = {INT32_MAX, 256, gated ? 128 : 256};  // LDS-tiled MFMA class
+    } else {
+        return EPARA_ERR_DTYPE;
+    }
+    *n_classes = n;
+    if (!classes) return EPARA_OK;
+    if (cap < n) return EPARA_ERR_CAPACITY;
+    std::memcpy(classes, table, sizeof(epara_tile_class) * n);
+    return EPARA_OK;
+}
+
+int32_t epara_ffn_swiglu_args(const epara_ffn_desc* ffn, int32_t G, int32_t in_dtype,
+                              epara_group_args* up_args, epara_group_args* down_args)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (G == 0) return EPARA_OK;
+    if (!ffn || !up_args || !down_args) return EPARA_ERR_NULL;
+    if (in_dtype != EPARA_BF16 && in_dtype != EPARA_FP8_E4M3) return EPARA_ERR_DTYPE;
+    const bool fp8 = in_dtype == EPARA_FP8_E4M3;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_ffn_desc& f = ffn[g];
+        if (f.M < 0 || f.d_model <= 0 || f.d_ff <= 0) return EPARA_ERR_SHAPE;
+        if (fp8 && !(f.s_x > 0.f && f.s_wgate > 0.f && f.s_wup > 0.f && f.s_h > 0.f && f.s_wdown > 0.f))
+            return EPARA_ERR_SHAPE;
+        epara_group_args u;
+        std::memset(&u, 0, sizeof u);
+        u.X = f.X; u.W = f.Wgate; u.W2 = f.Wup; u.bias = nullptr; u.Y = f.H;
+        u.M = f.M; u.K = f.d_model; u.N = f.d_ff; u.act = EPARA_ACT_SWIGLU;
+        u.scale = fp8 ? f.s_x * f.s_wgate : 1.f;
+        u.scale2 = fp8 ? f.s_x * f.s_wup : 1.f;
+        u.out_inv_scale = fp8 ? 1.f / f.s_h : 1.f;
+        epara_group_args d;
+        std::memset(&d, 0, sizeof d);
+        d.X = f.H; d.W = f.Wdown; d.W2 = nullptr; d.bias = nullptr; d.Y = f.Y;
+        d.M = f.M; d.K = f.d_ff; d.N = f.d_model; d.act = EPARA_ACT_NONE;
+        d.scale = fp8 ? f.s_h * f.s_wdown : 1.f;
+        d.scale2 = 1.f;
+        d.out_inv_scale = 1.f;
+        up_args[g] = u;
+        down_args[g] = d;
+    }
+    return EPARA_OK;
+}
+
+}  // extern "C"

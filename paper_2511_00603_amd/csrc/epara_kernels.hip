@@ -1,0 +1,683 @@
+// Device half of libepara: persistent grouped forward kernels for gfx950 (MI355X).
+//
+// One launch serves every co-located service (the MT operator of Sec. 3.1): persistent
+// workgroups walk a device tile table in a precomputed visit order; a tile is either
+//   - "big":    256 rows x 256 columns of one group, LDS-staged, 16x16x32 MFMA, or
+//   - "skinny": a whole batch of <= 64 rows x 32 columns, weights streamed from HBM straight
+//               into MFMA operand registers, K split over the eight waves of the workgroup.
+// Bias, activation, SwiGLU gating, fp8 scales and the output cast are fused in the epilogue.
+//
+// MFMA orientation.  D = A*B with A = a weight fragment (16 output columns x 64 bytes of K)
+// and B = an activation fragment (16 rows x 64 bytes of K): lane (r = lane%16, q = lane/16)
+// feeds the 16 bytes "k-chunk q" of column/row r to both operands and receives
+// D[n = 4q+i][m = r], i = 0..3 -- four consecutive output columns of one row, which is
+// what a row-major store wants.  Only the pairing of A and B chunks matters for the sum,
+// so the same code serves bf16 (8 values per chunk) and fp8 (16 values per chunk).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "epara.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int NT = 512;                 // threads per workgroup (8 waves)
+constexpr int STAGE_BYTES = 32768;      // one operand tile of one pipeline stage: 256 rows x 128 B
+constexpr int LDS_BYTES = 4 * STAGE_BYTES;
+constexpr int BIG_BM = 256;
+constexpr int SKINNY_BN = 32;
+constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
+
+// ------------------------------------------------------------------ small device helpers
+
+template <int ACT>
+__device__ __forceinline__ float act_apply(float z)
+{
+    if constexpr (ACT == EPARA_ACT_RELU)           return z > 0.f ? z : 0.f;
+    else if constexpr (ACT == EPARA_ACT_GELU_ERF)  return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
+    else if constexpr (ACT == EPARA_ACT_GELU_TANH) return 0.5f * z * (1.f + tanhf(0.79788456080286536f * (z + 0.044715f * z * z * z)));
+    else if constexpr (ACT == EPARA_ACT_SILU)      return z / (1.f + expf(-z));
+    else                                           return z;
+}
+
+// Calls f(tag) with tag an integral_constant of the runtime activation, so that the unrolled
+// epilogues are compiled once per activation instead of carrying a switch per element.
+template <int V> struct act_tag { static constexpr int value = V; };
+template <class F>
+__device__ __forceinline__ void with_act(int act, F&& f)
+{
+    switch (act) {
+    case EPARA_ACT_RELU:      f(act_tag<EPARA_ACT_RELU>{}); break;
+    case EPARA_ACT_GELU_ERF:  f(act_tag<EPARA_ACT_GELU_ERF>{}); break;
+    case EPARA_ACT_GELU_TANH: f(act_tag<EPARA_ACT_GELU_TANH>{}); break;
+    case EPARA_ACT_SILU:      f(act_tag<EPARA_ACT_SILU>{}); break;
+    default:                  f(act_tag<EPARA_ACT_NONE>{}); break;
+    }
+}
+
+__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
+
+// fp32 -> bf16 bits, round to nearest even.
+__device__ __forceinline__ uint32_t f32_to_bf16(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// fp32 -> OCP E4M3 code, round to nearest even, saturating at +-448 (NaN -> 0x7f).
+__device__ __forceinline__ uint32_t f32_to_e4m3(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    const uint32_t mag = u & 0x7fffffffu;
+    if (mag > 0x7f800000u) return 0x7fu;
+    const float a = __uint_as_float(mag);
+    if (!(a < 448.f)) return sign | 0x7eu;
+    if (a < 0.015625f)                                   // below 2^-6: multiples of 2^-9
+        return sign | static_cast<uint32_t>(rintf(a * 512.f));
+    uint32_t rnd = mag + 0x7ffffu + ((mag >> 20) & 1u);  // keep 3 mantissa bits
+    uint32_t code = (rnd >> 20) - (120u << 3);           // rebias 127 -> 7
+    return sign | (code > 0x7eu ? 0x7eu : code);
+}
+
+template <int DT>
+__device__ __forceinline__ void mma(v4f& c, const v4i& a, const v4i& b)
+{
+    if constexpr (DT == EPARA_BF16) {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        typedef long v2l __attribute__((ext_vector_type(2)));
+        const v2l al = __builtin_bit_cast(v2l, a), bl = __builtin_bit_cast(v2l, b);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(al[0], bl[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(al[1], bl[1], c, 0, 0, 0);
+    }
+}
+
+// Pointers read from the argument table are generic; the kernels know they are global memory.
+#define EPARA_GLOBAL __attribute__((address_space(1)))
+typedef const EPARA_GLOBAL char* gcptr;
+template <class T>
+__device__ __forceinline__ const EPARA_GLOBAL T* as_global(const void* p) { return (const EPARA_GLOBAL T*)p; }
+template <class T>
+__device__ __forceinline__ EPARA_GLOBAL T* as_global(void* p) { return (EPARA_GLOBAL T*)p; }
+
+__device__ __forceinline__ v4i ld16(gcptr p) { return *reinterpret_cast<const EPARA_GLOBAL v4i*>(p); }
+
+// Stores up to four consecutive outputs of one row, starting at column n (a multiple of 4).
+__device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, int N, const float* v, int valid, bool vec_ok)
+{
+    const size_t e = m * static_cast<size_t>(N) + n;
+    if (out_dtype == EPARA_BF16) {
+        EPARA_GLOBAL uint16_t* y = as_global<uint16_t>(Y) + e;
+        if (vec_ok && valid >= 4) {
+            v2u pk;
+            pk[0] = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+            pk[1] = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+            *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i < valid) y[i] = static_cast<uint16_t>(f32_to_bf16(v[i]));
+        }
+    } else {  // EPARA_FP8_E4M3
+        EPARA_GLOBAL uint8_t* y = as_global<uint8_t>(Y) + e;
+        if (vec_ok && valid >= 4) {
+            *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32_to_e4m3(v[0]) | (f32_to_e4m3(v[1]) << 8) |
+                                              (f32_to_e4m3(v[2]) << 16) | (f32_to_e4m3(v[3]) << 24);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i < valid) y[i] = static_cast<uint8_t>(f32_to_e4m3(v[i]));
+        }
+    }
+}
+
+// Epilogue of one 16x16 accumulator fragment (plain groups): lane holds columns nl..nl+3 of row ml.
+template <int ACT>
+__device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out_dtype, const v4f& a,
+                                             int m0, int ml, int rows, int n0, int nl, int cols, bool vec_ok)
+{
+    if (ml >= rows || nl >= cols) return;
+    const int valid = cols - nl;
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float b = 0.f;
+        if (ga.bias && i < valid) b = as_global<float>(ga.bias)[n0 + nl + i];
+        v[i] = act_apply<ACT>(ga.scale * a[i] + b) * ga.out_inv_scale;
+    }
+    store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, valid, vec_ok);
+}
+
+// Epilogue of a gate/up fragment pair (EPARA_ACT_SWIGLU groups).
+__device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out_dtype, const v4f& g, const v4f& u,
+                                             int m0, int ml, int rows, int n0, int nl, int cols, bool vec_ok)
+{
+    if (ml >= rows || nl >= cols) return;
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = silu(ga.scale * g[i]) * (ga.scale2 * u[i]) * ga.out_inv_scale;
+    store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, cols - nl, vec_ok);
+}
+
+// ------------------------------------------------------------------ big tiles (LDS + MFMA)
+
+// LDS: [X stage 0][X stage 1][W stage 0][W stage 1], 32 KiB each.
+//   X tile: row-major 256 rows x 128 B, 16-byte chunk kc of row stored at chunk kc ^ ((row/2)%8)
+//           so that the 16 rows one ds_read_b128 wavefront quarter touches hit distinct banks.
+//   W tile: verbatim image of the packed weights: [16 column blocks][2 fragments][64 lanes][16 B].
+// Loads never branch per lane: rows past the batch and column blocks past N are clamped to the
+// last valid one (they only feed outputs that are never stored); only the K tail needs zeros,
+// and that is confined to the last k-tile.
+template <int DT, bool GATED>
+__device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dtype,
+                                         int m0, int n0, int rows, int cols, char* lds)
+{
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
+    constexpr int KF = 4 * EPC;     // K elements per weight fragment
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int wn = wave & 1, wm = wave >> 1;
+    const int K = ga.K, N = ga.N;
+    const int KS = (K + KF - 1) / KF;
+    const int KT = (KS + 1) >> 1;
+    const int NB = (N + 15) >> 4;
+
+    // --- global -> register -> LDS staging: per k-tile each thread moves 4 X chunks and 4 W chunks
+    // X chunk j: row (tid/8) + 64 j, k-chunk tid%8.  W chunk j: column block (tid/128) + 4 j,
+    // fragment (tid/64)%2, lane slot tid%64 (gated tiles: j = 0,1 gate blocks, j = 2,3 up blocks).
+    const int srow = tid >> 3;
+    const int xkc = (tid & 7) * EPC;                       // element offset of my chunk inside a k-tile
+    const int wksl = (tid >> 6) & 1;
+    gcptr xbase = as_global<char>(ga.X) + static_cast<size_t>(m0) * K * ESZ;
+    gcptr wbase0 = as_global<char>(ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
+    gcptr wbase1 = GATED ? as_global<char>(ga.W2) + static_cast<size_t>(n0 >> 4) * KS * 1024 : wbase0;
+    uint32_t xoff[4], woff[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = min(srow + 64 * j, rows - 1);
+        xoff[j] = static_cast<uint32_t>((row * K + xkc) * ESZ);
+        const int nbrel = (tid >> 7) + 4 * (GATED ? (j & 1) : j);
+        const int nb = min(nbrel, NB - 1 - (n0 >> 4));
+        woff[j] = static_cast<uint32_t>(((nb * KS + wksl) * 64 + lane) * 16);
+    }
+    const int xs_off = srow * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);      // + j * 8192
+    const int ws_off = 2 * STAGE_BYTES + tid * 16;                              // + j * 8192
+
+    v4i xr[4], wr[4];
+    auto load_tile = [&](int kt) {                         // every chunk of this k-tile lies inside K
+        gcptr xb = xbase + static_cast<size_t>(kt) * 128;
+        gcptr w0 = wbase0 + static_cast<size_t>(kt) * 2048;
+        gcptr w1 = wbase1 + static_cast<size_t>(kt) * 2048;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xr[j] = ld16(xb + xoff[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wr[j] = ld16(((GATED && j >= 2) ? w1 : w0) + woff[j]);
+    };
+    auto load_tile_tail = [&](int kt) {                    // last k-tile: chunks past K become zeros
+        gcptr xb = xbase + static_cast<size_t>(kt) * 128;
+        gcptr w0 = wbase0 + static_cast<size_t>(kt) * 2048;
+        gcptr w1 = wbase1 + static_cast<size_t>(kt) * 2048;
+        const bool x_ok = kt * 2 * KF + xkc < K;
+        const bool w_ok = kt * 2 + wksl < KS;
+        const uint32_t xback = x_ok ? 0u : static_cast<uint32_t>(xkc * ESZ);   // fall back to chunk 0 / fragment 0
+        const uint32_t wback = w_ok ? 0u : 1024u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const v4i v = ld16(xb + (xoff[j] - xback));
+            xr[j] = x_ok ? v : v4i{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const v4i v = ld16(((GATED && j >= 2) ? w1 : w0) + (woff[j] - wback));
+            wr[j] = w_ok ? v : v4i{0, 0, 0, 0};
+        }
+    };
+    auto store_tile = [&](int stage) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(lds + stage * STAGE_BYTES + xs_off + j * 8192) = xr[j];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(lds + stage * STAGE_BYTES + ws_off + j * 8192) = wr[j];
+    };
+
+    // --- fragment read offsets: X fragment fm adds fm*2048, W fragment fn adds a constant too
+    int xf_off[2];
+#pragma unroll
+    for (int ksl = 0; ksl < 2; ++ksl)
+        xf_off[ksl] = (wm * 64 + r) * 128 + (((ksl * 4 + q) ^ ((r >> 1) & 7)) << 4);
+    const int wf_off = 2 * STAGE_BYTES + ((GATED ? wn * 4 : wn * 8) * 128 + lane) * 16;
+
+    v4f acc[8][4];
+#pragma unroll
+    for (int fn = 0; fn < 8; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm) acc[fn][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    __syncthreads();                       // the previous tile is done with the LDS
+    if (KT > 1) load_tile(0); else load_tile_tail(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < KT; ++kt) {
+        const int stage = kt & 1;
+        if (kt + 2 < KT) load_tile(kt + 1);
+        else if (kt + 1 < KT) load_tile_tail(kt + 1);
+#pragma unroll
+        for (int ksl = 0; ksl < 2; ++ksl) {
+            v4i wf[8], xf[4];
+#pragma unroll
+            for (int fn = 0; fn < 8; ++fn) {
+                const int nbrel = (GATED && fn >= 4) ? fn + 4 : fn;     // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
+                wf[fn] = *reinterpret_cast<const v4i*>(lds + stage * STAGE_BYTES + wf_off + nbrel * 2048 + ksl * 1024);
+            }
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm)
+                xf[fm] = *reinterpret_cast<const v4i*>(lds + stage * STAGE_BYTES + xf_off[ksl] + fm * 2048);
+#pragma unroll
+            for (int fn = 0; fn < 8; ++fn)
+#pragma unroll
+                for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[fn][fm], wf[fn], xf[fm]);
+        }
+        if (kt + 1 < KT) store_tile(stage ^ 1);
+        __syncthreads();
+    }
+
+    const bool vec_ok = (N & 3) == 0;
+    if constexpr (GATED) {
+#pragma unroll
+        for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm)
+                finish_gated(ga, out_dtype, acc[fn][fm], acc[fn + 4][fm], m0, wm * 64 + fm * 16 + r, rows,
+                             n0, (wn * 4 + fn) * 16 + 4 * q, cols, vec_ok);
+    } else {
+        with_act(ga.act, [&](auto tag) {
+#pragma unroll
+            for (int fn = 0; fn < 8; ++fn)
+#pragma unroll
+                for (int fm = 0; fm < 4; ++fm)
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, acc[fn][fm], m0, wm * 64 + fm * 16 + r, rows,
+                                                       n0, (wn * 8 + fn) * 16 + 4 * q, cols, vec_ok);
+        });
+    }
+}
+
+// ------------------------------------------------------------------ skinny tiles (weight streaming)
+
+// A batch of M <= 64 rows against 32 output columns.  Wave w takes the weight fragments
+// ks = w, w+8, ... of the K dimension, straight from HBM into MFMA operand registers (each
+// load instruction of a wave reads 1 KiB of contiguous packed weights); the eight partial
+// sums meet in LDS and are added in wave order, so the result does not depend on timing.
+template <int DT, bool GATED, int MB>
+__device__ __forceinline__ void skinny_tile(const epara_group_args& ga, int out_dtype, int n0, int cols, char* lds)
+{
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ;
+    constexpr int KF = 4 * EPC;
+    constexpr int NF = GATED ? 4 : 2;        // weight fragments per K step: 2 column blocks (x2 matrices when gated)
+    constexpr int U = 4;                     // K steps in flight per wave
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, q = lane >> 4;
+    const int M = ga.M, K = ga.K, N = ga.N;
+    const int KS = (K + KF - 1) / KF;
+    const int NB = (N + 15) >> 4;
+
+    gcptr wp[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int nb = min((n0 >> 4) + (f & 1), NB - 1);   // a block past N only feeds unstored columns
+        gcptr base = as_global<char>((GATED && f >= 2) ? ga.W2 : ga.W);
+        wp[f] = base + (static_cast<size_t>(nb) * KS * 64 + lane) * 16;
+    }
+    gcptr xp[MB];
+#pragma unroll
+    for (int fm = 0; fm < MB; ++fm) {
+        const int row = min(fm * 16 + r, M - 1);           // a row past the batch only feeds unstored rows
+        xp[fm] = as_global<char>(ga.X) + static_cast<size_t>(row) * K * ESZ;
+    }
+    const int xq = q * EPC;                                // my k offset inside a fragment
+
+    v4f acc[NF][MB];
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int fm = 0; fm < MB; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // Steps of this wave: ks = wave + 8 i.  U steps are loaded before any is consumed, so each
+    // wave keeps U * NF KiB of weights in flight.
+    const int n_steps = KS > wave ? (KS - wave + 7) >> 3 : 0;
+    for (int i0 = 0; i0 < n_steps; i0 += U) {
+        v4i wf[U][NF], xf[U][MB];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ks = wave + 8 * min(i0 + u, n_steps - 1);   // repeats the last step past the end (discarded)
+#pragma unroll
+            for (int f = 0; f < NF; ++f) wf[u][f] = ld16(wp[f] + static_cast<size_t>(ks) * 1024);
+            const bool k_ok = ks * KF + xq < K;                    // false only in a ragged last fragment
+            const int xo = (ks * KF + (k_ok ? xq : 0)) * ESZ;
+#pragma unroll
+            for (int fm = 0; fm < MB; ++fm) {
+                const v4i v = ld16(xp[fm] + xo);
+                xf[u][fm] = k_ok ? v : v4i{0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i0 + u < n_steps) {
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+#pragma unroll
+                    for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], wf[u][f], xf[u][fm]);
+            }
+        }
+    }
+
+    // cross-wave reduction through LDS: red[wave][f*MB+fm][lane]
+    v4f* red = reinterpret_cast<v4f*>(lds);
+    __syncthreads();
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int fm = 0; fm < MB; ++fm) red[(wave * (NF * MB) + f * MB + fm) * 64 + lane] = acc[f][fm];
+    __syncthreads();
+
+    const bool vec_ok = (N & 3) == 0;
+    for (int u = wave; u < 2 * MB; u += 8) {            // unit = (column block, row block)
+        const int cb = u / MB, fm = u % MB;
+        v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < 8; ++w) {
+            s0 += red[(w * (NF * MB) + cb * MB + fm) * 64 + lane];
+            if constexpr (GATED) s1 += red[(w * (NF * MB) + (cb + 2) * MB + fm) * 64 + lane];
+        }
+        if constexpr (GATED) finish_gated(ga, out_dtype, s0, s1, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
+        else with_act(ga.act, [&](auto tag) {
+            finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
+        });
+    }
+}
+
+template <int DT, bool GATED>
+__device__ __forceinline__ void skinny_dispatch(const epara_group_args& ga, int out_dtype, int n0, int cols, char* lds)
+{
+    const int mb = (ga.M + 15) >> 4;
+    if (mb <= 1)      skinny_tile<DT, GATED, 1>(ga, out_dtype, n0, cols, lds);
+    else if (mb == 2) skinny_tile<DT, GATED, 2>(ga, out_dtype, n0, cols, lds);
+    else if (mb == 3) skinny_tile<DT, GATED, 3>(ga, out_dtype, n0, cols, lds);
+    else              skinny_tile<DT, GATED, 4>(ga, out_dtype, n0, cols, lds);
+}
+
+// ------------------------------------------------------------------ persistent kernels
+
+template <int DT>
+__global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
+                                                     const epara_tile* __restrict__ tiles,
+                                                     const int32_t* __restrict__ order,
+                                                     long n_slots, int out_dtype)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    for (long s = blockIdx.x; s < n_slots; s += gridDim.x) {
+        const int t = order[s];
+        if (t < 0) continue;
+        const epara_tile tl = tiles[t];
+        const epara_group_args ga = args[tl.group];
+        const bool gated = ga.act == EPARA_ACT_SWIGLU;
+        if (tl.cls == 0) {
+            if (gated) skinny_dispatch<DT, true>(ga, out_dtype, tl.n0, tl.cols, lds);
+            else       skinny_dispatch<DT, false>(ga, out_dtype, tl.n0, tl.cols, lds);
+        } else {
+            if (gated) big_tile<DT, true>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+            else       big_tile<DT, false>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+        }
+    }
+}
+
+// fp32 groups: 64x64 tiles, plain FMA in fp32, K ascending.
+__global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_args* __restrict__ args,
+                                                             const epara_tile* __restrict__ tiles,
+                                                             const int32_t* __restrict__ order, long n_slots)
+{
+    __shared__ float Xs[F32_BK][F32_BM + 1];
+    __shared__ float Ws[F32_BK][F32_BN];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    for (long s = blockIdx.x; s < n_slots; s += gridDim.x) {
+        const int t = order[s];
+        if (t < 0) continue;
+        const epara_tile tl = tiles[t];
+        const epara_group_args ga = args[tl.group];
+        const EPARA_GLOBAL float* X = as_global<float>(ga.X);
+        const EPARA_GLOBAL float* W = as_global<float>(ga.W);
+        EPARA_GLOBAL float* Y = as_global<float>(ga.Y);
+        const int K = ga.K, N = ga.N;
+        float acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int k0 = 0; k0 < K; k0 += F32_BK) {
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = tid + F32_NT * j;
+                const int row = e >> 4, kk = e & 15;
+                float v = 0.f;
+                if (row < tl.rows && k0 + kk < K) v = X[static_cast<size_t>(tl.m0 + row) * K + k0 + kk];
+                Xs[kk][row] = v;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = tid + F32_NT * j;
+                const int kk = e >> 6, nn = e & 63;
+                float v = 0.f;
+                if (k0 + kk < K && nn < tl.cols) v = W[static_cast<size_t>(k0 + kk) * N + tl.n0 + nn];
+                Ws[kk][nn] = v;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < F32_BK; ++kk) {
+                float a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = Xs[kk][ty * 4 + i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[j] = Ws[kk][tx * 4 + j];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+            }
+        }
+        with_act(ga.act, [&](auto tag) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = ty * 4 + i;
+                if (row >= tl.rows) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = tx * 4 + j;
+                    if (col >= tl.cols) continue;
+                    const float b = ga.bias ? as_global<float>(ga.bias)[tl.n0 + col] : 0.f;
+                    Y[static_cast<size_t>(tl.m0 + row) * N + tl.n0 + col] =
+                        act_apply<decltype(tag)::value>(ga.scale * acc[i][j] + b);
+                }
+            }
+        });
+    }
+}
+
+// One 16-byte chunk of the packed weights per thread.
+template <int ESZ>
+__global__ void pack_kernel(const char* __restrict__ W, int K, int N, char* __restrict__ out, long n_chunks)
+{
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const long idx = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (idx >= n_chunks) return;
+    const int KS = (K + KF - 1) / KF;
+    const int slot = static_cast<int>(idx & 63);
+    const long frag = idx >> 6;
+    const int ks = static_cast<int>(frag % KS);
+    const long nb = frag / KS;
+    const int q = slot >> 4, r = slot & 15;
+    const long n = nb * 16 + r;
+    const int k0 = ks * KF + q * EPC;
+    alignas(16) char buf[16];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+        const int k = k0 + e;
+        const bool ok = k < K && n < N;
+        if constexpr (ESZ == 2) {
+            reinterpret_cast<uint16_t*>(buf)[e] = ok ? reinterpret_cast<const uint16_t*>(W)[static_cast<size_t>(k) * N + n] : 0;
+        } else {
+            reinterpret_cast<uint8_t*>(buf)[e] = ok ? reinterpret_cast<const uint8_t*>(W)[static_cast<size_t>(k) * N + n] : 0;
+        }
+    }
+    *reinterpret_cast<v4i*>(out + idx * 16) = *reinterpret_cast<const v4i*>(buf);
+}
+
+// ------------------------------------------------------------------ host-side validation
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dtype)
+{
+    if (!L) return EPARA_ERR_NULL;
+    const bool f32 = in_dtype == EPARA_F32;
+    if (f32) { if (out_dtype != EPARA_F32) return EPARA_ERR_DTYPE; }
+    else if (in_dtype == EPARA_BF16) { if (out_dtype != EPARA_BF16) return EPARA_ERR_DTYPE; }
+    else if (in_dtype == EPARA_FP8_E4M3) { if (out_dtype != EPARA_BF16 && out_dtype != EPARA_FP8_E4M3) return EPARA_ERR_DTYPE; }
+    else return EPARA_ERR_DTYPE;
+    if (L->G < 0 || L->n_tiles < 0 || L->n_slots < 0) return EPARA_ERR_SHAPE;
+    if (L->n_tiles == 0) return EPARA_OK;
+    if (!L->h_args || !L->d_args || !L->h_tiles || !L->d_tiles || !L->d_order) return EPARA_ERR_NULL;
+    if (L->n_workgroups <= 0 || L->n_slots < L->n_tiles || L->n_slots % L->n_workgroups != 0 || L->n_tiles > INT32_MAX)
+        return EPARA_ERR_SHAPE;
+    const int esz = f32 ? 4 : (in_dtype == EPARA_BF16 ? 2 : 1);
+    for (int32_t g = 0; g < L->G; ++g) {
+        const epara_group_args& a = L->h_args[g];
+        if (a.M < 0 || a.K <= 0 || a.N <= 0) return EPARA_ERR_SHAPE;
+        if (a.act < EPARA_ACT_NONE || a.act > EPARA_ACT_SWIGLU) return EPARA_ERR_DTYPE;
+        if (a.act == EPARA_ACT_SWIGLU && (f32 || a.bias)) return EPARA_ERR_DTYPE;
+        if (a.M == 0) continue;
+        if (!a.X || !a.W || !a.Y || (a.act == EPARA_ACT_SWIGLU && !a.W2)) return EPARA_ERR_NULL;
+        if (!aligned16(a.X) || !aligned16(a.W) || !aligned16(a.Y) || !aligned16(a.W2) || !aligned16(a.bias))
+            return EPARA_ERR_ALIGN;
+        if (!f32 && (static_cast<int64_t>(a.K) * esz) % 16 != 0) return EPARA_ERR_ALIGN;
+    }
+    epara_tile_class cls[2][2];
+    int32_t ncls[2] = {0, 0};
+    epara_kernel_classes(in_dtype, 0, cls[0], 2, &ncls[0]);
+    if (!f32) epara_kernel_classes(in_dtype, 1, cls[1], 2, &ncls[1]);
+    for (int64_t t = 0; t < L->n_tiles; ++t) {
+        const epara_tile& tl = L->h_tiles[t];
+        if (tl.group < 0 || tl.group >= L->G) return EPARA_ERR_SHAPE;
+        const epara_group_args& a = L->h_args[tl.group];
+        const int gated = a.act == EPARA_ACT_SWIGLU ? 1 : 0;
+        if (tl.cls < 0 || tl.cls >= ncls[gated]) return EPARA_ERR_SHAPE;
+        const epara_tile_class& c = cls[gated][tl.cls];
+        if (a.M > c.max_M || (tl.cls > 0 && a.M <= cls[gated][tl.cls - 1].max_M)) return EPARA_ERR_SHAPE;
+        if (tl.m0 < 0 || tl.n0 < 0 || tl.m0 >= a.M || tl.n0 >= a.N || tl.m0 % c.BM || tl.n0 % c.BN) return EPARA_ERR_SHAPE;
+        const int32_t rows = a.M - tl.m0 < c.BM ? a.M - tl.m0 : c.BM;
+        const int32_t cols = a.N - tl.n0 < c.BN ? a.N - tl.n0 : c.BN;
+        if (tl.rows != rows || tl.cols != cols) return EPARA_ERR_SHAPE;
+    }
+    return EPARA_OK;
+}
+
+int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, hipStream_t stream)
+{
+    if (L->n_tiles == 0) return EPARA_OK;
+    const dim3 grid(static_cast<unsigned>(L->n_workgroups));
+    (void)hipGetLastError();
+    if (in_dtype == EPARA_F32) {
+        hipLaunchKernelGGL(grouped_kernel_f32, grid, dim3(F32_NT), 0, stream, L->d_args, L->d_tiles, L->d_order,
+                           static_cast<long>(L->n_slots));
+    } else if (in_dtype == EPARA_BF16) {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<EPARA_BF16>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (attr != hipSuccess) return EPARA_ERR_HIP;
+        hipLaunchKernelGGL(grouped_kernel<EPARA_BF16>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype);
+    } else {
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<EPARA_FP8_E4M3>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (attr != hipSuccess) return EPARA_ERR_HIP;
+        hipLaunchKernelGGL(grouped_kernel<EPARA_FP8_E4M3>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype);
+    }
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype)
+{
+    if (K <= 0 || N <= 0) return -1;
+    if (dtype == EPARA_F32) return static_cast<int64_t>(K) * N * 4;
+    if (dtype != EPARA_BF16 && dtype != EPARA_FP8_E4M3) return -1;
+    const int64_t KF = dtype == EPARA_BF16 ? 32 : 64;
+    return ((static_cast<int64_t>(N) + 15) / 16) * ((K + KF - 1) / KF) * 1024;
+}
+
+int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
+                           void* d_packed, int64_t packed_bytes, void* stream)
+{
+    if (!d_W || !d_packed) return EPARA_ERR_NULL;
+    if (K <= 0 || N <= 0) return EPARA_ERR_SHAPE;
+    const int64_t need = epara_packed_weight_bytes(K, N, dtype);
+    if (need < 0) return EPARA_ERR_DTYPE;
+    if (packed_bytes < need) return EPARA_ERR_CAPACITY;
+    if (!aligned16(d_packed)) return EPARA_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    if (dtype == EPARA_F32) {
+        if (hipMemcpyAsync(d_packed, d_W, static_cast<size_t>(need), hipMemcpyDeviceToDevice, st) != hipSuccess)
+            return EPARA_ERR_HIP;
+        return EPARA_OK;
+    }
+    const long n_chunks = need / 16;
+    const unsigned blocks = static_cast<unsigned>((n_chunks + 255) / 256);
+    if (dtype == EPARA_BF16)
+        hipLaunchKernelGGL(pack_kernel<2>, dim3(blocks), dim3(256), 0, st, static_cast<const char*>(d_W), K, N,
+                           static_cast<char*>(d_packed), n_chunks);
+    else
+        hipLaunchKernelGGL(pack_kernel<1>, dim3(blocks), dim3(256), 0, st, static_cast<const char*>(d_W), K, N,
+                           static_cast<char*>(d_packed), n_chunks);
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int32_t out_dtype, void* stream)
+{
+    if (int32_t st = validate_launch(launch, in_dtype, out_dtype)) return st;
+    return enqueue(launch, in_dtype, out_dtype, static_cast<hipStream_t>(stream));
+}
+
+int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
+                                 int32_t in_dtype, int32_t h_dtype, int32_t out_dtype, void* stream)
+{
+    if (!up || !down) return EPARA_ERR_NULL;
+    if (in_dtype == EPARA_BF16) { if (h_dtype != EPARA_BF16 || out_dtype != EPARA_BF16) return EPARA_ERR_DTYPE; }
+    else if (in_dtype == EPARA_FP8_E4M3) { if (h_dtype != EPARA_FP8_E4M3 || out_dtype != EPARA_BF16) return EPARA_ERR_DTYPE; }
+    else return EPARA_ERR_DTYPE;
+    if (int32_t st = validate_launch(up, in_dtype, h_dtype)) return st;
+    if (int32_t st = validate_launch(down, in_dtype, out_dtype)) return st;
+    if (up->G != down->G) return EPARA_ERR_SHAPE;
+    if (up->n_tiles > 0 || down->n_tiles > 0) {
+        for (int32_t g = 0; g < up->G; ++g) {
+            const epara_group_args& u = up->h_args[g];
+            const epara_group_args& d = down->h_args[g];
+            if (u.act != EPARA_ACT_SWIGLU || d.act != EPARA_ACT_NONE) return EPARA_ERR_DTYPE;
+            if (u.M != d.M || u.N != d.K || u.K != d.N || u.Y != d.X) return EPARA_ERR_SHAPE;
+        }
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int32_t rc = enqueue(up, in_dtype, h_dtype, st)) return rc;
+    return enqueue(down, in_dtype, out_dtype, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+"""Marshalling between PyTorch device memory and libepara.  PyTorch is used for allocation,
+host<->device copies and streams only; every step of the forward path runs in the library."""
+import time
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+TORCH_DTYPE = {B.EPARA_F32: torch.float32, B.EPARA_BF16: torch.bfloat16, B.EPARA_FP8_E4M3: torch.uint8}
+
+
+def _require_gpu():
+    if not torch.cuda.is_available():
+        raise RuntimeError("libepara needs a GPU: no CPU fallback exists")
+
+
+def _upload(a, device):
+    """numpy array (any dtype) -> uint8 device tensor holding the same bytes (never empty)."""
+    raw = np.ascontiguousarray(a).view(np.uint8).reshape(-1)
+    if raw.size == 0:
+        return torch.zeros(16, dtype=torch.uint8, device=device)
+    return torch.from_numpy(raw.copy()).to(device)
+
+
+def current_stream_handle():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def n_compute_units(device=None):
+    return torch.cuda.get_device_properties(device if device is not None else torch.cuda.current_device()).multi_processor_count
+
+
+def device_tensor_from_bits(bits, dtype, device):
+    """Host bit patterns (float32 / uint16 bf16 / uint8 e4m3 arrays) -> device tensor of that storage type."""
+    if dtype == B.EPARA_F32:
+        return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.float32)).to(device)
+    if dtype == B.EPARA_BF16:
+        return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint8)).to(device)
+
+
+def pack_weights(W, dtype):
+    """W: device tensor holding the logical [K, N] weights in storage type `dtype` -> packed uint8 tensor."""
+    _require_gpu()
+    K, N = W.shape
+    W = W.contiguous()
+    nbytes = B.epara_packed_weight_bytes(K, N, dtype)
+    out = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
+    B.epara_pack_weights(W.data_ptr(), K, N, dtype, out.data_ptr(), nbytes, current_stream_handle())
+    return out
+
+
+def group_args(X, W, Y, M, K, N, act, bias=None, W2=None, scale=1.0, scale2=1.0, out_inv_scale=1.0):
+    """One GROUP_ARGS record from device tensors (or None)."""
+    a = np.zeros(1, dtype=B.GROUP_ARGS)[0]
+    ptr = lambda t: 0 if t is None else int(t.data_ptr())
+    a["X"], a["W"], a["W2"], a["bias"], a["Y"] = ptr(X), ptr(W), ptr(W2), ptr(bias), ptr(Y)
+    a["M"], a["K"], a["N"] = M, K, N
+    a["act"] = B.ACT_BY_NAME[act] if isinstance(act, str) else act
+    a["scale"], a["scale2"], a["out_inv_scale"] = scale, scale2, out_inv_scale
+    return a
+
+
+class LaunchPlan:
+    """Host plan + its device copy for one grouped launch (epara_launch)."""
+
+    def __init__(self, args, in_dtype, device, n_workgroups=None, n_xcd=8, panel_m=8, panel_n=4):
+        _require_gpu()
+        t0 = time.perf_counter()
+        self.args = np.ascontiguousarray(args, dtype=B.GROUP_ARGS)
+        G = len(self.args)
+        gated = bool(G) and bool(np.all(self.args["act"] == B.EPARA_ACT_SWIGLU))
+        if G and not gated and np.any(self.args["act"] == B.EPARA_ACT_SWIGLU):
+            raise ValueError("a launch is either all SwiGLU groups or none")
+        self.in_dtype = in_dtype
+        self.groups = np.zeros(G, dtype=B.GROUP_DESC)
+        for f in ("M", "K", "N", "act"):
+            self.groups[f] = self.args[f]
+        self.groups["has_bias"] = (self.args["bias"] != 0).astype(np.int32)
+        self.classes = B.epara_kernel_classes(in_dtype, gated)
+        self.row_off, self.x_off, self.y_off, self.tiles = B.epara_plan_groups(self.groups, self.classes)
+        if n_workgroups is None:
+            n_workgroups = n_compute_units(device)
+            n_workgroups -= n_workgroups % n_xcd
+        self.n_workgroups = n_workgroups
+        self.order = B.epara_schedule_tiles(self.groups, self.classes, self.tiles, n_workgroups, n_xcd, panel_m, panel_n)
+        self.plan_seconds = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        self.d_args = _upload(self.args, device)
+        self.d_tiles = _upload(self.tiles, device)
+        self.d_order = _upload(self.order, device)
+        torch.cuda.synchronize(device)
+        self.upload_seconds = time.perf_counter() - t0
+        self.c = B.Launch(self.args.ctypes.data, self.d_args.data_ptr(), self.tiles.ctypes.data, self.d_tiles.data_ptr(),
+                          self.d_order.data_ptr(), len(self.tiles), len(self.order), n_workgroups, G)
+
+
+def grouped_forward(plan, out_dtype, stream=None):
+    B.epara_grouped_forward(plan.c, plan.in_dtype, out_dtype, current_stream_handle() if stream is None else stream)
+
+
+def grouped_ffn_swiglu(up, down, h_dtype, out_dtype, stream=None):
+    B.epara_grouped_ffn_swiglu(up.c, down.c, up.in_dtype, h_dtype, out_dtype,
+                               current_stream_handle() if stream is None else stream)

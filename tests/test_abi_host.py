@@ -1,0 +1,256 @@
+"""CPU-side checks of libepara: every symbol the header declares is exported, the C++ planner and
+scheduler reproduce the reference planner integer for integer, and bad arguments come back as
+status codes (the launch functions validate on the host before touching the device)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import planner as P
+from paper_2511_00603_amd import binding as B
+from workloads import make_mix
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "epara.h")
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    names = sorted(set(re.findall(r"^(?:int32_t|int64_t|const char\*)\s+(epara_[a-z0-9_]+)\s*\(", text, re.M)))
+    assert len(names) >= 12, names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_sizes_match_header_layout():
+    assert B.GROUP_ARGS.itemsize == 72 and B.TILE.itemsize == 24 and B.FFN_DESC.itemsize == 80
+    assert ctypes.sizeof(B.Launch) == 64
+
+
+def _desc(groups):
+    g = np.zeros(len(groups), dtype=B.GROUP_DESC)
+    for i, (M, K, N) in enumerate(groups):
+        g[i]["M"], g[i]["K"], g[i]["N"] = M, K, N
+    return g
+
+
+def _classes(cl):
+    c = np.zeros(len(cl), dtype=B.TILE_CLASS)
+    for i, (mm, bm, bn) in enumerate(cl):
+        c[i]["max_M"], c[i]["BM"], c[i]["BN"] = mm, bm, bn
+    return c
+
+
+def mix_group_shapes():
+    """(M, K, N) lists of every launch of the five mixes, from the seeded structure draws."""
+    out = []
+    m1 = [4, 16]
+    out += [[(m, 256, 512) for m in m1], [(m, 512, 512) for m in m1], [(m, 512, 10) for m in m1]]
+    d = [512, 512, 1024, 256, 1024, 256, 256, 512, 1024, 1024, 256, 1024, 256, 256, 1024, 256]
+    rows = [6, 4, 9, 11, 5, 7, 7, 8, 8, 4, 14, 7, 4, 4, 6, 8]
+    out += [[(r, k, 4 * k) for r, k in zip(rows, d)], [(r, 4 * k, k) for r, k in zip(rows, d)]]
+    M3 = [197 * i for i in [32, 16, 1, 8, 4, 4, 2, 8]]
+    out += [[(m, 768, 2304) for m in M3] + [(m, 768, 3072) for m in M3], [(m, 3072, 768) for m in M3]]
+    out += [[(m, 4096, 11008) for m in (1, 8, 32, 64)], [(m, 11008, 4096) for m in (1, 8, 32, 64)]]
+    out += [[(4692, 5120, 13824), (3500, 5120, 13824)], [(4692, 13824, 5120), (3500, 13824, 5120)]]
+    return out
+
+
+ADVERSARIAL = [
+    [(1, 8, 10)], [(64, 8, 32), (65, 8, 33)], [(255, 16, 255), (256, 16, 256), (257, 16, 257)],
+    [(0, 8, 8), (3, 8, 8), (0, 8, 8)], [(0, 8, 8)], [],
+    [(63, 40, 31), (513, 24, 1)], [(1000, 64, 1000), (7, 2048, 77), (300, 128, 300), (64, 512, 64)],
+]
+CLASS_TABLES = [[(64, 64, 32), (P.INT32_MAX, 256, 256)], [(64, 64, 32), (P.INT32_MAX, 256, 128)],
+                [(P.INT32_MAX, 64, 64)], [(16, 16, 64), (64, 64, 64), (512, 128, 128), (P.INT32_MAX, 256, 256)]]
+
+
+@pytest.mark.parametrize("groups", mix_group_shapes() + ADVERSARIAL)
+@pytest.mark.parametrize("classes", CLASS_TABLES)
+def test_planner_and_scheduler_match_reference_bit_for_bit(groups, classes):
+    row_off, x_off, y_off, tiles = P.plan_groups(groups, classes)
+    r2, x2, y2, t2 = B.epara_plan_groups(_desc(groups), _classes(classes))
+    assert r2.tolist() == row_off and x2.tolist() == x_off and y2.tolist() == y_off
+    assert [tuple(int(v) for v in t) for t in t2] == tiles
+    for W, X, pm, pn in ((256, 8, 8, 4), (8, 8, 2, 2), (48, 4, 3, 5), (1, 1, 1, 1)):
+        order = P.schedule_tiles(groups, classes, tiles, W, X, pm, pn)
+        o2 = B.epara_schedule_tiles(_desc(groups), _classes(classes), t2, W, X, pm, pn)
+        assert o2.tolist() == order
+
+
+def test_mix_structures_are_the_seeded_draws():
+    m2, m3 = make_mix(2), make_mix(3, d=16, ffn=32)          # structure draws do not depend on the widths
+    assert [s.M for s in m2.services] == [6, 4, 9, 11, 5, 7, 7, 8, 8, 4, 14, 7, 4, 4, 6, 8]
+    assert [s.X.shape[1] for s in m2.services] == [512, 512, 1024, 256, 1024, 256, 256, 512, 1024, 1024, 256, 1024, 256, 256, 1024, 256]
+    assert [len(s.request_rows) for s in m3.services] == [32, 16, 1, 8, 4, 4, 2, 8]
+    m5 = make_mix(5, d=16, ffn=32)
+    assert [s.M for s in m5.services] == [4692, 3500] and m5.requests == 9
+    assert m5.services[0].request_rows == [881, 593, 1894, 882, 442]
+
+
+def status_of(fn, *a):
+    try:
+        fn(*a)
+    except B.EparaError as e:
+        return e.status
+    return B.EPARA_OK
+
+
+def test_planner_error_codes():
+    cl = _classes(CLASS_TABLES[0])
+    assert status_of(B.epara_plan_groups, _desc([(1, 0, 4)]), cl) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_plan_groups, _desc([(-1, 4, 4)]), cl) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_plan_groups, _desc([(1, 4, 0)]), cl) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_plan_groups, _desc([(1, 4, 4)]), _classes([(64, 64, 32), (64, 256, 256)])) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_plan_groups, _desc([(1, 4, 4)]), _classes([(64, 0, 32)])) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_plan_groups, _desc([(100, 4, 4)]), _classes([(64, 64, 32)])) == B.EPARA_ERR_SHAPE
+    L = B.lib()
+    n = np.zeros(1, dtype=np.int64)
+    g = _desc([(300, 8, 300)])
+    assert L.epara_plan_groups(g.ctypes.data, 1, cl.ctypes.data, 2, None, None, None, None, 0, None) == B.EPARA_ERR_NULL
+    assert L.epara_plan_groups(None, 1, cl.ctypes.data, 2, None, None, None, None, 0, n.ctypes.data) == B.EPARA_ERR_NULL
+    assert L.epara_plan_groups(g.ctypes.data, 1, None, 2, None, None, None, None, 0, n.ctypes.data) == B.EPARA_ERR_NULL
+    assert L.epara_plan_groups(g.ctypes.data, -1, cl.ctypes.data, 2, None, None, None, None, 0, n.ctypes.data) == B.EPARA_ERR_SHAPE
+    tiles = np.zeros(2, dtype=B.TILE)
+    assert L.epara_plan_groups(g.ctypes.data, 1, cl.ctypes.data, 2, None, None, None, tiles.ctypes.data, 2, n.ctypes.data) == B.EPARA_ERR_CAPACITY
+    assert n[0] == 4                                                     # needed size still reported
+    assert L.epara_plan_groups(None, 0, cl.ctypes.data, 2, None, None, None, None, 0, n.ctypes.data) == B.EPARA_OK and n[0] == 0
+    # scheduler: grid must be a positive multiple of the die count
+    _, _, _, t = B.epara_plan_groups(g, cl)
+    assert status_of(B.epara_schedule_tiles, g, cl, t, 12, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, t, 0, 8) == B.EPARA_ERR_SHAPE
+    bad = t.copy(); bad[1]["group"] = 5
+    assert status_of(B.epara_schedule_tiles, g, cl, bad, 8, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, t[:3], 8, 8) == B.EPARA_ERR_SHAPE   # not a whole table
+
+
+def test_batch_accounting_and_paper_numbers():
+    M, first = B.epara_batch_rows([197, 197, 197, 5, 0, 7], [0, 3, 3, 6])
+    assert M.tolist() == [591, 0, 12] and first.tolist() == [0, 197, 394, 0, 5, 5]
+    assert status_of(B.epara_batch_rows, [1, -2], [0, 2]) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_batch_rows, [1, 2], [0, 2, 1]) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_batch_rows, [2 ** 30, 2 ** 30, 2 ** 30], [0, 3]) == B.EPARA_ERR_SHAPE
+    golden = os.path.join(os.path.dirname(__file__), "golden", "paper_worked_numbers.txt")
+    for line in open(golden):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, args, expect, _ = [f.strip() for f in line.split(";", 3)]
+        a = [int(v) for v in args.split()]
+        if name == "dp_group_count":
+            assert B.epara_dp_group_count(*a) == int(expect)
+        elif name == "inter_request_count":
+            assert B.epara_inter_request_count(*a) == int(expect)
+    assert B.epara_dp_group_count(1, 0) == -1 and B.epara_inter_request_count(4, 0) == -1
+
+
+def test_kernel_classes_and_packed_sizes():
+    c = B.epara_kernel_classes(B.EPARA_BF16, 0)
+    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 32), (P.INT32_MAX, 256, 256)]
+    c = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
+    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 32), (P.INT32_MAX, 256, 128)]
+    assert [tuple(int(v) for v in x) for x in B.epara_kernel_classes(B.EPARA_F32, 0)] == [(P.INT32_MAX, 64, 64)]
+    assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
+    assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
+    assert B.epara_packed_weight_bytes(4096, 11008, B.EPARA_BF16) == 4096 * 11008 * 2
+    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_BF16) == 1 * 2 * 1024
+    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_FP8_E4M3) == 1024
+    assert B.epara_packed_weight_bytes(3, 5, B.EPARA_F32) == 60
+    assert B.epara_packed_weight_bytes(0, 5, B.EPARA_BF16) == -1 and B.epara_packed_weight_bytes(3, 5, 9) == -1
+
+
+def test_ffn_args_fill():
+    ffn = np.zeros(1, dtype=B.FFN_DESC)
+    r = ffn[0]
+    r["X"], r["Wgate"], r["Wup"], r["Wdown"], r["H"], r["Y"] = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000
+    r["M"], r["d_model"], r["d_ff"] = 7, 64, 256
+    r["s_x"], r["s_wgate"], r["s_wup"], r["s_h"], r["s_wdown"] = 0.5, 0.25, 2.0, 4.0, 0.125
+    up, down = B.epara_ffn_swiglu_args(ffn, B.EPARA_FP8_E4M3)
+    assert (up[0]["X"], up[0]["W"], up[0]["W2"], up[0]["Y"]) == (0x1000, 0x2000, 0x3000, 0x5000)
+    assert (up[0]["M"], up[0]["K"], up[0]["N"], up[0]["act"]) == (7, 64, 256, B.EPARA_ACT_SWIGLU)
+    assert (up[0]["scale"], up[0]["scale2"], up[0]["out_inv_scale"]) == (0.125, 1.0, 0.25)
+    assert (down[0]["X"], down[0]["W"], down[0]["Y"]) == (0x5000, 0x4000, 0x6000)
+    assert (down[0]["K"], down[0]["N"], down[0]["act"], down[0]["scale"]) == (256, 64, B.EPARA_ACT_NONE, 0.5)
+    up, down = B.epara_ffn_swiglu_args(ffn, B.EPARA_BF16)
+    assert up[0]["scale"] == 1.0 and down[0]["scale"] == 1.0 and up[0]["out_inv_scale"] == 1.0
+    assert status_of(B.epara_ffn_swiglu_args, ffn, B.EPARA_F32) == B.EPARA_ERR_DTYPE
+    ffn[0]["s_h"] = 0.0
+    assert status_of(B.epara_ffn_swiglu_args, ffn, B.EPARA_FP8_E4M3) == B.EPARA_ERR_SHAPE
+
+
+def _host_launch(args, tiles, order_len, W=8):
+    """A Launch whose device pointers are fake but non-NULL: only the host-side validation is exercised,
+    and every case below must be rejected before anything is enqueued."""
+    L = B.Launch(args.ctypes.data, 0x1000, tiles.ctypes.data if len(tiles) else None, 0x2000, 0x3000,
+                 len(tiles), order_len, W, len(args))
+    return L
+
+
+def test_launch_validation_rejects_bad_arguments_without_a_gpu():
+    from paper_2511_00603_amd.runtime import group_args
+    lib = B.lib()
+
+    class T:   # stand-in for a device tensor
+        def __init__(self, p): self.p = p
+        def data_ptr(self): return self.p
+    mk = lambda **kw: np.array([group_args(T(0x10000), T(0x20000), T(0x30000), kw.pop("M", 100), kw.pop("K", 64), kw.pop("N", 300),
+                                           kw.pop("act", "none"), **kw)], dtype=B.GROUP_ARGS)
+    cl = B.epara_kernel_classes(B.EPARA_BF16, 0)
+
+    def plan(a):
+        g = np.zeros(1, dtype=B.GROUP_DESC)
+        for f in ("M", "K", "N"): g[f] = a[f]
+        return B.epara_plan_groups(g, cl)[3]
+
+    fwd = lambda L, i=B.EPARA_BF16, o=B.EPARA_BF16: lib.epara_grouped_forward(ctypes.addressof(L), i, o, None)
+    a = mk(); t = plan(a)
+    assert lib.epara_grouped_forward(None, B.EPARA_BF16, B.EPARA_BF16, None) == B.EPARA_ERR_NULL
+    assert fwd(_host_launch(a, t, 8), B.EPARA_BF16, B.EPARA_F32) == B.EPARA_ERR_DTYPE
+    assert fwd(_host_launch(a, t, 8), 5, B.EPARA_BF16) == B.EPARA_ERR_DTYPE
+    assert fwd(_host_launch(a, t, 8), B.EPARA_F32, B.EPARA_BF16) == B.EPARA_ERR_DTYPE
+    assert fwd(_host_launch(a, t, 7)) == B.EPARA_ERR_SHAPE                     # slots not a multiple of the grid
+    assert fwd(_host_launch(a, t, 0)) == B.EPARA_ERR_SHAPE                     # fewer slots than tiles
+    L = _host_launch(a, t, 8); L.d_order = None
+    assert fwd(L) == B.EPARA_ERR_NULL
+    L = _host_launch(a, t, 8); L.n_workgroups = 0
+    assert fwd(L) == B.EPARA_ERR_SHAPE
+    b = mk(); b[0]["X"] = 0
+    assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_NULL
+    b = mk(); b[0]["W"] = 0x20008
+    assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_ALIGN
+    b = mk(K=36); assert fwd(_host_launch(b, plan(b), 8)) == B.EPARA_ERR_ALIGN   # 72-byte rows
+    b = mk(); b[0]["act"] = 9
+    assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_DTYPE
+    b = mk(act="swiglu")                                                         # no second weight matrix
+    assert fwd(_host_launch(b, t, 8)) in (B.EPARA_ERR_NULL, B.EPARA_ERR_SHAPE)
+    b = mk(); b[0]["K"] = 0
+    assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_SHAPE
+    bad = t.copy(); bad[0]["rows"] = 7
+    assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
+    bad = t.copy(); bad[1]["n0"] = 250
+    assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
+    bad = t.copy(); bad[0]["cls"] = 0                                            # 100 rows do not fit the skinny class
+    assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
+    bad = t.copy(); bad[0]["group"] = 3
+    assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
+    # nothing to do is fine and touches nothing: no tiles, G = 0
+    empty = np.zeros(0, dtype=B.GROUP_ARGS)
+    assert fwd(B.Launch(None, None, None, None, None, 0, 0, 8, 0)) == B.EPARA_OK
+    z = mk(M=0)
+    assert fwd(B.Launch(z.ctypes.data, None, None, None, None, 0, 0, 8, 1)) == B.EPARA_OK
+    # ffn wrapper: dtype rules and phase consistency
+    ffn = lambda u, d, i, h, o: lib.epara_grouped_ffn_swiglu(ctypes.addressof(u), ctypes.addressof(d), i, h, o, None)
+    e = B.Launch(None, None, None, None, None, 0, 0, 8, 0)
+    assert ffn(e, e, B.EPARA_BF16, B.EPARA_BF16, B.EPARA_BF16) == B.EPARA_OK
+    assert ffn(e, e, B.EPARA_BF16, B.EPARA_FP8_E4M3, B.EPARA_BF16) == B.EPARA_ERR_DTYPE
+    assert ffn(e, e, B.EPARA_F32, B.EPARA_F32, B.EPARA_F32) == B.EPARA_ERR_DTYPE
+    assert lib.epara_grouped_ffn_swiglu(None, None, 1, 1, 1, None) == B.EPARA_ERR_NULL
+    # pack: argument checks come before any enqueue
+    assert lib.epara_pack_weights(None, 8, 8, B.EPARA_BF16, 0x1000, 1024, None) == B.EPARA_ERR_NULL
+    assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2000, 16, None) == B.EPARA_ERR_CAPACITY
+    assert lib.epara_pack_weights(0x1000, 0, 8, B.EPARA_BF16, 0x2000, 1024, None) == B.EPARA_ERR_SHAPE
+    assert lib.epara_pack_weights(0x1000, 8, 8, 7, 0x2000, 1024, None) == B.EPARA_ERR_DTYPE
+    assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2004, 1024, None) == B.EPARA_ERR_ALIGN
+    assert B.epara_status_string(B.EPARA_ERR_ALIGN).startswith("pointer")
