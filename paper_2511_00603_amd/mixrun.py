@@ -27,7 +27,7 @@ def _bits(a, dtype, scale=None):
 
 
 class StagedMix:
-    def __init__(self, mix, dtype_name=None, device="cuda:0", copies=1, s_h=None, n_workgroups=None):
+    def __init__(self, mix, dtype_name=None, device="cuda:0", copies=1, s_h=None, n_workgroups=None, host_bits=None):
         """copies > 1 stages independent replicas of all weights and activations; pass `copy=i` to run()
         to rotate through them (keeps a timing loop out of the last-level cache).
         s_h: per-service scales of the hidden activations for the fp8 SwiGLU path (list of floats)."""
@@ -45,7 +45,10 @@ class StagedMix:
         self.pack_seconds = 0.0
         self.s_h = s_h
         self._keep = []
-        self._stage_host()
+        if host_bits is not None:        # already rounded by stage_host(); reused so a checker sees the same bits
+            self.host_bits = host_bits
+        else:
+            self._stage_host()
         for _ in range(copies):
             self._stage_device(n_workgroups)
         torch.cuda.synchronize(self.device)
@@ -68,6 +71,16 @@ class StagedMix:
                     s = casts.e4m3_scale(L.W) if self.fp8 else 1.0
                     hb["layers"].append({"W": _bits(L.W, dt, s), "s_w": s, "b": L.b, "act": L.act})
             self.host_bits.append(hb)
+
+    @classmethod
+    def stage_host(cls, mix, dtype_name=None):
+        """Only the host half: the rounded inputs of every service (no GPU needed)."""
+        self = cls.__new__(cls)
+        self.mix, self.host_bits = mix, []
+        self.dtype = B.DTYPE_BY_NAME[dtype_name or mix.dtype]
+        self.fp8 = self.dtype == B.EPARA_FP8_E4M3
+        self._stage_host()
+        return self.host_bits
 
     # ---- device side ------------------------------------------------------------------------
     def _dev(self, bits):

@@ -1,0 +1,267 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the CPU oracle on the same seeded
+inputs.  Tolerances (max relative error with the group's rms as floor, tests/parity_util.py):
+1e-5 fp32, 2e-2 bf16 inputs / fp32 accumulation, 6e-2 fp8 E4M3.  Integer-valued cases must
+match bit for bit.  Full-size mixes are checked on sampled rows the oracle computes one by one,
+in the launch configuration bench.py times.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as ref
+from paper_2511_00603_amd import binding as B
+from paper_2511_00603_amd import runtime as R
+from paper_2511_00603_amd.mixrun import StagedMix
+from workloads import make_mix
+
+import gpu_util as U
+import mix_oracle
+from parity_util import TOL, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(M, rng, n_random=10):
+    fixed = [0, 1, 15, 16, 63, 64, 255, 256, 257, M // 2, M - 2, M - 1]
+    rows = {r for r in fixed if 0 <= r < M}
+    rows |= {int(v) for v in rng.integers(0, M, n_random)}
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def check_mix(mix, dtype_name, rows=None, h_scales=None, host_bits=None):
+    staged = StagedMix(mix, dtype_name, U.DEV, s_h=h_scales, host_bits=host_bits)
+    staged.run()
+    torch.cuda.synchronize()
+    got = staged.results()
+    want = mix_oracle.expected(mix, staged.host_bits, dtype_name, rows=rows, h_scales=h_scales)
+    tol = TOL[dtype_name]
+    worst = 0.0
+    assert len(got) == len(want)
+    for lg, lw in zip(got, want):
+        assert len(lg) == len(lw)
+        for (g, label, Y), (g2, label2, Yref) in zip(lg, lw):
+            assert (g, label) == (g2, label2)
+            if rows is not None:
+                Y = Y[rows[g]]
+            if dtype_name == "fp8" and label == "H":
+                # Stored E4M3 codes.  The oracle rounds fp64 sums, the GPU fp32 MFMA sums, so the same value
+                # cannot be handed to both roundings: nearly all codes must agree exactly, a value on a
+                # rounding boundary may land one code apart, and near zero (where codes are an absolute
+                # 2^-9 * s_h apart) the difference is bounded by the accumulation error instead.
+                Y = Y * h_scales[g]
+                rms = float(np.sqrt(np.mean(Yref * Yref)))
+                step = np.maximum(0.13 * np.maximum(np.abs(Yref), h_scales[g] * 2.0 ** -6), 1e-3 * rms)
+                bad = np.argwhere(~(np.abs(Y - Yref) <= step))
+                assert len(bad) == 0, "H codes too far apart at %d places, e.g. %s" % (
+                    len(bad), [(tuple(int(v) for v in ij), float(Y[tuple(ij)]), float(Yref[tuple(ij)])) for ij in bad[:8]])
+                assert np.mean(Y != Yref) < 0.02
+                assert_close(Y, Yref, tol, "%s svc %d H" % (mix.name, g))
+                continue
+            worst = max(worst, assert_close(Y, Yref, tol, "%s svc %d %s" % (mix.name, g, label)))
+    return worst
+
+
+# ---- exactness on integer-valued inputs (layout, indexing, tails) -----------------------------
+
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16", "fp8"])
+def test_small_integers_are_bit_exact(dtype_name):
+    rng = np.random.default_rng(11)
+    shapes = [(5, 64, 40), (1, 32, 16), (64, 96, 33), (70, 160, 300), (300, 128, 260), (257, 256, 513), (16, 48, 10)]
+    specs = []
+    for M, K, N in shapes:
+        X = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        W = rng.integers(-3, 4, (K, N)).astype(np.float32)
+        b = rng.integers(-8, 9, N).astype(np.float32)
+        specs.append({"X": X, "W": W, "b": b, "act": "relu"})
+    G = U.Groups(specs, dtype_name)
+    got, want = G.run(), G.expected()
+    for (M, K, N), y, yref in zip(shapes, got, want):
+        if dtype_name != "f32":
+            yref = ref.bf16_decode(ref.bf16_encode(yref))
+        if dtype_name == "fp8":   # per-tensor scales amax/448 are not powers of two: tolerance, not bits
+            assert_close(y, yref, TOL["fp8"], "ints fp8 %s" % ((M, K, N),))
+        else:
+            assert np.array_equal(y, yref), (dtype_name, M, K, N, np.argwhere(y != yref)[:5])
+
+
+def test_identity_zero_and_ones_weights_bf16():
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((37, 64)).astype(np.float32)
+    b = (rng.standard_normal(64) * 0.5).astype(np.float32)
+    specs = [{"X": X, "W": np.eye(64, dtype=np.float32), "b": b, "act": "none"},
+             {"X": X, "W": np.zeros((64, 48), dtype=np.float32), "b": b[:48], "act": "gelu_erf"},
+             {"X": np.round(X * 4) / 4, "W": np.ones((64, 20), dtype=np.float32), "b": None, "act": "none"}]
+    G = U.Groups(specs, "bf16")
+    y, want = G.run(), G.expected()
+    Xb = ref.bf16_decode(G.bits[0]["X"])
+    assert np.array_equal(y[0], ref.bf16_decode(ref.bf16_encode(Xb + b.astype(np.float64))))
+    assert_close(y[1], want[1], TOL["bf16"], "zero weights")
+    assert np.all(y[1] == y[1][0])                                   # act(b) broadcast over rows
+    assert_close(y[2], want[2], TOL["bf16"], "ones weights")
+
+
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16"])
+def test_linearity_in_x(dtype_name):
+    rng = np.random.default_rng(13)
+    M, K, N = 90, 128, 72
+    X1, X2 = rng.standard_normal((M, K)).astype(np.float32), rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32)
+    a, c = 1.75, -0.375
+    f = lambda X: U.Groups([{"X": X, "W": W, "b": None, "act": "none"}], dtype_name).run()[0]
+    lhs, rhs = f(a * X1 + c * X2), a * f(X1) + c * f(X2)
+    assert_close(lhs, rhs, 3 * TOL[dtype_name], "linearity")
+
+
+# ---- independence and determinism ------------------------------------------------------------------
+
+def test_group_order_row_order_and_grid_size_do_not_change_a_single_bit():
+    rng = np.random.default_rng(14)
+    shapes = [(3, 256, 96, "gelu_erf"), (300, 128, 260, "relu"), (64, 512, 64, "none"), (17, 64, 10, "silu"), (700, 96, 300, "none")]
+    specs = [U.rand_spec(rng, M, K, N, act) for M, K, N, act in shapes]
+    base = U.Groups(specs, "bf16")
+    y0 = base.run()
+    raw0 = [t.view(torch.int16).cpu().numpy() for t in base.raw()]
+    perm = [3, 0, 4, 2, 1]
+    y1 = U.Groups([specs[i] for i in perm], "bf16").run()
+    for j, i in enumerate(perm):
+        assert np.array_equal(y1[j], y0[i])
+    for W in (8, 64, 128):
+        g = U.Groups(specs, "bf16", n_workgroups=W)
+        g.run()
+        for a, t in zip(raw0, g.raw()):
+            assert np.array_equal(a, t.view(torch.int16).cpu().numpy())
+    # permuting the rows of X permutes the rows of Y; splitting a batch in two reproduces the same rows
+    p = rng.permutation(300)
+    s = dict(specs[1]); s["X"] = specs[1]["X"][p]
+    top, bottom = dict(specs[1]), dict(specs[1])
+    top["X"], bottom["X"] = specs[1]["X"][:100], specs[1]["X"][100:]
+    ys = U.Groups([s, top, bottom], "bf16").run()
+    assert np.array_equal(ys[0], y0[1][p])
+    assert_close(np.vstack([ys[1], ys[2]]), y0[1], 1e-2, "split batch")   # tile classes differ: not bitwise
+    # run to run
+    again = base.run()
+    for a, b in zip(y0, again):
+        assert np.array_equal(a, b)
+
+
+# ---- edge cases -------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype_name", ["f32", "bf16", "fp8"])
+def test_ragged_and_degenerate_groups(dtype_name):
+    rng = np.random.default_rng(15)
+    kmul = 16 if dtype_name == "fp8" else 8
+    shapes = [(0, 64, 32, "none"), (1, kmul, 1, "none"), (1, 64, 10, "relu"), (64, 5 * kmul, 33, "gelu_erf"),
+              (65, 3 * kmul, 31, "silu"), (255, 7 * kmul, 255, "gelu_tanh"), (256, 128, 256, "none"),
+              (257, 64 + kmul, 257, "relu"), (0, 32, 8, "none"), (513, 2 * kmul, 7, "none")]
+    specs = [U.rand_spec(rng, M, K, N, act) for M, K, N, act in shapes]
+    G = U.Groups(specs, dtype_name)
+    got, want = G.run(), G.expected()
+    for sh, y, yref in zip(shapes, got, want):
+        assert y.shape == yref.shape
+        if y.size:
+            assert_close(y, yref, TOL[dtype_name], str(sh))
+
+
+def test_nothing_to_do_is_ok():
+    G = U.Groups([], "bf16")
+    assert G.run() == []
+    rng = np.random.default_rng(16)
+    G = U.Groups([U.rand_spec(rng, 0, 64, 32), U.rand_spec(rng, 0, 32, 8)], "bf16")
+    assert [y.shape for y in G.run()] == [(0, 32), (0, 8)]
+
+
+def test_every_activation_fp32():
+    rng = np.random.default_rng(17)
+    specs = [U.rand_spec(rng, 33, 100, 70, act, x_uniform=True) for act in ("none", "relu", "gelu_erf", "gelu_tanh", "silu")]
+    for s in specs:
+        s["X"] = s["X"] * 3
+    G = U.Groups(specs, "f32")
+    for s, y, yref in zip(specs, G.run(), G.expected()):
+        assert_close(y, yref, TOL["f32"], s["act"])
+
+
+def test_pack_weights_layout_round_trip():
+    # packed fragment (nb, ks), chunk q*16+r holds W[ks*32 + 8q .. +7][nb*16 + r] (bf16), zero padded
+    rng = np.random.default_rng(18)
+    K, N = 72, 37
+    bits = rng.integers(1, 2 ** 15, (K, N)).astype(np.uint16)
+    W = R.device_tensor_from_bits(bits, B.EPARA_BF16, U.DEV)
+    P = R.pack_weights(W, B.EPARA_BF16)
+    torch.cuda.synchronize()
+    p = P.cpu().numpy().view(np.uint16).reshape(3, 3, 4, 16, 8)          # [nb][ks][q][r][e]
+    want = np.zeros((3, 3, 4, 16, 8), dtype=np.uint16)
+    for nb in range(3):
+        for ks in range(3):
+            for q in range(4):
+                for r in range(16):
+                    for e in range(8):
+                        k, n = ks * 32 + q * 8 + e, nb * 16 + r
+                        if k < K and n < N:
+                            want[nb, ks, q, r, e] = bits[k, n]
+    assert np.array_equal(p, want)
+
+
+# ---- the five mixes ---------------------------------------------------------------------------------
+
+def test_mix1_mlp_fp32_full():
+    check_mix(make_mix(1), "f32")
+
+
+def test_mix2_small_models_bf16_full():
+    check_mix(make_mix(2), "bf16")
+
+
+def test_mix3_vit_reduced_all_rows():
+    check_mix(make_mix(3, images=[2, 1, 1, 3, 1, 2, 1, 1], d=192, ffn=768, tokens=197), "bf16")
+
+
+def test_mix3_vit_full_size_sampled_rows():
+    mix = make_mix(3)
+    rng = np.random.default_rng(31)
+    rows = [sample_rows(s.M, rng, 8) for s in mix.services]
+    check_mix(mix, "bf16", rows=rows)
+
+
+def test_mix4_decode_reduced_all_rows():
+    check_mix(make_mix(4, d=512, ffn=1376), "bf16")
+
+
+def test_mix4_decode_full_size():
+    check_mix(make_mix(4), "bf16")
+
+
+def _h_scales(mix, host_bits, rows):
+    """Static per-service scale of the hidden activations, calibrated from the oracle: amax(H)/448."""
+    out = []
+    for g, hb in enumerate(host_bits):
+        X = ref.e4m3_decode(hb["X"][rows[g]])
+        H = ref.swiglu_hidden(X, ref.e4m3_decode(hb["Wgate"]), ref.e4m3_decode(hb["Wup"]),
+                              hb["s_x"] * hb["s_wgate"], hb["s_x"] * hb["s_wup"])
+        out.append(float(np.abs(H).max()) / 448.0)
+    return out
+
+
+@pytest.mark.parametrize("dtype_name", ["bf16", "fp8"])
+def test_mix5_prefill_reduced_all_rows(dtype_name):
+    mix = make_mix(5, d=640, ffn=1664, total_rows=900, len_lo=60, len_hi=300)
+    hs = hb = None
+    if dtype_name == "fp8":
+        hb = StagedMix.stage_host(mix, "fp8")
+        hs = _h_scales(mix, hb, [slice(None)] * len(mix.services))
+    check_mix(mix, dtype_name, h_scales=hs, host_bits=hb)
+
+
+@pytest.fixture(scope="module")
+def mix5():
+    return make_mix(5)
+
+
+@pytest.mark.parametrize("dtype_name", ["bf16", "fp8"])
+def test_mix5_prefill_full_size_sampled_rows(mix5, dtype_name):
+    rng = np.random.default_rng(51)
+    rows = [sample_rows(s.M, rng, 6) for s in mix5.services]
+    hs = hb = None
+    if dtype_name == "fp8":
+        hb = StagedMix.stage_host(mix5, "fp8")
+        hs = _h_scales(mix5, hb, rows)
+    check_mix(mix5, dtype_name, rows=rows, h_scales=hs, host_bits=hb)
