@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the grouped forward on one MI355X.
+
+A step is one pass of a synthetic service mix through libepara (all its launches), inputs already
+resident in HBM.  The headline workload is the prefill mix (two 13B-shaped SwiGLU FFN services,
+8192 rows, bf16): `value` is its TFLOP/s.  The same JSON line carries, under "mixes", TFLOP/s,
+requests/s and the roofline fraction of every other mix (decode mix against HBM bandwidth), the
+roofline object of the headline mix's dominant kernel, and the CPU oracle timed on a bounded
+sample of the same workload.
+
+    python bench.py [--steps K] [--warmup W] [--mixes 5,4] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}
+LLC_BYTES = 256 << 20
+
+
+def launch_stats(staged, mix, dtype_name):
+    """Algorithmic flops and bytes of every launch of one pass: weights once, inputs once, outputs once."""
+    from paper_2511_00603_amd import binding as B
+    esz = {"f32": 4, "bf16": 2, "fp8": 1}[dtype_name]
+    stats = []
+    for plan in staged.plans():
+        flops = nbytes = 0
+        for a in plan.args:
+            M, K, N = int(a["M"]), int(a["K"]), int(a["N"])
+            gated = int(a["act"]) == B.EPARA_ACT_SWIGLU
+            nw = 2 if gated else 1
+            flops += 2 * M * K * N * nw
+            out_esz = 4 if dtype_name == "f32" else (1 if (gated and dtype_name == "fp8") else 2)
+            nbytes += K * N * nw * esz + M * K * esz + M * N * out_esz + (N * 4 if int(a["bias"]) else 0)
+        stats.append({"flops": flops, "bytes": nbytes, "tiles": int(len(plan.tiles)), "groups": int(len(plan.args))})
+    return stats
+
+
+def time_mix(mix, dtype_name, steps, warmup, s_h=None):
+    import torch
+    from paper_2511_00603_amd import runtime as R
+    from paper_2511_00603_amd.mixrun import StagedMix
+
+    esz = {"f32": 4, "bf16": 2, "fp8": 1}[dtype_name]
+    footprint = mix.weight_elems() * esz
+    copies = 1 if footprint >= 2 * LLC_BYTES else min(8, -(-2 * LLC_BYTES // max(footprint, 1)))
+    t0 = time.perf_counter()
+    staged = StagedMix(mix, dtype_name, "cuda:0", copies=copies, s_h=s_h)
+    stage_s = time.perf_counter() - t0
+    stats = launch_stats(staged, mix, dtype_name)
+    plan_us = sum(p.plan_seconds for p in staged.plans()) * 1e6
+    upload_us = sum(p.upload_seconds for p in staged.plans()) * 1e6
+
+    # (a) whole passes, the library's own entry points, events at both ends only
+    for i in range(warmup):
+        staged.run(copy=i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        staged.run(copy=i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / steps
+
+    # (b) the same launches one by one with an event between them: per-kernel durations
+    plans = [staged.plans(c) for c in range(copies)]
+    outs = []
+    for step in staged.programs[0]:
+        outs += [step[2]] if step[0] == "forward" else [step[3], 1]     # out dtype per launch (1 = bf16)
+    n_l = len(plans[0])
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_l + 1)] for _ in range(steps)]
+    for i in range(steps):
+        evs[i][0].record()
+        for l in range(n_l):
+            R.grouped_forward(plans[i % copies][l], outs[l])
+            evs[i][l + 1].record()
+    torch.cuda.synchronize()
+    per_launch_ms = [sum(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) / steps for l in range(n_l)]
+
+    flops = mix.flops()
+    res = {"name": mix.name, "dtype": dtype_name, "ms_per_step": ms_per_step,
+           "tflops": flops / (ms_per_step * 1e-3) / 1e12, "requests_per_s": mix.requests / (ms_per_step * 1e-3),
+           "requests": mix.requests, "rows": mix.rows, "flops": flops, "launches": n_l, "weight_copies": copies,
+           "plan_us": plan_us, "plan_upload_us": upload_us, "pack_weights_s": staged.pack_seconds / copies,
+           "stage_s": stage_s, "kernels": []}
+    for l in range(n_l):
+        t = per_launch_ms[l] * 1e-3
+        st = stats[l]
+        gbs, tf = st["bytes"] / t / 1e9, st["flops"] / t / 1e12
+        peak_tf = MFMA_PEAK_TFLOPS.get(dtype_name)
+        t_mfma = st["flops"] / (peak_tf * 1e12) if peak_tf else 0.0
+        t_hbm = st["bytes"] / (HBM_PEAK_GBS * 1e9)
+        bound = "mfma" if t_mfma > t_hbm else "hbm"
+        k = {"launch": l, "ms": per_launch_ms[l], "tiles": st["tiles"], "groups": st["groups"],
+             "flops": st["flops"], "bytes": st["bytes"], "bound": bound}
+        if bound == "mfma":
+            k.update(achieved=tf, peak=peak_tf, unit="TFLOP/s", frac=tf / peak_tf)
+        else:
+            k.update(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
+        res["kernels"].append(k)
+    dom = max(res["kernels"], key=lambda k: k["ms"])
+    res["roofline"] = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
+                       "frac": dom["frac"], "traffic": None, "kernel": "grouped_kernel launch %d" % dom["launch"],
+                       "avg_ms": dom["ms"]}
+    del staged
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(mix, budget_s=15.0):
+    """The oracle as it stands on the host cores, on a few rows of service 0 of the prefill mix (fp64)."""
+    from oracle import reference as ref
+    from workloads import casts
+    svc = mix.services[0]
+    dec = lambda a: ref.bf16_decode(casts.bf16_bits(a))
+    Wg, Wu, Wd = dec(svc.Wgate), dec(svc.Wup), dec(svc.Wdown)
+    d, f = svc.Wgate.shape
+    per_row = 2 * d * f * 3
+    threads = ref.threads()
+    X = dec(svc.X[:threads])                       # probe: one row per thread
+    t0 = time.perf_counter()
+    ref.ffn_swiglu(X, Wg, Wu, Wd)
+    t_probe = time.perf_counter() - t0
+    rows = threads * int(max(1, min(svc.M // threads, budget_s / max(t_probe, 1e-6))))
+    X = dec(svc.X[:rows])
+    t0 = time.perf_counter()
+    ref.ffn_swiglu(X, Wg, Wu, Wd)
+    dt = time.perf_counter() - t0
+    return {"value": per_row * rows / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": "%d rows of service 0 of the prefill mix (SwiGLU FFN d=%d f=%d), fp64 triple loop, %.1f s" % (rows, d, f, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--mixes", default="5,5fp8,4,3,2,1", help="comma list; the first is the headline (default prefill bf16)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: every service of a mix is resident on it and nothing is sharded; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from workloads import make_mix
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (libepara has no CPU path)", file=sys.stderr)
+        sys.exit(2)
+
+    results, cache, cpu = [], {}, None
+    for tag in a.mixes.split(","):
+        idx = int(tag[0])
+        dtype_name = "fp8" if tag.endswith("fp8") else None
+        if idx not in cache:
+            cache.clear()
+            cache[idx] = make_mix(idx)
+        mix = cache[idx]
+        dtype_name = dtype_name or mix.dtype
+        s_h = None
+        if dtype_name == "fp8":        # static hidden-activation scales from a calibration pass in bf16
+            from paper_2511_00603_amd.mixrun import StagedMix
+            cal = StagedMix(mix, "bf16", "cuda:0")
+            cal.run()
+            torch.cuda.synchronize()
+            s_h = [float(t.abs().max().float().item()) / 448.0 for (_, _, t) in cal.outputs[0][0]]
+            del cal
+            torch.cuda.empty_cache()
+        results.append(time_mix(mix, dtype_name, a.steps, a.warmup, s_h))
+        if idx == 5 and cpu is None and not a.no_cpu_baseline:
+            cpu = cpu_baseline(mix)
+        print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%" % (
+            mix.name, dtype_name, results[-1]["ms_per_step"], results[-1]["tflops"], results[-1]["requests_per_s"],
+            results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"]), file=sys.stderr, flush=True)
+
+    head = results[0]
+    line = {"metric": "grouped forward TFLOP/s + % MFMA/HBM roofline; requests/s per mix, 1 MI355X",
+            "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+            "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": head["dtype"], "data": "synthetic",
+            "config": {"workload": "%s (%s): %d rows, %d requests per pass, %d launches" % (
+                head["name"], head["dtype"], head["rows"], head["requests"], head["launches"])},
+            "requests_per_s": head["requests_per_s"],
+            "roofline": head["roofline"], "cpu_baseline": cpu,
+            "mixes": {("%s_%s" % (r["name"], r["dtype"])): r for r in results}}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
