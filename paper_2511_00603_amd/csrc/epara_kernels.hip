@@ -167,91 +167,86 @@ __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out
 
 // ------------------------------------------------------------------ big tiles (LDS + MFMA)
 
-// LDS: [X stage 0][X stage 1][W stage 0][W stage 1], 32 KiB each.
-//   X tile: row-major 256 rows x 128 B, 16-byte chunk kc of row stored at chunk kc ^ ((row/2)%8)
-//           so that the 16 rows one ds_read_b128 wavefront quarter touches hit distinct banks.
-//   W tile: verbatim image of the packed weights: [16 column blocks][2 fragments][64 lanes][16 B].
-// Loads never branch per lane: rows past the batch and column blocks past N are clamped to the
-// last valid one (they only feed outputs that are never stored); only the K tail needs zeros,
-// and that is confined to the last k-tile.
+// One 256 x 256 output tile (gated: 256 rows x 128 hidden columns, i.e. 128 gate + 128 up
+// weight columns).  K advances in stages of 64 bytes per row (one weight fragment per column
+// block); four stages of 32 KiB rotate through the LDS:
+//   [X: 256 rows x 64 B][W: 16 column blocks x 1 KiB]
+// and are filled by direct global->LDS loads (no staging registers), three stages ahead of the
+// one being multiplied, so a load has about three stage times to arrive.
+//   X stage: 16-byte chunk c of row `row` is stored at chunk c ^ ((row/4)%4): the 16 rows that one
+//            quarter of a ds_read_b128 touches then fall into 16 different bank groups.  A direct
+//            load writes 1 KiB of consecutive LDS per wave instruction, so lane l fetches the
+//            global chunk that belongs at position l (row l/4 of the instruction's 16 rows).
+//   W stage: verbatim image of the packed fragments, lane l's 16 bytes at position l.
+// Rows past the batch and column blocks past N are clamped to the last valid one (they only
+// feed outputs that are never stored).  In a ragged last stage the X chunks past K are clamped
+// to chunk 0: the packed weights are zero there, so the products vanish.
+// Synchronisation per stage: each wave waits for its own loads of the stage (vmcnt), then one
+// workgroup barrier makes every wave's part visible and also proves that the buffer about to
+// be refilled is no longer being read.
+typedef __attribute__((address_space(3))) char* ldsptr;
+
+constexpr int NS = 4;                    // pipeline stages
+constexpr int XSTAGE_BYTES = 16384;      // X part of a stage
+
+template <int N_OUTSTANDING>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N_OUTSTANDING < 16, "encoding below covers vmcnt < 16");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N_OUTSTANDING);      // vmcnt = N, expcnt / lgkmcnt untouched
+}
+
 template <int DT, bool GATED>
 __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dtype,
                                          int m0, int n0, int rows, int cols, char* lds)
 {
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
-    constexpr int KF = 4 * EPC;     // K elements per weight fragment
+    constexpr int KF = 4 * EPC;     // K elements per stage (one weight fragment)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, q = lane >> 4;
     const int wn = wave & 1, wm = wave >> 1;
     const int K = ga.K, N = ga.N;
     const int KS = (K + KF - 1) / KF;
-    const int KT = (KS + 1) >> 1;
     const int NB = (N + 15) >> 4;
+    ldsptr l3 = (ldsptr)lds;
 
-    // --- global -> register -> LDS staging: per k-tile each thread moves 4 X chunks and 4 W chunks
-    // X chunk j: row (tid/8) + 64 j, k-chunk tid%8.  W chunk j: column block (tid/128) + 4 j,
-    // fragment (tid/64)%2, lane slot tid%64 (gated tiles: j = 0,1 gate blocks, j = 2,3 up blocks).
-    const int srow = tid >> 3;
-    const int xkc = (tid & 7) * EPC;                       // element offset of my chunk inside a k-tile
-    const int wksl = (tid >> 6) & 1;
+    // --- direct-load descriptors: this wave fills X rows [32 wave, 32 wave + 32) and W blocks 2 wave, 2 wave + 1
+    const int xchunk = (lane & 3) ^ ((lane >> 4) & 3);
+    const int tail_k = K - (KS - 1) * KF;                       // elements in the last stage, 1..KF
+    const int xchunk_tail = (xchunk * EPC < tail_k) ? xchunk : 0;
     gcptr xbase = as_global<char>(ga.X) + static_cast<size_t>(m0) * K * ESZ;
-    gcptr wbase0 = as_global<char>(ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
-    gcptr wbase1 = GATED ? as_global<char>(ga.W2) + static_cast<size_t>(n0 >> 4) * KS * 1024 : wbase0;
-    uint32_t xoff[4], woff[4];
+    gcptr wbase = as_global<char>((GATED && wave >= 4) ? ga.W2 : ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
+    uint32_t xoff[2], xoff_tail[2], woff[2];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = min(srow + 64 * j, rows - 1);
-        xoff[j] = static_cast<uint32_t>((row * K + xkc) * ESZ);
-        const int nbrel = (tid >> 7) + 4 * (GATED ? (j & 1) : j);
+    for (int j = 0; j < 2; ++j) {
+        const int row = min(32 * wave + 16 * j + (lane >> 2), rows - 1);
+        xoff[j] = static_cast<uint32_t>((row * K + xchunk * EPC) * ESZ);
+        xoff_tail[j] = static_cast<uint32_t>((row * K + xchunk_tail * EPC) * ESZ);
+        const int nbrel = (GATED ? ((2 * wave) & 7) : 2 * wave) + j;
         const int nb = min(nbrel, NB - 1 - (n0 >> 4));
-        woff[j] = static_cast<uint32_t>(((nb * KS + wksl) * 64 + lane) * 16);
+        woff[j] = static_cast<uint32_t>((nb * KS * 64 + lane) * 16);
     }
-    const int xs_off = srow * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);      // + j * 8192
-    const int ws_off = 2 * STAGE_BYTES + tid * 16;                              // + j * 8192
+    const int dma_lds = 2 * wave * 1024;                        // my first 1 KiB slot inside the X (or W) part
 
-    v4i xr[4], wr[4];
-    auto load_tile = [&](int kt) {                         // every chunk of this k-tile lies inside K
-        gcptr xb = xbase + static_cast<size_t>(kt) * 128;
-        gcptr w0 = wbase0 + static_cast<size_t>(kt) * 2048;
-        gcptr w1 = wbase1 + static_cast<size_t>(kt) * 2048;
+    auto issue = [&](int kt) {
+        const int buf = (kt & (NS - 1)) * STAGE_BYTES;
+        gcptr xb = xbase + static_cast<size_t>(kt) * 64;
+        gcptr wb = wbase + static_cast<size_t>(kt) * 1024;
+        const bool tail = kt == KS - 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xr[j] = ld16(xb + xoff[j]);
+        for (int j = 0; j < 2; ++j)
+            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
+                                             (__attribute__((address_space(3))) void*)(l3 + buf + dma_lds + j * 1024), 16, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wr[j] = ld16(((GATED && j >= 2) ? w1 : w0) + woff[j]);
-    };
-    auto load_tile_tail = [&](int kt) {                    // last k-tile: chunks past K become zeros
-        gcptr xb = xbase + static_cast<size_t>(kt) * 128;
-        gcptr w0 = wbase0 + static_cast<size_t>(kt) * 2048;
-        gcptr w1 = wbase1 + static_cast<size_t>(kt) * 2048;
-        const bool x_ok = kt * 2 * KF + xkc < K;
-        const bool w_ok = kt * 2 + wksl < KS;
-        const uint32_t xback = x_ok ? 0u : static_cast<uint32_t>(xkc * ESZ);   // fall back to chunk 0 / fragment 0
-        const uint32_t wback = w_ok ? 0u : 1024u;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const v4i v = ld16(xb + (xoff[j] - xback));
-            xr[j] = x_ok ? v : v4i{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const v4i v = ld16(((GATED && j >= 2) ? w1 : w0) + (woff[j] - wback));
-            wr[j] = w_ok ? v : v4i{0, 0, 0, 0};
-        }
-    };
-    auto store_tile = [&](int stage) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(lds + stage * STAGE_BYTES + xs_off + j * 8192) = xr[j];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(lds + stage * STAGE_BYTES + ws_off + j * 8192) = wr[j];
+        for (int j = 0; j < 2; ++j)
+            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
+                                             (__attribute__((address_space(3))) void*)(l3 + buf + XSTAGE_BYTES + dma_lds + j * 1024), 16, 0, 0);
     };
 
-    // --- fragment read offsets: X fragment fm adds fm*2048, W fragment fn adds a constant too
-    int xf_off[2];
-#pragma unroll
-    for (int ksl = 0; ksl < 2; ++ksl)
-        xf_off[ksl] = (wm * 64 + r) * 128 + (((ksl * 4 + q) ^ ((r >> 1) & 7)) << 4);
-    const int wf_off = 2 * STAGE_BYTES + ((GATED ? wn * 4 : wn * 8) * 128 + lane) * 16;
+    // --- fragment read offsets inside a stage
+    const int xf_off = (wm * 64 + r) * 64 + ((q ^ (r >> 2)) << 4);                      // + fm * 1024
+    const int wf_off = XSTAGE_BYTES + ((GATED ? wn * 4 : wn * 8) * 64 + lane) * 16;    // + block * 1024
 
     v4f acc[8][4];
 #pragma unroll
@@ -260,32 +255,31 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
         for (int fm = 0; fm < 4; ++fm) acc[fn][fm] = v4f{0.f, 0.f, 0.f, 0.f};
 
     __syncthreads();                       // the previous tile is done with the LDS
-    if (KT > 1) load_tile(0); else load_tile_tail(0);
-    store_tile(0);
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < KS) issue(s);
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int stage = kt & 1;
-        if (kt + 2 < KT) load_tile(kt + 1);
-        else if (kt + 1 < KT) load_tile_tail(kt + 1);
+    for (int kt = 0; kt < KS; ++kt) {
+        const int ahead = min(NS - 2, KS - 1 - kt);            // stages that may still be in flight after this wait
+        if (ahead >= 2) wait_vmcnt<8>();
+        else if (ahead == 1) wait_vmcnt<4>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (kt + NS - 1 < KS) issue(kt + NS - 1);               // refills the buffer read in the previous iteration
+        const int buf = (kt & (NS - 1)) * STAGE_BYTES;
+        v4i wf[8], xf[4];
 #pragma unroll
-        for (int ksl = 0; ksl < 2; ++ksl) {
-            v4i wf[8], xf[4];
-#pragma unroll
-            for (int fn = 0; fn < 8; ++fn) {
-                const int nbrel = (GATED && fn >= 4) ? fn + 4 : fn;     // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
-                wf[fn] = *reinterpret_cast<const v4i*>(lds + stage * STAGE_BYTES + wf_off + nbrel * 2048 + ksl * 1024);
-            }
-#pragma unroll
-            for (int fm = 0; fm < 4; ++fm)
-                xf[fm] = *reinterpret_cast<const v4i*>(lds + stage * STAGE_BYTES + xf_off[ksl] + fm * 2048);
-#pragma unroll
-            for (int fn = 0; fn < 8; ++fn)
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[fn][fm], wf[fn], xf[fm]);
+        for (int fn = 0; fn < 8; ++fn) {
+            const int blk = (GATED && fn >= 4) ? fn + 4 : fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
+            wf[fn] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(l3 + buf + wf_off + blk * 1024);
         }
-        if (kt + 1 < KT) store_tile(stage ^ 1);
-        __syncthreads();
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+            xf[fm] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(l3 + buf + xf_off + fm * 1024);
+#pragma unroll
+        for (int fn = 0; fn < 8; ++fn)
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[fn][fm], wf[fn], xf[fm]);
     }
 
     const bool vec_ok = (N & 3) == 0;
