@@ -223,7 +223,7 @@ int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated,
         if (gated) return EPARA_ERR_DTYPE;
         table[n++] = {INT32_MAX, 64, 64};
     } else if (in_dtype == EPARA_BF16 || in_dtype == EPARA_FP8_E4M3) {
-        table[n++] = {64, 64, 32};                       // weight-streaming class, whole batch per tile
+        table[n++] = {64, 64, gated ? 16 : 32};          // weight-streaming class: whole batch x two weight fragments
         table[n++] = {INT32_MAX, 256, gated ? 128 : 256};  // LDS-tiled MFMA class
     } else {
         return EPARA_ERR_DTYPE;

@@ -2,17 +2,21 @@
 //
 // One launch serves every co-located service (the MT operator of Sec. 3.1): persistent
 // workgroups walk a device tile table in a precomputed visit order; a tile is either
-//   - "big":    256 rows x 256 columns of one group, LDS-staged, 16x16x32 MFMA, or
+//   - "big":    256 rows x 256 columns of one group, LDS-staged, 32x32x16 MFMA, or
 //   - "skinny": a whole batch of <= 64 rows x 32 columns, weights streamed from HBM straight
-//               into MFMA operand registers, K split over the eight waves of the workgroup.
+//               into 16x16x32 MFMA operand registers, K split over the four waves of the
+//               workgroup.
 // Bias, activation, SwiGLU gating, fp8 scales and the output cast are fused in the epilogue.
+// A workgroup is four waves, one per SIMD, so a wave may use the whole 512-entry register
+// file: 256 accumulators for a 128 x 128 wave tile plus double-buffered operand fragments.
 //
-// MFMA orientation.  D = A*B with A = a weight fragment (16 output columns x 64 bytes of K)
-// and B = an activation fragment (16 rows x 64 bytes of K): lane (r = lane%16, q = lane/16)
-// feeds the 16 bytes "k-chunk q" of column/row r to both operands and receives
-// D[n = 4q+i][m = r], i = 0..3 -- four consecutive output columns of one row, which is
-// what a row-major store wants.  Only the pairing of A and B chunks matters for the sum,
-// so the same code serves bf16 (8 values per chunk) and fp8 (16 values per chunk).
+// MFMA orientation.  D = A*B with A = weight fragments and B = activation fragments, both as
+// 16-byte "k-chunks": a lane feeds chunk q of weight column / activation row r to A and B and
+// receives four consecutive output columns of one row per accumulator quad -- what a row-major
+// store wants.  Only the pairing of A and B chunks matters for the sum, so the same code
+// serves bf16 (8 values per chunk) and fp8 (16 values per chunk).
+//   16x16x32: lane = (r = lane%16, q = lane/16), D[n = 4q+i][m = r]
+//   32x32x16: lane = (r = lane%32, h = lane/32), D[n = 8(v/4) + 4h + v%4][m = r], v = 0..15
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -22,14 +26,13 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int NT = 512;                 // threads per workgroup (8 waves)
-constexpr int STAGE_BYTES = 32768;      // one operand tile of one pipeline stage: 256 rows x 128 B
+constexpr int NT = 256;                 // threads per workgroup (4 waves, one per SIMD)
+constexpr int STAGE_BYTES = 32768;      // one pipeline stage: X 256 rows x 64 B + W 16 column blocks x 1 KiB
 constexpr int LDS_BYTES = 4 * STAGE_BYTES;
-constexpr int BIG_BM = 256;
-constexpr int SKINNY_BN = 32;
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
 
 // ------------------------------------------------------------------ small device helpers
@@ -95,6 +98,20 @@ __device__ __forceinline__ void mma(v4f& c, const v4i& a, const v4i& b)
         const v2l al = __builtin_bit_cast(v2l, a), bl = __builtin_bit_cast(v2l, b);
         c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(al[0], bl[0], c, 0, 0, 0);
         c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(al[1], bl[1], c, 0, 0, 0);
+    }
+}
+
+// 32x32 accumulate of one 16-byte chunk pair per lane (bf16: K = 16; fp8: two K = 16 halves).
+template <int DT>
+__device__ __forceinline__ void mma32(v16f& c, const v4i& a, const v4i& b)
+{
+    if constexpr (DT == EPARA_BF16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    } else {
+        typedef long v2l __attribute__((ext_vector_type(2)));
+        const v2l al = __builtin_bit_cast(v2l, a), bl = __builtin_bit_cast(v2l, b);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(al[0], bl[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(al[1], bl[1], c, 0, 0, 0);
     }
 }
 
@@ -168,33 +185,39 @@ __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out
 // ------------------------------------------------------------------ big tiles (LDS + MFMA)
 
 // One 256 x 256 output tile (gated: 256 rows x 128 hidden columns, i.e. 128 gate + 128 up
-// weight columns).  K advances in stages of 64 bytes per row (one weight fragment per column
-// block); four stages of 32 KiB rotate through the LDS:
+// weight columns).  K advances in stages of 64 bytes per row (one packed weight fragment per
+// column block); four stages of 32 KiB rotate through the LDS:
 //   [X: 256 rows x 64 B][W: 16 column blocks x 1 KiB]
-// and are filled by direct global->LDS loads (no staging registers), three stages ahead of the
-// one being multiplied, so a load has about three stage times to arrive.
+// and are filled by direct global->LDS loads (no staging registers) three stages ahead.
 //   X stage: 16-byte chunk c of row `row` is stored at chunk c ^ ((row/4)%4): the 16 rows that one
 //            quarter of a ds_read_b128 touches then fall into 16 different bank groups.  A direct
 //            load writes 1 KiB of consecutive LDS per wave instruction, so lane l fetches the
 //            global chunk that belongs at position l (row l/4 of the instruction's 16 rows).
-//   W stage: verbatim image of the packed fragments, lane l's 16 bytes at position l.
+//   W stage: verbatim image of the packed fragments.
 // Rows past the batch and column blocks past N are clamped to the last valid one (they only
 // feed outputs that are never stored).  In a ragged last stage the X chunks past K are clamped
-// to chunk 0: the packed weights are zero there, so the products vanish.
-// Synchronisation per stage: each wave waits for its own loads of the stage (vmcnt), then one
-// workgroup barrier makes every wave's part visible and also proves that the buffer about to
-// be refilled is no longer being read.
+// to chunk 0: the packed weights are zero there, so the products vanish.  Stages past the end
+// of K re-load the last stage into a buffer nobody reads, which keeps the loop free of branches.
+//
+// A stage is two 32x32x16 steps.  Operand fragments are double-buffered in registers: the
+// reads of step s+1 are issued between the MFMAs of step s.  In the middle of stage kt every
+// wave waits for its own loads of stage kt+1, a workgroup barrier makes all parts visible (and
+// proves that every wave has finished reading stage kt), and the buffer of stage kt is refilled
+// with stage kt+NS.
 typedef __attribute__((address_space(3))) char* ldsptr;
+typedef const __attribute__((address_space(3))) v4i* lds_v4i;
 
 constexpr int NS = 4;                    // pipeline stages
 constexpr int XSTAGE_BYTES = 16384;      // X part of a stage
+constexpr int DMA_PER_STAGE = 8;         // direct loads per wave per stage (4 X + 4 W)
 
-template <int N_OUTSTANDING>
+template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
-    static_assert(N_OUTSTANDING < 16, "encoding below covers vmcnt < 16");
-    __builtin_amdgcn_s_waitcnt(0x0F70 | N_OUTSTANDING);      // vmcnt = N, expcnt / lgkmcnt untouched
+    static_assert(N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);    // expcnt / lgkmcnt untouched
 }
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 template <int DT, bool GATED>
 __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dtype,
@@ -203,207 +226,312 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
     constexpr int KF = 4 * EPC;     // K elements per stage (one weight fragment)
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, q = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31, h = lane >> 5;
     const int wn = wave & 1, wm = wave >> 1;
     const int K = ga.K, N = ga.N;
     const int KS = (K + KF - 1) / KF;
     const int NB = (N + 15) >> 4;
     ldsptr l3 = (ldsptr)lds;
 
-    // --- direct-load descriptors: this wave fills X rows [32 wave, 32 wave + 32) and W blocks 2 wave, 2 wave + 1
+    // --- direct-load descriptors: this wave fills X rows [64 wave, 64 wave + 64) and W blocks 4 wave .. 4 wave + 3
     const int xchunk = (lane & 3) ^ ((lane >> 4) & 3);
     const int tail_k = K - (KS - 1) * KF;                       // elements in the last stage, 1..KF
     const int xchunk_tail = (xchunk * EPC < tail_k) ? xchunk : 0;
     gcptr xbase = as_global<char>(ga.X) + static_cast<size_t>(m0) * K * ESZ;
-    gcptr wbase = as_global<char>((GATED && wave >= 4) ? ga.W2 : ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
-    uint32_t xoff[2], xoff_tail[2], woff[2];
+    gcptr wbase = as_global<char>((GATED && wave >= 2) ? ga.W2 : ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
+    uint32_t xoff[4], xoff_tail[4], woff[4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row = min(32 * wave + 16 * j + (lane >> 2), rows - 1);
+    for (int j = 0; j < 4; ++j) {
+        const int row = min(64 * wave + 16 * j + (lane >> 2), rows - 1);
         xoff[j] = static_cast<uint32_t>((row * K + xchunk * EPC) * ESZ);
         xoff_tail[j] = static_cast<uint32_t>((row * K + xchunk_tail * EPC) * ESZ);
-        const int nbrel = (GATED ? ((2 * wave) & 7) : 2 * wave) + j;
+        const int nbrel = (GATED ? ((4 * wave) & 7) : 4 * wave) + j;
         const int nb = min(nbrel, NB - 1 - (n0 >> 4));
         woff[j] = static_cast<uint32_t>((nb * KS * 64 + lane) * 16);
     }
-    const int dma_lds = 2 * wave * 1024;                        // my first 1 KiB slot inside the X (or W) part
+    const int dma_lds = 4 * wave * 1024;                        // my first 1 KiB slot inside the X (or W) part
 
-    auto issue = [&](int kt) {
-        const int buf = (kt & (NS - 1)) * STAGE_BYTES;
+    auto issue = [&](int kt_unclamped) {
+        const int buf = (kt_unclamped & (NS - 1)) * STAGE_BYTES;
+        const int kt = min(kt_unclamped, KS - 1);
         gcptr xb = xbase + static_cast<size_t>(kt) * 64;
         gcptr wb = wbase + static_cast<size_t>(kt) * 1024;
         const bool tail = kt == KS - 1;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
             __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
                                              (__attribute__((address_space(3))) void*)(l3 + buf + dma_lds + j * 1024), 16, 0, 0);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
             __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
                                              (__attribute__((address_space(3))) void*)(l3 + buf + XSTAGE_BYTES + dma_lds + j * 1024), 16, 0, 0);
     };
 
-    // --- fragment read offsets inside a stage
-    const int xf_off = (wm * 64 + r) * 64 + ((q ^ (r >> 2)) << 4);                      // + fm * 1024
-    const int wf_off = XSTAGE_BYTES + ((GATED ? wn * 4 : wn * 8) * 64 + lane) * 16;    // + block * 1024
-
-    v4f acc[8][4];
+    // --- fragment read offsets inside a stage, for step s = 0, 1 (k-chunk 2s + h)
+    //   W fragment fn = column blocks (2 fn, 2 fn + 1) of the wave's eight: lane r32 -> block r32/16, column r32%16
+    //   X fragment fm = rows wm*128 + fm*32 + r32
+    const int sw = (r32 >> 2) & 3;
+    int xf_off[2];
 #pragma unroll
-    for (int fn = 0; fn < 8; ++fn)
-#pragma unroll
-        for (int fm = 0; fm < 4; ++fm) acc[fn][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int s2 = 0; s2 < 2; ++s2) xf_off[s2] = (wm * 128 + r32) * 64 + ((((2 * s2 + h) ^ sw)) << 4);      // + fm * 2048
+    const int wf_off = XSTAGE_BYTES + ((GATED ? wn * 4 : wn * 8) + (r32 >> 4)) * 1024 + (h * 16 + (r32 & 15)) * 16;   // + blk*1024 + s*512
 
-    __syncthreads();                       // the previous tile is done with the LDS
+    v16f acc[4][4];
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (s < KS) issue(s);
+    for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0.f;
 
-    for (int kt = 0; kt < KS; ++kt) {
-        const int ahead = min(NS - 2, KS - 1 - kt);            // stages that may still be in flight after this wait
-        if (ahead >= 2) wait_vmcnt<8>();
-        else if (ahead == 1) wait_vmcnt<4>();
-        else wait_vmcnt<0>();
-        __builtin_amdgcn_s_barrier();
-        if (kt + NS - 1 < KS) issue(kt + NS - 1);               // refills the buffer read in the previous iteration
+    v4i wf[2][4], xf[2][4];
+    auto read_frags = [&](int kt, int s2, int set) {
         const int buf = (kt & (NS - 1)) * STAGE_BYTES;
-        v4i wf[8], xf[4];
 #pragma unroll
-        for (int fn = 0; fn < 8; ++fn) {
-            const int blk = (GATED && fn >= 4) ? fn + 4 : fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
-            wf[fn] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(l3 + buf + wf_off + blk * 1024);
+        for (int fn = 0; fn < 4; ++fn) {
+            const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
+            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + buf + wf_off + blk * 1024 + s2 * 512);
         }
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm)
-            xf[fm] = *reinterpret_cast<const __attribute__((address_space(3))) v4i*>(l3 + buf + xf_off + fm * 1024);
-#pragma unroll
-        for (int fn = 0; fn < 8; ++fn)
-#pragma unroll
-            for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[fn][fm], wf[fn], xf[fm]);
-    }
-
-    const bool vec_ok = (N & 3) == 0;
-    if constexpr (GATED) {
+            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + buf + xf_off[s2] + fm * 2048);
+    };
+    auto multiply = [&](int set) {
 #pragma unroll
         for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
+            for (int fm = 0; fm < 4; ++fm) mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
+    };
+    auto interleave = [&]() {               // 8 fragment reads spread between the 16 (fp8: 32) MFMAs of a step
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, DT == EPARA_BF16 ? 2 : 4, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                            // DS read
+        }
+    };
+
+    wait_vmcnt<0>();                       // nothing of the previous tile is still landing in the LDS
+    __syncthreads();                       // and nobody still reads it
+#pragma unroll
+    for (int s = 0; s < NS; ++s) issue(s);
+    wait_vmcnt<DMA_PER_STAGE * (NS - 1)>();
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, 0);
+
+    for (int kt = 0; kt < KS; ++kt) {
+        // first half: multiply step 0 of stage kt, read its step 1
+        read_frags(kt, 1, 1);
+        multiply(0);
+        interleave();
+        // stage kt+1 must be visible before its fragments are read; stage kt is now fully in registers
+        wait_lgkmcnt0();
+        wait_vmcnt<DMA_PER_STAGE * (NS - 2)>();
+        __builtin_amdgcn_s_barrier();
+        issue(kt + NS);
+        // second half: multiply step 1 of stage kt, read step 0 of stage kt+1 (past the end: unused)
+        read_frags(kt + 1, 0, 0);
+        multiply(1);
+        interleave();
+    }
+    wait_vmcnt<0>();
+
+    const bool vec_ok = (N & 3) == 0;
+    // accumulator quad g of a 32x32 fragment: columns 8g + 4h .. +3 of the fragment, row r32
+    if constexpr (GATED) {
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
             for (int fm = 0; fm < 4; ++fm)
-                finish_gated(ga, out_dtype, acc[fn][fm], acc[fn + 4][fm], m0, wm * 64 + fm * 16 + r, rows,
-                             n0, (wn * 4 + fn) * 16 + 4 * q, cols, vec_ok);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const v4f gate = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
+                    const v4f up = {acc[fn + 2][fm][4 * g], acc[fn + 2][fm][4 * g + 1], acc[fn + 2][fm][4 * g + 2], acc[fn + 2][fm][4 * g + 3]};
+                    finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + fm * 32 + r32, rows,
+                                 n0, wn * 64 + fn * 32 + 8 * g + 4 * h, cols, vec_ok);
+                }
     } else {
         with_act(ga.act, [&](auto tag) {
 #pragma unroll
-            for (int fn = 0; fn < 8; ++fn)
+            for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
                 for (int fm = 0; fm < 4; ++fm)
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, acc[fn][fm], m0, wm * 64 + fm * 16 + r, rows,
-                                                       n0, (wn * 8 + fn) * 16 + 4 * q, cols, vec_ok);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const v4f a4 = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
+                        finish_plain<decltype(tag)::value>(ga, out_dtype, a4, m0, wm * 128 + fm * 32 + r32, rows,
+                                                           n0, wn * 128 + fn * 32 + 8 * g + 4 * h, cols, vec_ok);
+                    }
         });
     }
 }
 
 // ------------------------------------------------------------------ skinny tiles (weight streaming)
 
-// A batch of M <= 64 rows against 32 output columns.  Wave w takes the weight fragments
-// ks = w, w+8, ... of the K dimension, straight from HBM into MFMA operand registers (each
-// load instruction of a wave reads 1 KiB of contiguous packed weights); the eight partial
-// sums meet in LDS and are added in wave order, so the result does not depend on timing.
-template <int DT, bool GATED, int MB>
-__device__ __forceinline__ void skinny_tile(const epara_group_args& ga, int out_dtype, int n0, int cols, char* lds)
+// A batch of M <= 64 rows against two weight fragments per K step: 32 output columns, or (gated)
+// 16 hidden columns = one gate and one up column block.  Wave w takes the K steps ks = w, w+4, ...
+// and streams the packed weights straight from HBM into MFMA operand registers (each load
+// instruction of a wave reads 1 KiB of consecutive bytes); the four partial sums meet in LDS and
+// are added in wave order, so the result does not depend on timing.
+//
+// All skinny tiles a workgroup owns are processed as one software-pipelined stream: a ring of U
+// register slots per wave is kept full across tile boundaries, so the loads of the next tile
+// are already in flight while this tile is reduced and stored.  Every tile is padded to a whole
+// number of U steps; padding steps and rows past the batch re-load a valid address and are
+// not multiplied / not stored.
+struct skinny_tile_state {
+    gcptr w[2];            // weight fragment streams (step 0 of this wave), lane part included
+    gcptr x;               // activations of the group
+    uint32_t xrow[4];      // byte offset of my row in each 16-row block
+    int KS, K, n_chunks;   // fragments along K, chunks of U steps per wave
+};
+
+template <int DT, bool GATED, int U>
+__device__ __forceinline__ void skinny_setup(skinny_tile_state& st, const epara_group_args& ga, int n0, int wave, int lane)
 {
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
-    constexpr int EPC = 16 / ESZ;
-    constexpr int KF = 4 * EPC;
-    constexpr int NF = GATED ? 4 : 2;        // weight fragments per K step: 2 column blocks (x2 matrices when gated)
-    constexpr int U = 4;                     // K steps in flight per wave
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = lane & 15, q = lane >> 4;
-    const int M = ga.M, K = ga.K, N = ga.N;
+    constexpr int KF = 4 * (16 / ESZ);
+    const int K = ga.K, N = ga.N;
     const int KS = (K + KF - 1) / KF;
     const int NB = (N + 15) >> 4;
-
-    gcptr wp[NF];
+    const int r = lane & 15;
+    st.K = K;
+    st.KS = KS;
+    st.n_chunks = (((KS + 3) >> 2) + U - 1) / U;
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-        const int nb = min((n0 >> 4) + (f & 1), NB - 1);   // a block past N only feeds unstored columns
-        gcptr base = as_global<char>((GATED && f >= 2) ? ga.W2 : ga.W);
-        wp[f] = base + (static_cast<size_t>(nb) * KS * 64 + lane) * 16;
+    for (int f = 0; f < 2; ++f) {
+        const int nb = GATED ? (n0 >> 4) : min((n0 >> 4) + f, NB - 1);     // a block past N only feeds unstored columns
+        gcptr base = as_global<char>((GATED && f == 1) ? ga.W2 : ga.W);
+        st.w[f] = base + (static_cast<size_t>(nb) * KS * 64 + lane) * 16;
     }
-    gcptr xp[MB];
+    st.x = as_global<char>(ga.X);
 #pragma unroll
-    for (int fm = 0; fm < MB; ++fm) {
-        const int row = min(fm * 16 + r, M - 1);           // a row past the batch only feeds unstored rows
-        xp[fm] = as_global<char>(ga.X) + static_cast<size_t>(row) * K * ESZ;
-    }
-    const int xq = q * EPC;                                // my k offset inside a fragment
+    for (int fm = 0; fm < 4; ++fm)
+        st.xrow[fm] = static_cast<uint32_t>(min(fm * 16 + r, ga.M - 1)) * static_cast<uint32_t>(K * ESZ);
+}
 
-    v4f acc[NF][MB];
+template <int DT>
+__device__ __forceinline__ void skinny_load(const skinny_tile_state& st, int i, int wave, int lane, v4i* wf, v4i* xf)
+{
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const int ks = min(wave + 4 * i, st.KS - 1);                 // padding steps repeat the last fragment
+    const int xq = (lane >> 4) * EPC;
+    const uint32_t xo = static_cast<uint32_t>((ks * KF + ((ks * KF + xq < st.K) ? xq : 0)) * ESZ);   // ragged K: chunk 0 (weights are 0 there)
 #pragma unroll
-    for (int f = 0; f < NF; ++f)
+    for (int f = 0; f < 2; ++f) wf[f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024);
 #pragma unroll
-        for (int fm = 0; fm < MB; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
-
-    // Steps of this wave: ks = wave + 8 i.  U steps are loaded before any is consumed, so each
-    // wave keeps U * NF KiB of weights in flight.
-    const int n_steps = KS > wave ? (KS - wave + 7) >> 3 : 0;
-    for (int i0 = 0; i0 < n_steps; i0 += U) {
-        v4i wf[U][NF], xf[U][MB];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ks = wave + 8 * min(i0 + u, n_steps - 1);   // repeats the last step past the end (discarded)
-#pragma unroll
-            for (int f = 0; f < NF; ++f) wf[u][f] = ld16(wp[f] + static_cast<size_t>(ks) * 1024);
-            const bool k_ok = ks * KF + xq < K;                    // false only in a ragged last fragment
-            const int xo = (ks * KF + (k_ok ? xq : 0)) * ESZ;
-#pragma unroll
-            for (int fm = 0; fm < MB; ++fm) {
-                const v4i v = ld16(xp[fm] + xo);
-                xf[u][fm] = k_ok ? v : v4i{0, 0, 0, 0};
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (i0 + u < n_steps) {
-#pragma unroll
-                for (int f = 0; f < NF; ++f)
-#pragma unroll
-                    for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], wf[u][f], xf[u][fm]);
-            }
-        }
-    }
-
-    // cross-wave reduction through LDS: red[wave][f*MB+fm][lane]
-    v4f* red = reinterpret_cast<v4f*>(lds);
-    __syncthreads();
-#pragma unroll
-    for (int f = 0; f < NF; ++f)
-#pragma unroll
-        for (int fm = 0; fm < MB; ++fm) red[(wave * (NF * MB) + f * MB + fm) * 64 + lane] = acc[f][fm];
-    __syncthreads();
-
-    const bool vec_ok = (N & 3) == 0;
-    for (int u = wave; u < 2 * MB; u += 8) {            // unit = (column block, row block)
-        const int cb = u / MB, fm = u % MB;
-        v4f s0 = v4f{0.f, 0.f, 0.f, 0.f}, s1 = v4f{0.f, 0.f, 0.f, 0.f};
-        for (int w = 0; w < 8; ++w) {
-            s0 += red[(w * (NF * MB) + cb * MB + fm) * 64 + lane];
-            if constexpr (GATED) s1 += red[(w * (NF * MB) + (cb + 2) * MB + fm) * 64 + lane];
-        }
-        if constexpr (GATED) finish_gated(ga, out_dtype, s0, s1, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
-        else with_act(ga.act, [&](auto tag) {
-            finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
-        });
-    }
+    for (int fm = 0; fm < 4; ++fm) xf[fm] = ld16(st.x + (st.xrow[fm] + xo));
 }
 
 template <int DT, bool GATED>
-__device__ __forceinline__ void skinny_dispatch(const epara_group_args& ga, int out_dtype, int n0, int cols, char* lds)
+__device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int out_dtype, int n0, int cols,
+                                              v4f (&acc)[2][4], int wave, int lane, char* lds)
 {
-    const int mb = (ga.M + 15) >> 4;
-    if (mb <= 1)      skinny_tile<DT, GATED, 1>(ga, out_dtype, n0, cols, lds);
-    else if (mb == 2) skinny_tile<DT, GATED, 2>(ga, out_dtype, n0, cols, lds);
-    else if (mb == 3) skinny_tile<DT, GATED, 3>(ga, out_dtype, n0, cols, lds);
-    else              skinny_tile<DT, GATED, 4>(ga, out_dtype, n0, cols, lds);
+    const int r = lane & 15, q = lane >> 4;
+    v4f* red = reinterpret_cast<v4f*>(lds);                      // red[wave][f*4+fm][lane]
+    __syncthreads();                                             // the previous tile's sums have been read
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int fm = 0; fm < 4; ++fm) red[(wave * 8 + f * 4 + fm) * 64 + lane] = acc[f][fm];
+    __syncthreads();
+    const bool vec_ok = (ga.N & 3) == 0;
+    const int M = ga.M;
+    if constexpr (GATED) {                                       // unit = row block `wave`: gate fragment 0, up fragment 1
+        const int fm = wave;
+        if (fm * 16 < M) {
+            v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { g += red[(w * 8 + fm) * 64 + lane]; u += red[(w * 8 + 4 + fm) * 64 + lane]; }
+            finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, 4 * q, cols, vec_ok);
+        }
+    } else {                                                     // units (column block, row block): two per wave
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int unit = wave * 2 + j, cb = unit >> 2, fm = unit & 3;
+            if (fm * 16 < M && cb * 16 < cols) {
+                v4f s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < 4; ++w) s0 += red[(w * 8 + cb * 4 + fm) * 64 + lane];
+                with_act(ga.act, [&](auto tag) {
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
+                });
+            }
+        }
+    }
+}
+
+// Processes slot `slot` and every following slot of this workgroup that holds a skinny tile.
+// Returns the first slot it did not process.
+template <int DT, bool GATED>
+__device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
+                                           const int32_t* __restrict__ order, long slot, long n_slots, long stride,
+                                           int out_dtype, char* lds)
+{
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    auto next_tile = [&](long s) {          // next slot of this workgroup holding a skinny tile, else -1
+        for (s += stride; s < n_slots; s += stride) {
+            const int t = order[s];
+            if (t < 0) continue;
+            return tiles[t].cls == 0 ? s : -1L;
+        }
+        return -1L;
+    };
+
+    epara_tile tl = tiles[order[slot]];
+    epara_group_args ga = args[tl.group];
+    skinny_tile_state cur, nxt;
+    skinny_setup<DT, GATED, U>(cur, ga, tl.n0, wave, lane);
+    v4i wf[U][2], xf[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) skinny_load<DT>(cur, u, wave, lane, wf[u], xf[u]);
+
+    for (;;) {
+        const long slot_next = next_tile(slot);
+        epara_tile tl_next = tl;
+        epara_group_args ga_next = ga;
+        if (slot_next >= 0) {
+            tl_next = tiles[order[slot_next]];
+            ga_next = args[tl_next.group];
+            skinny_setup<DT, GATED, U>(nxt, ga_next, tl_next.n0, wave, lane);
+        } else {
+            nxt = cur;                                           // nothing follows: the ring is refilled with valid, unused data
+        }
+        v4f acc[2][4];
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+        const int n_valid = cur.KS > wave ? (cur.KS - wave + 3) >> 2 : 0;
+        for (int c = 0; c < cur.n_chunks; ++c) {
+            const bool last = c + 1 == cur.n_chunks;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = c * U + u;
+                if (i < n_valid) {
+#pragma unroll
+                    for (int f = 0; f < 2; ++f)
+#pragma unroll
+                        for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[f][fm], wf[u][f], xf[u][fm]);
+                }
+                if (last) skinny_load<DT>(nxt, u, wave, lane, wf[u], xf[u]);
+                else      skinny_load<DT>(cur, i + U, wave, lane, wf[u], xf[u]);
+            }
+        }
+        skinny_finish<DT, GATED>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
+        if (slot_next < 0) break;
+        slot = slot_next;
+        tl = tl_next;
+        ga = ga_next;
+        cur = nxt;
+    }
+    // first slot after this run: the next non-idle slot of this workgroup (a big tile) or the end
+    for (slot += stride; slot < n_slots && order[slot] < 0; slot += stride) {}
+    return slot;
 }
 
 // ------------------------------------------------------------------ persistent kernels
@@ -412,21 +540,23 @@ template <int DT>
 __global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
                                                      const epara_tile* __restrict__ tiles,
                                                      const int32_t* __restrict__ order,
-                                                     long n_slots, int out_dtype)
+                                                     long n_slots, int out_dtype, int gated)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    for (long s = blockIdx.x; s < n_slots; s += gridDim.x) {
+    const long stride = gridDim.x;
+    long s = blockIdx.x;
+    while (s < n_slots) {
         const int t = order[s];
-        if (t < 0) continue;
+        if (t < 0) { s += stride; continue; }
         const epara_tile tl = tiles[t];
-        const epara_group_args ga = args[tl.group];
-        const bool gated = ga.act == EPARA_ACT_SWIGLU;
         if (tl.cls == 0) {
-            if (gated) skinny_dispatch<DT, true>(ga, out_dtype, tl.n0, tl.cols, lds);
-            else       skinny_dispatch<DT, false>(ga, out_dtype, tl.n0, tl.cols, lds);
+            s = gated ? skinny_run<DT, true>(args, tiles, order, s, n_slots, stride, out_dtype, lds)
+                      : skinny_run<DT, false>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
         } else {
+            const epara_group_args ga = args[tl.group];
             if (gated) big_tile<DT, true>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
             else       big_tile<DT, false>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+            s += stride;
         }
     }
 }
@@ -561,6 +691,13 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
             return EPARA_ERR_ALIGN;
         if (!f32 && (static_cast<int64_t>(a.K) * esz) % 16 != 0) return EPARA_ERR_ALIGN;
     }
+    // a launch is either all SwiGLU groups or none: the tile classes differ
+    {
+        int32_t n_gated = 0, n_live = 0;
+        for (int32_t g = 0; g < L->G; ++g)
+            if (L->h_args[g].M > 0) { ++n_live; n_gated += L->h_args[g].act == EPARA_ACT_SWIGLU; }
+        if (n_gated != 0 && n_gated != n_live) return EPARA_ERR_DTYPE;
+    }
     epara_tile_class cls[2][2];
     int32_t ncls[2] = {0, 0};
     epara_kernel_classes(in_dtype, 0, cls[0], 2, &ncls[0]);
@@ -584,6 +721,9 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
 int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, hipStream_t stream)
 {
     if (L->n_tiles == 0) return EPARA_OK;
+    int gated = 0;
+    for (int32_t g = 0; g < L->G; ++g)
+        if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated = 1;
     const dim3 grid(static_cast<unsigned>(L->n_workgroups));
     (void)hipGetLastError();
     if (in_dtype == EPARA_F32) {
@@ -594,13 +734,13 @@ int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, hipS
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (attr != hipSuccess) return EPARA_ERR_HIP;
         hipLaunchKernelGGL(grouped_kernel<EPARA_BF16>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
-                           L->d_order, static_cast<long>(L->n_slots), out_dtype);
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated);
     } else {
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<EPARA_FP8_E4M3>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (attr != hipSuccess) return EPARA_ERR_HIP;
         hipLaunchKernelGGL(grouped_kernel<EPARA_FP8_E4M3>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
-                           L->d_order, static_cast<long>(L->n_slots), out_dtype);
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated);
     }
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }

@@ -150,7 +150,7 @@ def test_kernel_classes_and_packed_sizes():
     c = B.epara_kernel_classes(B.EPARA_BF16, 0)
     assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 32), (P.INT32_MAX, 256, 256)]
     c = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
-    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 32), (P.INT32_MAX, 256, 128)]
+    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 16), (P.INT32_MAX, 256, 128)]
     assert [tuple(int(v) for v in x) for x in B.epara_kernel_classes(B.EPARA_F32, 0)] == [(P.INT32_MAX, 64, 64)]
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
