@@ -133,27 +133,41 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
                           int64_t* row_off, int64_t* x_off, int64_t* y_off,
                           epara_tile* tiles, int64_t tiles_cap, int64_t* n_tiles);
 
-/* Visit order of the persistent workgroups.  Workgroup b of n_workgroups visits slots
- * b, b + n_workgroups, ...; order[slot] is a tile index or -1 (idle).
- *   1. locality sequence: classes by descending BM*BN (ties: lower class), inside a class
- *      groups by descending K (ties: lower group), inside a group panels of
- *      panel_m x panel_n tiles, n-panel outermost, m fastest inside a panel;
- *   2. the l-th tile of that sequence goes to slot j*W + i*X + x with j = l div W,
- *      w = l mod W, x = w div (W/X), i = w mod (W/X)   (W = n_workgroups, X = n_xcd),
- *      so the W/X workgroups of one compute die (workgroup b runs on die b mod X) work on
- *      neighbouring tiles and share operands in that die's L2.
- * *n_slots = ceil(n_tiles / W) * W.  order may be NULL to query.  W must be a positive
- * multiple of X.  Errors as above. */
+/* Visit order of the persistent workgroups.  Workgroup b of W = n_workgroups visits slots
+ * b, b + W, b + 2W, ...; order[slot] is a tile index or -1 (idle).  Every workgroup gets a list
+ * of tiles; slot j*W + b holds the j-th entry of workgroup b's list; *n_slots = W * (longest list).
+ * The first n_stream_classes classes of the table are weight-streaming classes (small batches,
+ * bandwidth bound), the others are panel classes (matrix-core bound).
+ *   1. panel tiles: classes by descending BM*BN (ties: lower class), inside a class groups by
+ *      descending K (ties: lower group), inside a group panels of panel_m x panel_n tiles,
+ *      n-panel outermost, m fastest inside a panel.  The l-th tile of that sequence goes to
+ *      workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X)  (X = n_xcd), so the
+ *      W/X workgroups of one compute die (workgroup b runs on die b mod X) work on neighbouring
+ *      tiles and share operands in that die's L2.
+ *   2. streaming tiles, longest first: cost = K * (cols * (2 for EPARA_ACT_SWIGLU groups) + BM)
+ *      for a streaming tile (weight columns streamed plus activation rows re-read) and 340 * K
+ *      for a panel tile; tiles by descending cost (ties: lower tile index) each go to the
+ *      workgroup with the smallest accumulated cost (ties: lower workgroup), after that
+ *      workgroup's panel tiles.
+ * order may be NULL to query *n_slots.  W must be a positive multiple of X;
+ * 0 <= n_stream_classes <= n_classes.  Errors as for epara_plan_groups; a tile table that is not
+ * the canonical one of (groups, classes) gives ERR_SHAPE. */
 int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
-                             const epara_tile_class* classes, int32_t n_classes,
+                             const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
                              const epara_tile* tiles, int64_t n_tiles,
                              int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
                              int32_t* order, int64_t order_cap, int64_t* n_slots);
 
 /* The tile classes the kernels implement for an input dtype (gated = EPARA_ACT_SWIGLU
- * launches, whose BN counts hidden columns).  Writes up to cap classes, *n_classes = count. */
-int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated,
-                             epara_tile_class* classes, int32_t cap, int32_t* n_classes);
+ * launches, whose BN counts hidden columns).  Writes up to cap classes, *n_classes = count and
+ * *n_stream_classes = how many of them (the first ones) are weight-streaming classes.
+ * bf16 / fp8 have two tables: the wide one (narrow = 0) gives batches of 33..64 rows tiles of 128
+ * (gated: 64) columns, which halves the activation re-reads; the narrow one (narrow = 1) gives
+ * them 64 (gated: 32) columns, for launches with too few columns to keep every workgroup busy
+ * with wide tiles.  A launch may use either. */
+int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
+                             epara_tile_class* classes, int32_t cap, int32_t* n_classes,
+                             int32_t* n_stream_classes);
 
 /* Fills the two phases' group arguments of a SwiGLU FFN from per-service descriptors:
  * up_args[g]   : X -> H, W = Wgate, W2 = Wup, act = SWIGLU, K = d_model, N = d_ff

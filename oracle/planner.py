@@ -18,7 +18,7 @@ offsets            row_off[g] = sum_{h<g} M_h,  x_off[g] = sum_{h<g} M_h*K_h,
 tile class         the first class c with M_g <= max_M[c]
 canonical tiles    for g ascending, m0 = 0, BM, 2BM, ... < M_g, n0 = 0, BN, ... < N_g:
                    (g, m0, n0, rows=min(BM, M_g-m0), cols=min(BN, N_g-n0), c)
-visit order        see `schedule_tiles`.
+visit order        see `schedule_tiles` (panel tiles die by die, streaming tiles longest first).
 """
 
 INT32_MAX = 2**31 - 1
@@ -87,51 +87,72 @@ def plan_groups(groups, classes):
     return row_off, x_off, y_off, tiles
 
 
-def schedule_tiles(groups, classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
+def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
     """Visit order of the persistent workgroups.
 
-    Workgroup b of a launch of W = n_workgroups visits slots b, b+W, b+2W, ... and the
-    hardware places workgroup b on compute die b mod n_xcd.  The order is built in two
-    steps.
+    groups: (M, K, N) or (M, K, N, gated) tuples.  Workgroup b of a launch of W = n_workgroups
+    visits slots b, b+W, b+2W, ... and the hardware places workgroup b on compute die
+    b mod n_xcd.  Every workgroup gets a list of tiles; slot j*W + b is the j-th entry of
+    workgroup b (-1 = idle), the order has W * (longest list) entries.  The first
+    n_stream_classes classes are weight-streaming classes, the others panel classes.
 
-    1. Locality sequence: classes by descending BM*BN (ties: lower class first); inside a
-       class the groups by descending K (ties: lower group first); inside a group the
-       tile grid TM x TN is cut into panels of panel_m x panel_n tiles, panels taken with
-       the n-panel index outermost, and inside a panel the m index runs fastest.
-    2. Slot of the l-th tile of that sequence: j = l div W, w = l mod W, die x = w div (W/X),
-       i = w mod (W/X), slot = j*W + i*X + x.  So the W/X tiles that run together on
-       one die are consecutive in the locality sequence.
-
-    Returns a list of length ceil(T/W)*W holding tile indices, -1 for idle slots.
+    1. Panel tiles.  Classes by descending BM*BN (ties: lower class first); inside a class the
+       groups by descending K (ties: lower group first); inside a group the tile grid TM x TN
+       is cut into panels of panel_m x panel_n tiles, panels taken with the n-panel index
+       outermost, and inside a panel the m index runs fastest.  The l-th tile of that sequence
+       goes to workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X): the W/X
+       tiles that run together on one die are consecutive in the sequence.
+    2. Streaming tiles, longest first.  cost = K * (cols * (2 if gated) + BM) for a streaming
+       tile (weight columns streamed plus activation rows re-read), 340 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
+       the workgroup with the smallest accumulated cost (ties: lower workgroup), after that
+       workgroup's panel tiles.
     """
+    import heapq
     W, X = n_workgroups, n_xcd
     if W <= 0 or X <= 0 or W % X != 0 or panel_m <= 0 or panel_n <= 0:
         raise ValueError("bad schedule parameters")
-    T = len(tiles)
-    # index ranges of each group's tiles in the canonical table
+    if not 0 <= n_stream_classes <= len(classes):
+        raise ValueError("bad number of streaming classes")
     first = {}
     for t, tile in enumerate(tiles):
         first.setdefault(tile[0], t)
-    seq = []
-    class_order = sorted(range(len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
-    for c in class_order:
+    lists = [[] for _ in range(W)]
+    load = [0] * W
+    per = W // X
+    l = 0
+    panel_classes = sorted(range(n_stream_classes, len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
+    for c in panel_classes:
         members = sorted({t[0] for t in tiles if t[5] == c}, key=lambda g: (-groups[g][1], g))
         _, bm, bn = classes[c]
         for g in members:
-            M, _K, N = groups[g]
+            M, K, N = groups[g][:3]
             TM, TN = -(-M // bm), -(-N // bn)
-            base = first[g]
             for pn in range(0, TN, panel_n):
                 for pm in range(0, TM, panel_m):
                     for tn in range(pn, min(pn + panel_n, TN)):
                         for tm in range(pm, min(pm + panel_m, TM)):
-                            seq.append(base + tm * TN + tn)
-    assert len(seq) == T
-    n_slots = -(-T // W) * W
-    order = [-1] * n_slots
-    per = W // X
-    for l, t in enumerate(seq):
-        j, w = divmod(l, W)
-        x, i = divmod(w, per)
-        order[j * W + i * X + x] = t
+                            x, i = divmod(l % W, per)
+                            b = i * X + x
+                            lists[b].append(first[g] + tm * TN + tn)
+                            load[b] += 340 * K
+                            l += 1
+    stream = []
+    for t, tile in enumerate(tiles):
+        if tile[5] < n_stream_classes:
+            g = groups[tile[0]]
+            gated = len(g) > 3 and bool(g[3])
+            stream.append((-(g[1] * (tile[4] * (2 if gated else 1) + classes[tile[5]][1])), t))
+    stream.sort()
+    heap = [(load[b], b) for b in range(W)]
+    heapq.heapify(heap)
+    for negcost, t in stream:
+        ld, b = heapq.heappop(heap)
+        lists[b].append(t)
+        heapq.heappush(heap, (ld - negcost, b))
+    assert l + len(stream) == len(tiles)
+    longest = max(len(v) for v in lists)
+    order = [-1] * (longest * W)
+    for b in range(W):
+        for j, t in enumerate(lists[b]):
+            order[j * W + b] = t
     return order

@@ -76,8 +76,8 @@ def lib():
         L.epara_inter_request_count.argtypes = [i64, i64]
         L.epara_inter_request_count.restype = i64
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
-        L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
-        L.epara_kernel_classes.argtypes = [i32, i32, vp, i32, vp]
+        L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
+        L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
         L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
         L.epara_packed_weight_bytes.argtypes = [i32, i32, i32]
         L.epara_packed_weight_bytes.restype = i64
@@ -139,12 +139,12 @@ def epara_plan_groups(groups, classes):
     return row_off, x_off, y_off, tiles
 
 
-def epara_schedule_tiles(groups, classes, tiles, n_workgroups, n_xcd=8, panel_m=8, panel_n=4):
+def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd=8, panel_m=8, panel_n=4):
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
     classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
     tiles = np.ascontiguousarray(tiles, dtype=TILE)
     n = np.zeros(1, dtype=np.int64)
-    args = (_ptr(groups), len(groups), _ptr(classes), len(classes), _ptr(tiles), len(tiles),
+    args = (_ptr(groups), len(groups), _ptr(classes), len(classes), int(n_stream_classes), _ptr(tiles), len(tiles),
             int(n_workgroups), int(n_xcd), int(panel_m), int(panel_n))
     _check(lib().epara_schedule_tiles(*args, None, 0, _ptr(n)), "epara_schedule_tiles")
     order = np.zeros(int(n[0]), dtype=np.int32)
@@ -152,12 +152,14 @@ def epara_schedule_tiles(groups, classes, tiles, n_workgroups, n_xcd=8, panel_m=
     return order
 
 
-def epara_kernel_classes(in_dtype, gated):
-    n = np.zeros(1, dtype=np.int32)
-    classes = np.zeros(4, dtype=TILE_CLASS)
-    _check(lib().epara_kernel_classes(int(in_dtype), int(bool(gated)), _ptr(classes), len(classes), _ptr(n)),
+def epara_kernel_classes(in_dtype, gated, narrow=False):
+    """-> (classes, n_stream_classes)."""
+    n = np.zeros(2, dtype=np.int32)
+    classes = np.zeros(8, dtype=TILE_CLASS)
+    _check(lib().epara_kernel_classes(int(in_dtype), int(bool(gated)), int(bool(narrow)), _ptr(classes), len(classes),
+                                      _ptr(n[0:1]), _ptr(n[1:2])),
            "epara_kernel_classes")
-    return classes[: int(n[0])].copy()
+    return classes[: int(n[0])].copy(), int(n[1])
 
 
 def epara_ffn_swiglu_args(ffn, in_dtype):

@@ -10,6 +10,9 @@
 #include <algorithm>
 #include <climits>
 #include <cstring>
+#include <functional>
+#include <queue>
+#include <utility>
 #include <vector>
 
 namespace {
@@ -142,7 +145,7 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
 }
 
 int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
-                             const epara_tile_class* classes, int32_t n_classes,
+                             const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
                              const epara_tile* tiles, int64_t n_tiles,
                              int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
                              int32_t* order, int64_t order_cap, int64_t* n_slots)
@@ -152,13 +155,10 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
     if (int32_t st = check_classes(classes, n_classes)) return st;
     if (n_workgroups <= 0 || n_xcd <= 0 || n_workgroups % n_xcd != 0 || panel_m <= 0 || panel_n <= 0)
         return EPARA_ERR_SHAPE;
+    if (n_stream_classes < 0 || n_stream_classes > n_classes) return EPARA_ERR_SHAPE;
     if (n_tiles > INT32_MAX) return EPARA_ERR_SHAPE;
 
     const int64_t W = n_workgroups, X = n_xcd, per_die = W / X;
-    const int64_t slots = ceil_div(n_tiles, W) * W;
-    *n_slots = slots;
-    if (!order) return EPARA_OK;
-    if (order_cap < slots) return EPARA_ERR_CAPACITY;
 
     // where each group's tiles start in the canonical table, and which class it was cut with
     std::vector<int64_t> first(G, -1);
@@ -180,19 +180,16 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
         if (expect != n_tiles) return EPARA_ERR_SHAPE;
     }
 
-    std::vector<int32_t> class_order(n_classes);
-    for (int32_t c = 0; c < n_classes; ++c) class_order[c] = c;
+    std::vector<std::vector<int32_t>> lists(static_cast<size_t>(W));
+    std::vector<int64_t> load(static_cast<size_t>(W), 0);
+
+    // 1. panel tiles
+    std::vector<int32_t> class_order;
+    for (int32_t c = n_stream_classes; c < n_classes; ++c) class_order.push_back(c);
     std::stable_sort(class_order.begin(), class_order.end(), [&](int32_t a, int32_t b) {
         return static_cast<int64_t>(classes[a].BM) * classes[a].BN > static_cast<int64_t>(classes[b].BM) * classes[b].BN;
     });
-
-    std::fill(order, order + slots, -1);
     int64_t l = 0;
-    auto place = [&](int64_t tile) {
-        const int64_t j = l / W, w = l % W, x = w / per_die, i = w % per_die;
-        order[j * W + i * X + x] = static_cast<int32_t>(tile);
-        ++l;
-    };
     std::vector<int32_t> members;
     for (int32_t c : class_order) {
         members.clear();
@@ -206,29 +203,71 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
             for (int64_t pn = 0; pn < TN; pn += panel_n)
                 for (int64_t pm = 0; pm < TM; pm += panel_m)
                     for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
-                        for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm)
-                            place(first[g] + tm * TN + tn);
+                        for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
+                            const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
+                            lists[b].push_back(static_cast<int32_t>(first[g] + tm * TN + tn));
+                            load[b] += 340 * static_cast<int64_t>(groups[g].K);
+                            ++l;
+                        }
         }
     }
-    return l == n_tiles ? EPARA_OK : EPARA_ERR_SHAPE;
+
+    // 2. streaming tiles, longest first onto the least loaded workgroup
+    struct item { int64_t cost; int32_t tile; };
+    std::vector<item> stream;
+    for (int64_t t = 0; t < n_tiles; ++t)
+        if (tiles[t].cls < n_stream_classes) {
+            const epara_group_desc& d = groups[tiles[t].group];
+            const int64_t units = static_cast<int64_t>(tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + classes[tiles[t].cls].BM;
+            stream.push_back({units * d.K, static_cast<int32_t>(t)});
+        }
+    std::stable_sort(stream.begin(), stream.end(), [](const item& a, const item& b) { return a.cost > b.cost; });
+    typedef std::pair<int64_t, int32_t> entry;                  // (load, workgroup): smallest first
+    std::priority_queue<entry, std::vector<entry>, std::greater<entry>> heap;
+    for (int32_t b = 0; b < W; ++b) heap.push({load[b], b});
+    for (const item& it : stream) {
+        entry e = heap.top();
+        heap.pop();
+        lists[e.second].push_back(it.tile);
+        heap.push({e.first + it.cost, e.second});
+    }
+    if (l + static_cast<int64_t>(stream.size()) != n_tiles) return EPARA_ERR_SHAPE;
+
+    size_t longest = 0;
+    for (const auto& v : lists) longest = std::max(longest, v.size());
+    const int64_t slots = static_cast<int64_t>(longest) * W;
+    *n_slots = slots;
+    if (!order) return EPARA_OK;
+    if (order_cap < slots) return EPARA_ERR_CAPACITY;
+    std::fill(order, order + slots, -1);
+    for (int64_t b = 0; b < W; ++b)
+        for (size_t j = 0; j < lists[b].size(); ++j) order[static_cast<int64_t>(j) * W + b] = lists[b][j];
+    return EPARA_OK;
 }
 
-int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated,
-                             epara_tile_class* classes, int32_t cap, int32_t* n_classes)
+int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
+                             epara_tile_class* classes, int32_t cap, int32_t* n_classes,
+                             int32_t* n_stream_classes)
 {
-    if (!n_classes) return EPARA_ERR_NULL;
-    epara_tile_class table[2];
-    int32_t n = 0;
+    if (!n_classes || !n_stream_classes) return EPARA_ERR_NULL;
+    epara_tile_class table[4];
+    int32_t n = 0, ns = 0;
     if (in_dtype == EPARA_F32) {
         if (gated) return EPARA_ERR_DTYPE;
         table[n++] = {INT32_MAX, 64, 64};
     } else if (in_dtype == EPARA_BF16 || in_dtype == EPARA_FP8_E4M3) {
-        table[n++] = {64, 64, gated ? 16 : 32};          // weight-streaming class: whole batch x two weight fragments
+        // weight-streaming classes: the whole batch (1, 2 or 4 blocks of 16 rows) against 2, 4 or 8
+        // weight column blocks, so that activations re-read per weight byte stay constant
+        table[n++] = {16, 16, gated ? 16 : 32};
+        table[n++] = {32, 32, gated ? 32 : 64};
+        table[n++] = {64, 64, (gated ? 64 : 128) >> (narrow ? 1 : 0)};
+        ns = 3;
         table[n++] = {INT32_MAX, 256, gated ? 128 : 256};  // LDS-tiled MFMA class
     } else {
         return EPARA_ERR_DTYPE;
     }
     *n_classes = n;
+    *n_stream_classes = ns;
     if (!classes) return EPARA_OK;
     if (cap < n) return EPARA_ERR_CAPACITY;
     std::memcpy(classes, table, sizeof(epara_tile_class) * n);

@@ -369,126 +369,165 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
 
 // ------------------------------------------------------------------ skinny tiles (weight streaming)
 
-// A batch of M <= 64 rows against two weight fragments per K step: 32 output columns, or (gated)
-// 16 hidden columns = one gate and one up column block.  Wave w takes the K steps ks = w, w+4, ...
-// and streams the packed weights straight from HBM into MFMA operand registers (each load
-// instruction of a wave reads 1 KiB of consecutive bytes); the four partial sums meet in LDS and
-// are added in wave order, so the result does not depend on timing.
+// Small batches are bandwidth bound: the weights are streamed from HBM exactly once, straight
+// into MFMA operand registers (each load instruction of a wave reads 1 KiB of consecutive packed
+// weights), while the activations are re-read from L2 by every tile.  To keep that re-read at
+// half the weight traffic, a tile of streaming class c = 0, 1, 2 pairs MB = 1, 2, 4 blocks of 16
+// rows (the whole batch) with NFR = 2, 4, 8 weight column blocks: 32 / 64 / 128 output columns,
+// or for gated groups NFR/2 gate blocks and the matching NFR/2 up blocks (16 / 32 / 64 hidden
+// columns).  K is walked in steps of two packed fragments (128 bytes of every activation row,
+// so a row's cache line is used whole); wave w takes the steps p = w, w+4, ....  The four
+// partial sums meet in LDS and are added in wave order: the result does not depend on timing.
 //
-// All skinny tiles a workgroup owns are processed as one software-pipelined stream: a ring of U
-// register slots per wave is kept full across tile boundaries, so the loads of the next tile
-// are already in flight while this tile is reduced and stored.  Every tile is padded to a whole
-// number of U steps; padding steps and rows past the batch re-load a valid address and are
-// not multiplied / not stored.
+// Consecutive tiles of one class that a workgroup owns are processed as one software-pipelined
+// stream: a ring of U register slots per wave stays full across tile boundaries, so the loads
+// of the next tile are in flight while this tile is reduced and stored.  Every tile is padded
+// to a whole number of U steps; padding steps, rows past the batch and column blocks past N
+// re-load a valid address and are not multiplied / not stored.  The scheduling barriers keep
+// the compiler from sinking the prefetch loads down to their first use.
+template <int NFR>
 struct skinny_tile_state {
-    gcptr w[2];            // weight fragment streams (step 0 of this wave), lane part included
-    gcptr x;               // activations of the group
-    uint32_t xrow[4];      // byte offset of my row in each 16-row block
-    int KS, K, n_chunks;   // fragments along K, chunks of U steps per wave
+    gcptr w[NFR];          // uniform: start of each weight column block's fragment stream
+    gcptr x;               // uniform: activations of the group
+    uint32_t xrow[4];      // per lane: byte offset of my row in each 16-row block (+ my k-chunk)
+    int KS, K;             // fragments along K, K
+    int n_chunks;          // chunks of U steps per wave
 };
 
-template <int DT, bool GATED, int U>
-__device__ __forceinline__ void skinny_setup(skinny_tile_state& st, const epara_group_args& ga, int n0, int wave, int lane)
-{
-    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
-    constexpr int KF = 4 * (16 / ESZ);
-    const int K = ga.K, N = ga.N;
-    const int KS = (K + KF - 1) / KF;
-    const int NB = (N + 15) >> 4;
-    const int r = lane & 15;
-    st.K = K;
-    st.KS = KS;
-    st.n_chunks = (((KS + 3) >> 2) + U - 1) / U;
-#pragma unroll
-    for (int f = 0; f < 2; ++f) {
-        const int nb = GATED ? (n0 >> 4) : min((n0 >> 4) + f, NB - 1);     // a block past N only feeds unstored columns
-        gcptr base = as_global<char>((GATED && f == 1) ? ga.W2 : ga.W);
-        st.w[f] = base + (static_cast<size_t>(nb) * KS * 64 + lane) * 16;
-    }
-    st.x = as_global<char>(ga.X);
-#pragma unroll
-    for (int fm = 0; fm < 4; ++fm)
-        st.xrow[fm] = static_cast<uint32_t>(min(fm * 16 + r, ga.M - 1)) * static_cast<uint32_t>(K * ESZ);
-}
-
-template <int DT>
-__device__ __forceinline__ void skinny_load(const skinny_tile_state& st, int i, int wave, int lane, v4i* wf, v4i* xf)
+template <int DT, bool GATED, int MB, int NFR, int U>
+__device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const epara_group_args& ga, int n0, int lane)
 {
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
-    const int ks = min(wave + 4 * i, st.KS - 1);                 // padding steps repeat the last fragment
-    const int xq = (lane >> 4) * EPC;
-    const uint32_t xo = static_cast<uint32_t>((ks * KF + ((ks * KF + xq < st.K) ? xq : 0)) * ESZ);   // ragged K: chunk 0 (weights are 0 there)
+    const int K = ga.K, N = ga.N;
+    const int KS = (K + KF - 1) / KF;
+    const int NB = (N + 15) >> 4;
+    st.K = K;
+    st.KS = KS;
+    const int steps = (KS + 1) >> 1;                             // two fragments per step
+    st.n_chunks = (((steps + 3) >> 2) + U - 1) / U;
 #pragma unroll
-    for (int f = 0; f < 2; ++f) wf[f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024);
+    for (int f = 0; f < NFR; ++f) {
+        // gated: fragments 0 .. NFR/2-1 are gate blocks, the rest the same blocks of the up matrix
+        const int rel = GATED ? (f % (NFR / 2)) : f;
+        const int nb = min((n0 >> 4) + rel, NB - 1);             // a block past N only feeds unstored columns
+        gcptr base = as_global<char>((GATED && f >= NFR / 2) ? ga.W2 : ga.W);
+        st.w[f] = base + static_cast<size_t>(nb) * KS * 1024;
+    }
+    st.x = as_global<char>(ga.X);
+    const int r = lane & 15, q = lane >> 4;
 #pragma unroll
-    for (int fm = 0; fm < 4; ++fm) xf[fm] = ld16(st.x + (st.xrow[fm] + xo));
+    for (int fm = 0; fm < MB; ++fm)
+        st.xrow[fm] = static_cast<uint32_t>(min(fm * 16 + r, ga.M - 1)) * static_cast<uint32_t>(K * ESZ) + q * 16;
 }
 
-template <int DT, bool GATED>
-__device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int out_dtype, int n0, int cols,
-                                              v4f (&acc)[2][4], int wave, int lane, char* lds)
+// One ring slot: fragments ks = 2p and 2p+1 of NFR column blocks and of MB row blocks.
+template <int MB, int NFR>
+struct skinny_slot { v4i w[2][NFR]; v4i x[2][MB]; };
+
+template <int DT, int MB, int NFR>
+__device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, int i, int wave, int lane, skinny_slot<MB, NFR>& sl)
 {
-    const int r = lane & 15, q = lane >> 4;
-    v4f* red = reinterpret_cast<v4f*>(lds);                      // red[wave][f*4+fm][lane]
-    __syncthreads();                                             // the previous tile's sums have been read
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const uint32_t lane16 = lane * 16;
+    const int xq = (lane >> 4) * EPC;
 #pragma unroll
-    for (int f = 0; f < 2; ++f)
+    for (int e = 0; e < 2; ++e) {
+        const int ks = min(2 * (wave + 4 * i) + e, st.KS - 1);   // padding repeats the last fragment
 #pragma unroll
-        for (int fm = 0; fm < 4; ++fm) red[(wave * 8 + f * 4 + fm) * 64 + lane] = acc[f][fm];
-    __syncthreads();
-    const bool vec_ok = (ga.N & 3) == 0;
-    const int M = ga.M;
-    if constexpr (GATED) {                                       // unit = row block `wave`: gate fragment 0, up fragment 1
-        const int fm = wave;
-        if (fm * 16 < M) {
-            v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+        for (int f = 0; f < NFR; ++f) sl.w[e][f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024 + lane16);
+        // ragged K: a chunk past K falls back to chunk 0 of the fragment (the packed weights are 0 there)
+        const uint32_t back = (ks * KF + xq < st.K) ? 0u : static_cast<uint32_t>((lane >> 4) * 16);
+        gcptr xk = st.x + static_cast<size_t>(ks) * 64;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) { g += red[(w * 8 + fm) * 64 + lane]; u += red[(w * 8 + 4 + fm) * 64 + lane]; }
-            finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, 4 * q, cols, vec_ok);
-        }
-    } else {                                                     // units (column block, row block): two per wave
+        for (int fm = 0; fm < MB; ++fm) sl.x[e][fm] = ld16(xk + (st.xrow[fm] - back));
+    }
+}
+
+template <int DT, int MB, int NFR>
+__device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int i, int wave, const skinny_slot<MB, NFR>& sl,
+                                           v4f (&acc)[NFR][MB])
+{
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int unit = wave * 2 + j, cb = unit >> 2, fm = unit & 3;
-            if (fm * 16 < M && cb * 16 < cols) {
-                v4f s0 = {0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < 2; ++e) {
+        if (2 * (wave + 4 * i) + e < st.KS) {
 #pragma unroll
-                for (int w = 0; w < 4; ++w) s0 += red[(w * 8 + cb * 4 + fm) * 64 + lane];
-                with_act(ga.act, [&](auto tag) {
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, cb * 16 + 4 * q, cols, vec_ok);
-                });
-            }
+            for (int f = 0; f < NFR; ++f)
+#pragma unroll
+                for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], sl.w[e][f], sl.x[e][fm]);
         }
     }
 }
 
-// Processes slot `slot` and every following slot of this workgroup that holds a skinny tile.
-// Returns the first slot it did not process.
-template <int DT, bool GATED>
+template <int DT, bool GATED, int MB, int NFR>
+__device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int out_dtype, int n0, int cols,
+                                              v4f (&acc)[NFR][MB], int wave, int lane, char* lds)
+{
+    const int r = lane & 15, q = lane >> 4;
+    v4f* red = reinterpret_cast<v4f*>(lds);                      // red[wave][f][fm][lane]: up to 4*8*4 KiB
+    __syncthreads();                                             // the previous tile's sums have been read
+#pragma unroll
+    for (int f = 0; f < NFR; ++f)
+#pragma unroll
+        for (int fm = 0; fm < MB; ++fm) red[((wave * NFR + f) * MB + fm) * 64 + lane] = acc[f][fm];
+    __syncthreads();
+    const bool vec_ok = (ga.N & 3) == 0;
+    const int M = ga.M;
+    if constexpr (GATED) {                                       // units (hidden column block p, row block fm)
+        constexpr int UNITS = (NFR / 2) * MB;
+        for (int unit = wave; unit < UNITS; unit += 4) {
+            const int p = unit / MB, fm = unit % MB;
+            if (fm * 16 >= M || p * 16 >= cols) continue;
+            v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                g += red[((w * NFR + p) * MB + fm) * 64 + lane];
+                u += red[((w * NFR + NFR / 2 + p) * MB + fm) * 64 + lane];
+            }
+            finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
+        }
+    } else {                                                     // units (column block f, row block fm)
+        constexpr int UNITS = NFR * MB;
+        with_act(ga.act, [&](auto tag) {
+            for (int unit = wave; unit < UNITS; unit += 4) {
+                const int f = unit / MB, fm = unit % MB;
+                if (fm * 16 >= M || f * 16 >= cols) continue;
+                v4f s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < 4; ++w) s0 += red[((w * NFR + f) * MB + fm) * 64 + lane];
+                finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
+            }
+        });
+    }
+}
+
+// Processes slot `slot` and every following slot of this workgroup that holds a tile of the same
+// streaming class.  Returns the first slot it did not process.
+template <int DT, bool GATED, int CLS, int MB, int NFR, int U>
 __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
                                            const int32_t* __restrict__ order, long slot, long n_slots, long stride,
                                            int out_dtype, char* lds)
 {
-    constexpr int U = 4;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    auto next_tile = [&](long s) {          // next slot of this workgroup holding a skinny tile, else -1
+    auto next_tile = [&](long s) {          // next slot of this workgroup holding a tile of this class, else -1
         for (s += stride; s < n_slots; s += stride) {
             const int t = order[s];
             if (t < 0) continue;
-            return tiles[t].cls == 0 ? s : -1L;
+            return tiles[t].cls == CLS ? s : -1L;
         }
         return -1L;
     };
 
     epara_tile tl = tiles[order[slot]];
     epara_group_args ga = args[tl.group];
-    skinny_tile_state cur, nxt;
-    skinny_setup<DT, GATED, U>(cur, ga, tl.n0, wave, lane);
-    v4i wf[U][2], xf[U][4];
+    skinny_tile_state<NFR> cur, nxt;
+    skinny_setup<DT, GATED, MB, NFR, U>(cur, ga, tl.n0, lane);
+    skinny_slot<MB, NFR> ring[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) skinny_load<DT>(cur, u, wave, lane, wf[u], xf[u]);
+    for (int u = 0; u < U; ++u) skinny_load<DT, MB, NFR>(cur, u, wave, lane, ring[u]);
+    __builtin_amdgcn_sched_barrier(0);
 
     for (;;) {
         const long slot_next = next_tile(slot);
@@ -497,68 +536,83 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         if (slot_next >= 0) {
             tl_next = tiles[order[slot_next]];
             ga_next = args[tl_next.group];
-            skinny_setup<DT, GATED, U>(nxt, ga_next, tl_next.n0, wave, lane);
+            skinny_setup<DT, GATED, MB, NFR, U>(nxt, ga_next, tl_next.n0, lane);
         } else {
             nxt = cur;                                           // nothing follows: the ring is refilled with valid, unused data
         }
-        v4f acc[2][4];
+        v4f acc[NFR][MB];
 #pragma unroll
-        for (int f = 0; f < 2; ++f)
+        for (int f = 0; f < NFR; ++f)
 #pragma unroll
-            for (int fm = 0; fm < 4; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
-        const int n_valid = cur.KS > wave ? (cur.KS - wave + 3) >> 2 : 0;
-        for (int c = 0; c < cur.n_chunks; ++c) {
-            const bool last = c + 1 == cur.n_chunks;
+            for (int fm = 0; fm < MB; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c + 1 < cur.n_chunks; ++c) {             // refill from this tile
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int i = c * U + u;
-                if (i < n_valid) {
-#pragma unroll
-                    for (int f = 0; f < 2; ++f)
-#pragma unroll
-                        for (int fm = 0; fm < 4; ++fm) mma<DT>(acc[f][fm], wf[u][f], xf[u][fm]);
-                }
-                if (last) skinny_load<DT>(nxt, u, wave, lane, wf[u], xf[u]);
-                else      skinny_load<DT>(cur, i + U, wave, lane, wf[u], xf[u]);
+                skinny_mma<DT, MB, NFR>(cur, c * U + u, wave, ring[u], acc);
+                __builtin_amdgcn_sched_barrier(0);
+                skinny_load<DT, MB, NFR>(cur, (c + 1) * U + u, wave, lane, ring[u]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        skinny_finish<DT, GATED>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
+        {
+            const int c = cur.n_chunks - 1;                      // last chunk: refill from the next tile
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                skinny_mma<DT, MB, NFR>(cur, c * U + u, wave, ring[u], acc);
+                __builtin_amdgcn_sched_barrier(0);
+                skinny_load<DT, MB, NFR>(nxt, u, wave, lane, ring[u]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        skinny_finish<DT, GATED, MB, NFR>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
         if (slot_next < 0) break;
         slot = slot_next;
         tl = tl_next;
         ga = ga_next;
         cur = nxt;
     }
-    // first slot after this run: the next non-idle slot of this workgroup (a big tile) or the end
+    // first slot after this run: the next non-idle slot of this workgroup or the end
     for (slot += stride; slot < n_slots && order[slot] < 0; slot += stride) {}
     return slot;
 }
 
 // ------------------------------------------------------------------ persistent kernels
 
-template <int DT>
-__global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
-                                                     const epara_tile* __restrict__ tiles,
-                                                     const int32_t* __restrict__ order,
-                                                     long n_slots, int out_dtype, int gated)
+constexpr int N_STREAM_CLASSES = 3;
+
+// Streaming classes: (row blocks, weight column blocks, ring depth) = (1, 2, 4), (2, 4, 3) and
+// (4, 8, 2) or, in a launch planned with the narrow table, (4, 4, 3).
+template <int DT, bool GATED>
+__device__ __forceinline__ void grouped_body(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
+                                             const int32_t* __restrict__ order, long n_slots, int out_dtype, int narrow, char* lds)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
     const long stride = gridDim.x;
     long s = blockIdx.x;
     while (s < n_slots) {
         const int t = order[s];
         if (t < 0) { s += stride; continue; }
         const epara_tile tl = tiles[t];
-        if (tl.cls == 0) {
-            s = gated ? skinny_run<DT, true>(args, tiles, order, s, n_slots, stride, out_dtype, lds)
-                      : skinny_run<DT, false>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
-        } else {
+        if (tl.cls == 0)      s = skinny_run<DT, GATED, 0, 1, 2, 4>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
+        else if (tl.cls == 1) s = skinny_run<DT, GATED, 1, 2, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
+        else if (tl.cls == 2 && !narrow) s = skinny_run<DT, GATED, 2, 4, 8, 2>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
+        else if (tl.cls == 2) s = skinny_run<DT, GATED, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
+        else {
             const epara_group_args ga = args[tl.group];
-            if (gated) big_tile<DT, true>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
-            else       big_tile<DT, false>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+            big_tile<DT, GATED>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
             s += stride;
         }
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
+                                                     const epara_tile* __restrict__ tiles,
+                                                     const int32_t* __restrict__ order,
+                                                     long n_slots, int out_dtype, int gated, int narrow)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    if (gated) grouped_body<DT, true>(args, tiles, order, n_slots, out_dtype, narrow, lds);
+    else       grouped_body<DT, false>(args, tiles, order, n_slots, out_dtype, narrow, lds);
 }
 
 // fp32 groups: 64x64 tiles, plain FMA in fp32, K ascending.
@@ -666,7 +720,31 @@ __global__ void pack_kernel(const char* __restrict__ W, int K, int N, char* __re
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dtype)
+// Every tile must be exactly what epara_plan_groups produces from one of the kernel class tables.
+int32_t check_tiles(const epara_launch* L, int32_t in_dtype, int narrow)
+{
+    const bool f32 = in_dtype == EPARA_F32;
+    epara_tile_class cls[2][4];
+    int32_t ncls[2] = {0, 0}, nstream = 0;
+    epara_kernel_classes(in_dtype, 0, narrow, cls[0], 4, &ncls[0], &nstream);
+    if (!f32) epara_kernel_classes(in_dtype, 1, narrow, cls[1], 4, &ncls[1], &nstream);
+    for (int64_t t = 0; t < L->n_tiles; ++t) {
+        const epara_tile& tl = L->h_tiles[t];
+        if (tl.group < 0 || tl.group >= L->G) return EPARA_ERR_SHAPE;
+        const epara_group_args& a = L->h_args[tl.group];
+        const int gated = a.act == EPARA_ACT_SWIGLU ? 1 : 0;
+        if (tl.cls < 0 || tl.cls >= ncls[gated]) return EPARA_ERR_SHAPE;
+        const epara_tile_class& c = cls[gated][tl.cls];
+        if (a.M > c.max_M || (tl.cls > 0 && a.M <= cls[gated][tl.cls - 1].max_M)) return EPARA_ERR_SHAPE;
+        if (tl.m0 < 0 || tl.n0 < 0 || tl.m0 >= a.M || tl.n0 >= a.N || tl.m0 % c.BM || tl.n0 % c.BN) return EPARA_ERR_SHAPE;
+        const int32_t rows = a.M - tl.m0 < c.BM ? a.M - tl.m0 : c.BM;
+        const int32_t cols = a.N - tl.n0 < c.BN ? a.N - tl.n0 : c.BN;
+        if (tl.rows != rows || tl.cols != cols) return EPARA_ERR_SHAPE;
+    }
+    return EPARA_OK;
+}
+
+int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, int* narrow_out = nullptr)
 {
     if (!L) return EPARA_ERR_NULL;
     const bool f32 = in_dtype == EPARA_F32;
@@ -698,27 +776,15 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
             if (L->h_args[g].M > 0) { ++n_live; n_gated += L->h_args[g].act == EPARA_ACT_SWIGLU; }
         if (n_gated != 0 && n_gated != n_live) return EPARA_ERR_DTYPE;
     }
-    epara_tile_class cls[2][2];
-    int32_t ncls[2] = {0, 0};
-    epara_kernel_classes(in_dtype, 0, cls[0], 2, &ncls[0]);
-    if (!f32) epara_kernel_classes(in_dtype, 1, cls[1], 2, &ncls[1]);
-    for (int64_t t = 0; t < L->n_tiles; ++t) {
-        const epara_tile& tl = L->h_tiles[t];
-        if (tl.group < 0 || tl.group >= L->G) return EPARA_ERR_SHAPE;
-        const epara_group_args& a = L->h_args[tl.group];
-        const int gated = a.act == EPARA_ACT_SWIGLU ? 1 : 0;
-        if (tl.cls < 0 || tl.cls >= ncls[gated]) return EPARA_ERR_SHAPE;
-        const epara_tile_class& c = cls[gated][tl.cls];
-        if (a.M > c.max_M || (tl.cls > 0 && a.M <= cls[gated][tl.cls - 1].max_M)) return EPARA_ERR_SHAPE;
-        if (tl.m0 < 0 || tl.n0 < 0 || tl.m0 >= a.M || tl.n0 >= a.N || tl.m0 % c.BM || tl.n0 % c.BN) return EPARA_ERR_SHAPE;
-        const int32_t rows = a.M - tl.m0 < c.BM ? a.M - tl.m0 : c.BM;
-        const int32_t cols = a.N - tl.n0 < c.BN ? a.N - tl.n0 : c.BN;
-        if (tl.rows != rows || tl.cols != cols) return EPARA_ERR_SHAPE;
+    int32_t last = EPARA_OK;
+    for (int narrow = 0; narrow < (f32 ? 1 : 2); ++narrow) {
+        last = check_tiles(L, in_dtype, narrow);
+        if (last == EPARA_OK) { if (narrow_out) *narrow_out = narrow; return EPARA_OK; }
     }
-    return EPARA_OK;
+    return last;
 }
 
-int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, hipStream_t stream)
+int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, int narrow, hipStream_t stream)
 {
     if (L->n_tiles == 0) return EPARA_OK;
     int gated = 0;
@@ -734,13 +800,13 @@ int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, hipS
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (attr != hipSuccess) return EPARA_ERR_HIP;
         hipLaunchKernelGGL(grouped_kernel<EPARA_BF16>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
-                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated);
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated, narrow);
     } else {
         static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<EPARA_FP8_E4M3>),
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (attr != hipSuccess) return EPARA_ERR_HIP;
         hipLaunchKernelGGL(grouped_kernel<EPARA_FP8_E4M3>, grid, dim3(NT), LDS_BYTES, stream, L->d_args, L->d_tiles,
-                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated);
+                           L->d_order, static_cast<long>(L->n_slots), out_dtype, gated, narrow);
     }
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
@@ -787,8 +853,9 @@ int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
 
 int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int32_t out_dtype, void* stream)
 {
-    if (int32_t st = validate_launch(launch, in_dtype, out_dtype)) return st;
-    return enqueue(launch, in_dtype, out_dtype, static_cast<hipStream_t>(stream));
+    int narrow = 0;
+    if (int32_t st = validate_launch(launch, in_dtype, out_dtype, &narrow)) return st;
+    return enqueue(launch, in_dtype, out_dtype, narrow, static_cast<hipStream_t>(stream));
 }
 
 int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
@@ -798,8 +865,9 @@ int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* dow
     if (in_dtype == EPARA_BF16) { if (h_dtype != EPARA_BF16 || out_dtype != EPARA_BF16) return EPARA_ERR_DTYPE; }
     else if (in_dtype == EPARA_FP8_E4M3) { if (h_dtype != EPARA_FP8_E4M3 || out_dtype != EPARA_BF16) return EPARA_ERR_DTYPE; }
     else return EPARA_ERR_DTYPE;
-    if (int32_t st = validate_launch(up, in_dtype, h_dtype)) return st;
-    if (int32_t st = validate_launch(down, in_dtype, out_dtype)) return st;
+    int narrow_up = 0, narrow_down = 0;
+    if (int32_t st = validate_launch(up, in_dtype, h_dtype, &narrow_up)) return st;
+    if (int32_t st = validate_launch(down, in_dtype, out_dtype, &narrow_down)) return st;
     if (up->G != down->G) return EPARA_ERR_SHAPE;
     if (up->n_tiles > 0 || down->n_tiles > 0) {
         for (int32_t g = 0; g < up->G; ++g) {
@@ -810,8 +878,8 @@ int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* dow
         }
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (int32_t rc = enqueue(up, in_dtype, h_dtype, st)) return rc;
-    return enqueue(down, in_dtype, out_dtype, st);
+    if (int32_t rc = enqueue(up, in_dtype, h_dtype, narrow_up, st)) return rc;
+    return enqueue(down, in_dtype, out_dtype, narrow_down, st);
 }
 
 }  // extern "C"

@@ -62,6 +62,18 @@ def group_args(X, W, Y, M, K, N, act, bias=None, W2=None, scale=1.0, scale2=1.0,
     return a
 
 
+def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
+    """Largest per-workgroup cost of a schedule, in the units epara_schedule_tiles balances with."""
+    if len(tiles) == 0:
+        return 0
+    g = groups[tiles["group"]]
+    stream = tiles["cls"] < n_stream
+    units = tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
+    cost = np.where(stream, units, 340) * g["K"].astype(np.int64)
+    per_slot = np.where(order >= 0, cost[np.maximum(order, 0)], 0).reshape(-1, n_workgroups)
+    return int(per_slot.sum(axis=0).max())
+
+
 class LaunchPlan:
     """Host plan + its device copy for one grouped launch (epara_launch)."""
 
@@ -78,13 +90,22 @@ class LaunchPlan:
         for f in ("M", "K", "N", "act"):
             self.groups[f] = self.args[f]
         self.groups["has_bias"] = (self.args["bias"] != 0).astype(np.int32)
-        self.classes = B.epara_kernel_classes(in_dtype, gated)
-        self.row_off, self.x_off, self.y_off, self.tiles = B.epara_plan_groups(self.groups, self.classes)
         if n_workgroups is None:
             n_workgroups = n_compute_units(device)
             n_workgroups -= n_workgroups % n_xcd
         self.n_workgroups = n_workgroups
-        self.order = B.epara_schedule_tiles(self.groups, self.classes, self.tiles, n_workgroups, n_xcd, panel_m, panel_n)
+        # two class tables exist for small batches (wide / narrow tiles): keep the one whose
+        # schedule finishes first under the scheduler's own cost model
+        best = None
+        for narrow in ((False, True) if (in_dtype != B.EPARA_F32 and G and int(self.groups["M"].max()) > 32) else (False,)):
+            classes, n_stream = B.epara_kernel_classes(in_dtype, gated, narrow)
+            row_off, x_off, y_off, tiles = B.epara_plan_groups(self.groups, classes)
+            order = B.epara_schedule_tiles(self.groups, classes, n_stream, tiles, n_workgroups, n_xcd, panel_m, panel_n)
+            span = _makespan(self.groups, classes, n_stream, tiles, order, n_workgroups)
+            if best is None or span < best[0]:
+                best = (span, narrow, classes, n_stream, row_off, x_off, y_off, tiles, order)
+        (self.makespan, self.narrow, self.classes, self.n_stream_classes, self.row_off, self.x_off, self.y_off,
+         self.tiles, self.order) = best
         self.plan_seconds = time.perf_counter() - t0
         t0 = time.perf_counter()
         self.d_args = _upload(self.args, device)

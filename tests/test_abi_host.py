@@ -29,10 +29,10 @@ def test_struct_sizes_match_header_layout():
     assert ctypes.sizeof(B.Launch) == 64
 
 
-def _desc(groups):
+def _desc(groups, act=0):
     g = np.zeros(len(groups), dtype=B.GROUP_DESC)
     for i, (M, K, N) in enumerate(groups):
-        g[i]["M"], g[i]["K"], g[i]["N"] = M, K, N
+        g[i]["M"], g[i]["K"], g[i]["N"], g[i]["act"] = M, K, N, act
     return g
 
 
@@ -63,21 +63,26 @@ ADVERSARIAL = [
     [(0, 8, 8), (3, 8, 8), (0, 8, 8)], [(0, 8, 8)], [],
     [(63, 40, 31), (513, 24, 1)], [(1000, 64, 1000), (7, 2048, 77), (300, 128, 300), (64, 512, 64)],
 ]
-CLASS_TABLES = [[(64, 64, 32), (P.INT32_MAX, 256, 256)], [(64, 64, 32), (P.INT32_MAX, 256, 128)],
-                [(P.INT32_MAX, 64, 64)], [(16, 16, 64), (64, 64, 64), (512, 128, 128), (P.INT32_MAX, 256, 256)]]
+# (class table, number of leading weight-streaming classes)
+CLASS_TABLES = [([(64, 64, 32), (P.INT32_MAX, 256, 256)], 1), ([(64, 64, 32), (P.INT32_MAX, 256, 128)], 0),
+                ([(P.INT32_MAX, 64, 64)], 0), ([(16, 16, 64), (64, 64, 64), (512, 128, 128), (P.INT32_MAX, 256, 256)], 2),
+                ([(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)], 3),
+                ([(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], 4)]
 
 
 @pytest.mark.parametrize("groups", mix_group_shapes() + ADVERSARIAL)
-@pytest.mark.parametrize("classes", CLASS_TABLES)
-def test_planner_and_scheduler_match_reference_bit_for_bit(groups, classes):
+@pytest.mark.parametrize("table", CLASS_TABLES)
+def test_planner_and_scheduler_match_reference_bit_for_bit(groups, table):
+    classes, n_stream = table
     row_off, x_off, y_off, tiles = P.plan_groups(groups, classes)
     r2, x2, y2, t2 = B.epara_plan_groups(_desc(groups), _classes(classes))
     assert r2.tolist() == row_off and x2.tolist() == x_off and y2.tolist() == y_off
     assert [tuple(int(v) for v in t) for t in t2] == tiles
     for W, X, pm, pn in ((256, 8, 8, 4), (8, 8, 2, 2), (48, 4, 3, 5), (1, 1, 1, 1)):
-        order = P.schedule_tiles(groups, classes, tiles, W, X, pm, pn)
-        o2 = B.epara_schedule_tiles(_desc(groups), _classes(classes), t2, W, X, pm, pn)
-        assert o2.tolist() == order
+        for gated in (False, True):
+            order = P.schedule_tiles([g + (gated,) for g in groups], classes, n_stream, tiles, W, X, pm, pn)
+            o2 = B.epara_schedule_tiles(_desc(groups, 5 if gated else 0), _classes(classes), n_stream, t2, W, X, pm, pn)
+            assert o2.tolist() == order
 
 
 def test_mix_structures_are_the_seeded_draws():
@@ -99,7 +104,7 @@ def status_of(fn, *a):
 
 
 def test_planner_error_codes():
-    cl = _classes(CLASS_TABLES[0])
+    cl = _classes(CLASS_TABLES[0][0])
     assert status_of(B.epara_plan_groups, _desc([(1, 0, 4)]), cl) == B.EPARA_ERR_SHAPE
     assert status_of(B.epara_plan_groups, _desc([(-1, 4, 4)]), cl) == B.EPARA_ERR_SHAPE
     assert status_of(B.epara_plan_groups, _desc([(1, 4, 0)]), cl) == B.EPARA_ERR_SHAPE
@@ -119,11 +124,13 @@ def test_planner_error_codes():
     assert L.epara_plan_groups(None, 0, cl.ctypes.data, 2, None, None, None, None, 0, n.ctypes.data) == B.EPARA_OK and n[0] == 0
     # scheduler: grid must be a positive multiple of the die count
     _, _, _, t = B.epara_plan_groups(g, cl)
-    assert status_of(B.epara_schedule_tiles, g, cl, t, 12, 8) == B.EPARA_ERR_SHAPE
-    assert status_of(B.epara_schedule_tiles, g, cl, t, 0, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, 1, t, 12, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, 1, t, 0, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, 3, t, 8, 8) == B.EPARA_ERR_SHAPE     # more streaming classes than classes
+    assert status_of(B.epara_schedule_tiles, g, cl, -1, t, 8, 8) == B.EPARA_ERR_SHAPE
     bad = t.copy(); bad[1]["group"] = 5
-    assert status_of(B.epara_schedule_tiles, g, cl, bad, 8, 8) == B.EPARA_ERR_SHAPE
-    assert status_of(B.epara_schedule_tiles, g, cl, t[:3], 8, 8) == B.EPARA_ERR_SHAPE   # not a whole table
+    assert status_of(B.epara_schedule_tiles, g, cl, 1, bad, 8, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_schedule_tiles, g, cl, 1, t[:3], 8, 8) == B.EPARA_ERR_SHAPE   # not a whole table
 
 
 def test_batch_accounting_and_paper_numbers():
@@ -147,11 +154,14 @@ def test_batch_accounting_and_paper_numbers():
 
 
 def test_kernel_classes_and_packed_sizes():
-    c = B.epara_kernel_classes(B.EPARA_BF16, 0)
-    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 32), (P.INT32_MAX, 256, 256)]
-    c = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
-    assert [tuple(int(v) for v in x) for x in c] == [(64, 64, 16), (P.INT32_MAX, 256, 128)]
-    assert [tuple(int(v) for v in x) for x in B.epara_kernel_classes(B.EPARA_F32, 0)] == [(P.INT32_MAX, 64, 64)]
+    c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0)
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)] and ns == 3
+    c, ns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)] and ns == 3
+    c, ns = B.epara_kernel_classes(B.EPARA_F32, 0)
+    assert [tuple(int(v) for v in x) for x in c] == [(P.INT32_MAX, 64, 64)] and ns == 0
+    c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0, narrow=True)
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)] and ns == 3
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
     assert B.epara_packed_weight_bytes(4096, 11008, B.EPARA_BF16) == 4096 * 11008 * 2
@@ -197,7 +207,7 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
         def data_ptr(self): return self.p
     mk = lambda **kw: np.array([group_args(T(0x10000), T(0x20000), T(0x30000), kw.pop("M", 100), kw.pop("K", 64), kw.pop("N", 300),
                                            kw.pop("act", "none"), **kw)], dtype=B.GROUP_ARGS)
-    cl = B.epara_kernel_classes(B.EPARA_BF16, 0)
+    cl, _ = B.epara_kernel_classes(B.EPARA_BF16, 0)
 
     def plan(a):
         g = np.zeros(1, dtype=B.GROUP_DESC)
@@ -231,7 +241,7 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
     assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
     bad = t.copy(); bad[1]["n0"] = 250
     assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
-    bad = t.copy(); bad[0]["cls"] = 0                                            # 100 rows do not fit the skinny class
+    bad = t.copy(); bad[0]["cls"] = 2                                            # 100 rows do not fit a streaming class
     assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
     bad = t.copy(); bad[0]["group"] = 3
     assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE

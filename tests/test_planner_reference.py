@@ -78,13 +78,45 @@ def test_closed_form_counts_decode_and_prefill():
 def test_schedule_is_a_permutation_with_idle_padding(W, X):
     groups = [(700, 64, 900), (3, 128, 100), (300, 256, 300), (64, 32, 64)]
     _, _, _, tiles = P.plan_groups(groups, CLASSES)
-    order = P.schedule_tiles(groups, CLASSES, tiles, W, X, 8, 4)
-    assert len(order) % W == 0 and len(order) - len(tiles) < W
+    order = P.schedule_tiles(groups, CLASSES, 1, tiles, W, X, 8, 4)
+    assert len(order) % W == 0
     used = [t for t in order if t >= 0]
     assert sorted(used) == list(range(len(tiles)))
-    # big-tile classes come first in slot rounds, and within them the larger K
-    first_round = [tiles[t] for t in order[:W] if t >= 0]
-    assert all(t[5] == 1 for t in first_round) or len(tiles) < W
+    # a workgroup's list has no holes, and its panel tiles come before its streaming tiles
+    for b in range(W):
+        mine = order[b::W]
+        live = [t for t in mine if t >= 0]
+        assert mine[:len(live)] == live
+        kinds = [tiles[t][5] for t in live]
+        assert kinds == sorted(kinds, reverse=True)
+
+
+def test_streaming_tiles_are_balanced_longest_first():
+    # decode-like launch: three streaming classes, every tile of a group costs cols * K
+    classes = [(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)]
+    groups = [(1, 11008, 4096), (8, 11008, 4096), (32, 11008, 4096), (64, 11008, 4096)]
+    _, _, _, tiles = P.plan_groups(groups, classes)
+    assert len(tiles) == 128 + 128 + 64 + 32
+    W = 256
+    order = P.schedule_tiles(groups, classes, 3, tiles, W, 8, 8, 4)
+    cost = lambda t: 11008 * (tiles[t][4] + classes[tiles[t][5]][1])     # weight columns + activation rows
+    loads = [sum(cost(t) for t in order[b::W] if t >= 0) for b in range(W)]
+    total = sum(cost(t) for t in range(len(tiles)))
+    # greedy longest-first never exceeds the mean by more than one largest tile
+    assert max(loads) <= total / W + 11008 * (128 + 64)
+    assert max(loads) == 11008 * (128 + 64)                 # a wide tile is all its owner gets
+    # the widest tiles are visited first by whoever owns them
+    firsts = [tiles[order[b]][4] for b in range(W)]
+    assert sorted(firsts, reverse=True)[:32] == [128] * 32
+    # the narrow table halves the widest tiles and the makespan
+    narrow = classes[:2] + [(64, 64, 64)] + classes[3:]
+    _, _, _, t2 = P.plan_groups(groups, narrow)
+    o2 = P.schedule_tiles(groups, narrow, 3, t2, W, 8, 8, 4)
+    loads2 = [sum(11008 * (t2[t][4] + narrow[t2[t][5]][1]) for t in o2[b::W] if t >= 0) for b in range(W)]
+    assert max(loads2) <= 11008 * (64 + 64 + 32 + 16) and max(loads2) < max(loads)
+    # gated groups count twice
+    o2 = P.schedule_tiles([g + (True,) for g in groups], classes, 3, tiles, W, 8, 8, 4)
+    assert o2 == order                                      # a uniform factor changes nothing
 
 
 def test_schedule_keeps_a_die_on_one_panel():
@@ -92,7 +124,7 @@ def test_schedule_keeps_a_die_on_one_panel():
     # die (slots congruent mod 8 within a round of 256) are exactly one panel
     groups = [(16 * 256, 64, 16 * 256)]
     _, _, _, tiles = P.plan_groups(groups, CLASSES)
-    order = P.schedule_tiles(groups, CLASSES, tiles, 256, 8, 8, 4)
+    order = P.schedule_tiles(groups, CLASSES, 1, tiles, 256, 8, 8, 4)
     assert len(order) == 256
     for x in range(8):
         mine = [tiles[order[s]] for s in range(x, 256, 8)]
