@@ -32,7 +32,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int NT = 256;                 // threads per workgroup (4 waves, one per SIMD)
 constexpr int STAGE_BYTES = 32768;      // one pipeline stage: X 256 rows x 64 B + W 16 column blocks x 1 KiB
-constexpr int LDS_BYTES = 4 * STAGE_BYTES;
+constexpr int BIAS_LDS_OFFSET = 4 * STAGE_BYTES;   // 256 floats: the bias of a panel tile
+constexpr int LDS_BYTES = 4 * STAGE_BYTES + 1024;
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
 
 // ------------------------------------------------------------------ small device helpers
@@ -154,9 +155,12 @@ __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, 
     }
 }
 
-// Epilogue of one 16x16 accumulator fragment (plain groups): lane holds columns nl..nl+3 of row ml.
-template <int ACT>
-__device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out_dtype, const v4f& a,
+// Epilogue of one accumulator quad (plain groups): the lane holds columns nl..nl+3 of row ml.
+// `bias` points at the bias of column n0 (global memory for streaming tiles; panel tiles stage the
+// tile's 256 bias values in LDS first, because a global load inside the store loop would make
+// every iteration wait for all earlier stores: loads and stores share one in-order counter).
+template <int ACT, class BiasPtr>
+__device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out_dtype, const v4f& a, BiasPtr bias,
                                              int m0, int ml, int rows, int n0, int nl, int cols, bool vec_ok)
 {
     if (ml >= rows || nl >= cols) return;
@@ -165,7 +169,7 @@ __device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float b = 0.f;
-        if (ga.bias && i < valid) b = as_global<float>(ga.bias)[n0 + nl + i];
+        if (bias && i < valid) b = bias[nl + i];
         v[i] = act_apply<ACT>(ga.scale * a[i] + b) * ga.out_inv_scale;
     }
     store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, valid, vec_ok);
@@ -316,6 +320,9 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     __syncthreads();                       // and nobody still reads it
 #pragma unroll
     for (int s = 0; s < NS; ++s) issue(s);
+    typedef __attribute__((address_space(3))) float* lds_float;
+    lds_float bias_tile = (lds_float)(l3 + BIAS_LDS_OFFSET);
+    if (!GATED && ga.bias) bias_tile[tid] = n0 + tid < N ? as_global<float>(ga.bias)[n0 + tid] : 0.f;
     wait_vmcnt<DMA_PER_STAGE * (NS - 1)>();
     __builtin_amdgcn_s_barrier();
     read_frags(0, 0, 0);
@@ -336,34 +343,48 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
         interleave();
     }
     wait_vmcnt<0>();
+    __syncthreads();                       // every wave is done with the stage buffers
 
+    // Epilogue.  The 256 accumulators of a lane cannot be indexed at run time, and an unrolled
+    // epilogue for all of them is tens of thousands of instructions that miss the instruction cache
+    // once per tile.  So each wave parks its accumulators in its own 32 KiB of the (now idle) LDS,
+    // half at a time, and a compact loop finishes one quad (4 consecutive columns of one row) per
+    // iteration.  Quad (fi, fm, g) of a half: fragment fn = fi-th of the half, rows fm*32 + r32,
+    // columns 8g + 4h .. +3 of the fragment.
+    v4f* stash = reinterpret_cast<v4f*>(lds) + wave * 2048 + lane;
     const bool vec_ok = (N & 3) == 0;
-    // accumulator quad g of a 32x32 fragment: columns 8g + 4h .. +3 of the fragment, row r32
-    if constexpr (GATED) {
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn)
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int fi = 0; fi < 2; ++fi) {
+            const int fn = GATED ? half + 2 * fi : 2 * half + fi;       // gated: a gate fragment and its up partner
 #pragma unroll
             for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const v4f gate = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
-                    const v4f up = {acc[fn + 2][fm][4 * g], acc[fn + 2][fm][4 * g + 1], acc[fn + 2][fm][4 * g + 2], acc[fn + 2][fm][4 * g + 3]};
-                    finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + fm * 32 + r32, rows,
-                                 n0, wn * 64 + fn * 32 + 8 * g + 4 * h, cols, vec_ok);
+                for (int g = 0; g < 4; ++g)
+                    stash[((fi * 4 + fm) * 4 + g) * 64] =
+                        v4f{acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
+        }
+        if constexpr (GATED) {
+#pragma unroll 2
+            for (int it = 0; it < 16; ++it) {                            // it = fm*4 + g
+                const int fm = it >> 2, g = it & 3;
+                const v4f gate = stash[it * 64], up = stash[(16 + it) * 64];
+                finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + fm * 32 + r32, rows,
+                             n0, wn * 64 + half * 32 + 8 * g + 4 * h, cols, vec_ok);
+            }
+        } else {
+            with_act(ga.act, [&](auto tag) {
+#pragma unroll 2
+                for (int it = 0; it < 32; ++it) {                        // it = (fi*4 + fm)*4 + g
+                    const int fi = it >> 4, fm = (it >> 2) & 3, g = it & 3;
+                    const v4f a4 = stash[it * 64];
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, ga.bias ? bias_tile : (lds_float)nullptr, m0,
+                                                       wm * 128 + fm * 32 + r32, rows,
+                                                       n0, wn * 128 + (2 * half + fi) * 32 + 8 * g + 4 * h, cols, vec_ok);
                 }
-    } else {
-        with_act(ga.act, [&](auto tag) {
-#pragma unroll
-            for (int fn = 0; fn < 4; ++fn)
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const v4f a4 = {acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
-                        finish_plain<decltype(tag)::value>(ga, out_dtype, a4, m0, wm * 128 + fm * 32 + r32, rows,
-                                                           n0, wn * 128 + fn * 32 + 8 * g + 4 * h, cols, vec_ok);
-                    }
-        });
+            });
+        }
     }
 }
 
@@ -496,7 +517,8 @@ __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int ou
                 v4f s0 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int w = 0; w < 4; ++w) s0 += red[((w * NFR + f) * MB + fm) * 64 + lane];
-                finish_plain<decltype(tag)::value>(ga, out_dtype, s0, 0, fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
+                finish_plain<decltype(tag)::value>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
+                                                   fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
             }
         });
     }
