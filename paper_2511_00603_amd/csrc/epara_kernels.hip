@@ -31,9 +31,8 @@ typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int NT = 256;                 // threads per workgroup (4 waves, one per SIMD)
-constexpr int STAGE_BYTES = 32768;      // one pipeline stage: X 256 rows x 64 B + W 16 column blocks x 1 KiB
-constexpr int BIAS_LDS_OFFSET = 4 * STAGE_BYTES;   // 256 floats: the bias of a panel tile
-constexpr int LDS_BYTES = 4 * STAGE_BYTES + 1024;
+constexpr int BIAS_LDS_OFFSET = 131072;  // after the operand buffers: 256 floats, the bias of a panel tile
+constexpr int LDS_BYTES = BIAS_LDS_OFFSET + 1024;
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
 
 // ------------------------------------------------------------------ small device helpers
@@ -190,30 +189,34 @@ __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out
 
 // One 256 x 256 output tile (gated: 256 rows x 128 hidden columns, i.e. 128 gate + 128 up
 // weight columns).  K advances in stages of 64 bytes per row (one packed weight fragment per
-// column block); four stages of 32 KiB rotate through the LDS:
-//   [X: 256 rows x 64 B][W: 16 column blocks x 1 KiB]
-// and are filled by direct global->LDS loads (no staging registers) three stages ahead.
-//   X stage: 16-byte chunk c of row `row` is stored at chunk c ^ ((row/4)%4): the 16 rows that one
-//            quarter of a ds_read_b128 touches then fall into 16 different bank groups.  A direct
-//            load writes 1 KiB of consecutive LDS per wave instruction, so lane l fetches the
-//            global chunk that belongs at position l (row l/4 of the instruction's 16 rows).
-//   W stage: verbatim image of the packed fragments.
+// column block).  All operands reach the LDS by direct global->LDS loads (no staging registers):
+//   W: four stage buffers of 16 KiB (16 column blocks x 1 KiB, a verbatim image of the packed
+//      fragments), refilled four stages ahead;
+//   X: two buffers of 32 KiB, each holding TWO stages (256 rows x 128 B), refilled two stages
+//      ahead.  A load instruction then covers whole 128-byte lines (8 rows x 128 B per wave
+//      instruction); fetching 64-byte half lines costs a full line slot in the L1 each.
+//      16-byte chunk c of row `row` is stored at chunk c ^ ((row/2)%8), so the 16 rows that one
+//      quarter of a ds_read_b128 touches fall into 16 different bank groups; a direct load writes
+//      1 KiB of consecutive LDS, so lane l fetches the global chunk that belongs at position l.
 // Rows past the batch and column blocks past N are clamped to the last valid one (they only
 // feed outputs that are never stored).  In a ragged last stage the X chunks past K are clamped
-// to chunk 0: the packed weights are zero there, so the products vanish.  Stages past the end
-// of K re-load the last stage into a buffer nobody reads, which keeps the loop free of branches.
+// to chunk 0 of the buffer: the packed weights are zero there, so the products vanish.  Loads past
+// the end of K re-load the last data into buffers nobody reads, which keeps the loop free of
+// branches.
 //
 // A stage is two 32x32x16 steps.  Operand fragments are double-buffered in registers: the
 // reads of step s+1 are issued between the MFMAs of step s.  In the middle of stage kt every
 // wave waits for its own loads of stage kt+1, a workgroup barrier makes all parts visible (and
-// proves that every wave has finished reading stage kt), and the buffer of stage kt is refilled
-// with stage kt+NS.
+// proves that every wave has finished reading stage kt), and the freed buffers are refilled:
+// W stage kt+4 always, X stages kt+3 and kt+4 when kt is odd.  Loads complete in issue order, so
+// "my loads of stage kt+1 have landed" is a bound on the number of loads still in flight: 16
+// in an even stage (two W stages and an X pair were issued later), 4 in an odd one.
 typedef __attribute__((address_space(3))) char* ldsptr;
 typedef const __attribute__((address_space(3))) v4i* lds_v4i;
 
-constexpr int NS = 4;                    // pipeline stages
-constexpr int XSTAGE_BYTES = 16384;      // X part of a stage
-constexpr int DMA_PER_STAGE = 8;         // direct loads per wave per stage (4 X + 4 W)
+constexpr int XBUF_BYTES = 32768;        // one X buffer: 256 rows x 128 B = two stages
+constexpr int WBUF_BYTES = 16384;        // one W stage: 16 column blocks x 1 KiB
+constexpr int W_LDS_OFFSET = 2 * XBUF_BYTES;
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -236,51 +239,58 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     const int wn = wave & 1, wm = wave >> 1;
     const int K = ga.K, N = ga.N;
     const int KS = (K + KF - 1) / KF;
+    const int KD = (KS + 1) >> 1;                               // X stage pairs
     const int NB = (N + 15) >> 4;
     ldsptr l3 = (ldsptr)lds;
 
     // --- direct-load descriptors: this wave fills X rows [64 wave, 64 wave + 64) and W blocks 4 wave .. 4 wave + 3
-    const int xchunk = (lane & 3) ^ ((lane >> 4) & 3);
-    const int tail_k = K - (KS - 1) * KF;                       // elements in the last stage, 1..KF
-    const int xchunk_tail = (xchunk * EPC < tail_k) ? xchunk : 0;
     gcptr xbase = as_global<char>(ga.X) + static_cast<size_t>(m0) * K * ESZ;
     gcptr wbase = as_global<char>((GATED && wave >= 2) ? ga.W2 : ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
-    uint32_t xoff[4], xoff_tail[4], woff[4];
+    const int tail_k = K - (KD - 1) * 2 * KF;                   // elements in the last stage pair, 1..2KF
+    uint32_t xoff[8], xoff_tail[8], woff[4];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {                               // instruction j: rows 64 wave + 8 j .. + 7, lane -> (row l/8, slot l%8)
+        const int row_in_tile = 64 * wave + 8 * j + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((4 * (j & 1) + (lane >> 4)) & 7);      // = slot ^ ((row/2)%8)
+        const int chunk_tail = (chunk * EPC < tail_k) ? chunk : 0;
+        const int row = min(row_in_tile, rows - 1);
+        xoff[j] = static_cast<uint32_t>((row * K + chunk * EPC) * ESZ);
+        xoff_tail[j] = static_cast<uint32_t>((row * K + chunk_tail * EPC) * ESZ);
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const int row = min(64 * wave + 16 * j + (lane >> 2), rows - 1);
-        xoff[j] = static_cast<uint32_t>((row * K + xchunk * EPC) * ESZ);
-        xoff_tail[j] = static_cast<uint32_t>((row * K + xchunk_tail * EPC) * ESZ);
         const int nbrel = (GATED ? ((4 * wave) & 7) : 4 * wave) + j;
         const int nb = min(nbrel, NB - 1 - (n0 >> 4));
         woff[j] = static_cast<uint32_t>((nb * KS * 64 + lane) * 16);
     }
-    const int dma_lds = 4 * wave * 1024;                        // my first 1 KiB slot inside the X (or W) part
 
-    auto issue = [&](int kt_unclamped) {
-        const int buf = (kt_unclamped & (NS - 1)) * STAGE_BYTES;
-        const int kt = min(kt_unclamped, KS - 1);
-        gcptr xb = xbase + static_cast<size_t>(kt) * 64;
-        gcptr wb = wbase + static_cast<size_t>(kt) * 1024;
-        const bool tail = kt == KS - 1;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
-                                             (__attribute__((address_space(3))) void*)(l3 + buf + dma_lds + j * 1024), 16, 0, 0);
+    auto issue_w = [&](int kt_unclamped) {
+        const int buf = W_LDS_OFFSET + (kt_unclamped & 3) * WBUF_BYTES + 4 * wave * 1024;
+        gcptr wb = wbase + static_cast<size_t>(min(kt_unclamped, KS - 1)) * 1024;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
-                                             (__attribute__((address_space(3))) void*)(l3 + buf + XSTAGE_BYTES + dma_lds + j * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+    };
+    auto issue_x = [&](int kd_unclamped) {
+        const int buf = (kd_unclamped & 1) * XBUF_BYTES + 8 * wave * 1024;
+        const int kd = min(kd_unclamped, KD - 1);
+        gcptr xb = xbase + static_cast<size_t>(kd) * 128;
+        const bool tail = kd == KD - 1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
+                                             (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
     };
 
-    // --- fragment read offsets inside a stage, for step s = 0, 1 (k-chunk 2s + h)
+    // --- fragment read offsets
+    //   X fragment fm of step s16 = 0..3 of a stage pair: rows wm*128 + fm*32 + r32, chunk 2 s16 + h
     //   W fragment fn = column blocks (2 fn, 2 fn + 1) of the wave's eight: lane r32 -> block r32/16, column r32%16
-    //   X fragment fm = rows wm*128 + fm*32 + r32
-    const int sw = (r32 >> 2) & 3;
-    int xf_off[2];
+    const int sw = (r32 >> 1) & 7;
+    int xf_off[4];
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2) xf_off[s2] = (wm * 128 + r32) * 64 + ((((2 * s2 + h) ^ sw)) << 4);      // + fm * 2048
-    const int wf_off = XSTAGE_BYTES + ((GATED ? wn * 4 : wn * 8) + (r32 >> 4)) * 1024 + (h * 16 + (r32 & 15)) * 16;   // + blk*1024 + s*512
+    for (int s16 = 0; s16 < 4; ++s16) xf_off[s16] = (wm * 128 + r32) * 128 + (((2 * s16 + h) ^ sw) << 4);   // + fm * 4096
+    const int wf_off = W_LDS_OFFSET + ((GATED ? wn * 4 : wn * 8) + (r32 >> 4)) * 1024 + (h * 16 + (r32 & 15)) * 16;   // + blk*1024 + s*512
 
     v16f acc[4][4];
 #pragma unroll
@@ -291,16 +301,18 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
             for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0.f;
 
     v4i wf[2][4], xf[2][4];
-    auto read_frags = [&](int kt, int s2, int set) {
-        const int buf = (kt & (NS - 1)) * STAGE_BYTES;
+    // kt_par = kt & 1 must be a compile-time value: it selects the X offsets
+    auto read_frags = [&](int kt, int kt_par, int s2, int set) {
+        const int wbuf = (kt & 3) * WBUF_BYTES;
+        const int xbuf = ((kt >> 1) & 1) * XBUF_BYTES;
 #pragma unroll
         for (int fn = 0; fn < 4; ++fn) {
             const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
-            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + buf + wf_off + blk * 1024 + s2 * 512);
+            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + wbuf + wf_off + blk * 1024 + s2 * 512);
         }
 #pragma unroll
         for (int fm = 0; fm < 4; ++fm)
-            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + buf + xf_off[s2] + fm * 2048);
+            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + xbuf + xf_off[2 * kt_par + s2] + fm * 4096);
     };
     auto multiply = [&](int set) {
 #pragma unroll
@@ -315,33 +327,51 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                            // DS read
         }
     };
-
-    wait_vmcnt<0>();                       // nothing of the previous tile is still landing in the LDS
-    __syncthreads();                       // and nobody still reads it
-#pragma unroll
-    for (int s = 0; s < NS; ++s) issue(s);
-    typedef __attribute__((address_space(3))) float* lds_float;
-    lds_float bias_tile = (lds_float)(l3 + BIAS_LDS_OFFSET);
-    if (!GATED && ga.bias) bias_tile[tid] = n0 + tid < N ? as_global<float>(ga.bias)[n0 + tid] : 0.f;
-    wait_vmcnt<DMA_PER_STAGE * (NS - 1)>();
-    __builtin_amdgcn_s_barrier();
-    read_frags(0, 0, 0);
-
-    for (int kt = 0; kt < KS; ++kt) {
-        // first half: multiply step 0 of stage kt, read its step 1
-        read_frags(kt, 1, 1);
+    // One stage; PAR = kt & 1.
+    auto stage_even = [&](int kt) {
+        read_frags(kt, 0, 1, 1);            // first half: multiply step 0, read step 1
         multiply(0);
         interleave();
-        // stage kt+1 must be visible before its fragments are read; stage kt is now fully in registers
-        wait_lgkmcnt0();
-        wait_vmcnt<DMA_PER_STAGE * (NS - 2)>();
+        wait_lgkmcnt0();                    // stage kt is now fully in registers
+        wait_vmcnt<16>();                   // my loads of stage kt+1 have landed
         __builtin_amdgcn_s_barrier();
-        issue(kt + NS);
-        // second half: multiply step 1 of stage kt, read step 0 of stage kt+1 (past the end: unused)
-        read_frags(kt + 1, 0, 0);
+        issue_w(kt + 4);
+        read_frags(kt + 1, 1, 0, 0);        // second half: multiply step 1, read step 0 of stage kt+1
         multiply(1);
         interleave();
+    };
+    auto stage_odd = [&](int kt) {
+        read_frags(kt, 1, 1, 1);
+        multiply(0);
+        interleave();
+        wait_lgkmcnt0();
+        wait_vmcnt<4>();
+        __builtin_amdgcn_s_barrier();
+        issue_w(kt + 4);
+        issue_x((kt + 3) >> 1);             // stages kt+3, kt+4 into the X buffer that held kt-1, kt
+        read_frags(kt + 1, 0, 0, 0);
+        multiply(1);
+        interleave();
+    };
+
+    typedef __attribute__((address_space(3))) float* lds_float;
+    lds_float bias_tile = (lds_float)(l3 + BIAS_LDS_OFFSET);
+    float my_bias = 0.f;                   // fetched before the direct loads start, so that waiting for it is free
+    if (!GATED && ga.bias && n0 + tid < N) my_bias = as_global<float>(ga.bias)[n0 + tid];
+    wait_vmcnt<0>();                       // nothing of the previous tile is still landing in the LDS
+    __syncthreads();                       // and nobody still reads it
+    if (!GATED && ga.bias) bias_tile[tid] = my_bias;
+    issue_w(0); issue_w(1); issue_x(0); issue_w(2); issue_w(3); issue_x(1);
+    wait_vmcnt<16>();                      // W0, W1, X(0,1) have landed
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, 0, 0);
+
+    int kt = 0;
+    for (; kt + 1 < KS; kt += 2) {
+        stage_even(kt);
+        stage_odd(kt + 1);
     }
+    if (kt < KS) stage_even(kt);           // KS odd: one more even stage (its look-ahead reads are unused)
     wait_vmcnt<0>();
     __syncthreads();                       // every wave is done with the stage buffers
 
