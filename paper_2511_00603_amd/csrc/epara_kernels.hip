@@ -264,23 +264,28 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
         woff[j] = static_cast<uint32_t>((nb * KS * 64 + lane) * 16);
     }
 
-    auto issue_w = [&](int kt_unclamped) {
+    // direct loads, one instruction at a time so that they can be spread between the MFMAs
+    auto issue_w1 = [&](int kt_unclamped, int j) {
         const int buf = W_LDS_OFFSET + (kt_unclamped & 3) * WBUF_BYTES + 4 * wave * 1024;
         gcptr wb = wbase + static_cast<size_t>(min(kt_unclamped, KS - 1)) * 1024;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
-                                             (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
+                                         (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
     };
-    auto issue_x = [&](int kd_unclamped) {
+    auto issue_x1 = [&](int kd_unclamped, int j) {
         const int buf = (kd_unclamped & 1) * XBUF_BYTES + 8 * wave * 1024;
         const int kd = min(kd_unclamped, KD - 1);
         gcptr xb = xbase + static_cast<size_t>(kd) * 128;
         const bool tail = kd == KD - 1;
+        __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
+                                         (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+    };
+    auto issue_w = [&](int kt) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
-                                             (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+        for (int j = 0; j < 4; ++j) issue_w1(kt, j);
+    };
+    auto issue_x = [&](int kd) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) issue_x1(kd, j);
     };
 
     // --- fragment read offsets
@@ -301,57 +306,46 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
             for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0.f;
 
     v4i wf[2][4], xf[2][4];
-    // kt_par = kt & 1 must be a compile-time value: it selects the X offsets
-    auto read_frags = [&](int kt, int kt_par, int s2, int set) {
-        const int wbuf = (kt & 3) * WBUF_BYTES;
-        const int xbuf = ((kt >> 1) & 1) * XBUF_BYTES;
-#pragma unroll
-        for (int fn = 0; fn < 4; ++fn) {
+    // Fragment i = 0..7 of step (kt, s2), in the order the next half's MFMAs need them:
+    // W0, X0, X1, X2, X3, W1, W2, W3.  kt_par = kt & 1 must be a compile-time value.
+    auto read_frag = [&](int kt, int kt_par, int s2, int set, int i) {
+        if (i == 0 || i >= 5) {
+            const int fn = i == 0 ? 0 : i - 4;
             const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
-            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + wbuf + wf_off + blk * 1024 + s2 * 512);
+            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + (kt & 3) * WBUF_BYTES + wf_off + blk * 1024 + s2 * 512);
+        } else {
+            const int fm = i - 1;
+            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + ((kt >> 1) & 1) * XBUF_BYTES + xf_off[2 * kt_par + s2] + fm * 4096);
         }
-#pragma unroll
-        for (int fm = 0; fm < 4; ++fm)
-            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + xbuf + xf_off[2 * kt_par + s2] + fm * 4096);
     };
-    auto multiply = [&](int set) {
-#pragma unroll
-        for (int fn = 0; fn < 4; ++fn)
-#pragma unroll
-            for (int fm = 0; fm < 4; ++fm) mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
-    };
-    auto interleave = [&]() {               // 8 fragment reads spread between the 16 (fp8: 32) MFMAs of a step
+    // Half a stage: 16 MFMAs on register set `set` in eight groups of two; after group i fragment i
+    // of the next step is read into the other set and up to two direct loads are issued.  The
+    // scheduling barriers pin this interleaving: one wave per SIMD has nobody else to hide a stall.
+    auto half = [&](int set, int kt_read, int par_read, int s2_read, int kt_w, int kd_x) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, DT == EPARA_BF16 ? 2 : 4, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                            // DS read
+            const int fn = i >> 1, fm = 2 * (i & 1);
+            mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
+            mma32<DT>(acc[fn][fm + 1], wf[set][fn], xf[set][fm + 1]);
+            read_frag(kt_read, par_read, s2_read, set ^ 1, i);
+            if (kt_w >= 0 && i < 4) issue_w1(kt_w, i);
+            if (kd_x >= 0) issue_x1(kd_x, i);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // One stage; PAR = kt & 1.
     auto stage_even = [&](int kt) {
-        read_frags(kt, 0, 1, 1);            // first half: multiply step 0, read step 1
-        multiply(0);
-        interleave();
+        half(0, kt, 0, 1, -1, -1);          // multiply step 0, read step 1
         wait_lgkmcnt0();                    // stage kt is now fully in registers
         wait_vmcnt<16>();                   // my loads of stage kt+1 have landed
         __builtin_amdgcn_s_barrier();
-        issue_w(kt + 4);
-        read_frags(kt + 1, 1, 0, 0);        // second half: multiply step 1, read step 0 of stage kt+1
-        multiply(1);
-        interleave();
+        half(1, kt + 1, 1, 0, kt + 4, -1);  // multiply step 1, read step 0 of stage kt+1, refill W stage kt+4
     };
     auto stage_odd = [&](int kt) {
-        read_frags(kt, 1, 1, 1);
-        multiply(0);
-        interleave();
+        half(0, kt, 1, 1, -1, -1);
         wait_lgkmcnt0();
         wait_vmcnt<4>();
         __builtin_amdgcn_s_barrier();
-        issue_w(kt + 4);
-        issue_x((kt + 3) >> 1);             // stages kt+3, kt+4 into the X buffer that held kt-1, kt
-        read_frags(kt + 1, 0, 0, 0);
-        multiply(1);
-        interleave();
+        half(1, kt + 1, 0, 0, kt + 4, (kt + 3) >> 1);   // also refill X stages kt+3, kt+4 (buffer of kt-1, kt)
     };
 
     typedef __attribute__((address_space(3))) float* lds_float;
@@ -364,7 +358,8 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     issue_w(0); issue_w(1); issue_x(0); issue_w(2); issue_w(3); issue_x(1);
     wait_vmcnt<16>();                      // W0, W1, X(0,1) have landed
     __builtin_amdgcn_s_barrier();
-    read_frags(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) read_frag(0, 0, 0, 0, i);
 
     int kt = 0;
     for (; kt + 1 < KS; kt += 2) {
