@@ -106,13 +106,51 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         else:
             k.update(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
         res["kernels"].append(k)
+    from paper_2511_00603_amd.profile_summary import lookup_traffic
     dom = max(res["kernels"], key=lambda k: k["ms"])
     res["roofline"] = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
-                       "frac": dom["frac"], "traffic": None, "kernel": "grouped_kernel launch %d" % dom["launch"],
-                       "avg_ms": dom["ms"]}
+                       "frac": dom["frac"], "traffic": lookup_traffic("%s_%s" % (mix.name, dtype_name), dom["launch"]),
+                       "algorithmic_bytes": dom["bytes"], "algorithmic_flops": dom["flops"],
+                       "kernel": "grouped_kernel launch %d" % dom["launch"], "avg_ms": dom["ms"]}
     del staged
     torch.cuda.empty_cache()
     return res
+
+
+def measure_peaks():
+    """What this GPU sustains on the library's own probes: streaming read bandwidth, and the bf16 MFMA rate
+    on all-zero operands and on N(0,1) operands (the matrix clock is power limited and data dependent)."""
+    import numpy as np
+    import torch
+    from paper_2511_00603_amd import binding as B
+    from workloads import casts
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(16, dtype=torch.uint8, device=dev)
+    out = {}
+    nbytes = 2 << 30
+    buf = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.epara_probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
+    e0.record()
+    for _ in range(5):
+        B.epara_probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    out["hbm_read_GBs"] = 5 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del buf
+    rng = np.random.default_rng(7)
+    for name, vals in (("zeros", np.zeros(16384, dtype=np.float32)), ("normal", rng.standard_normal(16384).astype(np.float32))):
+        ops = torch.from_numpy(casts.bf16_bits(vals).view(np.int16)).to(dev)
+        iters = 20000
+        B.epara_probe_mfma(ops.data_ptr(), 2000, sink.data_ptr(), 256, stream)
+        e0.record()
+        B.epara_probe_mfma(ops.data_ptr(), iters, sink.data_ptr(), 256, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        out["mfma_bf16_TFLOPs_%s_operands" % name] = 256 * 4 * iters * 16 * 2 * 32 * 32 * 16 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(mix, budget_s=15.0):
@@ -145,6 +183,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--mixes", default="5,5fp8,4,3,2,1", help="comma list; the first is the headline (default prefill bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling probes")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: every service of a mix is resident on it and nothing is sharded; "
@@ -156,6 +195,7 @@ def main():
         print("bench.py needs a GPU (libepara has no CPU path)", file=sys.stderr)
         sys.exit(2)
 
+    peaks = None if a.no_peaks else measure_peaks()
     results, cache, cpu = [], {}, None
     for tag in a.mixes.split(","):
         idx = int(tag[0])
@@ -189,7 +229,7 @@ def main():
             "config": {"workload": "%s (%s): %d rows, %d requests per pass, %d launches" % (
                 head["name"], head["dtype"], head["rows"], head["requests"], head["launches"])},
             "requests_per_s": head["requests_per_s"],
-            "roofline": head["roofline"], "cpu_baseline": cpu,
+            "roofline": head["roofline"], "cpu_baseline": cpu, "measured_peaks": peaks,
             "mixes": {("%s_%s" % (r["name"], r["dtype"])): r for r in results}}
     print(json.dumps(line))
 

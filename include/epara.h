@@ -206,6 +206,24 @@ int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int3
 int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
                                  int32_t in_dtype, int32_t h_dtype, int32_t out_dtype, void* stream);
 
+/* ---- measurement helpers (not part of the forward path) ------------------------------------- */
+
+/* Streams `bytes` (>= 8 KiB, rounded down to 8 KiB per wave step) of d_buf once with n_workgroups
+ * workgroups of 256 threads, 16-byte loads, each wave reading consecutive 1 KiB chunks: the read
+ * bandwidth this GPU sustains.  d_sink: 4 writable bytes. */
+int32_t epara_probe_read(const void* d_buf, int64_t bytes, void* d_sink, int32_t n_workgroups, void* stream);
+
+/* Plain copy kernel d_dst[0..bytes) = d_src[0..bytes) (bytes a multiple of 16): a kernel of known HBM
+ * traffic against which profiler byte counters are calibrated. */
+int32_t epara_probe_copy(const void* d_src, void* d_dst, int64_t bytes, void* stream);
+
+/* Register-resident bf16 MFMA loop: every wave of n_workgroups x 256 threads issues iters x 16
+ * v_mfma_f32_32x32x16_bf16 (16 independent accumulators) on operands taken from d_operands
+ * (8 x 256 x 16 bytes).  The sustained rate depends on the operand VALUES (clocks are power
+ * limited), so the caller passes data distributed like its workload.  d_sink: 4 writable bytes.
+ * Flops per call = n_workgroups * 4 * iters * 16 * 2*32*32*16. */
+int32_t epara_probe_mfma(const void* d_operands, int32_t iters, void* d_sink, int32_t n_workgroups, void* stream);
+
 const char* epara_status_string(int32_t status);
 
 #ifdef __cplusplus

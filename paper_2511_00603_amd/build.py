@@ -4,7 +4,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "epara_kernels.hip"), os.path.join(HERE, "csrc", "epara_host.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", "epara_kernels.hip"), os.path.join(HERE, "csrc", "epara_probe.hip"),
+           os.path.join(HERE, "csrc", "epara_host.cpp")]
 HEADER = os.path.join(ROOT, "include", "epara.h")
 LIB = os.path.join(HERE, "libepara.so")
 

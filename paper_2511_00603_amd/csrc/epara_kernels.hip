@@ -318,8 +318,9 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
             xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + ((kt >> 1) & 1) * XBUF_BYTES + xf_off[2 * kt_par + s2] + fm * 4096);
         }
     };
-    // Half a stage: 16 MFMAs on register set `set` in eight groups of two; after group i fragment i
-    // of the next step is read into the other set and up to two direct loads are issued.  The
+    // Half a stage: 16 MFMAs on register set `set` in eight groups of two; after each of the first
+    // four groups two fragments of the next step are read into the other set, and after each
+    // group up to two direct loads are issued.  The
     // scheduling barriers pin this interleaving: one wave per SIMD has nobody else to hide a stall.
     auto half = [&](int set, int kt_read, int par_read, int s2_read, int kt_w, int kd_x) {
 #pragma unroll
@@ -327,7 +328,10 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
             const int fn = i >> 1, fm = 2 * (i & 1);
             mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
             mma32<DT>(acc[fn][fm + 1], wf[set][fn], xf[set][fm + 1]);
-            read_frag(kt_read, par_read, s2_read, set ^ 1, i);
+            if (i < 4) {                    // all eight reads early: the last MFMAs of the half cover their latency
+                read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i);
+                read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i + 1);
+            }
             if (kt_w >= 0 && i < 4) issue_w1(kt_w, i);
             if (kd_x >= 0) issue_x1(kd_x, i);
             __builtin_amdgcn_sched_barrier(0);

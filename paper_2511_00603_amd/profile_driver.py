@@ -1,0 +1,44 @@
+"""Small driver for rocprofv3 runs: a few passes of one synthetic mix, then the plain copy kernel
+of known size whose HBM traffic calibrates the byte counters.
+
+    rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- python3 -m paper_2511_00603_amd.profile_driver 5 bf16 6
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 -m paper_2511_00603_amd.profile_driver 5 bf16 3
+"""
+import sys
+
+import torch
+
+from workloads import make_mix
+
+from . import binding as B
+from .mixrun import StagedMix
+
+COPY_BYTES = 1 << 30
+
+
+def main():
+    idx = int(sys.argv[1])
+    dtype = sys.argv[2] if len(sys.argv) > 2 else None
+    steps = int(sys.argv[3]) if len(sys.argv) > 3 else 4
+    mix = make_mix(idx)
+    s_h = None
+    if dtype == "fp8":
+        cal = StagedMix(mix, "bf16", "cuda:0")
+        cal.run()
+        torch.cuda.synchronize()
+        s_h = [float(t.abs().max().float().item()) / 448.0 for (_, _, t) in cal.outputs[0][0]]
+        del cal
+    staged = StagedMix(mix, dtype, "cuda:0")
+    for _ in range(steps):
+        staged.run()
+    torch.cuda.synchronize()
+    src = torch.ones(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):
+        B.epara_probe_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    print("profile_driver: mix %d %s, %d passes, copy probe %d bytes" % (idx, dtype or mix.dtype, steps, COPY_BYTES))
+
+
+if __name__ == "__main__":
+    main()
