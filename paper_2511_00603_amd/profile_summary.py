@@ -47,9 +47,9 @@ def kernels(trace_csv, command, out_txt, launches_per_pass):
         d = [t[1] for i, t in enumerate(g) if i % launches_per_pass == l and i >= launches_per_pass]
         if d:
             r = g[l][2]
-            L.append("  launch %d  n=%3d  avg %9.2f  median %9.2f  min %9.2f  max %9.2f   grid %s x %s threads, LDS %s B, scratch %s B/lane"
+            L.append("  launch %d  n=%3d  avg %9.2f  median %9.2f  min %9.2f  max %9.2f   grid %s x %s threads, scratch %s B/lane"
                      % (l, len(d), sum(d) / len(d), statistics.median(d), min(d), max(d),
-                        int(r["Grid_Size"]) // int(r["Workgroup_Size"]), r["Workgroup_Size"], r["LDS_Block_Size"], r["Scratch_Size"]))
+                        int(r["Grid_Size_X"]) // int(r["Workgroup_Size_X"]), r["Workgroup_Size_X"], r["Scratch_Size"]))
     open(out_txt, "w").write("\n".join(L) + "\n")
     print("\n".join(L))
 
