@@ -305,53 +305,6 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fn][fm][v] = 0.f;
 
-    v4i wf[2][4], xf[2][4];
-    // Fragment i = 0..7 of step (kt, s2), in the order the next half's MFMAs need them:
-    // W0, X0, X1, X2, X3, W1, W2, W3.  kt_par = kt & 1 must be a compile-time value.
-    auto read_frag = [&](int kt, int kt_par, int s2, int set, int i) {
-        if (i == 0 || i >= 5) {
-            const int fn = i == 0 ? 0 : i - 4;
-            const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
-            wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + (kt & 3) * WBUF_BYTES + wf_off + blk * 1024 + s2 * 512);
-        } else {
-            const int fm = i - 1;
-            xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + ((kt >> 1) & 1) * XBUF_BYTES + xf_off[2 * kt_par + s2] + fm * 4096);
-        }
-    };
-    // Half a stage: 16 MFMAs on register set `set` in eight groups of two; after each of the first
-    // four groups two fragments of the next step are read into the other set, and after each
-    // group up to two direct loads are issued.  The
-    // scheduling barriers pin this interleaving: one wave per SIMD has nobody else to hide a stall.
-    auto half = [&](int set, int kt_read, int par_read, int s2_read, int kt_w, int kd_x) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int fn = i >> 1, fm = 2 * (i & 1);
-            mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
-            mma32<DT>(acc[fn][fm + 1], wf[set][fn], xf[set][fm + 1]);
-            if (i < 4) {                    // all eight reads early: the last MFMAs of the half cover their latency
-                read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i);
-                read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i + 1);
-            }
-            if (kt_w >= 0 && i < 4) issue_w1(kt_w, i);
-            if (kd_x >= 0) issue_x1(kd_x, i);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-    auto stage_even = [&](int kt) {
-        half(0, kt, 0, 1, -1, -1);          // multiply step 0, read step 1
-        wait_lgkmcnt0();                    // stage kt is now fully in registers
-        wait_vmcnt<16>();                   // my loads of stage kt+1 have landed
-        __builtin_amdgcn_s_barrier();
-        half(1, kt + 1, 1, 0, kt + 4, -1);  // multiply step 1, read step 0 of stage kt+1, refill W stage kt+4
-    };
-    auto stage_odd = [&](int kt) {
-        half(0, kt, 1, 1, -1, -1);
-        wait_lgkmcnt0();
-        wait_vmcnt<4>();
-        __builtin_amdgcn_s_barrier();
-        half(1, kt + 1, 0, 0, kt + 4, (kt + 3) >> 1);   // also refill X stages kt+3, kt+4 (buffer of kt-1, kt)
-    };
-
     typedef __attribute__((address_space(3))) float* lds_float;
     lds_float bias_tile = (lds_float)(l3 + BIAS_LDS_OFFSET);
     float my_bias = 0.f;                   // fetched before the direct loads start, so that waiting for it is free
@@ -362,15 +315,111 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     issue_w(0); issue_w(1); issue_x(0); issue_w(2); issue_w(3); issue_x(1);
     wait_vmcnt<16>();                      // W0, W1, X(0,1) have landed
     __builtin_amdgcn_s_barrier();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) read_frag(0, 0, 0, 0, i);
+    if constexpr (DT == EPARA_BF16) {
+        v4i wf[2][4], xf[2][4];
+        // Fragment i = 0..7 of step (kt, s2), in the order the next half's MFMAs need them:
+        // W0, X0, X1, X2, X3, W1, W2, W3.  kt_par = kt & 1 must be a compile-time value.
+        auto read_frag = [&](int kt, int kt_par, int s2, int set, int i) {
+            if (i == 0 || i >= 5) {
+                const int fn = i == 0 ? 0 : i - 4;
+                const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;   // gate blocks 0..3, up blocks 8..11 (+ 4 wn)
+                wf[set][fn] = *reinterpret_cast<lds_v4i>(l3 + (kt & 3) * WBUF_BYTES + wf_off + blk * 1024 + s2 * 512);
+            } else {
+                const int fm = i - 1;
+                xf[set][fm] = *reinterpret_cast<lds_v4i>(l3 + ((kt >> 1) & 1) * XBUF_BYTES + xf_off[2 * kt_par + s2] + fm * 4096);
+            }
+        };
+        // Half a stage: 16 MFMAs on register set `set` in eight groups of two; after each of the first
+        // four groups two fragments of the next step are read into the other set, and after each
+        // group up to two direct loads are issued.  The
+        // scheduling barriers pin this interleaving: one wave per SIMD has nobody else to hide a stall.
+        auto half = [&](int set, int kt_read, int par_read, int s2_read, int kt_w, int kd_x) {
+    #pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int fn = i >> 1, fm = 2 * (i & 1);
+                mma32<DT>(acc[fn][fm], wf[set][fn], xf[set][fm]);
+                mma32<DT>(acc[fn][fm + 1], wf[set][fn], xf[set][fm + 1]);
+                if (i < 4) {                    // all eight reads early: the last MFMAs of the half cover their latency
+                    read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i);
+                    read_frag(kt_read, par_read, s2_read, set ^ 1, 2 * i + 1);
+                }
+                if (kt_w >= 0 && i < 4) issue_w1(kt_w, i);
+                if (kd_x >= 0) issue_x1(kd_x, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        auto stage_even = [&](int kt) {
+            half(0, kt, 0, 1, -1, -1);          // multiply step 0, read step 1
+            wait_lgkmcnt0();                    // stage kt is now fully in registers
+            wait_vmcnt<16>();                   // my loads of stage kt+1 have landed
+            __builtin_amdgcn_s_barrier();
+            half(1, kt + 1, 1, 0, kt + 4, -1);  // multiply step 1, read step 0 of stage kt+1, refill W stage kt+4
+        };
+        auto stage_odd = [&](int kt) {
+            half(0, kt, 1, 1, -1, -1);
+            wait_lgkmcnt0();
+            wait_vmcnt<4>();
+            __builtin_amdgcn_s_barrier();
+            half(1, kt + 1, 0, 0, kt + 4, (kt + 3) >> 1);   // also refill X stages kt+3, kt+4 (buffer of kt-1, kt)
+        };
 
-    int kt = 0;
-    for (; kt + 1 < KS; kt += 2) {
-        stage_even(kt);
-        stage_odd(kt + 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) read_frag(0, 0, 0, 0, i);
+        int kt = 0;
+        for (; kt + 1 < KS; kt += 2) {
+            stage_even(kt);
+            stage_odd(kt + 1);
+        }
+        if (kt < KS) stage_even(kt);       // KS odd: one more even stage (its look-ahead reads are unused)
+    } else {
+        // fp8: a stage is 64 bytes = 64 values of K per row, exactly one v_mfma_f32_32x32x64_f8f6f4 per
+        // accumulator (twice the flops per cycle of the K = 16 form).  A lane feeds the two 16-byte
+        // chunks h and 2 + h of its weight column / activation row; the fragments of a whole stage
+        // live in one of two register banks, the other bank is filled during the second half.
+        typedef int v8i __attribute__((ext_vector_type(8)));
+        v4i wq[2][2][4], xq[2][2][4];      // [bank][chunk 0/1][fragment]
+        auto read_frag8 = [&](int kt, int kt_par, int bank, int i16) {
+            const int s2 = i16 >> 3, i = i16 & 7;
+            if (i < 4) {
+                const int fn = i;
+                const int blk = GATED ? (fn < 2 ? 2 * fn : 8 + 2 * (fn - 2)) : 2 * fn;
+                wq[bank][s2][fn] = *reinterpret_cast<lds_v4i>(l3 + (kt & 3) * WBUF_BYTES + wf_off + blk * 1024 + s2 * 512);
+            } else {
+                const int fm = i - 4;
+                xq[bank][s2][fm] = *reinterpret_cast<lds_v4i>(l3 + ((kt >> 1) & 1) * XBUF_BYTES + xf_off[2 * kt_par + s2] + fm * 4096);
+            }
+        };
+        auto mma64 = [&](int bank, int fn, int fm) {
+            const v8i a8 = __builtin_shufflevector(wq[bank][0][fn], wq[bank][1][fn], 0, 1, 2, 3, 4, 5, 6, 7);
+            const v8i b8 = __builtin_shufflevector(xq[bank][0][fm], xq[bank][1][fm], 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[fn][fm] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc[fn][fm], 0, 0, 0, 0, 0, 0);
+        };
+        // PAR = kt & 1 = register bank of stage kt
+        auto stage8 = [&](int kt, int par) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mma64(par, i >> 2, i & 3);
+            wait_lgkmcnt0();
+            if (par) wait_vmcnt<4>(); else wait_vmcnt<16>();
+            __builtin_amdgcn_s_barrier();
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mma64(par, 2 + (i >> 2), i & 3);
+                read_frag8(kt + 1, par ^ 1, par ^ 1, 2 * i);
+                read_frag8(kt + 1, par ^ 1, par ^ 1, 2 * i + 1);
+                if (i < 4) issue_w1(kt + 4, i);
+                if (par) issue_x1((kt + 3) >> 1, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < 16; ++i) read_frag8(0, 0, 0, i);
+        int kt = 0;
+        for (; kt + 1 < KS; kt += 2) {
+            stage8(kt, 0);
+            stage8(kt + 1, 1);
+        }
+        if (kt < KS) stage8(kt, 0);
     }
-    if (kt < KS) stage_even(kt);           // KS odd: one more even stage (its look-ahead reads are unused)
     wait_vmcnt<0>();
     __syncthreads();                       // every wave is done with the stage buffers
 
