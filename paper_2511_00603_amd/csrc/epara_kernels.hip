@@ -62,7 +62,31 @@ __device__ __forceinline__ void with_act(int act, F&& f)
     }
 }
 
-__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
+// The same activations for the 16- and 8-bit paths, whose outputs keep 8 or 3 mantissa bits: the
+// exponential and the reciprocal are the hardware's (about 1 ulp in fp32) instead of the exactly
+// rounded library forms, and erf is the rational-times-Gaussian approximation of Abramowitz and
+// Stegun (7.1.26, absolute error below 1.5e-7).  One wave per SIMD has nobody to overlap an
+// epilogue with, so its instruction count is paid in full on every tile.
+__device__ __forceinline__ float fast_logistic(float t)      // 1 / (1 + e^-t)
+{
+    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * t));
+}
+template <int ACT>
+__device__ __forceinline__ float act_fast(float z)
+{
+    if constexpr (ACT == EPARA_ACT_RELU)           return fmaxf(z, 0.f);
+    else if constexpr (ACT == EPARA_ACT_GELU_ERF) {
+        const float x = fabsf(z) * 0.70710678118654752f;
+        const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * x);
+        const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+        const float tail = poly * __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);   // 1 - erf(x)
+        return 0.5f * z * (z < 0.f ? tail : 2.f - tail);
+    }
+    else if constexpr (ACT == EPARA_ACT_GELU_TANH) // 0.5 z (1 + tanh u) = z / (1 + e^-2u)
+        return z * fast_logistic(1.5957691216057308f * (z + 0.044715f * z * z * z));
+    else if constexpr (ACT == EPARA_ACT_SILU)      return z * fast_logistic(z);
+    else                                           return z;
+}
 
 // fp32 -> bf16 bits, round to nearest even.
 __device__ __forceinline__ uint32_t f32_to_bf16(float x)
@@ -132,9 +156,11 @@ __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, 
     if (out_dtype == EPARA_BF16) {
         EPARA_GLOBAL uint16_t* y = as_global<uint16_t>(Y) + e;
         if (vec_ok && valid >= 4) {
-            v2u pk;
-            pk[0] = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-            pk[1] = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+            typedef float v2f __attribute__((ext_vector_type(2)));
+            typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+            v2u pk;                               // round to nearest even in hardware, two values per instruction
+            pk[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[0], v[1]}), v2bf));
+            pk[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[2], v[3]}), v2bf));
             *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
         } else {
 #pragma unroll
@@ -169,7 +195,7 @@ __device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out
     for (int i = 0; i < 4; ++i) {
         float b = 0.f;
         if (bias && i < valid) b = bias[nl + i];
-        v[i] = act_apply<ACT>(ga.scale * a[i] + b) * ga.out_inv_scale;
+        v[i] = act_fast<ACT>(ga.scale * a[i] + b) * ga.out_inv_scale;
     }
     store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, valid, vec_ok);
 }
@@ -181,7 +207,7 @@ __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out
     if (ml >= rows || nl >= cols) return;
     float v[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = silu(ga.scale * g[i]) * (ga.scale2 * u[i]) * ga.out_inv_scale;
+    for (int i = 0; i < 4; ++i) v[i] = act_fast<EPARA_ACT_SILU>(ga.scale * g[i]) * (ga.scale2 * u[i]) * ga.out_inv_scale;
     store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, cols - nl, vec_ok);
 }
 
@@ -426,43 +452,58 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     // Epilogue.  The 256 accumulators of a lane cannot be indexed at run time, and an unrolled
     // epilogue for all of them is tens of thousands of instructions that miss the instruction cache
     // once per tile.  So each wave parks its accumulators in its own 32 KiB of the (now idle) LDS,
-    // half at a time, and a compact loop finishes one quad (4 consecutive columns of one row) per
-    // iteration.  Quad (fi, fm, g) of a half: fragment fn = fi-th of the half, rows fm*32 + r32,
-    // columns 8g + 4h .. +3 of the fragment.
-    v4f* stash = reinterpret_cast<v4f*>(lds) + wave * 2048 + lane;
+    // 64 rows at a time, and a compact loop finishes one quad (4 consecutive columns of one row)
+    // per lane and iteration.  The loop reads the quads back transposed: the QPR lanes that share
+    // a row hold consecutive columns, so a store instruction writes whole 128-byte pieces of RPI
+    // rows instead of 16 bytes in each of 32 rows.
+    //   slot (fn, fmi, g) = 64 quads: rows fmi*32 + r32 of the 64, columns 8g + 4h .. +3 of fragment fn;
+    //   the quad of lane L sits at position L ^ swz(fn, g, h), swz = ((fn%2)*4 + g)*2 + h, so the
+    //   16 quads of a row that one quarter of a ds_read_b128 fetches fall into 16 different bank groups.
+    v4f* stash = reinterpret_cast<v4f*>(lds) + wave * 2048;
     const bool vec_ok = (N & 3) == 0;
+    constexpr int QPR = GATED ? 16 : 32;            // output quads per row of this wave's part of the tile
+    constexpr int RPI = 64 / QPR;                   // rows per iteration
+    const int q = lane % QPR, rr = lane / QPR;
+    const int fq = q >> 3, gq = (q >> 1) & 3, hq = q & 1;
+    const int swz_q = ((fq & 1) * 4 + gq) * 2 + hq;
+    const int nl = (GATED ? wn * 64 : wn * 128) + 4 * q;
+    auto park = [&](int half) {
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+        for (int fn = 0; fn < 4; ++fn)
 #pragma unroll
-        for (int fi = 0; fi < 2; ++fi) {
-            const int fn = GATED ? half + 2 * fi : 2 * half + fi;       // gated: a gate fragment and its up partner
-#pragma unroll
-            for (int fm = 0; fm < 4; ++fm)
+            for (int fmi = 0; fmi < 2; ++fmi)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    stash[((fi * 4 + fm) * 4 + g) * 64] =
-                        v4f{acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
-        }
-        if constexpr (GATED) {
+                    stash[((fn * 2 + fmi) * 4 + g) * 64 + (lane ^ (((fn & 1) * 4 + g) * 2 + h))] =
+                        v4f{acc[fn][2 * half + fmi][4 * g], acc[fn][2 * half + fmi][4 * g + 1],
+                            acc[fn][2 * half + fmi][4 * g + 2], acc[fn][2 * half + fmi][4 * g + 3]};
+    };
+    if constexpr (GATED) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            park(half);
 #pragma unroll 2
-            for (int it = 0; it < 16; ++it) {                            // it = fm*4 + g
-                const int fm = it >> 2, g = it & 3;
-                const v4f gate = stash[it * 64], up = stash[(16 + it) * 64];
-                finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + fm * 32 + r32, rows,
-                             n0, wn * 64 + half * 32 + 8 * g + 4 * h, cols, vec_ok);
+            for (int it = 0; it < 64 / RPI; ++it) {
+                const int row = it * RPI + rr, fmi = row >> 5;
+                const int at = ((hq * 32 + (row & 31)) ^ swz_q) + gq * 64 + fmi * 256 + fq * 512;
+                const v4f gate = stash[at], up = stash[at + 1024];
+                finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
             }
-        } else {
-            with_act(ga.act, [&](auto tag) {
-#pragma unroll 2
-                for (int it = 0; it < 32; ++it) {                        // it = (fi*4 + fm)*4 + g
-                    const int fi = it >> 4, fm = (it >> 2) & 3, g = it & 3;
-                    const v4f a4 = stash[it * 64];
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, ga.bias ? bias_tile : (lds_float)nullptr, m0,
-                                                       wm * 128 + fm * 32 + r32, rows,
-                                                       n0, wn * 128 + (2 * half + fi) * 32 + 8 * g + 4 * h, cols, vec_ok);
-                }
-            });
         }
+    } else {
+        with_act(ga.act, [&](auto tag) {
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                park(half);
+#pragma unroll 2
+                for (int it = 0; it < 64 / RPI; ++it) {
+                    const int row = it * RPI + rr, fmi = row >> 5;
+                    const v4f a4 = stash[((hq * 32 + (row & 31)) ^ swz_q) + gq * 64 + fmi * 256 + fq * 512];
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, ga.bias ? bias_tile : (lds_float)nullptr, m0,
+                                                       wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
+                }
+            }
+        });
     }
 }
 
