@@ -337,7 +337,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     if (!GATED && ga.bias && n0 + tid < N) my_bias = as_global<float>(ga.bias)[n0 + tid];
     wait_vmcnt<0>();                       // nothing of the previous tile is still landing in the LDS
     __syncthreads();                       // and nobody still reads it
-    if (!GATED && ga.bias) bias_tile[tid] = my_bias;
+    if (!GATED) bias_tile[tid] = my_bias;   // zeros when the group has no bias: the epilogue adds it unconditionally
     issue_w(0); issue_w(1); issue_x(0); issue_w(2); issue_w(3); issue_x(1);
     wait_vmcnt<16>();                      // W0, W1, X(0,1) have landed
     __builtin_amdgcn_s_barrier();
@@ -449,18 +449,21 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     wait_vmcnt<0>();
     __syncthreads();                       // every wave is done with the stage buffers
 
-    // Epilogue.  The 256 accumulators of a lane cannot be indexed at run time, and an unrolled
-    // epilogue for all of them is tens of thousands of instructions that miss the instruction cache
-    // once per tile.  So each wave parks its accumulators in its own 32 KiB of the (now idle) LDS,
-    // 64 rows at a time, and a compact loop finishes one quad (4 consecutive columns of one row)
-    // per lane and iteration.  The loop reads the quads back transposed: the QPR lanes that share
-    // a row hold consecutive columns, so a store instruction writes whole 128-byte pieces of RPI
-    // rows instead of 16 bytes in each of 32 rows.
+    // Epilogue.  The 256 accumulators of a lane sit in the AGPR half of the register file: they can
+    // be stored but not computed on there, and they cannot be indexed at run time.  So each wave
+    // parks them in its own 32 KiB of the (now idle) LDS, 64 rows at a time, and reads them back
+    // transposed, one quad (4 consecutive columns of one row) per lane: the QPR lanes that share a
+    // row hold consecutive columns, so a store instruction writes whole 128-byte pieces of RPI rows
+    // (quads stored from the MFMA layout would hit 32 rows per instruction, and the L2 takes such
+    // fragments one request each).
     //   slot (fn, fmi, g) = 64 quads: rows fmi*32 + r32 of the 64, columns 8g + 4h .. +3 of fragment fn;
     //   the quad of lane L sits at position L ^ swz(fn, g, h), swz = ((fn%2)*4 + g)*2 + h, so the
     //   16 quads of a row that one quarter of a ds_read_b128 fetches fall into 16 different bank groups.
+    // One wave per SIMD cannot overlap this with anybody's MFMAs, so what counts is the number of
+    // vector instructions.  A whole tile (the common case) runs the loop fully unrolled: constant
+    // LDS offsets, no bounds checks, one scalar pointer step per row group.  Ragged tiles run a
+    // compact loop with the checks.
     v4f* stash = reinterpret_cast<v4f*>(lds) + wave * 2048;
-    const bool vec_ok = (N & 3) == 0;
     constexpr int QPR = GATED ? 16 : 32;            // output quads per row of this wave's part of the tile
     constexpr int RPI = 64 / QPR;                   // rows per iteration
     const int q = lane % QPR, rr = lane / QPR;
@@ -478,6 +481,56 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                         v4f{acc[fn][2 * half + fmi][4 * g], acc[fn][2 * half + fmi][4 * g + 1],
                             acc[fn][2 * half + fmi][4 * g + 2], acc[fn][2 * half + fmi][4 * g + 3]};
     };
+    const bool vec_ok = (N & 3) == 0;
+    if (vec_ok && rows == 256 && cols == (GATED ? 128 : 256)) {
+        auto whole = [&](auto out_tag, auto tag) {
+            constexpr int OUT = decltype(out_tag)::value, ACT = decltype(tag)::value;
+            constexpr int OSZ = OUT == EPARA_BF16 ? 2 : 1;
+            typedef float v2f __attribute__((ext_vector_type(2)));
+            typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+            EPARA_GLOBAL char* ybase = as_global<char>(ga.Y) + (static_cast<size_t>(m0 + wm * 128) * N + n0) * OSZ;   // uniform
+            const uint32_t lane_off = static_cast<uint32_t>((rr * N + nl) * OSZ);
+            const int base_l = ((hq * 32) | rr) ^ swz_q;         // row & 31 = (it*RPI & 31) | rr, and | of disjoint bits = ^
+            const float sg = ga.scale, su = ga.scale2 * ga.out_inv_scale, inv = ga.out_inv_scale;
+            v4f b4 = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (!GATED) b4 = *reinterpret_cast<const __attribute__((address_space(3))) v4f*>(bias_tile + nl);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                park(half);
+#pragma unroll
+                for (int it = 0; it < 64 / RPI; ++it) {
+                    const int at = (base_l ^ ((it * RPI) & 31)) + gq * 64 + ((it * RPI) >> 5) * 256 + fq * 512;
+                    float v[4];
+                    if constexpr (GATED) {
+                        const v4f gate = stash[at], up = stash[at + 1024];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = act_fast<EPARA_ACT_SILU>(sg * gate[i]) * (su * up[i]);
+                    } else {
+                        const v4f a4 = stash[at];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(sg * a4[i] + b4[i]) * inv;
+                    }
+                    EPARA_GLOBAL char* y = ybase + static_cast<size_t>(half * 64 + it * RPI) * N * OSZ + lane_off;
+                    if constexpr (OUT == EPARA_BF16) {
+                        v2u pk;
+                        pk[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[0], v[1]}), v2bf));
+                        pk[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[2], v[3]}), v2bf));
+                        *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
+                    } else {
+                        *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32_to_e4m3(v[0]) | (f32_to_e4m3(v[1]) << 8) |
+                                                                       (f32_to_e4m3(v[2]) << 16) | (f32_to_e4m3(v[3]) << 24);
+                    }
+                }
+            }
+        };
+        auto by_out = [&](auto tag) {
+            if (DT == EPARA_BF16 || out_dtype == EPARA_BF16) whole(act_tag<EPARA_BF16>{}, tag);
+            else if constexpr (DT != EPARA_BF16)              whole(act_tag<EPARA_FP8_E4M3>{}, tag);
+        };
+        if constexpr (GATED) by_out(act_tag<EPARA_ACT_SILU>{});
+        else                 with_act(ga.act, by_out);
+        return;
+    }
     if constexpr (GATED) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -499,7 +552,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                 for (int it = 0; it < 64 / RPI; ++it) {
                     const int row = it * RPI + rr, fmi = row >> 5;
                     const v4f a4 = stash[((hq * 32 + (row & 31)) ^ swz_q) + gq * 64 + fmi * 256 + fq * 512];
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, ga.bias ? bias_tile : (lds_float)nullptr, m0,
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, bias_tile, m0,
                                                        wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
                 }
             }
