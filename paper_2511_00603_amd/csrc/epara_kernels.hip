@@ -270,8 +270,6 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     ldsptr l3 = (ldsptr)lds;
 
     // --- direct-load descriptors: this wave fills X rows [64 wave, 64 wave + 64) and W blocks 4 wave .. 4 wave + 3
-    gcptr xbase = as_global<char>(ga.X) + static_cast<size_t>(m0) * K * ESZ;
-    gcptr wbase = as_global<char>((GATED && wave >= 2) ? ga.W2 : ga.W) + static_cast<size_t>(n0 >> 4) * KS * 1024;
     const int tail_k = K - (KD - 1) * 2 * KF;                   // elements in the last stage pair, 1..2KF
     uint32_t xoff[8], xoff_tail[8], woff[4];
 #pragma unroll
@@ -290,20 +288,25 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
         woff[j] = static_cast<uint32_t>((nb * KS * 64 + lane) * 16);
     }
 
+    // Direct loads go through buffer descriptors spanning the whole address space (every offset
+    // below is already clamped to valid memory): a wave issues this form a little faster than the
+    // flat-encoded one, and it leaves the compiler's count of outstanding loads exact.
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(static_cast<const char*>((GATED && wave >= 2) ? ga.W2 : ga.W)) + static_cast<size_t>(n0 >> 4) * KS * 1024, 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(static_cast<const char*>(ga.X)) + static_cast<size_t>(m0) * K * ESZ, 0, -1, 0x00020000);
     // direct loads, one instruction at a time so that they can be spread between the MFMAs
     auto issue_w1 = [&](int kt_unclamped, int j) {
         const int buf = W_LDS_OFFSET + (kt_unclamped & 3) * WBUF_BYTES + 4 * wave * 1024;
-        gcptr wb = wbase + static_cast<size_t>(min(kt_unclamped, KS - 1)) * 1024;
-        __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(wb + woff[j]),
-                                         (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wrsrc, (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16,
+                                                 woff[j], min(kt_unclamped, KS - 1) * 1024, 0, 0);
     };
     auto issue_x1 = [&](int kd_unclamped, int j) {
         const int buf = (kd_unclamped & 1) * XBUF_BYTES + 8 * wave * 1024;
         const int kd = min(kd_unclamped, KD - 1);
-        gcptr xb = xbase + static_cast<size_t>(kd) * 128;
         const bool tail = kd == KD - 1;
-        __builtin_amdgcn_global_load_lds((const EPARA_GLOBAL void*)(xb + (tail ? xoff_tail[j] : xoff[j])),
-                                         (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(l3 + buf + j * 1024), 16,
+                                                 tail ? xoff_tail[j] : xoff[j], kd * 128, 0, 0);
     };
     auto issue_w = [&](int kt) {
 #pragma unroll
