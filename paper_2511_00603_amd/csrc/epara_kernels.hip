@@ -32,7 +32,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int NT = 256;                 // threads per workgroup (4 waves, one per SIMD)
 constexpr int BIAS_LDS_OFFSET = 131072;  // after the operand buffers: 256 floats, the bias of a panel tile
-constexpr int LDS_BYTES = BIAS_LDS_OFFSET + 1024;
+constexpr int LDS_BYTES = 163840;          // the whole LDS of a compute unit (one workgroup per unit)
+constexpr int RING_LDS_OFFSET = 65536;   // streaming tiles: partial sums below, the waves' activation rings above
 constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
 
 // ------------------------------------------------------------------ small device helpers
@@ -584,12 +585,19 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
 template <int NFR>
 struct skinny_tile_state {
     gcptr w[NFR];          // uniform: start of each weight column block's fragment stream
-    gcptr x;               // uniform: activations of the group
-    uint32_t xrow[4];      // per lane: byte offset of my row in each 16-row block (+ my k-chunk)
+    const char* x;         // uniform: activations of the group
+    uint32_t xoff[8];      // per lane, per direct-load instruction j < 2 MB: byte offset of my row + my chunk's 16 c
     int KS, K;             // fragments along K, K
     int n_chunks;          // chunks of U steps per wave
 };
 
+// Activations of a step (two fragments = 128 bytes of K for MB x 16 rows) go through a per-wave LDS
+// slot: direct-load instruction j covers rows 8j .. 8j+7 whole (8 x 128 bytes, eight cache lines),
+// where loading MFMA operands straight from memory touches 16 half lines per instruction - the
+// lines, not the bytes, are what the re-read of the activations costs next to the weight stream.
+// Lane l of instruction j writes LDS chunk s = l%8 of row 8j + l/8 and fetches the global chunk
+// c = s ^ ((row/2)%8); operand reads (16 rows x one chunk per quarter wave) then fall into 16
+// different bank groups.
 template <int DT, bool GATED, int MB, int NFR, int U>
 __device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const epara_group_args& ga, int n0, int lane)
 {
@@ -610,48 +618,79 @@ __device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const e
         gcptr base = as_global<char>((GATED && f >= NFR / 2) ? ga.W2 : ga.W);
         st.w[f] = base + static_cast<size_t>(nb) * KS * 1024;
     }
-    st.x = as_global<char>(ga.X);
-    const int r = lane & 15, q = lane >> 4;
+    st.x = static_cast<const char*>(ga.X);
 #pragma unroll
-    for (int fm = 0; fm < MB; ++fm)
-        st.xrow[fm] = static_cast<uint32_t>(min(fm * 16 + r, ga.M - 1)) * static_cast<uint32_t>(K * ESZ) + q * 16;
-}
-
-// One ring slot: fragments ks = 2p and 2p+1 of NFR column blocks and of MB row blocks.
-template <int MB, int NFR>
-struct skinny_slot { v4i w[2][NFR]; v4i x[2][MB]; };
-
-template <int DT, int MB, int NFR>
-__device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, int i, int wave, int lane, skinny_slot<MB, NFR>& sl)
-{
-    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
-    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
-    const uint32_t lane16 = lane * 16;
-    const int xq = (lane >> 4) * EPC;
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int ks = min(2 * (wave + 4 * i) + e, st.KS - 1);   // padding repeats the last fragment
-#pragma unroll
-        for (int f = 0; f < NFR; ++f) sl.w[e][f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024 + lane16);
-        // ragged K: a chunk past K falls back to chunk 0 of the fragment (the packed weights are 0 there)
-        const uint32_t back = (ks * KF + xq < st.K) ? 0u : static_cast<uint32_t>((lane >> 4) * 16);
-        gcptr xk = st.x + static_cast<size_t>(ks) * 64;
-#pragma unroll
-        for (int fm = 0; fm < MB; ++fm) sl.x[e][fm] = ld16(xk + (st.xrow[fm] - back));
+    for (int j = 0; j < 2 * MB; ++j) {
+        const int row = 8 * j + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        st.xoff[j] = static_cast<uint32_t>(min(row, ga.M - 1)) * static_cast<uint32_t>(K * ESZ) + c * 16;
     }
 }
 
+// One ring slot: weight fragments ks = 2p and 2p+1 of NFR column blocks (the activations of the
+// step sit in the wave's LDS slot of the same index).
+template <int NFR>
+struct skinny_slot { v4i w[2][NFR]; };
+
 template <int DT, int MB, int NFR>
-__device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int i, int wave, const skinny_slot<MB, NFR>& sl,
-                                           v4f (&acc)[NFR][MB])
+__device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, int i, int wave, int lane, skinny_slot<NFR>& sl,
+                                            char* xslot_generic)
 {
+    ldsptr xslot = (ldsptr)xslot_generic;
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const int p = wave + 4 * i;                                  // step: fragments 2p and 2p+1
+    // activations first: loads complete in issue order, so once the weights of this slot are in
+    // their registers the slot's LDS image is complete too
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(st.x), 0, -1, 0x00020000);
+    if ((2 * p + 2) * KF <= st.K) {                              // both fragments lie inside K
+#pragma unroll
+        for (int j = 0; j < 2 * MB; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(xslot + j * 1024), 16,
+                                                     static_cast<int>(st.xoff[j]), p * 128, 0, 0);
+    } else {
+        // ragged or padding step: a fragment past the last one repeats the last, a chunk past K
+        // falls back to chunk 0 of its fragment (the packed weights are zero there)
+#pragma unroll
+        for (int j = 0; j < 2 * MB; ++j) {
+            const int c = (lane & 7) ^ ((4 * j + (lane >> 4)) & 7);
+            const int ks = min(2 * p + (c >> 2), st.KS - 1);
+            const int cc = (ks * KF + (c & 3) * EPC < st.K) ? (c & 3) : 0;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(xslot + j * 1024), 16,
+                                                     static_cast<int>(st.xoff[j]) - c * 16 + ks * 64 + cc * 16, 0, 0, 0);
+        }
+    }
+    const uint32_t lane16 = lane * 16;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int ks = min(2 * p + e, st.KS - 1);                // padding repeats the last fragment
+#pragma unroll
+        for (int f = 0; f < NFR; ++f) sl.w[e][f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024 + lane16);
+    }
+}
+
+template <int DT, int MB, int NFR, int U>
+__device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int i, int wave, int lane, const skinny_slot<NFR>& sl,
+                                           char* xslot_generic, v4f (&acc)[NFR][MB])
+{
+    ldsptr xslot = (ldsptr)xslot_generic;
+    // every load issued after this slot's belongs to one of the U - 1 slots filled since
+    wait_vmcnt<(U - 1) * (2 * NFR + 2 * MB)>();
+    __builtin_amdgcn_sched_barrier(0);
+    const int r = lane & 15, q = lane >> 4;
+    v4i x[2][MB];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int fm = 0; fm < MB; ++fm)
+            x[e][fm] = *reinterpret_cast<lds_v4i>(xslot + (fm * 16 + r) * 128 + (((e * 4 + q) ^ ((r >> 1) & 7)) << 4));
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         if (2 * (wave + 4 * i) + e < st.KS) {
 #pragma unroll
             for (int f = 0; f < NFR; ++f)
 #pragma unroll
-                for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], sl.w[e][f], sl.x[e][fm]);
+                for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], sl.w[e][f], x[e][fm]);
         }
     }
 }
@@ -661,41 +700,50 @@ __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int ou
                                               v4f (&acc)[NFR][MB], int wave, int lane, char* lds)
 {
     const int r = lane & 15, q = lane >> 4;
-    v4f* red = reinterpret_cast<v4f*>(lds);                      // red[wave][f][fm][lane]: up to 4*8*4 KiB
-    __syncthreads();                                             // the previous tile's sums have been read
-#pragma unroll
-    for (int f = 0; f < NFR; ++f)
-#pragma unroll
-        for (int fm = 0; fm < MB; ++fm) red[((wave * NFR + f) * MB + fm) * 64 + lane] = acc[f][fm];
-    __syncthreads();
+    // red[wave][block of the pass][fm][lane]: at most 64 KiB, so the widest tile takes two passes
+    constexpr int PASSES = (NFR * MB * 4096 + RING_LDS_OFFSET - 1) / RING_LDS_OFFSET;
+    constexpr int NP = NFR / PASSES;                             // column blocks per pass
+    v4f* red = reinterpret_cast<v4f*>(lds);
     const bool vec_ok = (ga.N & 3) == 0;
     const int M = ga.M;
-    if constexpr (GATED) {                                       // units (hidden column block p, row block fm)
-        constexpr int UNITS = (NFR / 2) * MB;
-        for (int unit = wave; unit < UNITS; unit += 4) {
-            const int p = unit / MB, fm = unit % MB;
-            if (fm * 16 >= M || p * 16 >= cols) continue;
-            v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                g += red[((w * NFR + p) * MB + fm) * 64 + lane];
-                u += red[((w * NFR + NFR / 2 + p) * MB + fm) * 64 + lane];
-            }
-            finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
+    for (int pass = 0; pass < PASSES; ++pass) {
+        __syncthreads();                                         // the previous sums have been read
+#pragma unroll
+        for (int fi = 0; fi < NP; ++fi) {
+            // gated: a pass holds NP/2 gate blocks and the matching up blocks
+            const int f = GATED ? (fi < NP / 2 ? pass * (NP / 2) + fi : NFR / 2 + pass * (NP / 2) + fi - NP / 2) : pass * NP + fi;
+#pragma unroll
+            for (int fm = 0; fm < MB; ++fm) red[((wave * NP + fi) * MB + fm) * 64 + lane] = acc[f][fm];
         }
-    } else {                                                     // units (column block f, row block fm)
-        constexpr int UNITS = NFR * MB;
-        with_act(ga.act, [&](auto tag) {
+        __syncthreads();
+        if constexpr (GATED) {                                   // units (hidden column block p, row block fm)
+            constexpr int UNITS = (NP / 2) * MB;
             for (int unit = wave; unit < UNITS; unit += 4) {
-                const int f = unit / MB, fm = unit % MB;
-                if (fm * 16 >= M || f * 16 >= cols) continue;
-                v4f s0 = {0.f, 0.f, 0.f, 0.f};
+                const int pi = unit / MB, fm = unit % MB, p = pass * (NP / 2) + pi;
+                if (fm * 16 >= M || p * 16 >= cols) continue;
+                v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int w = 0; w < 4; ++w) s0 += red[((w * NFR + f) * MB + fm) * 64 + lane];
-                finish_plain<decltype(tag)::value>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
-                                                   fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
+                for (int w = 0; w < 4; ++w) {
+                    g += red[((w * NP + pi) * MB + fm) * 64 + lane];
+                    u += red[((w * NP + NP / 2 + pi) * MB + fm) * 64 + lane];
+                }
+                finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
             }
-        });
+        } else {                                                 // units (column block f, row block fm)
+            constexpr int UNITS = NP * MB;
+            with_act(ga.act, [&](auto tag) {
+                for (int unit = wave; unit < UNITS; unit += 4) {
+                    const int fi = unit / MB, fm = unit % MB, f = pass * NP + fi;
+                    if (fm * 16 >= M || f * 16 >= cols) continue;
+                    v4f s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) s0 += red[((w * NP + fi) * MB + fm) * 64 + lane];
+                    finish_plain<decltype(tag)::value>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
+                                                       fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
+                }
+            });
+        }
     }
 }
 
@@ -721,9 +769,15 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
     epara_group_args ga = args[tl.group];
     skinny_tile_state<NFR> cur, nxt;
     skinny_setup<DT, GATED, MB, NFR, U>(cur, ga, tl.n0, lane);
-    skinny_slot<MB, NFR> ring[U];
+    skinny_slot<NFR> ring[U];
+    constexpr int XSLOT_BYTES = MB * 2048;
+    char* xring = lds + RING_LDS_OFFSET + wave * (U * XSLOT_BYTES);
+    static_assert(RING_LDS_OFFSET + 4 * U * XSLOT_BYTES <= LDS_BYTES, "activation rings do not fit");
+    // The rings overlay whatever used this part of the LDS before (a panel tile's epilogue, the
+    // rings of another streaming class, whose last refills every wave has waited for below).
+    __syncthreads();
 #pragma unroll
-    for (int u = 0; u < U; ++u) skinny_load<DT, MB, NFR>(cur, u, wave, lane, ring[u]);
+    for (int u = 0; u < U; ++u) skinny_load<DT, MB, NFR>(cur, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
     __builtin_amdgcn_sched_barrier(0);
 
     for (;;) {
@@ -745,9 +799,9 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         for (int c = 0; c + 1 < cur.n_chunks; ++c) {             // refill from this tile
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                skinny_mma<DT, MB, NFR>(cur, c * U + u, wave, ring[u], acc);
+                skinny_mma<DT, MB, NFR, U>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
                 __builtin_amdgcn_sched_barrier(0);
-                skinny_load<DT, MB, NFR>(cur, (c + 1) * U + u, wave, lane, ring[u]);
+                skinny_load<DT, MB, NFR>(cur, (c + 1) * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -755,9 +809,9 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
             const int c = cur.n_chunks - 1;                      // last chunk: refill from the next tile
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                skinny_mma<DT, MB, NFR>(cur, c * U + u, wave, ring[u], acc);
+                skinny_mma<DT, MB, NFR, U>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
                 __builtin_amdgcn_sched_barrier(0);
-                skinny_load<DT, MB, NFR>(nxt, u, wave, lane, ring[u]);
+                skinny_load<DT, MB, NFR>(nxt, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -768,6 +822,7 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         ga = ga_next;
         cur = nxt;
     }
+    wait_vmcnt<0>();                                             // the last refill (unused data) has landed in the rings
     // first slot after this run: the next non-idle slot of this workgroup or the end
     for (slot += stride; slot < n_slots && order[slot] < 0; slot += stride) {}
     return slot;

@@ -77,7 +77,11 @@ def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
 class LaunchPlan:
     """Host plan + its device copy for one grouped launch (epara_launch)."""
 
-    def __init__(self, args, in_dtype, device, n_workgroups=None, n_xcd=8, panel_m=8, panel_n=4):
+    def __init__(self, args, in_dtype, device, n_workgroups=None, n_xcd=8, panel_m=1, panel_n=4):
+        # panel 1 x 4: panel tiles are visited strip by strip (4 tile columns), row by row, so the 32
+        # tiles that run together on one die are 8 whole rows of a strip wherever a strip begins
+        # (with 8 x 4 panels a group whose rows are not a multiple of 8 tiles shifts every later
+        # panel across two dies, and each die then fetches more rows and columns than 8 + 4).
         _require_gpu()
         t0 = time.perf_counter()
         self.args = np.ascontiguousarray(args, dtype=B.GROUP_ARGS)
