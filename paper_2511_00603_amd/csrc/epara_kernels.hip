@@ -669,13 +669,13 @@ __device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, in
     }
 }
 
-template <int DT, int MB, int NFR, int U>
+template <int DT, int MB, int NFR, int AFTER>
 __device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int i, int wave, int lane, const skinny_slot<NFR>& sl,
                                            char* xslot_generic, v4f (&acc)[NFR][MB])
 {
     ldsptr xslot = (ldsptr)xslot_generic;
-    // every load issued after this slot's belongs to one of the U - 1 slots filled since
-    wait_vmcnt<(U - 1) * (2 * NFR + 2 * MB)>();
+    // every load issued after this slot's belongs to one of the AFTER slots filled since
+    wait_vmcnt<AFTER * (2 * NFR + 2 * MB)>();
     __builtin_amdgcn_sched_barrier(0);
     const int r = lane & 15, q = lane >> 4;
     v4i x[2][MB];
@@ -747,6 +747,18 @@ __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int ou
     }
 }
 
+// The last chunk of a run: slot I has U - 1 - I slots issued after it and nothing is refilled.
+template <int DT, int MB, int NFR, int U, int I>
+__device__ __forceinline__ void skinny_drain(const skinny_tile_state<NFR>& st, int c, int wave, int lane, const skinny_slot<NFR> (&ring)[U],
+                                             char* xring, v4f (&acc)[NFR][MB])
+{
+    if constexpr (I < U) {
+        skinny_mma<DT, MB, NFR, U - 1 - I>(st, c * U + I, wave, lane, ring[I], xring + I * (MB * 2048), acc);
+        __builtin_amdgcn_sched_barrier(0);
+        skinny_drain<DT, MB, NFR, U, I + 1>(st, c, wave, lane, ring, xring, acc);
+    }
+}
+
 // Processes slot `slot` and every following slot of this workgroup that holds a tile of the same
 // streaming class.  Returns the first slot it did not process.
 template <int DT, bool GATED, int CLS, int MB, int NFR, int U>
@@ -756,15 +768,6 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    auto next_tile = [&](long s) {          // next slot of this workgroup holding a tile of this class, else -1
-        for (s += stride; s < n_slots; s += stride) {
-            const int t = order[s];
-            if (t < 0) continue;
-            return tiles[t].cls == CLS ? s : -1L;
-        }
-        return -1L;
-    };
-
     epara_tile tl = tiles[order[slot]];
     epara_group_args ga = args[tl.group];
     skinny_tile_state<NFR> cur, nxt;
@@ -774,23 +777,27 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
     char* xring = lds + RING_LDS_OFFSET + wave * (U * XSLOT_BYTES);
     static_assert(RING_LDS_OFFSET + 4 * U * XSLOT_BYTES <= LDS_BYTES, "activation rings do not fit");
     // The rings overlay whatever used this part of the LDS before (a panel tile's epilogue, the
-    // rings of another streaming class, whose last refills every wave has waited for below).
+    // rings of another streaming class: a run ends with every slot consumed, nothing in flight).
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < U; ++u) skinny_load<DT, MB, NFR>(cur, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
     __builtin_amdgcn_sched_barrier(0);
 
     for (;;) {
-        const long slot_next = next_tile(slot);
+        // What follows this tile in the workgroup's list (a list has no holes, so an idle slot ends
+        // it) is found by three dependent scalar loads: order -> tile -> group arguments.  Each
+        // link is issued after one chunk of the tile and read after the next, so that its latency
+        // passes while the wave waits for weights anyway instead of stopping the stream.
+        int t_next = -1, stage = 0;
+        bool have_next = false;
         epara_tile tl_next = tl;
         epara_group_args ga_next = ga;
-        if (slot_next >= 0) {
-            tl_next = tiles[order[slot_next]];
-            ga_next = args[tl_next.group];
-            skinny_setup<DT, GATED, MB, NFR, U>(nxt, ga_next, tl_next.n0, lane);
-        } else {
-            nxt = cur;                                           // nothing follows: the ring is refilled with valid, unused data
-        }
+        auto advance = [&]() {
+            if (stage == 0)      { const long s1 = slot + stride; t_next = s1 < n_slots ? order[s1] : -1; }
+            else if (stage == 1) { if (t_next >= 0) tl_next = tiles[t_next]; }
+            else                 { have_next = t_next >= 0 && tl_next.cls == CLS; if (have_next) ga_next = args[tl_next.group]; }
+            ++stage;
+        };
         v4f acc[NFR][MB];
 #pragma unroll
         for (int f = 0; f < NFR; ++f)
@@ -799,21 +806,28 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         for (int c = 0; c + 1 < cur.n_chunks; ++c) {             // refill from this tile
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                skinny_mma<DT, MB, NFR, U>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
+                skinny_mma<DT, MB, NFR, U - 1>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
                 __builtin_amdgcn_sched_barrier(0);
                 skinny_load<DT, MB, NFR>(cur, (c + 1) * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (stage < 3) advance();
+            __builtin_amdgcn_sched_barrier(0);
         }
-        {
-            const int c = cur.n_chunks - 1;                      // last chunk: refill from the next tile
+        while (stage < 3) advance();                             // short tiles: the rest of the chain at once
+        const long slot_next = have_next ? slot + stride : -1L;
+        const int c_last = cur.n_chunks - 1;
+        if (have_next) {                                         // last chunk: refill from the next tile
+            skinny_setup<DT, GATED, MB, NFR, U>(nxt, ga_next, tl_next.n0, lane);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                skinny_mma<DT, MB, NFR, U>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
+                skinny_mma<DT, MB, NFR, U - 1>(cur, c_last * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
                 __builtin_amdgcn_sched_barrier(0);
                 skinny_load<DT, MB, NFR>(nxt, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        } else {                                                 // nothing follows: the ring drains
+            skinny_drain<DT, MB, NFR, U, 0>(cur, c_last, wave, lane, ring, xring, acc);
         }
         skinny_finish<DT, GATED, MB, NFR>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
         if (slot_next < 0) break;
@@ -822,7 +836,6 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         ga = ga_next;
         cur = nxt;
     }
-    wait_vmcnt<0>();                                             // the last refill (unused data) has landed in the rings
     // first slot after this run: the next non-idle slot of this workgroup or the end
     for (slot += stride; slot < n_slots && order[slot] < 0; slot += stride) {}
     return slot;
