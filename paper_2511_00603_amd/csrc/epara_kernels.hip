@@ -568,20 +568,22 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
 
 // Small batches are bandwidth bound: the weights are streamed from HBM exactly once, straight
 // into MFMA operand registers (each load instruction of a wave reads 1 KiB of consecutive packed
-// weights), while the activations are re-read from L2 by every tile.  To keep that re-read at
-// half the weight traffic, a tile of streaming class c = 0, 1, 2 pairs MB = 1, 2, 4 blocks of 16
-// rows (the whole batch) with NFR = 2, 4, 8 weight column blocks: 32 / 64 / 128 output columns,
-// or for gated groups NFR/2 gate blocks and the matching NFR/2 up blocks (16 / 32 / 64 hidden
-// columns).  K is walked in steps of two packed fragments (128 bytes of every activation row,
-// so a row's cache line is used whole); wave w takes the steps p = w, w+4, ....  The four
-// partial sums meet in LDS and are added in wave order: the result does not depend on timing.
+// weights), while the activations are re-read from L2 by every tile, through a small LDS ring per
+// wave (see skinny_setup).  To keep that re-read at half the weight traffic, a tile of streaming
+// class c = 0, 1, 2 pairs MB = 1, 2, 4 blocks of 16 rows (the whole batch) with NFR = 2, 4, 8
+// weight column blocks: 32 / 64 / 128 output columns, or for gated groups NFR/2 gate blocks and
+// the matching NFR/2 up blocks (16 / 32 / 64 hidden columns).  K is walked in steps of two packed
+// fragments (128 bytes of every activation row, so a row's cache line is used whole); wave w takes
+// the steps p = w, w+4, ....  The four partial sums meet in LDS and are added in wave order: the
+// result does not depend on timing.
 //
 // Consecutive tiles of one class that a workgroup owns are processed as one software-pipelined
-// stream: a ring of U register slots per wave stays full across tile boundaries, so the loads
-// of the next tile are in flight while this tile is reduced and stored.  Every tile is padded
-// to a whole number of U steps; padding steps, rows past the batch and column blocks past N
-// re-load a valid address and are not multiplied / not stored.  The scheduling barriers keep
-// the compiler from sinking the prefetch loads down to their first use.
+// stream: a ring of U slots per wave (weights in registers, activations in LDS) stays full across
+// tile boundaries, so the loads of the next tile are in flight while this tile is reduced and
+// stored; the last tile of a run drains the ring.  Every tile is padded to a whole number of U
+// steps; padding steps, rows past the batch and column blocks past N re-load a valid address and
+// are not multiplied / not stored.  The scheduling barriers keep the compiler from sinking the
+// prefetch loads down to their first use.
 template <int NFR>
 struct skinny_tile_state {
     gcptr w[NFR];          // uniform: start of each weight column block's fragment stream

@@ -3,6 +3,7 @@ short text summaries kept under profiles/ and into profiles/traffic.json.
 
     python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt
     python -m paper_2511_00603_amd.profile_summary traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
+    python -m paper_2511_00603_amd.profile_summary report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
 
 Per-launch figures: the launches of one pass alternate (launch 0, launch 1, ...), so dispatch i of
 grouped_kernel belongs to launch i mod L.  HBM traffic of a launch = counter value (KiB) x 1024 x
@@ -96,8 +97,31 @@ def lookup_traffic(workload, launch):
     return None
 
 
+def report(out_dir, workload, mix, dtype, launches_per_pass=2):
+    """profiles/grouped_kernel_WORKLOAD.txt and the WORKLOAD entry of profiles/traffic.json from the three
+    runs of the profile driver (kernel trace with 8 passes, FETCH_SIZE and WRITE_SIZE with 4 passes each)."""
+    drv = "python3 -m paper_2511_00603_amd.profile_driver %s %s" % (mix, dtype)
+    txt = os.path.join(ROOT, "profiles", "grouped_kernel_%s.txt" % workload)
+    kernels(os.path.join(out_dir, "run_kernel_trace.csv"),
+            "rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- %s 8" % drv, txt, launches_per_pass)
+    traffic(os.path.join(out_dir, "fetch_counter_collection.csv"), os.path.join(out_dir, "write_counter_collection.csv"),
+            workload, launches_per_pass)
+    rec = json.load(open(TRAFFIC_JSON))[workload]
+    L = ["", "HBM-side traffic per launch (profiles/traffic.json, kernel source %s), from" % rec["kernel_source_sha256_16"],
+         "  rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- %s 4" % drv,
+         "  rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT -o write -- %s 4" % drv,
+         "each scaled by what the same counter reads for the 1 GiB copy kernel of the same run (fetch x %.3f, write x %.3f):"
+         % (rec["fetch_scale"], rec["write_scale"])]
+    for l in rec["launches"]:
+        L.append("  launch %d: fetch %.3f GB, write %.3f GB" % (l["launch"], l["fetch_bytes"] / 1e9, l["write_bytes"] / 1e9))
+    open(txt, "a").write("\n".join(L) + "\n")
+    print("\n".join(L))
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "kernels":
+    if sys.argv[1] == "report":
+        report(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], int(sys.argv[6]) if len(sys.argv) > 6 else 2)
+    elif sys.argv[1] == "kernels":
         kernels(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2)
     elif sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2)
