@@ -105,6 +105,18 @@ typedef struct {
     float s_x, s_wgate, s_wup, s_h, s_wdown;   /* per-tensor fp8 scales; ignored (1) otherwise */
 } epara_ffn_desc;
 
+/* One contiguous run of rows that moves between a request's own buffer and its place in the
+ * ragged batch of its service (Sec. 3.1 BS / MF: a batch is formed from the rows of many requests
+ * and its result rows go back to them).  40 bytes; the same bytes on host and device. */
+typedef struct {
+    const void* src;           /* device */
+    void*       dst;           /* device */
+    int64_t     bytes;         /* of the source; a multiple of 16, may be 0 */
+    int64_t     first_chunk;   /* 16-KiB chunks of all earlier segments: sum ceil(bytes / 16384) */
+    int32_t     group;         /* the service whose batch this run belongs to */
+    int32_t     reserved;
+} epara_segment;
+
 /* ---- host side: batch accounting and planning (integers only, deterministic) ---------- */
 
 /* Batch accounting (Sec. 3.1 BS / MF; Sec. 4.1): service g owns requests
@@ -113,6 +125,23 @@ typedef struct {
  * before request r.  ERR_SHAPE on a negative count, a decreasing offset or an M beyond int32. */
 int32_t epara_batch_rows(const int32_t* request_rows, const int64_t* request_off, int32_t G,
                          int32_t* M, int64_t* first_row);
+
+/* Batch forming (Sec. 3.1 BS / MF), the copy plan.  Requests are numbered as in epara_batch_rows;
+ * request r of service g brings request_rows[r] rows of request_row_bytes[g] bytes in its own buffer
+ * request_ptr[r]; the batch of service g is batch_ptr[g], dense rows of batch_row_bytes[g] bytes
+ * (the same as request_row_bytes for a copy; a quarter or half of it when the rows are
+ * quantised to one byte per element on the way).  With at = batch_ptr[g] + first_row[r] * batch_row_bytes[g]:
+ *   to_batch != 0 (gather):  src = request_ptr[r], dst = at, bytes = request_rows[r] * request_row_bytes[g]
+ *   to_batch == 0 (scatter): src = at, dst = request_ptr[r], bytes = request_rows[r] * batch_row_bytes[g]
+ * first_chunk = running sum of ceil(bytes / 16384); group = g.  One segment per request, in request
+ * order (requests without rows give bytes = 0).  *n_chunks receives the total.  Pointers are only
+ * computed with, never dereferenced.
+ * Errors: ERR_NULL; ERR_SHAPE for a negative count, a decreasing offset or a row size <= 0;
+ * ERR_ALIGN if a row size is not a multiple of 16. */
+int32_t epara_request_segments(const int32_t* request_rows, const int64_t* request_off, int32_t G,
+                               const int64_t* request_row_bytes, const int64_t* batch_row_bytes,
+                               const void* const* request_ptr, const void* const* batch_ptr, int32_t to_batch,
+                               epara_segment* segments, int64_t* n_chunks);
 
 /* Sec. 4.1, Eq. "DP group count" = ceil(required rate / rate of one group); -1 on bad input. */
 int64_t epara_dp_group_count(int64_t rate_required, int64_t rate_of_one_group);
@@ -205,6 +234,38 @@ int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int3
  * FP8_E4M3 (codes sat(RNE(h / s_h))), out_dtype = BF16. */
 int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
                                  int32_t in_dtype, int32_t h_dtype, int32_t out_dtype, void* stream);
+
+/* ---- device side: the step before and after the path (batch forming) --------------------- */
+
+/* Copies every segment (gather of request rows into the batches, or scatter of result rows back):
+ * dst[0..bytes) = src[0..bytes).  One kernel; a workgroup copies 16-KiB chunks and finds the
+ * segment of a chunk by bisection over first_chunk.  n_segments = 0 or n_chunks = 0 enqueues nothing.
+ * Validates h_segments: ERR_NULL (src or dst NULL with bytes > 0), ERR_SHAPE (negative bytes,
+ * first_chunk not the running sum, n_chunks not the total), ERR_ALIGN (pointer or bytes not a
+ * multiple of 16). */
+int32_t epara_copy_segments(const epara_segment* h_segments, const epara_segment* d_segments,
+                            int64_t n_segments, int64_t n_chunks, void* stream);
+
+/* Gather with dynamic per-tensor fp8 quantisation: the rows of all requests of service g are one
+ * tensor; d_amax[g] = max |x| over it, d_scale[g] = d_amax[g] / 448 (1 if the tensor is all zero or
+ * empty), and dst receives the E4M3 codes sat(RNE(x / d_scale[g])) (quotient and rounding in
+ * fp32; one byte per source element, so dst holds bytes / sizeof(src element)).  src_dtype is
+ * EPARA_F32 or EPARA_BF16.  d_amax and d_scale are float[G] outputs in device memory.  Four
+ * kernels on `stream`: clear, amax (integer max on the bit patterns: order independent),
+ * scales, quantise.  Validation as for epara_copy_segments plus ERR_DTYPE and ERR_SHAPE for a
+ * group index outside [0, G).  A NaN in the input gives unspecified codes for its tensor. */
+int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epara_segment* d_segments,
+                                     int64_t n_segments, int64_t n_chunks, int32_t G, int32_t src_dtype,
+                                     float* d_amax, float* d_scale, void* stream);
+
+/* Writes scale products computed on the device into the device copy of the group arguments, so
+ * that a launch can use scales that only exist in device memory (dynamic quantisation):
+ *   d_args[g].scale = d_sx[g] * d_sw[g];  if d_sw2: d_args[g].scale2 = d_sx[g] * d_sw2[g];
+ *   if d_sout: d_args[g].out_inv_scale = 1 / d_sout[g].
+ * d_sx, d_sw: float[G] (required); d_sw2, d_sout may be NULL (fields left as they are).  The host
+ * copy h_args is not touched: launch validation does not read the scale fields. */
+int32_t epara_patch_scales(epara_group_args* d_args, int32_t G, const float* d_sx, const float* d_sw,
+                           const float* d_sw2, const float* d_sout, void* stream);
 
 /* ---- measurement helpers (not part of the forward path) ------------------------------------- */
 

@@ -19,6 +19,7 @@ tile class         the first class c with M_g <= max_M[c]
 canonical tiles    for g ascending, m0 = 0, BM, 2BM, ... < M_g, n0 = 0, BN, ... < N_g:
                    (g, m0, n0, rows=min(BM, M_g-m0), cols=min(BN, N_g-n0), c)
 visit order        see `schedule_tiles` (panel tiles die by die, streaming tiles longest first).
+batch forming      see `request_segments` (where each request's rows go in its service's batch).
 """
 
 INT32_MAX = 2**31 - 1
@@ -37,6 +38,30 @@ def batch_rows(request_rows_per_service):
         M.append(acc)
         first.append(starts)
     return M, first
+
+
+def request_segments(request_rows_per_service, request_row_bytes, batch_row_bytes, request_ptr_per_service, batch_ptr, to_batch):
+    """The copy plan of batch forming: one (src, dst, bytes, first_chunk, group) per request, in
+    request order.  A request's rows sit in the batch of its service after the rows of the
+    service's earlier requests (rows of batch_row_bytes[g] bytes there, of request_row_bytes[g] in
+    the request's own buffer: the two differ when the rows are quantised on the way); bytes
+    counts the source side; first_chunk counts the 16-KiB chunks of all earlier segments."""
+    segs, chunks = [], 0
+    for g, reqs in enumerate(request_rows_per_service):
+        for rb in (request_row_bytes[g], batch_row_bytes[g]):
+            if rb <= 0 or rb % 16:
+                raise ValueError("row size must be a positive multiple of 16 bytes")
+        first = 0
+        for i, rows in enumerate(reqs):
+            if rows < 0:
+                raise ValueError("negative row count")
+            in_batch = batch_ptr[g] + first * batch_row_bytes[g]
+            own = request_ptr_per_service[g][i]
+            nbytes = rows * (request_row_bytes[g] if to_batch else batch_row_bytes[g])
+            segs.append((own, in_batch, nbytes, chunks, g) if to_batch else (in_batch, own, nbytes, chunks, g))
+            chunks += -(-nbytes // 16384)
+            first += rows
+    return segs, chunks
 
 
 def dp_group_count(rate_required, rate_of_one_group):

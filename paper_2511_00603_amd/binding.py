@@ -31,7 +31,8 @@ GROUP_ARGS = np.dtype([("X", "<u8"), ("W", "<u8"), ("W2", "<u8"), ("bias", "<u8"
 FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "<u8"), ("H", "<u8"), ("Y", "<u8"),
                      ("M", "<i4"), ("d_model", "<i4"), ("d_ff", "<i4"),
                      ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
-assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24
+SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<i8"), ("first_chunk", "<i8"), ("group", "<i4"), ("reserved", "<i4")])
+assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
 assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
 
 
@@ -84,13 +85,18 @@ def lib():
         L.epara_pack_weights.argtypes = [vp, i32, i32, i32, vp, i64, vp]
         L.epara_grouped_forward.argtypes = [vp, i32, i32, vp]
         L.epara_grouped_ffn_swiglu.argtypes = [vp, vp, i32, i32, i32, vp]
+        L.epara_request_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, vp]
+        L.epara_copy_segments.argtypes = [vp, vp, i64, i64, vp]
+        L.epara_quantize_segments_e4m3.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
+        L.epara_patch_scales.argtypes = [vp, i32, vp, vp, vp, vp, vp]
         L.epara_probe_read.argtypes = [vp, i64, vp, i32, vp]
         L.epara_probe_copy.argtypes = [vp, vp, i64, vp]
         L.epara_probe_mfma.argtypes = [vp, i32, vp, i32, vp]
         for name in ("epara_probe_read", "epara_probe_copy", "epara_probe_mfma"):
             getattr(L, name).restype = i32
         for name in ("epara_batch_rows", "epara_plan_groups", "epara_schedule_tiles", "epara_kernel_classes",
-                     "epara_ffn_swiglu_args", "epara_pack_weights", "epara_grouped_forward", "epara_grouped_ffn_swiglu"):
+                     "epara_ffn_swiglu_args", "epara_pack_weights", "epara_grouped_forward", "epara_grouped_ffn_swiglu",
+                     "epara_request_segments", "epara_copy_segments", "epara_quantize_segments_e4m3", "epara_patch_scales"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -119,6 +125,40 @@ def epara_batch_rows(request_rows, request_off):
     first = np.zeros(len(request_rows), dtype=np.int64)
     _check(lib().epara_batch_rows(_ptr(request_rows), _ptr(request_off), G, _ptr(M), _ptr(first)), "epara_batch_rows")
     return M, first
+
+
+def epara_request_segments(request_rows, request_off, request_row_bytes, batch_row_bytes, request_ptr, batch_ptr, to_batch):
+    """-> (segments SEGMENT[R], n_chunks).  request_ptr / batch_ptr: integer device addresses."""
+    request_rows = np.ascontiguousarray(request_rows, dtype=np.int32)
+    request_off = np.ascontiguousarray(request_off, dtype=np.int64)
+    request_row_bytes = np.ascontiguousarray(request_row_bytes, dtype=np.int64)
+    batch_row_bytes = np.ascontiguousarray(batch_row_bytes, dtype=np.int64)
+    request_ptr = np.ascontiguousarray(request_ptr, dtype=np.uint64)
+    batch_ptr = np.ascontiguousarray(batch_ptr, dtype=np.uint64)
+    G = len(request_off) - 1
+    segs = np.zeros(len(request_rows), dtype=SEGMENT)
+    n = np.zeros(1, dtype=np.int64)
+    _check(lib().epara_request_segments(_ptr(request_rows), _ptr(request_off), G, _ptr(request_row_bytes), _ptr(batch_row_bytes), _ptr(request_ptr),
+                                        _ptr(batch_ptr), int(bool(to_batch)), _ptr(segs), _ptr(n)), "epara_request_segments")
+    return segs, int(n[0])
+
+
+def epara_copy_segments(h_segments, d_segments, n_chunks, stream=0):
+    h_segments = np.ascontiguousarray(h_segments, dtype=SEGMENT)
+    _check(lib().epara_copy_segments(_ptr(h_segments), int(d_segments) or None, len(h_segments), int(n_chunks),
+                                     int(stream) or None), "epara_copy_segments")
+
+
+def epara_quantize_segments_e4m3(h_segments, d_segments, n_chunks, G, src_dtype, d_amax, d_scale, stream=0):
+    h_segments = np.ascontiguousarray(h_segments, dtype=SEGMENT)
+    _check(lib().epara_quantize_segments_e4m3(_ptr(h_segments), int(d_segments) or None, len(h_segments), int(n_chunks), int(G),
+                                              int(src_dtype), int(d_amax) or None, int(d_scale) or None, int(stream) or None),
+           "epara_quantize_segments_e4m3")
+
+
+def epara_patch_scales(d_args, G, d_sx, d_sw, d_sw2=0, d_sout=0, stream=0):
+    _check(lib().epara_patch_scales(int(d_args) or None, int(G), int(d_sx) or None, int(d_sw) or None, int(d_sw2) or None,
+                                    int(d_sout) or None, int(stream) or None), "epara_patch_scales")
 
 
 def epara_dp_group_count(rate_required, rate_of_one_group):

@@ -4,9 +4,10 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = [os.path.join(HERE, "csrc", "epara_kernels.hip"), os.path.join(HERE, "csrc", "epara_probe.hip"),
-           os.path.join(HERE, "csrc", "epara_host.cpp")]
+SOURCES = [os.path.join(HERE, "csrc", "epara_kernels.hip"), os.path.join(HERE, "csrc", "epara_rows.hip"),
+           os.path.join(HERE, "csrc", "epara_probe.hip"), os.path.join(HERE, "csrc", "epara_host.cpp")]
 HEADER = os.path.join(ROOT, "include", "epara.h")
+CAST_HEADER = os.path.join(HERE, "csrc", "epara_cast.h")
 LIB = os.path.join(HERE, "libepara.so")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -18,7 +19,7 @@ def is_stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > t for p in SOURCES + [HEADER])
+    return any(os.path.getmtime(p) > t for p in SOURCES + [HEADER, CAST_HEADER])
 
 
 def build(force=True, verbose=False):

@@ -78,6 +78,42 @@ int32_t epara_batch_rows(const int32_t* request_rows, const int64_t* request_off
     return EPARA_OK;
 }
 
+int32_t epara_request_segments(const int32_t* request_rows, const int64_t* request_off, int32_t G,
+                               const int64_t* request_row_bytes, const int64_t* batch_row_bytes,
+                               const void* const* request_ptr, const void* const* batch_ptr, int32_t to_batch,
+                               epara_segment* segments, int64_t* n_chunks)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (!n_chunks) return EPARA_ERR_NULL;
+    *n_chunks = 0;
+    if (G == 0) return EPARA_OK;
+    if (!request_off || !request_row_bytes || !batch_row_bytes || !batch_ptr) return EPARA_ERR_NULL;
+    if (request_off[0] < 0) return EPARA_ERR_SHAPE;
+    int64_t chunks = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const int64_t lo = request_off[g], hi = request_off[g + 1];
+        if (hi < lo || request_row_bytes[g] <= 0 || batch_row_bytes[g] <= 0) return EPARA_ERR_SHAPE;
+        if (request_row_bytes[g] % 16 || batch_row_bytes[g] % 16) return EPARA_ERR_ALIGN;
+        if (hi > lo && (!request_rows || !request_ptr || !segments)) return EPARA_ERR_NULL;
+        int64_t first_row = 0;
+        for (int64_t r = lo; r < hi; ++r) {
+            if (request_rows[r] < 0) return EPARA_ERR_SHAPE;
+            const char* in_batch = static_cast<const char*>(batch_ptr[g]) + first_row * batch_row_bytes[g];
+            epara_segment& sg = segments[r];
+            sg.src = to_batch ? request_ptr[r] : in_batch;
+            sg.dst = const_cast<void*>(to_batch ? static_cast<const void*>(in_batch) : request_ptr[r]);
+            sg.bytes = static_cast<int64_t>(request_rows[r]) * (to_batch ? request_row_bytes[g] : batch_row_bytes[g]);
+            sg.first_chunk = chunks;
+            sg.group = g;
+            sg.reserved = 0;
+            chunks += ceil_div(sg.bytes, 16384);
+            first_row += request_rows[r];
+        }
+    }
+    *n_chunks = chunks;
+    return EPARA_OK;
+}
+
 int64_t epara_dp_group_count(int64_t rate_required, int64_t rate_of_one_group)
 {
     if (rate_required < 0 || rate_of_one_group <= 0) return -1;

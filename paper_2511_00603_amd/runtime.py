@@ -128,3 +128,45 @@ def grouped_forward(plan, out_dtype, stream=None):
 def grouped_ffn_swiglu(up, down, h_dtype, out_dtype, stream=None):
     B.epara_grouped_ffn_swiglu(up.c, down.c, up.in_dtype, h_dtype, out_dtype,
                                current_stream_handle() if stream is None else stream)
+
+
+# ---- batch forming (the step before and after the grouped forward) ---------------------------------
+
+class SegmentPlan:
+    """Copy plan between the requests' own buffers and the services' batches (epara_request_segments),
+    host copy + device copy.  request_tensors[g] = list of [rows_r, width] device tensors of service g,
+    batch_tensors[g] = [M_g, width] device tensor."""
+
+    def __init__(self, request_tensors, batch_tensors, to_batch, device):
+        _require_gpu()
+        rows, off, ptrs, row_bytes, batch_row_bytes, bptr = [], [0], [], [], [], []
+        for reqs, batch in zip(request_tensors, batch_tensors):
+            for t in reqs:
+                rows.append(t.shape[0])
+                ptrs.append(t.data_ptr() if t.shape[0] else 0)
+            off.append(len(rows))
+            row_bytes.append((reqs[0].shape[1] * reqs[0].element_size()) if reqs else 16)
+            batch_row_bytes.append((batch.shape[1] * batch.element_size()) if batch is not None and batch.dim() == 2 else row_bytes[-1])
+            bptr.append(batch.data_ptr() if batch is not None else 0)
+        self.G = len(batch_tensors)
+        self.segments, self.n_chunks = B.epara_request_segments(rows, off, row_bytes, batch_row_bytes, ptrs, bptr, to_batch)
+        self.d_segments = _upload(self.segments, device)
+        self.bytes = int(self.segments["bytes"].sum())
+
+
+def copy_segments(plan, stream=None):
+    B.epara_copy_segments(plan.segments, plan.d_segments.data_ptr(), plan.n_chunks,
+                          current_stream_handle() if stream is None else stream)
+
+
+def quantize_segments_e4m3(plan, src_dtype, d_amax, d_scale, stream=None):
+    """plan: SegmentPlan whose destinations are the uint8 code tensors; d_amax, d_scale: float32[G] device tensors."""
+    B.epara_quantize_segments_e4m3(plan.segments, plan.d_segments.data_ptr(), plan.n_chunks, plan.G, src_dtype,
+                                   d_amax.data_ptr(), d_scale.data_ptr(), current_stream_handle() if stream is None else stream)
+
+
+def patch_scales(launch_plan, d_sx, d_sw, d_sw2=None, d_sout=None, stream=None):
+    """Scale products from device memory into the device copy of a launch's group arguments."""
+    ptr = lambda t: 0 if t is None else t.data_ptr()
+    B.epara_patch_scales(launch_plan.d_args.data_ptr(), len(launch_plan.args), ptr(d_sx), ptr(d_sw), ptr(d_sw2), ptr(d_sout),
+                         current_stream_handle() if stream is None else stream)
