@@ -153,6 +153,58 @@ def measure_peaks():
     return out
 
 
+def time_batch_forming(mix, steps, warmup):
+    """The step before and after the path on the prefill mix's own requests: every prompt's rows (bf16, in a
+    buffer of its own) gathered into its service's batch, gathered with dynamic per-tensor E4M3 quantisation,
+    and the result rows scattered back.  HBM-bound: bytes = what each variant has to move."""
+    import numpy as np
+    import torch
+    from paper_2511_00603_amd import binding as B
+    from paper_2511_00603_amd import runtime as R
+    from workloads import casts
+    dev = "cuda:0"
+    reqs, batches, codes = [], [], []
+    for svc in mix.services:
+        bits = casts.bf16_bits(svc.X)
+        at, mine = 0, []
+        for n in svc.request_rows:
+            mine.append(torch.from_numpy(bits[at:at + n].view(np.int16).copy()).to(dev).view(torch.bfloat16))
+            at += n
+        reqs.append(mine)
+        batches.append(torch.zeros(svc.X.shape, dtype=torch.bfloat16, device=dev))
+        codes.append(torch.zeros(svc.X.shape, dtype=torch.uint8, device=dev))
+    G = len(reqs)
+    gather, quant, scatter = R.SegmentPlan(reqs, batches, True, dev), R.SegmentPlan(reqs, codes, True, dev), R.SegmentPlan(reqs, batches, False, dev)
+    amax, scale = torch.zeros(G, dtype=torch.float32, device=dev), torch.zeros(G, dtype=torch.float32, device=dev)
+    src = gather.bytes
+    cases = {"gather_bf16": (lambda: R.copy_segments(gather), 2 * src),
+             "gather_quantize_e4m3": (lambda: R.quantize_segments_e4m3(quant, B.EPARA_BF16, amax, scale), 2 * src + src // 2),
+             "scatter_bf16": (lambda: R.copy_segments(scatter), 2 * src)}
+    out = {"rows": int(mix.rows), "requests": int(mix.requests), "source_bytes": int(src)}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, (fn, nbytes) in cases.items():
+        for _ in range(warmup):
+            fn()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / steps * 1e3
+        out[name] = {"us": us, "bytes": int(nbytes), "GBs": nbytes / us / 1e3, "frac_hbm": nbytes / us / 1e3 / HBM_PEAK_GBS}
+    # the numpy reference on the host, same requests
+    from oracle import reference as ref
+    from oracle import rows as RW
+    t0 = time.perf_counter()
+    for svc in mix.services:
+        x = ref.bf16_decode(casts.bf16_bits(svc.X)).astype(np.float32)
+        _a, sc = RW.amax_scale(x)
+        RW.quantize_e4m3(x, sc)
+    dt = time.perf_counter() - t0
+    out["cpu_reference"] = {"GBs": (2 * src + src // 2) / dt / 1e9, "kind": "oracle", "sample": "all rows, amax + quantise in numpy, %.1f s" % dt}
+    return out
+
+
 def cpu_baseline(mix, budget_s=15.0):
     """The oracle as it stands on the host cores, on a few rows of service 0 of the prefill mix (fp64)."""
     from oracle import reference as ref
@@ -196,7 +248,7 @@ def main():
         sys.exit(2)
 
     peaks = None if a.no_peaks else measure_peaks()
-    results, cache, cpu = [], {}, None
+    results, cache, cpu, forming = [], {}, None, None
     for tag in a.mixes.split(","):
         idx = int(tag[0])
         dtype_name = "fp8" if tag.endswith("fp8") else None
@@ -217,6 +269,8 @@ def main():
         results.append(time_mix(mix, dtype_name, a.steps, a.warmup, s_h))
         if idx == 5 and cpu is None and not a.no_cpu_baseline:
             cpu = cpu_baseline(mix)
+        if idx == 5 and forming is None:
+            forming = time_batch_forming(mix, a.steps, a.warmup)
         print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%" % (
             mix.name, dtype_name, results[-1]["ms_per_step"], results[-1]["tflops"], results[-1]["requests_per_s"],
             results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"]), file=sys.stderr, flush=True)
@@ -229,7 +283,7 @@ def main():
             "config": {"workload": "%s (%s): %d rows, %d requests per pass, %d launches" % (
                 head["name"], head["dtype"], head["rows"], head["requests"], head["launches"])},
             "requests_per_s": head["requests_per_s"],
-            "roofline": head["roofline"], "cpu_baseline": cpu, "measured_peaks": peaks,
+            "roofline": head["roofline"], "cpu_baseline": cpu, "measured_peaks": peaks, "batch_forming": forming,
             "mixes": {("%s_%s" % (r["name"], r["dtype"])): r for r in results}}
     print(json.dumps(line))
 

@@ -248,11 +248,12 @@ int32_t epara_copy_segments(const epara_segment* h_segments, const epara_segment
 
 /* Gather with dynamic per-tensor fp8 quantisation: the rows of all requests of service g are one
  * tensor; d_amax[g] = max |x| over it, d_scale[g] = d_amax[g] / 448 (1 if the tensor is all zero or
- * empty), and dst receives the E4M3 codes sat(RNE(x / d_scale[g])) (quotient and rounding in
- * fp32; one byte per source element, so dst holds bytes / sizeof(src element)).  src_dtype is
- * EPARA_F32 or EPARA_BF16.  d_amax and d_scale are float[G] outputs in device memory.  Four
+ * empty), and dst receives the E4M3 codes sat(RNE(x * (1 / d_scale[g]))) (reciprocal, product and
+ * rounding in fp32, the same form as the forward path's out_inv_scale; one byte per source
+ * element, so dst holds bytes / sizeof(src element)).  src_dtype is
+ * EPARA_F32 or EPARA_BF16.  d_amax and d_scale are float[G] outputs in device memory.  Three
  * kernels on `stream`: clear, amax (integer max on the bit patterns: order independent),
- * scales, quantise.  Validation as for epara_copy_segments plus ERR_DTYPE and ERR_SHAPE for a
+ * quantise (which also writes the scales).  Validation as for epara_copy_segments plus ERR_DTYPE and ERR_SHAPE for a
  * group index outside [0, G).  A NaN in the input gives unspecified codes for its tensor. */
 int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epara_segment* d_segments,
                                      int64_t n_segments, int64_t n_chunks, int32_t G, int32_t src_dtype,

@@ -4,9 +4,10 @@ The allocator's BS / MF operators (Sec. 3.1 of the paper) make one ragged batch 
 the rows its requests bring, and every request gets its own result rows back.  Nothing here is
 arithmetic except the dynamic per-tensor fp8 scale: the rows of all requests of a service are one
 tensor, amax = max |x|, scale = amax / 448 (1 for an all-zero or empty tensor; 448 is the largest
-finite E4M3 value), code = sat(RNE(x / scale)).  Quotient and rounding are taken in fp32, the
-precision the GPU kernel decides the integer code in, so the codes can be compared bit for bit;
-the fp32 quotient is an exact double, which the oracle's own E4M3 encoder then rounds.
+finite E4M3 value), code = sat(RNE(x * (1 / scale))) -- the form in which the forward path itself
+quantises its hidden activations (a stored reciprocal scale).  Reciprocal and product are taken in
+fp32, the precision the GPU kernel decides the integer code in, so the codes can be compared bit
+for bit; the fp32 product is an exact double, which the oracle's own E4M3 encoder then rounds.
 """
 import numpy as np
 
@@ -45,8 +46,9 @@ def amax_scale(x):
 
 
 def quantize_e4m3(x, scale):
-    """E4M3 codes of x / scale with the quotient rounded to fp32 first."""
-    q = (np.asarray(x, dtype=np.float32) / np.float32(scale)).astype(np.float32)
+    """E4M3 codes of x * (1 / scale), reciprocal and product rounded to fp32."""
+    inv = np.float32(1.0) / np.float32(scale)
+    q = (np.asarray(x, dtype=np.float32) * inv).astype(np.float32)
     return ref.e4m3_encode(q.astype(np.float64), 1.0)
 
 

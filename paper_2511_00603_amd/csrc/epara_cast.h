@@ -32,6 +32,19 @@ __device__ __forceinline__ uint32_t f32_to_e4m3(float x)
     return sign | (code > 0x7eu ? 0x7eu : code);
 }
 
+// Four fp32 values -> four E4M3 codes packed low byte first, round to nearest even, saturating at
+// +-448 (v_cvt_pk_fp8_f32 after a clamp; gfx950 converts to the OCP format).  Finite inputs give the
+// codes of f32_to_e4m3; a NaN input gives an unspecified code.
+__device__ __forceinline__ uint32_t f32x4_to_e4m3(float a, float b, float c, float d)
+{
+    a = __builtin_amdgcn_fmed3f(a, -448.f, 448.f);
+    b = __builtin_amdgcn_fmed3f(b, -448.f, 448.f);
+    c = __builtin_amdgcn_fmed3f(c, -448.f, 448.f);
+    d = __builtin_amdgcn_fmed3f(d, -448.f, 448.f);
+    const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+    return static_cast<uint32_t>(__builtin_amdgcn_cvt_pk_fp8_f32(c, d, pk, true));
+}
+
 }  // namespace epara_cast
 
 #endif

@@ -27,6 +27,7 @@ namespace {
 
 using epara_cast::f32_to_bf16;
 using epara_cast::f32_to_e4m3;
+using epara_cast::f32x4_to_e4m3;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -151,8 +152,7 @@ __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, 
     } else {  // EPARA_FP8_E4M3
         EPARA_GLOBAL uint8_t* y = as_global<uint8_t>(Y) + e;
         if (vec_ok && valid >= 4) {
-            *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32_to_e4m3(v[0]) | (f32_to_e4m3(v[1]) << 8) |
-                                              (f32_to_e4m3(v[2]) << 16) | (f32_to_e4m3(v[3]) << 24);
+            *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32x4_to_e4m3(v[0], v[1], v[2], v[3]);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -501,8 +501,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                         pk[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[2], v[3]}), v2bf));
                         *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
                     } else {
-                        *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32_to_e4m3(v[0]) | (f32_to_e4m3(v[1]) << 8) |
-                                                                       (f32_to_e4m3(v[2]) << 16) | (f32_to_e4m3(v[3]) << 24);
+                        *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32x4_to_e4m3(v[0], v[1], v[2], v[3]);
                     }
                 }
             }

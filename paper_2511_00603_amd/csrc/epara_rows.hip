@@ -81,13 +81,34 @@ template <int SRC>
 __global__ __launch_bounds__(NT) void amax_segments_kernel(const epara_segment* __restrict__ segs, int64_t n, int64_t n_chunks,
                                                            unsigned int* __restrict__ amax_bits)
 {
+    // A workgroup keeps the maximum of its chunks in registers while they belong to one service and
+    // publishes it when the service changes or its work ends: atomics on one address serialise,
+    // one per chunk would cost more than reading the data.
     __shared__ uint32_t part[NT / 64];
+    uint32_t m = 0;
+    int group = -1;
+    auto publish = [&]() {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) m = max(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), d)));
+        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t w = max(max(part[0], part[1]), max(part[2], part[3]));
+            // integer maximum: the order of arrival cannot matter; skipped when it cannot raise the value
+            if (w > __hip_atomic_load(amax_bits + group, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits + group, w);
+        }
+        __syncthreads();
+        m = 0;
+    };
     for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const epara_segment sg = segs[find_segment(segs, n, c)];
+        if (sg.group != group) {
+            if (group >= 0) publish();
+            group = sg.group;
+        }
         const int64_t base = (c - sg.first_chunk) * CHUNK;
         const EPARA_GLOBAL char* src = (const EPARA_GLOBAL char*)sg.src + base;
         const int64_t left = sg.bytes - base;
-        uint32_t m = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t off = (i * NT + threadIdx.x) * 16;
@@ -96,16 +117,8 @@ __global__ __launch_bounds__(NT) void amax_segments_kernel(const epara_segment* 
                 m = max(m, max_abs_bits<SRC>(v));
             }
         }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) m = max(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), d)));
-        if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            const uint32_t w = max(max(part[0], part[1]), max(part[2], part[3]));
-            if (w) atomicMax(amax_bits + sg.group, w);       // integer maximum: the order of arrival cannot matter
-        }
-        __syncthreads();
     }
+    if (group >= 0) publish();
 }
 
 __global__ void clear_kernel(unsigned int* p, int n)
@@ -114,21 +127,18 @@ __global__ void clear_kernel(unsigned int* p, int n)
     if (i < n) p[i] = 0u;
 }
 
-__global__ void scales_kernel(const float* __restrict__ amax, float* __restrict__ scale, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) scale[i] = amax[i] > 0.f ? amax[i] / 448.f : 1.f;
-}
+__device__ __forceinline__ float scale_of(float amax) { return amax > 0.f ? amax / 448.f : 1.f; }
 
 template <int SRC>
 __global__ __launch_bounds__(NT) void quantize_segments_kernel(const epara_segment* __restrict__ segs, int64_t n, int64_t n_chunks,
-                                                               const float* __restrict__ scale)
+                                                               const float* __restrict__ amax, float* __restrict__ scale, int G)
 {
-    using epara_cast::f32_to_e4m3;
     constexpr int ESZ = SRC == EPARA_F32 ? 4 : 2;
+    if (blockIdx.x == 0)
+        for (int g = threadIdx.x; g < G; g += NT) scale[g] = scale_of(amax[g]);
     for (int64_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
         const epara_segment sg = segs[find_segment(segs, n, c)];
-        const float s = scale[sg.group];
+        const float inv = 1.f / scale_of(amax[sg.group]);      // codes = RNE(x * (1 / scale)), as the forward path's epilogue does
         const int64_t base = (c - sg.first_chunk) * CHUNK;
         const EPARA_GLOBAL char* src = (const EPARA_GLOBAL char*)sg.src + base;
         EPARA_GLOBAL char* dst = (EPARA_GLOBAL char*)sg.dst + base / ESZ;
@@ -144,18 +154,19 @@ __global__ __launch_bounds__(NT) void quantize_segments_kernel(const epara_segme
             const int64_t off = (i * NT + threadIdx.x) * 16;
             if (off >= left) continue;
             if constexpr (SRC == EPARA_F32) {
-                uint32_t pk = 0;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) pk |= f32_to_e4m3(__int_as_float(v[i][j]) / s) << (8 * j);
-                *reinterpret_cast<EPARA_GLOBAL uint32_t*>(dst + off / 4) = pk;
+                *reinterpret_cast<EPARA_GLOBAL uint32_t*>(dst + off / 4) =
+                    epara_cast::f32x4_to_e4m3(__int_as_float(v[i][0]) * inv, __int_as_float(v[i][1]) * inv, __int_as_float(v[i][2]) * inv, __int_as_float(v[i][3]) * inv);
             } else {
-                v2u pk = {0u, 0u};
+                float f[8];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t u = static_cast<uint32_t>(v[i][j]);
-                    const float lo = __uint_as_float(u << 16), hi = __uint_as_float(u & 0xffff0000u);
-                    pk[j >> 1] |= (f32_to_e4m3(lo / s) | (f32_to_e4m3(hi / s) << 8)) << (16 * (j & 1));
+                    f[2 * j] = __uint_as_float(u << 16) * inv;
+                    f[2 * j + 1] = __uint_as_float(u & 0xffff0000u) * inv;
                 }
+                v2u pk;
+                pk[0] = epara_cast::f32x4_to_e4m3(f[0], f[1], f[2], f[3]);
+                pk[1] = epara_cast::f32x4_to_e4m3(f[4], f[5], f[6], f[7]);
                 *reinterpret_cast<EPARA_GLOBAL v2u*>(dst + off / 2) = pk;
             }
         }
@@ -216,7 +227,7 @@ int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epar
     if (G == 0) return EPARA_OK;
     if (!d_amax || !d_scale) return EPARA_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const dim3 small((G + 255) / 256), grid(grid_for(n_chunks));
+    const dim3 small((G + 255) / 256), grid(static_cast<int>(n_chunks < 1024 ? (n_chunks > 0 ? n_chunks : 1) : 1024));
     // the maxima are cleared by a kernel, not a memset: a caller may capture this stream in a graph
     hipLaunchKernelGGL(clear_kernel, small, dim3(256), 0, s, reinterpret_cast<unsigned int*>(d_amax), G);
     if (n_chunks > 0) {
@@ -227,13 +238,12 @@ int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epar
             hipLaunchKernelGGL(amax_segments_kernel<EPARA_BF16>, grid, dim3(NT), 0, s, d_segments, n_segments, n_chunks,
                                reinterpret_cast<unsigned int*>(d_amax));
     }
-    hipLaunchKernelGGL(scales_kernel, small, dim3(256), 0, s, d_amax, d_scale, G);
-    if (n_chunks > 0) {
-        if (src_dtype == EPARA_F32)
-            hipLaunchKernelGGL(quantize_segments_kernel<EPARA_F32>, grid, dim3(NT), 0, s, d_segments, n_segments, n_chunks, d_scale);
-        else
-            hipLaunchKernelGGL(quantize_segments_kernel<EPARA_BF16>, grid, dim3(NT), 0, s, d_segments, n_segments, n_chunks, d_scale);
-    }
+    // the quantising kernel also writes the scales (workgroup 0); with no data it runs for that alone
+    const dim3 qgrid(n_chunks > 0 ? grid_for(n_chunks) : 1);
+    if (src_dtype == EPARA_F32)
+        hipLaunchKernelGGL(quantize_segments_kernel<EPARA_F32>, qgrid, dim3(NT), 0, s, d_segments, n_segments, n_chunks, d_amax, d_scale, G);
+    else
+        hipLaunchKernelGGL(quantize_segments_kernel<EPARA_BF16>, qgrid, dim3(NT), 0, s, d_segments, n_segments, n_chunks, d_amax, d_scale, G);
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 

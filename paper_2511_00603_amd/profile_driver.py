@@ -16,11 +16,40 @@ from .mixrun import StagedMix
 COPY_BYTES = 1 << 30
 
 
+def batch_forming(mix, steps):
+    """Gather, gather + dynamic E4M3 quantisation and scatter of the mix's requests (bf16 rows), `steps` times."""
+    import numpy as np
+    from workloads import casts
+    from . import runtime as R
+    dev = "cuda:0"
+    reqs, batches, codes = [], [], []
+    for svc in mix.services:
+        bits = casts.bf16_bits(svc.X)
+        at, mine = 0, []
+        for n in svc.request_rows:
+            mine.append(torch.from_numpy(bits[at:at + n].view(np.int16).copy()).to(dev).view(torch.bfloat16))
+            at += n
+        reqs.append(mine)
+        batches.append(torch.zeros(svc.X.shape, dtype=torch.bfloat16, device=dev))
+        codes.append(torch.zeros(svc.X.shape, dtype=torch.uint8, device=dev))
+    G = len(reqs)
+    gather, quant, scatter = R.SegmentPlan(reqs, batches, True, dev), R.SegmentPlan(reqs, codes, True, dev), R.SegmentPlan(reqs, batches, False, dev)
+    amax, scale = torch.zeros(G, dtype=torch.float32, device=dev), torch.zeros(G, dtype=torch.float32, device=dev)
+    for _ in range(steps):
+        R.copy_segments(gather)
+        R.quantize_segments_e4m3(quant, B.EPARA_BF16, amax, scale)
+        R.copy_segments(scatter)
+    torch.cuda.synchronize()
+    print("profile_driver: batch forming of mix %d, %d passes, %d source bytes per pass" % (mix.index, steps, gather.bytes))
+
+
 def main():
     idx = int(sys.argv[1])
     dtype = sys.argv[2] if len(sys.argv) > 2 else None
     steps = int(sys.argv[3]) if len(sys.argv) > 3 else 4
     mix = make_mix(idx)
+    if dtype == "rows":          # batch forming of the mix's requests instead of its forward pass
+        return batch_forming(mix, steps)
     s_h = None
     if dtype == "fp8":
         cal = StagedMix(mix, "bf16", "cuda:0")

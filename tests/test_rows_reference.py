@@ -48,14 +48,14 @@ def test_scale_closed_forms():
         assert (q[np.argmax(np.abs(v))] & 0x7f) == 0x7e and np.all((q & 0x7f) <= 0x7e)
 
 
-def test_codes_agree_with_an_independent_cast_of_the_fp32_quotient():
+def test_codes_agree_with_an_independent_cast_of_the_fp32_product():
     # PyTorch's CPU conversion to float8_e4m3fn rounds the same fp32 numbers to nearest even
     rng = np.random.default_rng(33)
     for shape, spread in (((37, 48), 1.0), ((5, 1024), 30.0), ((1, 16), 1e-3)):
         x = (rng.standard_normal(shape) * spread).astype(np.float32)
         x.flat[::7] *= 2.0 ** rng.integers(-12, 3)                   # reach the subnormal codes too
         a, s = RW.amax_scale(x)
-        q = (x / s).astype(np.float32)
+        q = (x * (np.float32(1.0) / s)).astype(np.float32)
         want = torch.from_numpy(q).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
         assert np.array_equal(RW.quantize_e4m3(x, s), want)
         # and decoding gives back x to within half a code step (relative 2^-4, absolute 2^-10 of the scale)
