@@ -148,6 +148,29 @@ int64_t epara_dp_group_count(int64_t rate_required, int64_t rate_of_one_group);
 /* Sec. 4.1, Eq. "inter request count" = floor(BS / max inter-frame count); -1 on bad input. */
 int64_t epara_inter_request_count(int64_t batch_size, int64_t max_inter_frame_count);
 
+/* Allocation operators of Sec. 3.1 as bits. */
+typedef enum { EPARA_OP_BS = 1, EPARA_OP_MT = 2, EPARA_OP_MP = 4, EPARA_OP_MF = 8, EPARA_OP_DP = 16 } epara_operator;
+
+/* Sec. 3.1 "Performing operators to categories": the operators the allocator applies to a task of
+ * `category` (epara_category) that fits one GPU (multi_gpu = 0) or needs several (multi_gpu != 0):
+ *   latency,   one GPU : BS | MT            latency,   several : BS | MT | MP
+ *   frequency, one GPU : MF | MT | BS       frequency, several : MF | MT | BS | DP | MP
+ * -1 for an unknown category. */
+int32_t epara_operator_set(int32_t category, int32_t multi_gpu);
+
+/* Sec. 4.1 "DP and MF configuration": batching MF frames of a stream raises its latency from 1/fps to
+ * MF/fps, so MF is set to the largest count the latency requirement allows:
+ * floor(latency_us * fps_milli / 1e9), at least 1 (fps_milli = 1000 * frames per second).
+ * -1 on a negative latency or a rate <= 0. */
+int64_t epara_max_inter_frame_count(int64_t latency_us, int64_t fps_milli);
+
+/* DP (Sec. 3.1): the frames of a task go to its DP groups in a round robin manner.  Frame j of the
+ * n_frames frames that start at stream position first_frame goes to group (first_frame + j) mod n_groups.
+ * Writes frames_per_group[n_groups] (may be NULL) and group_of_frame[n_frames] (may be NULL).
+ * ERR_SHAPE for n_groups <= 0 or a negative count / position. */
+int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
+                      int64_t* frames_per_group, int32_t* group_of_frame);
+
 /* Group planning: the single-GPU part of the allocator's "parallel mode per task" decision.
  *   row_off[g] = sum_{h<g} M_h ; x_off[g] = sum_{h<g} M_h K_h ; y_off[g] = sum_{h<g} M_h N_h
  *   (each G+1 entries; x_off / y_off are element offsets for callers that pack groups

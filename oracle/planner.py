@@ -78,6 +78,33 @@ def inter_request_count(batch_size, max_inter_frame_count):
     return batch_size // max_inter_frame_count
 
 
+OPERATORS = {"BS": 1, "MT": 2, "MP": 4, "MF": 8, "DP": 16}
+
+
+def operator_set(frequency_sensitive, multi_gpu):
+    """Sec. 3.1 "Performing operators to categories", the four paragraphs as a table of names."""
+    if not frequency_sensitive:
+        ops = ["BS", "MT"] + (["MP"] if multi_gpu else [])                 # first / second category
+    else:
+        ops = ["MF", "MT", "BS"] + (["DP", "MP"] if multi_gpu else [])     # third / fourth category
+    return sorted(ops)
+
+
+def max_inter_frame_count(latency_us, fps_milli):
+    """Sec. 4.1: MF frames per batch make the latency MF / fps; the largest MF within the requirement, >= 1."""
+    if latency_us < 0 or fps_milli <= 0:
+        raise ValueError("bad latency or rate")
+    return max(1, latency_us * fps_milli // 10**9)
+
+
+def dp_deal(first_frame, n_frames, n_groups):
+    """Sec. 3.1 DP: frames go to the DP groups round robin -> (frames per group, group of each frame)."""
+    if n_groups <= 0 or n_frames < 0 or first_frame < 0:
+        raise ValueError("bad counts")
+    group = [(first_frame + j) % n_groups for j in range(n_frames)]
+    return [group.count(g) for g in range(n_groups)], group
+
+
 def pick_class(M, classes):
     for c, (max_M, _bm, _bn) in enumerate(classes):
         if M <= max_M:

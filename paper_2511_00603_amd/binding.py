@@ -76,6 +76,12 @@ def lib():
         L.epara_dp_group_count.restype = i64
         L.epara_inter_request_count.argtypes = [i64, i64]
         L.epara_inter_request_count.restype = i64
+        L.epara_operator_set.argtypes = [i32, i32]
+        L.epara_operator_set.restype = i32
+        L.epara_max_inter_frame_count.argtypes = [i64, i64]
+        L.epara_max_inter_frame_count.restype = i64
+        L.epara_dp_deal.argtypes = [i64, i64, i64, vp, vp]
+        L.epara_dp_deal.restype = i32
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
@@ -167,6 +173,26 @@ def epara_dp_group_count(rate_required, rate_of_one_group):
 
 def epara_inter_request_count(batch_size, max_inter_frame_count):
     return int(lib().epara_inter_request_count(int(batch_size), int(max_inter_frame_count)))
+
+
+EPARA_OP_BS, EPARA_OP_MT, EPARA_OP_MP, EPARA_OP_MF, EPARA_OP_DP = 1, 2, 4, 8, 16
+
+
+def epara_operator_set(category, multi_gpu):
+    return int(lib().epara_operator_set(int(category), int(bool(multi_gpu))))
+
+
+def epara_max_inter_frame_count(latency_us, fps_milli):
+    return int(lib().epara_max_inter_frame_count(int(latency_us), int(fps_milli)))
+
+
+def epara_dp_deal(first_frame, n_frames, n_groups):
+    """-> (frames_per_group int64[n_groups], group_of_frame int32[n_frames])."""
+    per = np.zeros(max(int(n_groups), 0), dtype=np.int64)
+    who = np.zeros(max(int(n_frames), 0), dtype=np.int32)
+    _check(lib().epara_dp_deal(int(first_frame), int(n_frames), int(n_groups), _ptr(per) if per.size else None,
+                               _ptr(who) if who.size else None), "epara_dp_deal")
+    return per, who
 
 
 def epara_plan_groups(groups, classes):

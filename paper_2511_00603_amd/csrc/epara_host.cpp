@@ -78,6 +78,37 @@ int32_t epara_batch_rows(const int32_t* request_rows, const int64_t* request_off
     return EPARA_OK;
 }
 
+int32_t epara_operator_set(int32_t category, int32_t multi_gpu)
+{
+    int32_t ops;
+    if (category == EPARA_CAT_LATENCY)        ops = EPARA_OP_BS | EPARA_OP_MT;
+    else if (category == EPARA_CAT_FREQUENCY) ops = EPARA_OP_MF | EPARA_OP_MT | EPARA_OP_BS;
+    else return -1;
+    if (multi_gpu) ops |= EPARA_OP_MP | (category == EPARA_CAT_FREQUENCY ? EPARA_OP_DP : 0);
+    return ops;
+}
+
+int64_t epara_max_inter_frame_count(int64_t latency_us, int64_t fps_milli)
+{
+    if (latency_us < 0 || fps_milli <= 0) return -1;
+    const __int128 frames = static_cast<__int128>(latency_us) * fps_milli / 1000000000;
+    return frames < 1 ? 1 : static_cast<int64_t>(frames);
+}
+
+int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
+                      int64_t* frames_per_group, int32_t* group_of_frame)
+{
+    if (n_groups <= 0 || n_groups > INT32_MAX || n_frames < 0 || first_frame < 0) return EPARA_ERR_SHAPE;
+    if (frames_per_group) {
+        const int64_t base = n_frames / n_groups, extra = n_frames % n_groups, start = first_frame % n_groups;
+        for (int64_t g = 0; g < n_groups; ++g)                    // the `extra` groups from `start` on get one more
+            frames_per_group[g] = base + (((g - start) % n_groups + n_groups) % n_groups < extra ? 1 : 0);
+    }
+    if (group_of_frame)
+        for (int64_t j = 0; j < n_frames; ++j) group_of_frame[j] = static_cast<int32_t>((first_frame % n_groups + j) % n_groups);
+    return EPARA_OK;
+}
+
 int32_t epara_request_segments(const int32_t* request_rows, const int64_t* request_off, int32_t G,
                                const int64_t* request_row_bytes, const int64_t* batch_row_bytes,
                                const void* const* request_ptr, const void* const* batch_ptr, int32_t to_batch,

@@ -156,3 +156,65 @@ def test_paper_worked_numbers():
             raise AssertionError(name)
         seen += 1
     assert seen >= 6
+
+
+# ---- allocator helpers (Sec. 3.1 operator table, Sec. 4.1 MF bound, DP dealing) ----------------------
+
+PAPER_OPERATOR_TABLE = {            # Sec. 3.1 "Performing operators to categories", the four paragraphs
+    ("latency", False): {"BS", "MT"},
+    ("latency", True): {"BS", "MT", "MP"},
+    ("frequency", False): {"MF", "MT", "BS"},
+    ("frequency", True): {"MF", "MT", "BS", "DP", "MP"},
+}
+
+
+def test_operator_sets_are_the_papers_four_categories():
+    from paper_2511_00603_amd import binding as B
+    for (cat, multi), names in PAPER_OPERATOR_TABLE.items():
+        assert set(P.operator_set(cat == "frequency", multi)) == names
+        bits = B.epara_operator_set(B.EPARA_CAT_FREQUENCY if cat == "frequency" else B.EPARA_CAT_LATENCY, multi)
+        assert bits == sum(P.OPERATORS[n] for n in names)
+    assert B.epara_operator_set(7, 0) == -1
+    # DP only ever appears together with MP and MF (the fourth category)
+    assert all(("DP" not in v) or {"MP", "MF"} <= v for v in PAPER_OPERATOR_TABLE.values())
+
+
+def test_max_inter_frame_count_keeps_the_latency_of_a_batched_stream_within_its_requirement():
+    from paper_2511_00603_amd import binding as B
+    # MF frames per batch -> latency MF / fps (Sec. 4.1): at 60 fps a 66.7 ms budget admits 4 frames, 66.6 ms only 3
+    assert P.max_inter_frame_count(66667, 60000) == B.epara_max_inter_frame_count(66667, 60000) == 4
+    assert P.max_inter_frame_count(66666, 60000) == B.epara_max_inter_frame_count(66666, 60000) == 3
+    assert B.epara_max_inter_frame_count(1, 30000) == 1                 # never below one frame
+    assert B.epara_max_inter_frame_count(-1, 30000) == -1 and B.epara_max_inter_frame_count(5, 0) == -1
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        lat, fps = int(rng.integers(0, 10**7)), int(rng.integers(1, 240001))
+        mf = B.epara_max_inter_frame_count(lat, fps)
+        assert mf == P.max_inter_frame_count(lat, fps)
+        assert mf == 1 or (mf * 10**9 <= lat * fps < (mf + 1) * 10**9)   # MF/fps <= latency < (MF+1)/fps
+
+
+def test_dp_deal_is_round_robin_over_the_stream():
+    from paper_2511_00603_amd import binding as B
+    per, who = B.epara_dp_deal(0, 9, 2)
+    assert who.tolist() == [0, 1, 0, 1, 0, 1, 0, 1, 0] and per.tolist() == [5, 4]     # frames alternate between two groups
+    rng = np.random.default_rng(6)
+    for _ in range(100):
+        first, n, k = int(rng.integers(0, 1000)), int(rng.integers(0, 200)), int(rng.integers(1, 9))
+        per, who = B.epara_dp_deal(first, n, k)
+        want_per, want_who = P.dp_deal(first, n, k)
+        assert per.tolist() == want_per and who.tolist() == want_who
+        assert per.sum() == n and per.max() - per.min() <= 1
+        # dealing a stream in two pieces continues the rotation
+        cut = int(rng.integers(0, n + 1))
+        a, b = B.epara_dp_deal(first, cut, k), B.epara_dp_deal(first + cut, n - cut, k)
+        assert np.array_equal(np.concatenate([a[1], b[1]]), who) and np.array_equal(a[0] + b[0], per)
+    with pytest.raises(B.EparaError):
+        B.epara_dp_deal(0, 5, 0)
+    with pytest.raises(B.EparaError):
+        B.epara_dp_deal(-1, 5, 2)
+    # with the group count the paper's equation gives, every group stays within its own frame rate
+    need, one = 97, 49
+    k = B.epara_dp_group_count(need, one)
+    per, _ = B.epara_dp_deal(0, need, k)
+    assert k == 2 and per.max() <= one
