@@ -233,7 +233,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--mixes", default="5,5fp8,4,3,2,1", help="comma list; the first is the headline (default prefill bf16)")
+    ap.add_argument("--mixes", default="5,5fp8,4,4fp8,3,2,1", help="comma list; the first is the headline (default prefill bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the measured-ceiling probes")
     a = ap.parse_args()

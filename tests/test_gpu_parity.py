@@ -225,6 +225,14 @@ def test_mix4_decode_reduced_all_rows():
     check_mix(make_mix(4, d=512, ffn=1376), "bf16")
 
 
+def test_mix4_decode_fp8_reduced_all_rows():
+    # the weight-streaming classes with E4M3 inputs and E4M3 hidden activations (static scale from the oracle)
+    mix = make_mix(4, d=1024, ffn=2752)
+    hb = StagedMix.stage_host(mix, "fp8")
+    hs = _h_scales(mix, hb, [slice(None)] * len(mix.services))
+    check_mix(mix, "fp8", h_scales=hs, host_bits=hb)
+
+
 def test_mix4_decode_full_size():
     check_mix(make_mix(4), "bf16")
 
