@@ -2,10 +2,11 @@
 //
 // One launch serves every co-located service (the MT operator of Sec. 3.1): persistent
 // workgroups walk a device tile table in a precomputed visit order; a tile is either
-//   - "big":    256 rows x 256 columns of one group, LDS-staged, 32x32x16 MFMA, or
-//   - "skinny": a whole batch of <= 64 rows x 32 columns, weights streamed from HBM straight
-//               into 16x16x32 MFMA operand registers, K split over the four waves of the
-//               workgroup.
+//   - "big":    256 rows x 256 columns of one group, both operands LDS-staged by direct loads,
+//               32x32x16 MFMA (fp8: 32x32x64), or
+//   - "skinny": a whole batch of <= 64 rows x 32 .. 128 columns, weights streamed from HBM
+//               straight into 16x16x32 MFMA operand registers, activations through a small
+//               LDS ring per wave, K split over the four waves of the workgroup.
 // Bias, activation, SwiGLU gating, fp8 scales and the output cast are fused in the epilogue.
 // A workgroup is four waves, one per SIMD, so a wave may use the whole 512-entry register
 // file: 256 accumulators for a 128 x 128 wave tile plus double-buffered operand fragments.

@@ -161,6 +161,24 @@ def test_ragged_and_degenerate_groups(dtype_name):
             assert_close(y, yref, TOL[dtype_name], str(sh))
 
 
+@pytest.mark.parametrize("dtype_name", ["bf16", "fp8"])
+def test_every_activation_on_whole_and_ragged_panel_tiles(dtype_name):
+    """The matrix-core kernels use the hardware's exp / reciprocal and a rational erf in their epilogue;
+    whole 256 x 256 tiles run an unrolled epilogue, ragged ones a loop: both against the fp64 oracle, with
+    bias, K of one to five stages incl. an odd stage count and a ragged last stage."""
+    rng = np.random.default_rng(16)
+    kmul = 16 if dtype_name == "fp8" else 8
+    acts = ["none", "relu", "gelu_erf", "gelu_tanh", "silu"]
+    shapes = [(512, 24 * kmul, 512, acts[i % 5]) if i < 5 else (300, (4 * i + 1) * kmul, 520, acts[i % 5]) for i in range(10)]
+    specs = [U.rand_spec(rng, M, K, N, act) for M, K, N, act in shapes]
+    for sp in specs:                                                     # activations need arguments of both signs and sizes
+        sp["X"] *= 2.0
+    G = U.Groups(specs, dtype_name)
+    got, want = G.run(), G.expected()
+    for sh, y, yref in zip(shapes, got, want):
+        assert_close(y, yref, TOL[dtype_name], str(sh))
+
+
 def test_nothing_to_do_is_ok():
     G = U.Groups([], "bf16")
     assert G.run() == []
