@@ -4,6 +4,7 @@ short text summaries kept under profiles/ and into profiles/traffic.json.
     python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt
     python -m paper_2511_00603_amd.profile_summary traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
     python -m paper_2511_00603_amd.profile_summary report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
+    python -m paper_2511_00603_amd.profile_summary counters OUT WORKLOAD MIX DTYPE    (OUT/{sq,tcc}_counter_collection.csv)
 
 Per-launch figures: the launches of one pass alternate (launch 0, launch 1, ...), so dispatch i of
 grouped_kernel belongs to launch i mod L.  HBM traffic of a launch = counter value (KiB) x 1024 x
@@ -118,8 +119,60 @@ def report(out_dir, workload, mix, dtype, launches_per_pass=2):
     print("\n".join(L))
 
 
+SQ_COUNTERS = "SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_WAIT_INST_LDS SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE"
+TCC_COUNTERS = "TCC_HIT_sum TCC_MISS_sum"
+N_XCD, N_SIMD = 8, 256 * 4
+
+
+def _per_launch(path, launches_per_pass):
+    """counter name -> list over launches of the median (over passes, first pass skipped) of the per-dispatch sums;
+    "_us" -> the same for the dispatch durations."""
+    vals, dur = {}, {}
+    for r in _rows(path):
+        if "grouped_kernel" not in r["Kernel_Name"]:
+            continue
+        d = int(r["Dispatch_Id"])
+        vals.setdefault(r["Counter_Name"], {})
+        vals[r["Counter_Name"]][d] = vals[r["Counter_Name"]].get(d, 0.0) + float(r["Counter_Value"])
+        dur[d] = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+    order = sorted(dur)
+    out = {}
+    for name, per in list(vals.items()) + [("_us", dur)]:
+        out[name] = [statistics.median([per[d] for i, d in enumerate(order) if i % launches_per_pass == l and i >= launches_per_pass])
+                     for l in range(launches_per_pass)]
+    return out
+
+
+def counters(out_dir, workload, mix, dtype, launches_per_pass=2):
+    """profiles/counters_WORKLOAD.txt: clocks, matrix-core busy share, LDS bank conflicts and L2 hit rate per launch."""
+    drv = "python3 -m paper_2511_00603_amd.profile_driver %s %s 4" % (mix, dtype)
+    sq = _per_launch(os.path.join(out_dir, "sq_counter_collection.csv"), launches_per_pass)
+    tcc = _per_launch(os.path.join(out_dir, "tcc_counter_collection.csv"), launches_per_pass)
+    L = ["rocprofv3 counter summary of grouped_kernel, per launch of a pass (medians over passes, first pass skipped)",
+         "commands: rocprofv3 --pmc %s --output-format csv -d OUT -o sq -- %s" % (SQ_COUNTERS, drv),
+         "          rocprofv3 --pmc %s --output-format csv -d OUT -o tcc -- %s" % (TCC_COUNTERS, drv),
+         "counter values are sums over the chip: GRBM_GUI_ACTIVE over %d dies, SQ_VALU_MFMA_BUSY_CYCLES over %d SIMDs" % (N_XCD, N_SIMD), ""]
+    for l in range(launches_per_pass):
+        clk = sq["GRBM_GUI_ACTIVE"][l] / N_XCD                       # cycles one die was active
+        L += ["launch %d (%.0f us under the counter run)" % (l, sq["_us"][l]),
+              "  average clock while active        %.2f GHz   (GRBM_GUI_ACTIVE / %d / duration)" % (clk / sq["_us"][l] / 1e3, N_XCD),
+              "  matrix cores busy                 %.1f %%     (SQ_VALU_MFMA_BUSY_CYCLES / %d / active cycles)"
+              % (100 * sq["SQ_VALU_MFMA_BUSY_CYCLES"][l] / N_SIMD / clk, N_SIMD),
+              "  LDS bank conflict cycles          %.2f %%     of SQ_LDS_IDX_ACTIVE (%.3g of %.3g)"
+              % (100 * sq["SQ_LDS_BANK_CONFLICT"][l] / max(sq["SQ_LDS_IDX_ACTIVE"][l], 1), sq["SQ_LDS_BANK_CONFLICT"][l], sq["SQ_LDS_IDX_ACTIVE"][l]),
+              "  wave cycles waiting on LDS / any  %.1f %% / %.1f %%   (SQ_WAIT_INST_LDS, SQ_WAIT_INST_ANY over SQ_WAVE_CYCLES)"
+              % (100 * sq["SQ_WAIT_INST_LDS"][l] / sq["SQ_WAVE_CYCLES"][l], 100 * sq["SQ_WAIT_INST_ANY"][l] / sq["SQ_WAVE_CYCLES"][l]),
+              "  L2 hit rate                       %.1f %%     (TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum), %.3g requests)"
+              % (100 * tcc["TCC_HIT_sum"][l] / (tcc["TCC_HIT_sum"][l] + tcc["TCC_MISS_sum"][l]), tcc["TCC_HIT_sum"][l] + tcc["TCC_MISS_sum"][l]), ""]
+    txt = os.path.join(ROOT, "profiles", "counters_%s.txt" % workload)
+    open(txt, "w").write("\n".join(L))
+    print("\n".join(L))
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "report":
+    if sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], int(sys.argv[6]) if len(sys.argv) > 6 else 2)
+    elif sys.argv[1] == "report":
         report(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], int(sys.argv[6]) if len(sys.argv) > 6 else 2)
     elif sys.argv[1] == "kernels":
         kernels(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2)
