@@ -40,7 +40,8 @@ constexpr int NT = 256;                 // threads per workgroup (4 waves, one p
 constexpr int BIAS_LDS_OFFSET = 131072;  // after the operand buffers: 256 floats, the bias of a panel tile
 constexpr int LDS_BYTES = 163840;          // the whole LDS of a compute unit (one workgroup per unit)
 constexpr int RING_LDS_OFFSET = 65536;   // streaming tiles: partial sums below, the waves' activation rings above
-constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 16, F32_NT = 256;
+constexpr int F32_BM = 64, F32_BN = 64, F32_BK = 64, F32_NT = 256;
+constexpr int F32_PER = F32_BM * F32_BK / F32_NT;      // elements of X (and of W) a thread stages per K step
 
 // ------------------------------------------------------------------ small device helpers
 
@@ -884,25 +885,31 @@ __global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_a
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        // The K steps are software pipelined through registers: the loads of step k0 + BK are in flight
+        // while step k0 is multiplied (a tile of a small model is a chain of dependent memory
+        // latencies otherwise).  The sums still run over K in ascending order.
+        float xr[F32_PER], wr[F32_PER];
+        auto fetch = [&](int k0) {
+#pragma unroll
+            for (int j = 0; j < F32_PER; ++j) {
+                const int e = tid + F32_NT * j;
+                const int row = e / F32_BK, kk = e % F32_BK;
+                xr[j] = (row < tl.rows && k0 + kk < K) ? X[static_cast<size_t>(tl.m0 + row) * K + k0 + kk] : 0.f;
+                const int kw = e >> 6, nn = e & 63;
+                wr[j] = (k0 + kw < K && nn < tl.cols) ? W[static_cast<size_t>(k0 + kw) * N + tl.n0 + nn] : 0.f;
+            }
+        };
+        fetch(0);
         for (int k0 = 0; k0 < K; k0 += F32_BK) {
             __syncthreads();
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < F32_PER; ++j) {
                 const int e = tid + F32_NT * j;
-                const int row = e >> 4, kk = e & 15;
-                float v = 0.f;
-                if (row < tl.rows && k0 + kk < K) v = X[static_cast<size_t>(tl.m0 + row) * K + k0 + kk];
-                Xs[kk][row] = v;
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int e = tid + F32_NT * j;
-                const int kk = e >> 6, nn = e & 63;
-                float v = 0.f;
-                if (k0 + kk < K && nn < tl.cols) v = W[static_cast<size_t>(k0 + kk) * N + tl.n0 + nn];
-                Ws[kk][nn] = v;
+                Xs[e % F32_BK][e / F32_BK] = xr[j];
+                Ws[e >> 6][e & 63] = wr[j];
             }
             __syncthreads();
+            if (k0 + F32_BK < K) fetch(k0 + F32_BK);
 #pragma unroll
             for (int kk = 0; kk < F32_BK; ++kk) {
                 float a[4], b[4];
