@@ -83,7 +83,8 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
             R.grouped_forward(plans[i % copies][l], outs[l])
             evs[i][l + 1].record()
     torch.cuda.synchronize()
-    per_launch_ms = [sum(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) / steps for l in range(n_l)]
+    samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
+    per_launch_ms = [sum(v) / steps for v in samples]
 
     flops = mix.flops()
     res = {"name": mix.name, "dtype": dtype_name, "ms_per_step": ms_per_step,
@@ -99,7 +100,8 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         t_mfma = st["flops"] / (peak_tf * 1e12) if peak_tf else 0.0
         t_hbm = st["bytes"] / (HBM_PEAK_GBS * 1e9)
         bound = "mfma" if t_mfma > t_hbm else "hbm"
-        k = {"launch": l, "ms": per_launch_ms[l], "tiles": st["tiles"], "groups": st["groups"],
+        k = {"launch": l, "ms": per_launch_ms[l], "ms_median": samples[l][steps // 2], "ms_min": samples[l][0],
+             "tiles": st["tiles"], "groups": st["groups"],
              "flops": st["flops"], "bytes": st["bytes"], "bound": bound}
         if bound == "mfma":
             k.update(achieved=tf, peak=peak_tf, unit="TFLOP/s", frac=tf / peak_tf)
