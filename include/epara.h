@@ -20,7 +20,8 @@
  *     never synchronises and keeps no mutable global state.  Launch functions only
  *     enqueue work on `stream` (a hipStream_t passed as void*; NULL = default stream).
  *   - X_g and Y_g are dense row-major ([M,K] and [M,N]); device pointers must be 16-byte
- *     aligned and K*sizeof(element) must be a multiple of 16 for bf16/fp8 inputs.
+ *     aligned and K*sizeof(element) must be a multiple of 16, and at most 8 MiB, for bf16/fp8
+ *     inputs (ERR_ALIGN / ERR_SHAPE otherwise).
  *   - weights: logical W_g is [K,N] row-major.  fp32 kernels read that layout directly;
  *     bf16 / fp8 kernels read the tile-packed layout written by epara_pack_weights
  *     (done once when a service is placed on the GPU, ahead of its requests -- the paper

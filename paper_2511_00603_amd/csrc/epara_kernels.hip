@@ -1022,6 +1022,8 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
         if (!aligned16(a.X) || !aligned16(a.W) || !aligned16(a.Y) || !aligned16(a.W2) || !aligned16(a.bias))
             return EPARA_ERR_ALIGN;
         if (!f32 && (static_cast<int64_t>(a.K) * esz) % 16 != 0) return EPARA_ERR_ALIGN;
+        // the matrix-core kernels address a tile's operands with 32-bit byte offsets (256 rows, 16 column blocks)
+        if (!f32 && static_cast<int64_t>(a.K) * esz > (1 << 23)) return EPARA_ERR_SHAPE;
     }
     // a launch is either all SwiGLU groups or none: the tile classes differ
     {

@@ -231,6 +231,7 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
     b = mk(); b[0]["W"] = 0x20008
     assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_ALIGN
     b = mk(K=36); assert fwd(_host_launch(b, plan(b), 8)) == B.EPARA_ERR_ALIGN   # 72-byte rows
+    b = mk(K=(1 << 22) + 8); assert fwd(_host_launch(b, plan(b), 8)) == B.EPARA_ERR_SHAPE   # a row longer than 8 MiB
     b = mk(); b[0]["act"] = 9
     assert fwd(_host_launch(b, t, 8)) == B.EPARA_ERR_DTYPE
     b = mk(act="swiglu")                                                         # no second weight matrix

@@ -12,7 +12,7 @@ from oracle import reference as ref
 from paper_2511_00603_amd import binding as B
 from paper_2511_00603_amd import runtime as R
 from paper_2511_00603_amd.mixrun import StagedMix
-from workloads import make_mix
+from workloads import casts, make_mix
 
 import gpu_util as U
 import mix_oracle
@@ -177,6 +177,33 @@ def test_every_activation_on_whole_and_ragged_panel_tiles(dtype_name):
     got, want = G.run(), G.expected()
     for sh, y, yref in zip(shapes, got, want):
         assert_close(y, yref, TOL[dtype_name], str(sh))
+
+
+def test_output_beyond_four_gibibytes_is_addressed_with_64_bits():
+    """One group whose output has more than 2^32 bytes (and its last rows more than 2^31 elements in): rows
+    sampled from the start, the 4 GiB boundary and the end against the oracle, panel tiles whole and ragged."""
+    rng = np.random.default_rng(17)
+    M, K, N = 36100, 16, 60040
+    sp = U.rand_spec(rng, M, K, N, "relu")
+    xb, wb = casts.bf16_bits(sp["X"]), casts.bf16_bits(sp["W"])
+    dX = R.device_tensor_from_bits(xb, B.EPARA_BF16, U.DEV)
+    dW = R.pack_weights(R.device_tensor_from_bits(wb, B.EPARA_BF16, U.DEV), B.EPARA_BF16)
+    db = torch.from_numpy(sp["b"]).to(U.DEV)
+    dY = torch.zeros((M, N), dtype=torch.bfloat16, device=U.DEV)
+    assert dY.numel() * 2 > 2 ** 32
+    plan = R.LaunchPlan(np.array([R.group_args(dX, dW, dY, M, K, N, "relu", bias=db)], dtype=B.GROUP_ARGS), B.EPARA_BF16, U.DEV)
+    R.grouped_forward(plan, B.EPARA_BF16)
+    torch.cuda.synchronize()
+    edge = 2 ** 32 // (2 * N)                                            # the row that straddles byte 2^32
+    rows = sorted({0, 1, 255, 256, edge - 1, edge, edge + 1, 2 ** 31 // N, 2 ** 31 // N + 1, M - 257, M - 2, M - 1}
+                  | set(int(r) for r in rng.integers(0, M, 12)))
+    got = dY[torch.tensor(rows, device=U.DEV)].float().cpu().numpy()
+    want = ref.dense_forward(ref.bf16_decode(xb[rows]), ref.bf16_decode(wb), sp["b"], "relu")
+    assert_close(got, want, TOL["bf16"], "rows around the 4 GiB boundary")
+    # nothing outside the group's rows x columns was touched: the padding rows of the last tile row stay unwritten
+    assert torch.count_nonzero(dY[M - 1]).item() > 0
+    del dY
+    torch.cuda.empty_cache()
 
 
 def test_nothing_to_do_is_ok():
