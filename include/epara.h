@@ -172,6 +172,35 @@ int64_t epara_max_inter_frame_count(int64_t latency_us, int64_t fps_milli);
 int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
                       int64_t* frames_per_group, int32_t* group_of_frame);
 
+/* ---- host side: service placement (Sec. 3.3, Alg. 1 and 2) --------------------------------- */
+
+/* The objective phi(Theta) of Eq. "optimal": how many requests of the period the placement list
+ * Theta (placements[0..n), opaque non-negative ids of "service l on server n") lets the request
+ * handler satisfy.  Supplied by the caller (it owns the request list and the handling model);
+ * must be deterministic.  `user` is passed through. */
+typedef double (*epara_phi_fn)(const int32_t* placements, int32_t n, void* user);
+
+/* Alg. 2, submodular placement for full models: starting from theta0, repeatedly evaluate
+ * phi(Theta + delta) for every candidate delta -- all of `candidates` each round if is_set != 0 (a
+ * placement may be chosen again: replicas), else those not chosen yet (a list, without
+ * replacement) -- and append one that maximises it (ties: the earliest candidate; the paper says
+ * "arbitrary").  The round's addition is kept while phi does not decrease (keep_equal != 0, step S1
+ * of Alg. 1) or while it strictly increases (keep_equal == 0); the first addition that fails the
+ * test is dropped and the list before it is returned, as is the list when no candidate is left.
+ * Writes theta_out[0..*n_out) (theta0 first).  Errors: ERR_NULL; ERR_SHAPE for negative counts or
+ * ids; ERR_CAPACITY when the list would outgrow cap (also bounds a phi that never stops improving). */
+int32_t epara_place_full_models(const int32_t* candidates, int32_t n_candidates, int32_t is_set, int32_t keep_equal,
+                                const int32_t* theta0, int32_t n0, epara_phi_fn phi, void* user,
+                                int32_t* theta_out, int32_t cap, int32_t* n_out);
+
+/* Alg. 1, state-aware service placement: S1 places the prioritised partial configurations (a list,
+ * kept while phi does not decrease), S2 places from the set X of all (service, server)
+ * placements, S3 from the set X_dot of placements on the hypothetical server that aggregates every
+ * GPU (multi-GPU parallelism across servers); each step continues from the previous list. */
+int32_t epara_place_services(const int32_t* partial, int32_t n_partial, const int32_t* X, int32_t n_x,
+                             const int32_t* X_dot, int32_t n_xdot, epara_phi_fn phi, void* user,
+                             int32_t* theta_out, int32_t cap, int32_t* n_out);
+
 /* Group planning: the single-GPU part of the allocator's "parallel mode per task" decision.
  *   row_off[g] = sum_{h<g} M_h ; x_off[g] = sum_{h<g} M_h K_h ; y_off[g] = sum_{h<g} M_h N_h
  *   (each G+1 entries; x_off / y_off are element offsets for callers that pack groups

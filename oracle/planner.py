@@ -105,6 +105,44 @@ def dp_deal(first_frame, n_frames, n_groups):
     return [group.count(g) for g in range(n_groups)], group
 
 
+def place_full_models(candidates, is_set, keep_equal, theta0, phi):
+    """Alg. 2 (submodular placement for full models), round by round as the pseudo-code runs:
+    evaluate phi(Theta + delta) for every admissible delta, collect the maximisers, add one of them
+    (the earliest: the paper allows any), and stop -- dropping that addition -- as soon as phi fails
+    to grow (step S1: to not shrink).  A set offers all its elements every round, a list only the
+    ones not chosen yet."""
+    theta = list(theta0)
+    chosen_positions = set()
+    while True:
+        before = phi(theta)
+        best_positions, best_value = [], None
+        for pos, delta in enumerate(candidates):
+            if not is_set and pos in chosen_positions:
+                continue
+            v = phi(theta + [delta])
+            if best_value is None or v > best_value:
+                best_positions, best_value = [pos], v
+            elif v == best_value:
+                best_positions.append(pos)
+        if not best_positions:
+            return theta
+        grown = theta + [candidates[best_positions[0]]]
+        ok = phi(grown) >= before if keep_equal else phi(grown) > before
+        if not ok:
+            return theta
+        theta = grown
+        chosen_positions.add(best_positions[0])
+
+
+def place_services(partial, X, X_dot, phi):
+    """Alg. 1 (state-aware service placement): prioritised partial configurations first (a list, kept
+    while phi does not shrink), then the set of all placements, then the placements on the
+    hypothetical all-GPU server."""
+    theta1 = place_full_models(partial, False, True, [], phi)
+    theta2 = place_full_models(X, True, False, theta1, phi)
+    return place_full_models(X_dot, True, False, theta2, phi)
+
+
 def pick_class(M, classes):
     for c, (max_M, _bm, _bn) in enumerate(classes):
         if M <= max_M:

@@ -47,6 +47,9 @@ class Launch(ctypes.Structure):
 assert ctypes.sizeof(Launch) == 64
 
 
+PHI_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p)   # epara_phi_fn
+
+
 class EparaError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -82,6 +85,10 @@ def lib():
         L.epara_max_inter_frame_count.restype = i64
         L.epara_dp_deal.argtypes = [i64, i64, i64, vp, vp]
         L.epara_dp_deal.restype = i32
+        L.epara_place_full_models.argtypes = [vp, i32, i32, i32, vp, i32, PHI_FN, vp, vp, i32, vp]
+        L.epara_place_full_models.restype = i32
+        L.epara_place_services.argtypes = [vp, i32, vp, i32, vp, i32, PHI_FN, vp, vp, i32, vp]
+        L.epara_place_services.restype = i32
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
@@ -193,6 +200,31 @@ def epara_dp_deal(first_frame, n_frames, n_groups):
     _check(lib().epara_dp_deal(int(first_frame), int(n_frames), int(n_groups), _ptr(per) if per.size else None,
                                _ptr(who) if who.size else None), "epara_dp_deal")
     return per, who
+
+
+def _phi_callback(phi):
+    """Python callable on a list of placement ids -> C callback."""
+    return PHI_FN(lambda p, n, _user: float(phi([p[i] for i in range(n)])))
+
+
+def epara_place_full_models(candidates, is_set, keep_equal, theta0, phi, cap=4096):
+    candidates = np.ascontiguousarray(candidates, dtype=np.int32)
+    theta0 = np.ascontiguousarray(theta0, dtype=np.int32)
+    out, n, cb = np.zeros(max(cap, 1), dtype=np.int32), np.zeros(1, dtype=np.int32), _phi_callback(phi)
+    _check(lib().epara_place_full_models(_ptr(candidates) if candidates.size else None, len(candidates), int(bool(is_set)), int(bool(keep_equal)),
+                                         _ptr(theta0) if theta0.size else None, len(theta0), cb, None, _ptr(out), int(cap), _ptr(n)),
+           "epara_place_full_models")
+    return out[: int(n[0])].tolist()
+
+
+def epara_place_services(partial, X, X_dot, phi, cap=4096):
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in (partial, X, X_dot)]
+    out, n, cb = np.zeros(max(cap, 1), dtype=np.int32), np.zeros(1, dtype=np.int32), _phi_callback(phi)
+    args = []
+    for a in arrs:
+        args += [_ptr(a) if a.size else None, len(a)]
+    _check(lib().epara_place_services(*args, cb, None, _ptr(out), int(cap), _ptr(n)), "epara_place_services")
+    return out[: int(n[0])].tolist()
 
 
 def epara_plan_groups(groups, classes):

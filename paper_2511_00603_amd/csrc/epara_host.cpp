@@ -109,6 +109,57 @@ int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
     return EPARA_OK;
 }
 
+int32_t epara_place_full_models(const int32_t* candidates, int32_t n_candidates, int32_t is_set, int32_t keep_equal,
+                                const int32_t* theta0, int32_t n0, epara_phi_fn phi, void* user,
+                                int32_t* theta_out, int32_t cap, int32_t* n_out)
+{
+    if (n_candidates < 0 || n0 < 0 || cap < 0) return EPARA_ERR_SHAPE;
+    if (!phi || !n_out || (n_candidates > 0 && !candidates) || (n0 > 0 && !theta0) || (cap > 0 && !theta_out)) return EPARA_ERR_NULL;
+    for (int32_t i = 0; i < n_candidates; ++i) if (candidates[i] < 0) return EPARA_ERR_SHAPE;
+    for (int32_t i = 0; i < n0; ++i) if (theta0[i] < 0) return EPARA_ERR_SHAPE;
+    if (n0 > cap) { *n_out = n0; return EPARA_ERR_CAPACITY; }
+    std::vector<int32_t> theta(theta0, theta0 + n0);
+    std::vector<char> used(static_cast<size_t>(n_candidates), 0);      // list semantics: chosen positions
+    double value = phi(theta.data(), static_cast<int32_t>(theta.size()), user);
+    for (;;) {
+        int32_t best = -1;
+        double best_value = 0.0;
+        theta.push_back(0);
+        for (int32_t i = 0; i < n_candidates; ++i) {
+            if (!is_set && used[i]) continue;
+            theta.back() = candidates[i];
+            const double v = phi(theta.data(), static_cast<int32_t>(theta.size()), user);
+            if (best < 0 || v > best_value) { best = i; best_value = v; }      // ties keep the earliest
+        }
+        theta.pop_back();
+        if (best < 0) break;                                             // no candidate left
+        if (!(keep_equal ? best_value >= value : best_value > value)) break;   // this addition is dropped
+        if (static_cast<int32_t>(theta.size()) + 1 > cap) { *n_out = static_cast<int32_t>(theta.size()) + 1; return EPARA_ERR_CAPACITY; }
+        theta.push_back(candidates[best]);
+        used[best] = 1;
+        value = best_value;
+    }
+    *n_out = static_cast<int32_t>(theta.size());
+    std::copy(theta.begin(), theta.end(), theta_out);
+    return EPARA_OK;
+}
+
+int32_t epara_place_services(const int32_t* partial, int32_t n_partial, const int32_t* X, int32_t n_x,
+                             const int32_t* X_dot, int32_t n_xdot, epara_phi_fn phi, void* user,
+                             int32_t* theta_out, int32_t cap, int32_t* n_out)
+{
+    if (cap < 0) return EPARA_ERR_SHAPE;
+    if (!n_out || (cap > 0 && !theta_out)) return EPARA_ERR_NULL;
+    std::vector<int32_t> a(static_cast<size_t>(cap) + 1), b(static_cast<size_t>(cap) + 1);
+    int32_t na = 0, nb = 0;
+    if (int32_t st = epara_place_full_models(partial, n_partial, 0, 1, nullptr, 0, phi, user, a.data(), cap, &na)) { *n_out = na; return st; }
+    if (int32_t st = epara_place_full_models(X, n_x, 1, 0, a.data(), na, phi, user, b.data(), cap, &nb)) { *n_out = nb; return st; }
+    if (int32_t st = epara_place_full_models(X_dot, n_xdot, 1, 0, b.data(), nb, phi, user, a.data(), cap, &na)) { *n_out = na; return st; }
+    *n_out = na;
+    std::copy(a.begin(), a.begin() + na, theta_out);
+    return EPARA_OK;
+}
+
 int32_t epara_request_segments(const int32_t* request_rows, const int64_t* request_off, int32_t G,
                                const int64_t* request_row_bytes, const int64_t* batch_row_bytes,
                                const void* const* request_ptr, const void* const* batch_ptr, int32_t to_batch,

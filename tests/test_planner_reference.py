@@ -218,3 +218,80 @@ def test_dp_deal_is_round_robin_over_the_stream():
     k = B.epara_dp_group_count(need, one)
     per, _ = B.epara_dp_deal(0, need, k)
     assert k == 2 and per.max() <= one
+
+
+# ---- service placement (Sec. 3.3, Alg. 1 and 2) ---------------------------------------------------------
+
+def coverage_phi(requests_of, capacity, n_servers):
+    """A small stand-in for the paper's objective: placement id = service * n_servers + server; a server holds at
+    most `capacity` placements (later ones are ignored, as a full GPU would ignore them); phi = number of
+    distinct requests covered.  Monotone and submodular, with a partition-matroid constraint inside."""
+    def phi(theta):
+        load, covered = {}, set()
+        for x in theta:
+            srv = x % n_servers
+            if load.get(srv, 0) >= capacity:
+                continue
+            load[srv] = load.get(srv, 0) + 1
+            covered |= requests_of[x]
+        return float(len(covered))
+    return phi
+
+
+def test_alg2_on_a_modular_objective_takes_exactly_the_useful_placements_best_first():
+    from paper_2511_00603_amd import binding as B
+    w = {0: 3.0, 1: 0.0, 2: 5.0, 3: 1.0, 4: 0.0}
+    phi = lambda theta: sum(w[x] for x in set(theta))
+    cand = [0, 1, 2, 3, 4]
+    # strict rule (steps S2, S3): only placements that raise phi, in descending order of gain; a set offers
+    # chosen placements again, but a repeat adds nothing and ends the loop
+    assert P.place_full_models(cand, True, False, [], phi) == [2, 0, 3]
+    # S1 rule on a list: every listed configuration is placed, the useless ones too (gain 0 is kept), earliest first
+    assert P.place_full_models(cand, False, True, [], phi) == [2, 0, 3, 1, 4]
+    for is_set, keep in ((True, False), (False, True), (False, False)):
+        assert B.epara_place_full_models(cand, is_set, keep, [], phi) == P.place_full_models(cand, is_set, keep, [], phi)
+    # the list it starts from is kept in front
+    assert B.epara_place_full_models(cand, True, False, [3], phi) == [3, 2, 0]
+
+
+def test_alg2_matches_the_reference_and_the_greedy_bound_on_small_coverage_instances():
+    import itertools
+    from paper_2511_00603_amd import binding as B
+    rng = np.random.default_rng(9)
+    for trial in range(25):
+        n_services, n_servers, capacity = int(rng.integers(2, 5)), int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        ids = [l * n_servers + n for l in range(n_services) for n in range(n_servers)]
+        requests_of = {x: set(int(r) for r in rng.choice(12, size=rng.integers(0, 6), replace=False)) for x in ids}
+        phi = coverage_phi(requests_of, capacity, n_servers)
+        got = B.epara_place_full_models(ids, True, False, [], phi)
+        assert got == P.place_full_models(ids, True, False, [], phi)
+        # the best any placement list can do (one list per choice of <= capacity placements per server)
+        per_server = [[x for x in ids if x % n_servers == s] for s in range(n_servers)]
+        best = 0.0
+        for pick in itertools.product(*[[c for k in range(capacity + 1) for c in itertools.combinations(ps, k)] for ps in per_server]):
+            best = max(best, phi([x for grp in pick for x in grp]))
+        assert phi(got) >= best / 2.0            # greedy on a monotone submodular objective under a matroid: at least half
+        assert len(got) == len(set(got))         # a repeated placement never raises phi here, so none is kept
+
+
+def test_alg1_runs_the_three_steps_in_order_and_errors_are_reported():
+    from paper_2511_00603_amd import binding as B
+    n_servers = 2
+    requests_of = {0: {1, 2}, 1: {2, 3}, 2: {4}, 3: {1, 2, 3, 4, 5}, 100: {6, 7}, 101: set()}
+    phi = coverage_phi(requests_of, 2, n_servers)
+    partial, X, X_dot = [2, 101], [0, 1, 2, 3], [100, 101]
+    want = P.place_services(partial, X, X_dot, phi)
+    assert want[:2] == [2, 101]                  # S1 keeps both prioritised configurations, the useless one too
+    assert 100 in want and want.index(100) > want.index(3)      # S3 comes after S2
+    assert B.epara_place_services(partial, X, X_dot, phi) == want
+    assert B.epara_place_services([], [], [], phi) == []
+    with pytest.raises(B.EparaError) as e:
+        B.epara_place_full_models([0, 2], True, False, [], phi, cap=1)          # two useful placements, room for one
+    assert e.value.status == B.EPARA_ERR_CAPACITY
+    with pytest.raises(B.EparaError) as e:
+        B.epara_place_full_models([0, -1], True, False, [], phi)
+    assert e.value.status == B.EPARA_ERR_SHAPE
+    # an objective that never stops growing is cut off by the capacity instead of looping for ever
+    with pytest.raises(B.EparaError) as e:
+        B.epara_place_full_models([0], True, False, [], lambda theta: float(len(theta)), cap=50)
+    assert e.value.status == B.EPARA_ERR_CAPACITY
