@@ -172,6 +172,31 @@ int64_t epara_max_inter_frame_count(int64_t latency_us, int64_t fps_milli);
 int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
                       int64_t* frames_per_group, int32_t* group_of_frame);
 
+/* ---- host side: request handling (Sec. 3.2) ------------------------------------------------- */
+
+typedef enum {
+    EPARA_HANDLE_TIMEOUT = 0,            /* the request already violates its SLO */
+    EPARA_HANDLE_LOCAL = 1,              /* the locally placed services suffice */
+    EPARA_HANDLE_OFFLOAD = 2,            /* sent on to *destination */
+    EPARA_HANDLE_OFFLOAD_EXCEEDED = 3,   /* local resources insufficient and the offload count is used up */
+    EPARA_HANDLE_INSUFFICIENT = 4        /* no server can take it, by this server's information */
+} epara_handle_decision;
+
+/* One scheduling decision of edge server `self` for one request, the steps of Sec. 3.2 in order:
+ * timed out (now_us > deadline_us) -> TIMEOUT; local_can_serve != 0 -> LOCAL; otherwise
+ * offload_count >= max_offload -> OFFLOAD_EXCEEDED; otherwise offload to a feasible server m != self
+ * drawn with the probability of Eq. (1), idle[m] / sum of idle over the feasible servers, where
+ * idle[m] = theoretical[m] - actual[m] (goodput the server could still add) must be positive and a
+ * server is infeasible when the computation queued on it, queued_us[m], exceeds sync_delay_us +
+ * slo_us; no feasible server -> INSUFFICIENT.  The draw is the caller's: u in [0, 1) picks the first
+ * feasible m (ascending) whose cumulative share exceeds u.  Writes *decision (and *destination, -1
+ * unless OFFLOAD).  ERR_NULL / ERR_SHAPE (n_servers <= 0, self outside, u outside [0, 1)). */
+int32_t epara_handle_request(int64_t now_us, int64_t deadline_us, int32_t local_can_serve,
+                             int32_t offload_count, int32_t max_offload,
+                             const double* theoretical, const double* actual, const int64_t* queued_us,
+                             int32_t n_servers, int32_t self, int64_t sync_delay_us, int64_t slo_us, double u,
+                             int32_t* decision, int32_t* destination);
+
 /* ---- host side: service placement (Sec. 3.3, Alg. 1 and 2) --------------------------------- */
 
 /* The objective phi(Theta) of Eq. "optimal": how many requests of the period the placement list

@@ -105,6 +105,38 @@ def dp_deal(first_frame, n_frames, n_groups):
     return [group.count(g) for g in range(n_groups)], group
 
 
+def handle_request(now_us, deadline_us, local_can_serve, offload_count, max_offload, theoretical, actual, queued_us,
+                   self_index, sync_delay_us, slo_us, u):
+    """Sec. 3.2, the handler's steps in the paper's order -> (decision name, destination or None).
+    Offloading follows Eq. (1): among the other servers whose queued computation does not exceed
+    sync delay + SLO and whose idle goodput (theoretical - actual) is positive, server m is drawn
+    with probability idle_m / sum(idle); the uniform draw u is an input."""
+    if now_us > deadline_us:
+        return "timeout", None
+    if local_can_serve:
+        return "local", None
+    if offload_count >= max_offload:
+        return "offload_exceeded", None
+    shares = []
+    for m in range(len(theoretical)):
+        feasible = m != self_index and queued_us[m] <= sync_delay_us + slo_us and theoretical[m] - actual[m] > 0
+        shares.append(theoretical[m] - actual[m] if feasible else 0.0)
+    total = 0.0
+    for v in shares:
+        total += v
+    if not total > 0:
+        return "insufficient", None
+    acc, last = 0.0, None
+    for m, v in enumerate(shares):
+        if v <= 0:
+            continue
+        acc += v
+        last = m
+        if acc > u * total:
+            break
+    return "offload", last
+
+
 def place_full_models(candidates, is_set, keep_equal, theta0, phi):
     """Alg. 2 (submodular placement for full models), round by round as the pseudo-code runs:
     evaluate phi(Theta + delta) for every admissible delta, collect the maximisers, add one of them

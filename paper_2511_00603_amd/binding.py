@@ -85,6 +85,8 @@ def lib():
         L.epara_max_inter_frame_count.restype = i64
         L.epara_dp_deal.argtypes = [i64, i64, i64, vp, vp]
         L.epara_dp_deal.restype = i32
+        L.epara_handle_request.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp, i32, i32, i64, i64, ctypes.c_double, vp, vp]
+        L.epara_handle_request.restype = i32
         L.epara_place_full_models.argtypes = [vp, i32, i32, i32, vp, i32, PHI_FN, vp, vp, i32, vp]
         L.epara_place_full_models.restype = i32
         L.epara_place_services.argtypes = [vp, i32, vp, i32, vp, i32, PHI_FN, vp, vp, i32, vp]
@@ -200,6 +202,22 @@ def epara_dp_deal(first_frame, n_frames, n_groups):
     _check(lib().epara_dp_deal(int(first_frame), int(n_frames), int(n_groups), _ptr(per) if per.size else None,
                                _ptr(who) if who.size else None), "epara_dp_deal")
     return per, who
+
+
+HANDLE_NAMES = ["timeout", "local", "offload", "offload_exceeded", "insufficient"]
+
+
+def epara_handle_request(now_us, deadline_us, local_can_serve, offload_count, max_offload, theoretical, actual, queued_us,
+                         self_index, sync_delay_us, slo_us, u):
+    """-> (decision name, destination or None)."""
+    th = np.ascontiguousarray(theoretical, dtype=np.float64)
+    ac = np.ascontiguousarray(actual, dtype=np.float64)
+    qu = np.ascontiguousarray(queued_us, dtype=np.int64)
+    out = np.zeros(2, dtype=np.int32)
+    _check(lib().epara_handle_request(int(now_us), int(deadline_us), int(bool(local_can_serve)), int(offload_count), int(max_offload),
+                                      _ptr(th), _ptr(ac), _ptr(qu), len(th), int(self_index), int(sync_delay_us), int(slo_us),
+                                      float(u), _ptr(out[0:1]), _ptr(out[1:2])), "epara_handle_request")
+    return HANDLE_NAMES[int(out[0])], (int(out[1]) if out[1] >= 0 else None)
 
 
 def _phi_callback(phi):

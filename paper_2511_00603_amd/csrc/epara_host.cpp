@@ -109,6 +109,41 @@ int32_t epara_dp_deal(int64_t first_frame, int64_t n_frames, int64_t n_groups,
     return EPARA_OK;
 }
 
+int32_t epara_handle_request(int64_t now_us, int64_t deadline_us, int32_t local_can_serve,
+                             int32_t offload_count, int32_t max_offload,
+                             const double* theoretical, const double* actual, const int64_t* queued_us,
+                             int32_t n_servers, int32_t self, int64_t sync_delay_us, int64_t slo_us, double u,
+                             int32_t* decision, int32_t* destination)
+{
+    if (!decision || !destination) return EPARA_ERR_NULL;
+    *destination = -1;
+    if (n_servers <= 0 || self < 0 || self >= n_servers || !(u >= 0.0 && u < 1.0)) return EPARA_ERR_SHAPE;
+    if (now_us > deadline_us) { *decision = EPARA_HANDLE_TIMEOUT; return EPARA_OK; }
+    if (local_can_serve) { *decision = EPARA_HANDLE_LOCAL; return EPARA_OK; }
+    if (offload_count >= max_offload) { *decision = EPARA_HANDLE_OFFLOAD_EXCEEDED; return EPARA_OK; }
+    if (!theoretical || !actual || !queued_us) return EPARA_ERR_NULL;
+    auto idle = [&](int32_t m) {
+        if (m == self || queued_us[m] > sync_delay_us + slo_us) return 0.0;
+        const double v = theoretical[m] - actual[m];
+        return v > 0.0 ? v : 0.0;
+    };
+    double total = 0.0;
+    for (int32_t m = 0; m < n_servers; ++m) total += idle(m);
+    if (!(total > 0.0)) { *decision = EPARA_HANDLE_INSUFFICIENT; return EPARA_OK; }
+    double acc = 0.0;
+    int32_t last = -1;
+    for (int32_t m = 0; m < n_servers; ++m) {
+        const double v = idle(m);
+        if (v <= 0.0) continue;
+        acc += v;
+        last = m;
+        if (acc > u * total) break;
+    }
+    *decision = EPARA_HANDLE_OFFLOAD;
+    *destination = last;                     // rounding can leave acc == u * total at the end: the last feasible server
+    return EPARA_OK;
+}
+
 int32_t epara_place_full_models(const int32_t* candidates, int32_t n_candidates, int32_t is_set, int32_t keep_equal,
                                 const int32_t* theta0, int32_t n0, epara_phi_fn phi, void* user,
                                 int32_t* theta_out, int32_t cap, int32_t* n_out)

@@ -295,3 +295,35 @@ def test_alg1_runs_the_three_steps_in_order_and_errors_are_reported():
     with pytest.raises(B.EparaError) as e:
         B.epara_place_full_models([0], True, False, [], lambda theta: float(len(theta)), cap=50)
     assert e.value.status == B.EPARA_ERR_CAPACITY
+
+
+# ---- request handling (Sec. 3.2) -----------------------------------------------------------------------
+
+def test_handler_steps_come_in_the_papers_order():
+    from paper_2511_00603_amd import binding as B
+    th, ac, qu = [10.0, 8.0, 6.0], [10.0, 2.0, 3.0], [0, 0, 0]
+    both = lambda *a: (B.epara_handle_request(*a), P.handle_request(*a))
+    g, w = both(101, 100, True, 0, 5, th, ac, qu, 0, 10, 50, 0.3);  assert g == w == ("timeout", None)      # a late request is dropped even if it could be served
+    g, w = both(100, 100, True, 9, 5, th, ac, qu, 0, 10, 50, 0.3);  assert g == w == ("local", None)        # local first, whatever the offload count
+    g, w = both(0, 100, False, 5, 5, th, ac, qu, 0, 10, 50, 0.3);   assert g == w == ("offload_exceeded", None)
+    g, w = both(0, 100, False, 4, 5, th, ac, qu, 0, 10, 50, 0.3);   assert g == w and g[0] == "offload" and g[1] in (1, 2)
+    g, w = both(0, 100, False, 0, 5, th, th, qu, 0, 10, 50, 0.3);   assert g == w == ("insufficient", None)   # nobody has idle goodput
+    g, w = both(0, 100, False, 0, 5, th, ac, [0, 61, 61], 0, 10, 50, 0.3); assert g == w == ("insufficient", None)  # queues beyond sync delay + SLO
+    g, w = both(0, 100, False, 0, 5, th, ac, [0, 61, 60], 0, 10, 50, 0.99); assert g == w == ("offload", 2)
+    # the deciding server never offloads to itself, however idle it is
+    g, w = both(0, 100, False, 0, 5, [50.0, 1.0], [0.0, 0.5], [0, 0], 0, 10, 50, 0.0);  assert g == w == ("offload", 1)
+    with pytest.raises(B.EparaError):
+        B.epara_handle_request(0, 1, False, 0, 5, th, ac, qu, 3, 10, 50, 0.3)
+    with pytest.raises(B.EparaError):
+        B.epara_handle_request(0, 1, False, 0, 5, th, ac, qu, 0, 10, 50, 1.0)
+
+
+def test_offloading_probabilities_are_the_idle_goodput_shares_of_eq_1():
+    from paper_2511_00603_amd import binding as B
+    # idle goodput 0 (self), 1, 0 (saturated), 3, 4 (queue too long -> excluded): shares 1/4 and 3/4
+    th, ac, qu = [9.0, 5.0, 2.0, 7.0, 8.0], [1.0, 4.0, 2.0, 4.0, 4.0], [0, 0, 0, 10, 99]
+    n = 4000
+    picks = [B.epara_handle_request(0, 100, False, 0, 5, th, ac, qu, 0, 20, 30, (i + 0.5) / n) for i in range(n)]
+    assert all(p == P.handle_request(0, 100, False, 0, 5, th, ac, qu, 0, 20, 30, (i + 0.5) / n) for i, p in enumerate(picks))
+    count = {m: sum(1 for p in picks if p == ("offload", m)) for m in range(5)}
+    assert count == {0: 0, 1: n // 4, 2: 0, 3: 3 * n // 4, 4: 0}
