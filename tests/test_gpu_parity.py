@@ -245,6 +245,44 @@ def test_pack_weights_layout_round_trip():
     assert np.array_equal(p, want)
 
 
+# ---- what the kernel reads is what the reference planner wrote ----------------------------------------
+
+@pytest.mark.parametrize("index,shrink", [(4, {}), (3, {}), (2, {})])
+def test_device_copies_of_the_tile_table_and_visit_order_are_the_reference_planners(index, shrink):
+    from oracle import planner as P
+    staged = StagedMix(make_mix(index, **shrink), None, U.DEV)
+    for plan in staged.plans():
+        tiles = plan.d_tiles.cpu().numpy()[: plan.tiles.nbytes].view(B.TILE)
+        order = plan.d_order.cpu().numpy()[: plan.order.nbytes].view(np.int32)
+        args = plan.d_args.cpu().numpy()[: plan.args.nbytes].view(B.GROUP_ARGS)
+        assert np.array_equal(args, plan.args)
+        gated = bool(np.all(plan.args["act"] == B.EPARA_ACT_SWIGLU))
+        groups = [(int(a["M"]), int(a["K"]), int(a["N"])) + ((True,) if gated else ()) for a in plan.args]
+        classes = [tuple(int(v) for v in c) for c in plan.classes]
+        row_off, x_off, y_off, want_tiles = P.plan_groups([g[:3] for g in groups], classes)
+        assert [tuple(int(v) for v in t) for t in tiles] == want_tiles
+        want_order = P.schedule_tiles(groups, classes, plan.n_stream_classes, want_tiles, plan.n_workgroups, 8, 1, 4)
+        assert order.tolist() == want_order
+        assert plan.row_off.tolist() == row_off and plan.x_off.tolist() == x_off and plan.y_off.tolist() == y_off
+
+
+def test_end_to_end_error_against_the_unrounded_masters_is_reported():
+    """Informative: the parity gate compares against an oracle fed the same rounded inputs; this is the error
+    against the fp32 masters, i.e. including the storage formats' own rounding (bf16: about 2^-9 per operand)."""
+    mix = make_mix(4, d=512, ffn=1376)
+    staged = StagedMix(mix, "bf16", U.DEV)
+    staged.run()
+    torch.cuda.synchronize()
+    from parity_util import rel_err
+    worst = 0.0
+    for (g, label, Y) in staged.results()[-1]:
+        svc = mix.services[g]
+        _H, Yref = ref.ffn_swiglu(svc.X.astype(np.float64), svc.Wgate.astype(np.float64), svc.Wup.astype(np.float64), svc.Wdown.astype(np.float64))
+        worst = max(worst, rel_err(Y, Yref))
+    print("end-to-end max relative error vs fp32 masters (bf16 decode FFN, reduced): %.3e" % worst)
+    assert worst < 5e-2
+
+
 # ---- the five mixes ---------------------------------------------------------------------------------
 
 def test_mix1_mlp_fp32_full():
