@@ -97,6 +97,40 @@ typedef struct {
     int32_t G;
 } epara_launch;
 
+/* ---- chains of launches in one kernel -----------------------------------------------------
+ * The requests of a batch cross every layer of their service (Sec. 3.1: a batch is executed as a
+ * whole), so consecutive grouped launches form a chain in which a group of one launch reads what a
+ * group of the launch before wrote.  A chain runs as ONE persistent kernel: every workgroup walks
+ * its list of the first launch ("phase"), then of the second, ...; a tile whose group reads a
+ * produced tensor first waits until every tile of the producing group has been stored. */
+
+/* What group g of a phase waits for: counter `counter` (or -1: nothing) must reach `need` = the
+ * number of tiles of the producing group.  8 bytes; the same bytes on host and device. */
+typedef struct { int32_t counter; int32_t need; } epara_chain_wait;
+
+/* One phase of epara_schedule_chain: inputs as for epara_schedule_tiles, outputs order / n_slots. */
+typedef struct {
+    const epara_group_desc* groups;   /* host, G entries */
+    const epara_tile_class* classes;  /* host, n_classes entries */
+    const epara_tile*       tiles;    /* host, canonical table of (groups, classes) */
+    int32_t*                order;    /* host, out: order_cap entries; NULL to query n_slots */
+    int64_t n_tiles;
+    int64_t order_cap;
+    int64_t n_slots;                  /* out */
+    int32_t G, n_classes, n_stream_classes, reserved;
+} epara_phase_schedule;
+
+/* One phase of epara_grouped_chain. */
+typedef struct {
+    const epara_launch*     launch;   /* host; all phases share n_workgroups */
+    const epara_chain_wait* h_waits;  /* host, launch->G entries; NULL for a phase that waits for nothing */
+    const epara_chain_wait* d_waits;  /* device, same bytes */
+    int32_t out_dtype;
+    int32_t counter_base;             /* tiles of group g of this phase count on counter counter_base + g */
+} epara_chain_phase;
+
+#define EPARA_MAX_CHAIN_PHASES 4
+
 /* SwiGLU FFN of one service: Y = (SiLU(X Wgate) * (X Wup)) Wdown, H = the hidden
  * activations [M, d_ff] (caller-provided scratch, written then read). */
 typedef struct {
@@ -265,6 +299,29 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
                              int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
                              int32_t* order, int64_t order_cap, int64_t* n_slots);
 
+/* Visit orders for a chain of launches that one kernel runs phase after phase (a workgroup's
+ * list of phase p+1 follows its list of phase p).  The rule of epara_schedule_tiles with the
+ * workgroup loads shared by all phases, so that a workgroup with much work in one phase gets less in
+ * another:
+ *   1. panel tiles phase by phase, each phase's sequence as in epara_schedule_tiles; the position l
+ *      of the round-robin is not reset between phases.
+ *   2. the streaming tiles of ALL phases together, by descending cost (ties: earlier phase, then
+ *      lower tile index), each onto the workgroup with the smallest accumulated cost (ties: lower
+ *      workgroup); it joins that workgroup's list of its own phase, after the panel tiles.
+ * Per phase: n_slots = W * (longest list of that phase) and order as in epara_schedule_tiles.
+ * With n_phases = 1 this IS epara_schedule_tiles.  Errors as there; ERR_CAPACITY (every n_slots
+ * written) if an order array is too small. */
+int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
+                             int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n);
+
+/* The waits of one phase of a chain: producer[g] = the group of the phase before whose output Y is
+ * group g's input X, or -1.  waits[g] = { counter_base + producer[g], number of tiles of that group
+ * in producer_tiles } or { -1, 0 }; counter_base is the producing phase's.  Host only.
+ * ERR_SHAPE for an index outside [-1, G_producer) or a tile whose group is outside. */
+int32_t epara_chain_waits(const epara_tile* producer_tiles, int64_t n_producer_tiles, int32_t G_producer,
+                          int32_t counter_base, const int32_t* producer, int32_t G_consumer,
+                          epara_chain_wait* waits);
+
 /* The tile classes the kernels implement for an input dtype (gated = EPARA_ACT_SWIGLU
  * launches, whose BN counts hidden columns).  Writes up to cap classes, *n_classes = count and
  * *n_stream_classes = how many of them (the first ones) are weight-streaming classes.
@@ -312,6 +369,37 @@ int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int3
  * FP8_E4M3 (codes sat(RNE(h / s_h))), out_dtype = BF16. */
 int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* down,
                                  int32_t in_dtype, int32_t h_dtype, int32_t out_dtype, void* stream);
+
+/* Bytes of the device workspace of a chain with n_counters completion counters (the sum of G
+ * over its phases): a 16-byte header (error flag, exit count) and the counters. */
+int64_t epara_chain_workspace_bytes(int32_t n_counters);
+
+/* Zeroes a chain workspace (one small kernel).  Needed once: a chain kernel leaves the counters
+ * zero again when its last workgroup exits. */
+int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* stream);
+
+/* The n_phases (1..EPARA_MAX_CHAIN_PHASES) launches of a chain in ONE persistent kernel of
+ * n_workgroups workgroups: the same tiles, arithmetic and results as epara_grouped_forward called
+ * phase by phase (bit-identical), without the launch boundaries: a workgroup that finishes its
+ * share of a phase goes on with the next phase at once, and a tile of group g waits only for the
+ * group that produces its input (phase[p].h_waits[g]).  Completion is counted per group in
+ * d_workspace (counter counter_base + g of phase p rises by one per stored tile, made visible with
+ * device-scope release / acquire); counter ranges of different phases must not overlap.
+ * Requirements beyond epara_grouped_forward's, checked before anything is enqueued: every phase has
+ * the same n_workgroups, which must not exceed what the GPU keeps resident at once (a waiting
+ * workgroup must never keep the one it waits for from running) -> ERR_SHAPE; a wait must name a
+ * counter of the phase before, with need = that group's tile count, and the waiting group's X must
+ * be that group's Y with matching shape -> ERR_SHAPE; workspace too small -> ERR_CAPACITY.
+ * A wait polls at most spin_limit times (0 = the default, some seconds); if it runs out the kernel
+ * sets the error flag, goes on without the data and still terminates, and the outputs of the chain
+ * are invalid: read the flag with epara_chain_status.  Two chains that use one workspace must not
+ * overlap in time. */
+int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                            void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream);
+
+/* Waits for `stream`, then *flag = the workspace's error flag (0 = every wait of every chain since
+ * the last call ended normally) and clears it. */
+int32_t epara_chain_status(void* d_workspace, void* stream, int32_t* flag);
 
 /* ---- device side: the step before and after the path (batch forming) --------------------- */
 

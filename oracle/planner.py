@@ -229,52 +229,77 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        the workgroup with the smallest accumulated cost (ties: lower workgroup), after that
        workgroup's panel tiles.
     """
+    return schedule_chain([(groups, classes, n_stream_classes, tiles)], n_workgroups, n_xcd, panel_m, panel_n)[0]
+
+
+def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
+    """Visit orders of a chain of launches run by one kernel, phase after phase in every workgroup.
+
+    phases: list of (groups, classes, n_stream_classes, tiles).  The rule of schedule_tiles with the
+    workgroup loads shared by all phases: step 1 phase by phase without resetting the round-robin
+    position l; step 2 once over the streaming tiles of all phases (ties of equal cost: earlier
+    phase, then lower tile index), each tile joining its workgroup's list of its own phase.
+    Returns one order per phase (W * longest list of that phase entries).
+    """
     import heapq
     W, X = n_workgroups, n_xcd
     if W <= 0 or X <= 0 or W % X != 0 or panel_m <= 0 or panel_n <= 0:
         raise ValueError("bad schedule parameters")
-    if not 0 <= n_stream_classes <= len(classes):
-        raise ValueError("bad number of streaming classes")
-    first = {}
-    for t, tile in enumerate(tiles):
-        first.setdefault(tile[0], t)
-    lists = [[] for _ in range(W)]
-    load = [0] * W
     per = W // X
+    lists = [[[] for _ in range(W)] for _ in phases]
+    load = [0] * W
     l = 0
-    panel_classes = sorted(range(n_stream_classes, len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
-    for c in panel_classes:
-        members = sorted({t[0] for t in tiles if t[5] == c}, key=lambda g: (-groups[g][1], g))
-        _, bm, bn = classes[c]
-        for g in members:
-            M, K, N = groups[g][:3]
-            TM, TN = -(-M // bm), -(-N // bn)
-            for pn in range(0, TN, panel_n):
-                for pm in range(0, TM, panel_m):
-                    for tn in range(pn, min(pn + panel_n, TN)):
-                        for tm in range(pm, min(pm + panel_m, TM)):
-                            x, i = divmod(l % W, per)
-                            b = i * X + x
-                            lists[b].append(first[g] + tm * TN + tn)
-                            load[b] += 340 * K
-                            l += 1
     stream = []
-    for t, tile in enumerate(tiles):
-        if tile[5] < n_stream_classes:
-            g = groups[tile[0]]
-            gated = len(g) > 3 and bool(g[3])
-            stream.append((-(g[1] * (tile[4] * (2 if gated else 1) + classes[tile[5]][1])), t))
+    for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
+        if not 0 <= n_stream_classes <= len(classes):
+            raise ValueError("bad number of streaming classes")
+        first = {}
+        for t, tile in enumerate(tiles):
+            first.setdefault(tile[0], t)
+        panel_classes = sorted(range(n_stream_classes, len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
+        for c in panel_classes:
+            members = sorted({t[0] for t in tiles if t[5] == c}, key=lambda g: (-groups[g][1], g))
+            _, bm, bn = classes[c]
+            for g in members:
+                M, K, N = groups[g][:3]
+                TM, TN = -(-M // bm), -(-N // bn)
+                for pn in range(0, TN, panel_n):
+                    for pm in range(0, TM, panel_m):
+                        for tn in range(pn, min(pn + panel_n, TN)):
+                            for tm in range(pm, min(pm + panel_m, TM)):
+                                x, i = divmod(l % W, per)
+                                b = i * X + x
+                                lists[p][b].append(first[g] + tm * TN + tn)
+                                load[b] += 340 * K
+                                l += 1
+        for t, tile in enumerate(tiles):
+            if tile[5] < n_stream_classes:
+                g = groups[tile[0]]
+                gated = len(g) > 3 and bool(g[3])
+                stream.append((-(g[1] * (tile[4] * (2 if gated else 1) + classes[tile[5]][1])), p, t))
     stream.sort()
     heap = [(load[b], b) for b in range(W)]
     heapq.heapify(heap)
-    for negcost, t in stream:
+    for negcost, p, t in stream:
         ld, b = heapq.heappop(heap)
-        lists[b].append(t)
+        lists[p][b].append(t)
         heapq.heappush(heap, (ld - negcost, b))
-    assert l + len(stream) == len(tiles)
-    longest = max(len(v) for v in lists)
-    order = [-1] * (longest * W)
-    for b in range(W):
-        for j, t in enumerate(lists[b]):
-            order[j * W + b] = t
-    return order
+    orders = []
+    for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
+        assert sum(len(v) for v in lists[p]) == len(tiles)
+        longest = max(len(v) for v in lists[p])
+        order = [-1] * (longest * W)
+        for b in range(W):
+            for j, t in enumerate(lists[p][b]):
+                order[j * W + b] = t
+        orders.append(order)
+    return orders
+
+
+def chain_waits(producer_tiles, counter_base, producer):
+    """What each group of a phase waits for: (counter, need) = (counter_base + q, number of tiles of
+    group q in the phase before) for producer[g] = q >= 0, (-1, 0) otherwise."""
+    count = {}
+    for tile in producer_tiles:
+        count[tile[0]] = count.get(tile[0], 0) + 1
+    return [(-1, 0) if q < 0 else (counter_base + q, count.get(q, 0)) for q in producer]

@@ -32,6 +32,9 @@ FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "
                      ("M", "<i4"), ("d_model", "<i4"), ("d_ff", "<i4"),
                      ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
 SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<i8"), ("first_chunk", "<i8"), ("group", "<i4"), ("reserved", "<i4")])
+CHAIN_WAIT = np.dtype([("counter", "<i4"), ("need", "<i4")])
+EPARA_MAX_CHAIN_PHASES = 4
+assert CHAIN_WAIT.itemsize == 8
 assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
 assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
 
@@ -45,6 +48,23 @@ class Launch(ctypes.Structure):
 
 
 assert ctypes.sizeof(Launch) == 64
+
+
+class PhaseSchedule(ctypes.Structure):
+    """struct epara_phase_schedule."""
+    _fields_ = [("groups", ctypes.c_void_p), ("classes", ctypes.c_void_p), ("tiles", ctypes.c_void_p), ("order", ctypes.c_void_p),
+                ("n_tiles", ctypes.c_int64), ("order_cap", ctypes.c_int64), ("n_slots", ctypes.c_int64),
+                ("G", ctypes.c_int32), ("n_classes", ctypes.c_int32), ("n_stream_classes", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class ChainPhase(ctypes.Structure):
+    """struct epara_chain_phase."""
+    _fields_ = [("launch", ctypes.POINTER(Launch)), ("h_waits", ctypes.c_void_p), ("d_waits", ctypes.c_void_p),
+                ("out_dtype", ctypes.c_int32), ("counter_base", ctypes.c_int32)]
+
+
+assert ctypes.sizeof(PhaseSchedule) == 72 and ctypes.sizeof(ChainPhase) == 32
 
 
 PHI_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, ctypes.c_void_p)   # epara_phi_fn
@@ -94,6 +114,16 @@ def lib():
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
+        L.epara_schedule_chain.argtypes = [vp, i32, i32, i32, i32, i32]
+        L.epara_chain_waits.argtypes = [vp, i64, i32, i32, vp, i32, vp]
+        L.epara_chain_workspace_bytes.argtypes = [i32]
+        L.epara_chain_workspace_bytes.restype = i64
+        L.epara_chain_workspace_init.argtypes = [vp, i64, vp]
+        L.epara_grouped_chain.argtypes = [vp, i32, i32, vp, i64, ctypes.c_uint32, vp]
+        L.epara_chain_status.argtypes = [vp, vp, vp]
+        for name in ("epara_schedule_chain", "epara_chain_waits", "epara_chain_workspace_init", "epara_grouped_chain",
+                     "epara_chain_status"):
+            getattr(L, name).restype = i32
         L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
         L.epara_packed_weight_bytes.argtypes = [i32, i32, i32]
         L.epara_packed_weight_bytes.restype = i64
@@ -271,6 +301,56 @@ def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups,
     order = np.zeros(int(n[0]), dtype=np.int32)
     _check(lib().epara_schedule_tiles(*args, _ptr(order), len(order), _ptr(n)), "epara_schedule_tiles")
     return order
+
+
+def epara_schedule_chain(phases, n_workgroups, n_xcd=8, panel_m=8, panel_n=4):
+    """phases: list of (groups, classes, n_stream_classes, tiles) -> list of order arrays (one per phase)."""
+    keep, arr = [], (PhaseSchedule * max(len(phases), 1))()
+    for i, (groups, classes, n_stream, tiles) in enumerate(phases):
+        groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+        classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
+        tiles = np.ascontiguousarray(tiles, dtype=TILE)
+        keep.append((groups, classes, tiles))
+        arr[i].groups, arr[i].classes, arr[i].tiles, arr[i].order = _ptr(groups), _ptr(classes), _ptr(tiles), None
+        arr[i].n_tiles, arr[i].order_cap, arr[i].n_slots = len(tiles), 0, 0
+        arr[i].G, arr[i].n_classes, arr[i].n_stream_classes = len(groups), len(classes), int(n_stream)
+    args = (len(phases), int(n_workgroups), int(n_xcd), int(panel_m), int(panel_n))
+    _check(lib().epara_schedule_chain(ctypes.addressof(arr), *args), "epara_schedule_chain")
+    orders = [np.zeros(int(arr[i].n_slots), dtype=np.int32) for i in range(len(phases))]
+    for i, o in enumerate(orders):
+        arr[i].order, arr[i].order_cap = _ptr(o) if len(o) else None, len(o)
+    _check(lib().epara_schedule_chain(ctypes.addressof(arr), *args), "epara_schedule_chain")
+    return orders
+
+
+def epara_chain_waits(producer_tiles, G_producer, counter_base, producer):
+    """-> CHAIN_WAIT[len(producer)]."""
+    producer_tiles = np.ascontiguousarray(producer_tiles, dtype=TILE)
+    producer = np.ascontiguousarray(producer, dtype=np.int32)
+    waits = np.zeros(len(producer), dtype=CHAIN_WAIT)
+    _check(lib().epara_chain_waits(_ptr(producer_tiles), len(producer_tiles), int(G_producer), int(counter_base),
+                                   _ptr(producer), len(producer), _ptr(waits)), "epara_chain_waits")
+    return waits
+
+
+def epara_chain_workspace_bytes(n_counters):
+    return int(lib().epara_chain_workspace_bytes(int(n_counters)))
+
+
+def epara_chain_workspace_init(d_workspace, nbytes, stream):
+    _check(lib().epara_chain_workspace_init(int(d_workspace), int(nbytes), stream), "epara_chain_workspace_init")
+
+
+def epara_grouped_chain(phases, in_dtype, d_workspace, workspace_bytes, stream, spin_limit=0):
+    """phases: a ctypes array of ChainPhase (kept alive by the caller)."""
+    _check(lib().epara_grouped_chain(ctypes.addressof(phases), len(phases), int(in_dtype), int(d_workspace),
+                                     int(workspace_bytes), int(spin_limit), stream), "epara_grouped_chain")
+
+
+def epara_chain_status(d_workspace, stream):
+    flag = np.zeros(1, dtype=np.int32)
+    _check(lib().epara_chain_status(int(d_workspace), stream, _ptr(flag)), "epara_chain_status")
+    return int(flag[0])
 
 
 def epara_kernel_classes(in_dtype, gated, narrow=False):

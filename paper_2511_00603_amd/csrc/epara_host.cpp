@@ -297,6 +297,118 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
     return EPARA_OK;
 }
 
+int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
+                             int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n)
+{
+    if (n_phases < 0) return EPARA_ERR_SHAPE;
+    if (n_phases > 0 && !phases) return EPARA_ERR_NULL;
+    if (n_workgroups <= 0 || n_xcd <= 0 || n_workgroups % n_xcd != 0 || panel_m <= 0 || panel_n <= 0)
+        return EPARA_ERR_SHAPE;
+    const int64_t W = n_workgroups, X = n_xcd, per_die = W / X;
+
+    // per phase: where each group's tiles start in the canonical table, and which class it was cut with
+    std::vector<std::vector<int64_t>> first(static_cast<size_t>(n_phases));
+    std::vector<std::vector<int32_t>> cls(static_cast<size_t>(n_phases));
+    for (int32_t p = 0; p < n_phases; ++p) {
+        const epara_phase_schedule& ph = phases[p];
+        if (ph.G < 0 || ph.n_tiles < 0) return EPARA_ERR_SHAPE;
+        if ((ph.G > 0 && !ph.groups) || (ph.n_tiles > 0 && !ph.tiles)) return EPARA_ERR_NULL;
+        if (int32_t st = check_classes(ph.classes, ph.n_classes)) return st;
+        if (ph.n_stream_classes < 0 || ph.n_stream_classes > ph.n_classes) return EPARA_ERR_SHAPE;
+        if (ph.n_tiles > INT32_MAX) return EPARA_ERR_SHAPE;
+        first[p].assign(static_cast<size_t>(ph.G), -1);
+        cls[p].assign(static_cast<size_t>(ph.G), -1);
+        for (int64_t t = 0; t < ph.n_tiles; ++t) {
+            const epara_tile& tl = ph.tiles[t];
+            if (tl.group < 0 || tl.group >= ph.G || tl.cls < 0 || tl.cls >= ph.n_classes) return EPARA_ERR_SHAPE;
+            if (first[p][tl.group] < 0) { first[p][tl.group] = t; cls[p][tl.group] = tl.cls; }
+            else if (cls[p][tl.group] != tl.cls) return EPARA_ERR_SHAPE;
+        }
+        // every group's tile count must be what the grid rule gives, or the table is not canonical
+        int64_t expect = 0;
+        for (int32_t g = 0; g < ph.G; ++g)
+            if (first[p][g] >= 0) {
+                if (first[p][g] != expect) return EPARA_ERR_SHAPE;
+                expect += ceil_div(ph.groups[g].M, ph.classes[cls[p][g]].BM) * ceil_div(ph.groups[g].N, ph.classes[cls[p][g]].BN);
+            }
+        if (expect != ph.n_tiles) return EPARA_ERR_SHAPE;
+    }
+
+    std::vector<std::vector<std::vector<int32_t>>> lists(static_cast<size_t>(n_phases),
+                                                          std::vector<std::vector<int32_t>>(static_cast<size_t>(W)));
+    std::vector<int64_t> load(static_cast<size_t>(W), 0);
+
+    // 1. panel tiles, phase after phase; the round-robin position carries over
+    int64_t l = 0;
+    std::vector<int32_t> class_order, members;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        const epara_phase_schedule& ph = phases[p];
+        class_order.clear();
+        for (int32_t c = ph.n_stream_classes; c < ph.n_classes; ++c) class_order.push_back(c);
+        std::stable_sort(class_order.begin(), class_order.end(), [&](int32_t a, int32_t b) {
+            return static_cast<int64_t>(ph.classes[a].BM) * ph.classes[a].BN > static_cast<int64_t>(ph.classes[b].BM) * ph.classes[b].BN;
+        });
+        for (int32_t c : class_order) {
+            members.clear();
+            for (int32_t g = 0; g < ph.G; ++g)
+                if (cls[p][g] == c) members.push_back(g);
+            std::stable_sort(members.begin(), members.end(),
+                             [&](int32_t a, int32_t b) { return ph.groups[a].K > ph.groups[b].K; });
+            const int64_t BM = ph.classes[c].BM, BN = ph.classes[c].BN;
+            for (int32_t g : members) {
+                const int64_t TM = ceil_div(ph.groups[g].M, BM), TN = ceil_div(ph.groups[g].N, BN);
+                for (int64_t pn = 0; pn < TN; pn += panel_n)
+                    for (int64_t pm = 0; pm < TM; pm += panel_m)
+                        for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
+                            for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
+                                const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
+                                lists[p][b].push_back(static_cast<int32_t>(first[p][g] + tm * TN + tn));
+                                load[b] += 340 * static_cast<int64_t>(ph.groups[g].K);
+                                ++l;
+                            }
+            }
+        }
+    }
+
+    // 2. streaming tiles of every phase together, longest first onto the least loaded workgroup
+    struct item { int64_t cost; int32_t phase; int32_t tile; };
+    std::vector<item> stream;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        const epara_phase_schedule& ph = phases[p];
+        for (int64_t t = 0; t < ph.n_tiles; ++t)
+            if (ph.tiles[t].cls < ph.n_stream_classes) {
+                const epara_group_desc& d = ph.groups[ph.tiles[t].group];
+                const int64_t units = static_cast<int64_t>(ph.tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + ph.classes[ph.tiles[t].cls].BM;
+                stream.push_back({units * d.K, p, static_cast<int32_t>(t)});
+            }
+    }
+    std::stable_sort(stream.begin(), stream.end(), [](const item& a, const item& b) { return a.cost > b.cost; });
+    typedef std::pair<int64_t, int32_t> entry;                  // (load, workgroup): smallest first
+    std::priority_queue<entry, std::vector<entry>, std::greater<entry>> heap;
+    for (int32_t b = 0; b < W; ++b) heap.push({load[b], b});
+    for (const item& it : stream) {
+        entry e = heap.top();
+        heap.pop();
+        lists[it.phase][e.second].push_back(it.tile);
+        heap.push({e.first + it.cost, e.second});
+    }
+
+    int32_t status = EPARA_OK;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        epara_phase_schedule& ph = phases[p];
+        size_t longest = 0, total = 0;
+        for (const auto& v : lists[p]) { longest = std::max(longest, v.size()); total += v.size(); }
+        if (static_cast<int64_t>(total) != ph.n_tiles) return EPARA_ERR_SHAPE;
+        ph.n_slots = static_cast<int64_t>(longest) * W;
+        if (!ph.order) continue;
+        if (ph.order_cap < ph.n_slots) { status = EPARA_ERR_CAPACITY; continue; }
+        std::fill(ph.order, ph.order + ph.n_slots, -1);
+        for (int64_t b = 0; b < W; ++b)
+            for (size_t j = 0; j < lists[p][b].size(); ++j) ph.order[static_cast<int64_t>(j) * W + b] = lists[p][b][j];
+    }
+    return status;
+}
+
 int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
                              const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
                              const epara_tile* tiles, int64_t n_tiles,
@@ -305,96 +417,35 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
 {
     if (G < 0 || n_tiles < 0) return EPARA_ERR_SHAPE;
     if (!n_slots || (G > 0 && !groups) || (n_tiles > 0 && !tiles)) return EPARA_ERR_NULL;
-    if (int32_t st = check_classes(classes, n_classes)) return st;
-    if (n_workgroups <= 0 || n_xcd <= 0 || n_workgroups % n_xcd != 0 || panel_m <= 0 || panel_n <= 0)
-        return EPARA_ERR_SHAPE;
-    if (n_stream_classes < 0 || n_stream_classes > n_classes) return EPARA_ERR_SHAPE;
-    if (n_tiles > INT32_MAX) return EPARA_ERR_SHAPE;
+    epara_phase_schedule ph;
+    std::memset(&ph, 0, sizeof ph);
+    ph.groups = groups; ph.classes = classes; ph.tiles = tiles; ph.order = order;
+    ph.n_tiles = n_tiles; ph.order_cap = order_cap;
+    ph.G = G; ph.n_classes = n_classes; ph.n_stream_classes = n_stream_classes;
+    const int32_t st = epara_schedule_chain(&ph, 1, n_workgroups, n_xcd, panel_m, panel_n);
+    if (st == EPARA_OK || st == EPARA_ERR_CAPACITY) *n_slots = ph.n_slots;
+    return st;
+}
 
-    const int64_t W = n_workgroups, X = n_xcd, per_die = W / X;
-
-    // where each group's tiles start in the canonical table, and which class it was cut with
-    std::vector<int64_t> first(G, -1);
-    std::vector<int32_t> cls(G, -1);
-    for (int64_t t = 0; t < n_tiles; ++t) {
-        const epara_tile& tl = tiles[t];
-        if (tl.group < 0 || tl.group >= G || tl.cls < 0 || tl.cls >= n_classes) return EPARA_ERR_SHAPE;
-        if (first[tl.group] < 0) { first[tl.group] = t; cls[tl.group] = tl.cls; }
-        else if (cls[tl.group] != tl.cls) return EPARA_ERR_SHAPE;
+int32_t epara_chain_waits(const epara_tile* producer_tiles, int64_t n_producer_tiles, int32_t G_producer,
+                          int32_t counter_base, const int32_t* producer, int32_t G_consumer,
+                          epara_chain_wait* waits)
+{
+    if (n_producer_tiles < 0 || G_producer < 0 || G_consumer < 0 || counter_base < 0) return EPARA_ERR_SHAPE;
+    if ((n_producer_tiles > 0 && !producer_tiles) || (G_consumer > 0 && (!producer || !waits))) return EPARA_ERR_NULL;
+    std::vector<int64_t> count(static_cast<size_t>(G_producer), 0);
+    for (int64_t t = 0; t < n_producer_tiles; ++t) {
+        const int32_t g = producer_tiles[t].group;
+        if (g < 0 || g >= G_producer) return EPARA_ERR_SHAPE;
+        ++count[g];
     }
-    // every group's tile count must be what the grid rule gives, or the table is not canonical
-    {
-        int64_t expect = 0;
-        for (int32_t g = 0; g < G; ++g)
-            if (first[g] >= 0) {
-                if (first[g] != expect) return EPARA_ERR_SHAPE;
-                expect += ceil_div(groups[g].M, classes[cls[g]].BM) * ceil_div(groups[g].N, classes[cls[g]].BN);
-            }
-        if (expect != n_tiles) return EPARA_ERR_SHAPE;
+    for (int32_t g = 0; g < G_consumer; ++g)
+        if (producer[g] >= G_producer || producer[g] < -1) return EPARA_ERR_SHAPE;
+    for (int32_t g = 0; g < G_consumer; ++g) {
+        const int32_t q = producer[g];
+        waits[g].counter = q < 0 ? -1 : counter_base + q;
+        waits[g].need = q < 0 ? 0 : static_cast<int32_t>(count[q]);
     }
-
-    std::vector<std::vector<int32_t>> lists(static_cast<size_t>(W));
-    std::vector<int64_t> load(static_cast<size_t>(W), 0);
-
-    // 1. panel tiles
-    std::vector<int32_t> class_order;
-    for (int32_t c = n_stream_classes; c < n_classes; ++c) class_order.push_back(c);
-    std::stable_sort(class_order.begin(), class_order.end(), [&](int32_t a, int32_t b) {
-        return static_cast<int64_t>(classes[a].BM) * classes[a].BN > static_cast<int64_t>(classes[b].BM) * classes[b].BN;
-    });
-    int64_t l = 0;
-    std::vector<int32_t> members;
-    for (int32_t c : class_order) {
-        members.clear();
-        for (int32_t g = 0; g < G; ++g)
-            if (cls[g] == c) members.push_back(g);
-        std::stable_sort(members.begin(), members.end(),
-                         [&](int32_t a, int32_t b) { return groups[a].K > groups[b].K; });
-        const int64_t BM = classes[c].BM, BN = classes[c].BN;
-        for (int32_t g : members) {
-            const int64_t TM = ceil_div(groups[g].M, BM), TN = ceil_div(groups[g].N, BN);
-            for (int64_t pn = 0; pn < TN; pn += panel_n)
-                for (int64_t pm = 0; pm < TM; pm += panel_m)
-                    for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
-                        for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
-                            const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
-                            lists[b].push_back(static_cast<int32_t>(first[g] + tm * TN + tn));
-                            load[b] += 340 * static_cast<int64_t>(groups[g].K);
-                            ++l;
-                        }
-        }
-    }
-
-    // 2. streaming tiles, longest first onto the least loaded workgroup
-    struct item { int64_t cost; int32_t tile; };
-    std::vector<item> stream;
-    for (int64_t t = 0; t < n_tiles; ++t)
-        if (tiles[t].cls < n_stream_classes) {
-            const epara_group_desc& d = groups[tiles[t].group];
-            const int64_t units = static_cast<int64_t>(tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + classes[tiles[t].cls].BM;
-            stream.push_back({units * d.K, static_cast<int32_t>(t)});
-        }
-    std::stable_sort(stream.begin(), stream.end(), [](const item& a, const item& b) { return a.cost > b.cost; });
-    typedef std::pair<int64_t, int32_t> entry;                  // (load, workgroup): smallest first
-    std::priority_queue<entry, std::vector<entry>, std::greater<entry>> heap;
-    for (int32_t b = 0; b < W; ++b) heap.push({load[b], b});
-    for (const item& it : stream) {
-        entry e = heap.top();
-        heap.pop();
-        lists[e.second].push_back(it.tile);
-        heap.push({e.first + it.cost, e.second});
-    }
-    if (l + static_cast<int64_t>(stream.size()) != n_tiles) return EPARA_ERR_SHAPE;
-
-    size_t longest = 0;
-    for (const auto& v : lists) longest = std::max(longest, v.size());
-    const int64_t slots = static_cast<int64_t>(longest) * W;
-    *n_slots = slots;
-    if (!order) return EPARA_OK;
-    if (order_cap < slots) return EPARA_ERR_CAPACITY;
-    std::fill(order, order + slots, -1);
-    for (int64_t b = 0; b < W; ++b)
-        for (size_t j = 0; j < lists[b].size(); ++j) order[static_cast<int64_t>(j) * W + b] = lists[b][j];
     return EPARA_OK;
 }
 

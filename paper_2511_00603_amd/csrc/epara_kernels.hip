@@ -21,6 +21,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
 #include "epara.h"
 #include "epara_cast.h"
 
@@ -742,12 +746,91 @@ __device__ __forceinline__ void skinny_drain(const skinny_tile_state<NFR>& st, i
     }
 }
 
+// ------------------------------------------------------------------ chains of launches in one kernel
+//
+// Completion counters in device memory order the phases of a chain: a workgroup adds the number of
+// tiles of a group it has stored to that group's counter (after a device-scope release: the
+// compute dies have separate L2 caches), and a tile whose group reads that output first polls the
+// counter until it holds the group's tile count, then acquires.  All fields are the same in every
+// thread of the workgroup, so every thread takes the same barriers.
+constexpr int CHAIN_HEADER_WORDS = 4;    // [0] error flag, [1] workgroups that have left the kernel
+
+struct chain_ctx {
+    const epara_chain_wait* waits;   // of the current phase, or null
+    uint32_t* ws;                    // workspace: header, then the counters
+    uint32_t spin_limit;
+    int counter_base;                // of the current phase
+    int pend_group, pend_n;          // stored tiles not yet counted
+    int ok_group;                    // the group whose wait was passed last
+};
+
+__device__ __forceinline__ void chain_flush(chain_ctx& c)
+{
+    if (c.pend_n == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");           // every wave: its stores of the tiles
+    __syncthreads();
+    if (threadIdx.x == 0)
+        __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group, static_cast<uint32_t>(c.pend_n),
+                               __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    c.pend_n = 0;
+}
+
+__device__ __forceinline__ void chain_done(chain_ctx& c, int group)
+{
+    if (c.pend_n > 0 && c.pend_group != group) chain_flush(c);
+    c.pend_group = group;
+    ++c.pend_n;
+}
+
+// True if a tile of `group` has to wait (or may have to) before its input can be read.
+__device__ __forceinline__ bool chain_must_wait(const chain_ctx& c, int group)
+{
+    return c.waits != nullptr && group != c.ok_group && c.waits[group].counter >= 0 && c.waits[group].need > 0;
+}
+
+__device__ __forceinline__ void chain_wait(chain_ctx& c, int group)
+{
+    if (!chain_must_wait(c, group)) { c.ok_group = group; return; }
+    const epara_chain_wait w = c.waits[group];
+    if (threadIdx.x == 0) {
+        const uint32_t* ctr = c.ws + CHAIN_HEADER_WORDS + w.counter;
+        uint32_t polls = 0;
+        while (__hip_atomic_load(ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(w.need)) {
+            if (++polls >= c.spin_limit) {                       // bounded: report and go on, the kernel always ends
+                __hip_atomic_store(c.ws, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            // once any wait has run out the chain's results are lost anyway: nobody waits any longer
+            if ((polls & 63u) == 0 && __hip_atomic_load(c.ws, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");           // every wave, before it reads the produced rows
+    c.ok_group = group;
+}
+
+// The last workgroup to leave puts the counters back to zero for the next chain on this workspace.
+__device__ __forceinline__ void chain_exit(chain_ctx& c, int n_counters)
+{
+    chain_flush(c);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t left = __hip_atomic_fetch_add(c.ws + 1, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (left + 1 == gridDim.x) {
+            for (int i = 0; i < n_counters; ++i)
+                __hip_atomic_store(c.ws + CHAIN_HEADER_WORDS + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(c.ws + 1, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // Processes slot `slot` and every following slot of this workgroup that holds a tile of the same
 // streaming class.  Returns the first slot it did not process.
-template <int DT, bool GATED, int CLS, int MB, int NFR, int U>
+template <int DT, bool GATED, bool CHAIN, int CLS, int MB, int NFR, int U>
 __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
                                            const int32_t* __restrict__ order, long slot, long n_slots, long stride,
-                                           int out_dtype, char* lds)
+                                           int out_dtype, char* lds, chain_ctx* chain)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -778,7 +861,12 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         auto advance = [&]() {
             if (stage == 0)      { const long s1 = slot + stride; t_next = s1 < n_slots ? order[s1] : -1; }
             else if (stage == 1) { if (t_next >= 0) tl_next = tiles[t_next]; }
-            else                 { have_next = t_next >= 0 && tl_next.cls == CLS; if (have_next) ga_next = args[tl_next.group]; }
+            else {
+                have_next = t_next >= 0 && tl_next.cls == CLS;
+                // in a chain the run ends before a tile that may have to wait for its input
+                if constexpr (CHAIN) have_next = have_next && (tl_next.group == tl.group || !chain_must_wait(*chain, tl_next.group));
+                if (have_next) ga_next = args[tl_next.group];
+            }
             ++stage;
         };
         v4f acc[NFR][MB];
@@ -813,6 +901,7 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
             skinny_drain<DT, MB, NFR, U, 0>(cur, c_last, wave, lane, ring, xring, acc);
         }
         skinny_finish<DT, GATED, MB, NFR>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
+        if constexpr (CHAIN) chain_done(*chain, tl.group);
         if (slot_next < 0) break;
         slot = slot_next;
         tl = tl_next;
@@ -830,9 +919,10 @@ constexpr int N_STREAM_CLASSES = 3;
 
 // Streaming classes: (row blocks, weight column blocks, ring depth) = (1, 2, 4), (2, 4, 3) and
 // (4, 8, 2) or, in a launch planned with the narrow table, (4, 4, 3).
-template <int DT, bool GATED>
+template <int DT, bool GATED, bool CHAIN = false>
 __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
-                                             const int32_t* __restrict__ order, long n_slots, int out_dtype, int narrow, char* lds)
+                                             const int32_t* __restrict__ order, long n_slots, int out_dtype, int narrow, char* lds,
+                                             chain_ctx* chain = nullptr)
 {
     const long stride = gridDim.x;
     long s = blockIdx.x;
@@ -840,13 +930,15 @@ __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict_
         const int t = order[s];
         if (t < 0) { s += stride; continue; }
         const epara_tile tl = tiles[t];
-        if (tl.cls == 0)      s = skinny_run<DT, GATED, 0, 1, 2, 4>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
-        else if (tl.cls == 1) s = skinny_run<DT, GATED, 1, 2, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
-        else if (tl.cls == 2 && !narrow) s = skinny_run<DT, GATED, 2, 4, 8, 2>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
-        else if (tl.cls == 2) s = skinny_run<DT, GATED, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds);
+        if constexpr (CHAIN) chain_wait(*chain, tl.group);
+        if (tl.cls == 0)      s = skinny_run<DT, GATED, CHAIN, 0, 1, 2, 4>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
+        else if (tl.cls == 1) s = skinny_run<DT, GATED, CHAIN, 1, 2, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
+        else if (tl.cls == 2 && !narrow) s = skinny_run<DT, GATED, CHAIN, 2, 4, 8, 2>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
+        else if (tl.cls == 2) s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
         else {
             const epara_group_args ga = args[tl.group];
             big_tile<DT, GATED>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+            if constexpr (CHAIN) chain_done(*chain, tl.group);
             s += stride;
         }
     }
@@ -864,9 +956,9 @@ __global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __r
 }
 
 // fp32 groups: 64x64 tiles, plain FMA in fp32, K ascending.
-__global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_args* __restrict__ args,
-                                                             const epara_tile* __restrict__ tiles,
-                                                             const int32_t* __restrict__ order, long n_slots)
+template <bool CHAIN>
+__device__ __forceinline__ void f32_body(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
+                                         const int32_t* __restrict__ order, long n_slots, chain_ctx* chain)
 {
     __shared__ float Xs[F32_BK][F32_BM + 1];
     __shared__ float Ws[F32_BK][F32_BN];
@@ -875,6 +967,7 @@ __global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_a
         const int t = order[s];
         if (t < 0) continue;
         const epara_tile tl = tiles[t];
+        if constexpr (CHAIN) chain_wait(*chain, tl.group);
         const epara_group_args ga = args[tl.group];
         const EPARA_GLOBAL float* X = as_global<float>(ga.X);
         const EPARA_GLOBAL float* W = as_global<float>(ga.W);
@@ -938,7 +1031,86 @@ __global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_a
                 }
             }
         });
+        if constexpr (CHAIN) chain_done(*chain, tl.group);
     }
+}
+
+__global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_args* __restrict__ args,
+                                                             const epara_tile* __restrict__ tiles,
+                                                             const int32_t* __restrict__ order, long n_slots)
+{
+    f32_body<false>(args, tiles, order, n_slots, nullptr);
+}
+
+// ---- a chain of launches as one kernel: the phases one after the other in every workgroup
+struct chain_phase_dev {
+    const epara_group_args* args;
+    const epara_tile* tiles;
+    const int32_t* order;
+    const epara_chain_wait* waits;
+    long n_slots;
+    int out_dtype, gated, narrow, counter_base;
+};
+struct chain_params {
+    chain_phase_dev ph[EPARA_MAX_CHAIN_PHASES];
+    uint32_t* ws;
+    uint32_t spin_limit;
+    int n_phases, n_counters;
+};
+
+__device__ __forceinline__ chain_ctx chain_begin(const chain_params& P)
+{
+    chain_ctx c;
+    c.waits = nullptr; c.ws = P.ws; c.spin_limit = P.spin_limit; c.counter_base = 0;
+    c.pend_group = -1; c.pend_n = 0; c.ok_group = -1;
+    return c;
+}
+
+__device__ __forceinline__ void chain_enter_phase(chain_ctx& c, const chain_phase_dev& ph)
+{
+    chain_flush(c);                          // counts of the phase before go to that phase's counters
+    c.waits = ph.waits;
+    c.counter_base = ph.counter_base;
+    c.pend_group = -1;
+    c.ok_group = -1;
+}
+
+// One phase as a function of its own: the register allocation of a phase body is then the same as
+// in the single-launch kernel instead of one allocation over both bodies and the loop around them.
+template <int DT, bool GATED>
+__device__ __attribute__((noinline)) void chain_phase_body(const chain_phase_dev ph, char* lds, chain_ctx* c)
+{
+    grouped_body<DT, GATED, true>(ph.args, ph.tiles, ph.order, ph.n_slots, ph.out_dtype, ph.narrow, lds, c);
+}
+
+template <int DT>
+__global__ __launch_bounds__(NT) void grouped_chain_kernel(const chain_params P)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    chain_ctx c = chain_begin(P);
+    for (int p = 0; p < P.n_phases; ++p) {
+        const chain_phase_dev ph = P.ph[p];
+        chain_enter_phase(c, ph);
+        if (ph.gated) chain_phase_body<DT, true>(ph, lds, &c);
+        else          chain_phase_body<DT, false>(ph, lds, &c);
+    }
+    chain_exit(c, P.n_counters);
+}
+
+__global__ __launch_bounds__(F32_NT) void grouped_chain_kernel_f32(const chain_params P)
+{
+    chain_ctx c = chain_begin(P);
+    for (int p = 0; p < P.n_phases; ++p) {
+        const chain_phase_dev& ph = P.ph[p];
+        chain_enter_phase(c, ph);
+        f32_body<true>(ph.args, ph.tiles, ph.order, ph.n_slots, &c);
+    }
+    chain_exit(c, P.n_counters);
+}
+
+__global__ void fill_words_kernel(uint32_t* p, long n, uint32_t v)
+{
+    for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += static_cast<long>(gridDim.x) * blockDim.x) p[i] = v;
 }
 
 // One 16-byte chunk of the packed weights per thread.
@@ -1136,6 +1308,124 @@ int32_t epara_grouped_ffn_swiglu(const epara_launch* up, const epara_launch* dow
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (int32_t rc = enqueue(up, in_dtype, h_dtype, narrow_up, st)) return rc;
     return enqueue(down, in_dtype, out_dtype, narrow_down, st);
+}
+
+int64_t epara_chain_workspace_bytes(int32_t n_counters)
+{
+    if (n_counters < 0) return -1;
+    return ((static_cast<int64_t>(CHAIN_HEADER_WORDS) + n_counters) * 4 + 255) / 256 * 256;
+}
+
+int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* stream)
+{
+    if (!d_workspace) return EPARA_ERR_NULL;
+    if (bytes < 16 || bytes % 4) return EPARA_ERR_SHAPE;
+    if (!aligned16(d_workspace)) return EPARA_ERR_ALIGN;
+    (void)hipGetLastError();
+    const long n = bytes / 4;
+    hipLaunchKernelGGL(fill_words_kernel, dim3(static_cast<unsigned>(n < 65536 ? (n + 255) / 256 : 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<uint32_t*>(d_workspace), n, 0u);
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                            void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream)
+{
+    if (!phases || !d_workspace) return EPARA_ERR_NULL;
+    if (n_phases < 1 || n_phases > EPARA_MAX_CHAIN_PHASES) return EPARA_ERR_SHAPE;
+    if (!aligned16(d_workspace)) return EPARA_ERR_ALIGN;
+    chain_params P;
+    std::memset(&P, 0, sizeof P);
+    int32_t n_counters = 0, n_workgroups = 0;
+    bool any = false;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        const epara_chain_phase& ph = phases[p];
+        const epara_launch* L = ph.launch;
+        int narrow = 0;
+        if (int32_t st = validate_launch(L, in_dtype, ph.out_dtype, &narrow)) return st;
+        if (ph.counter_base < 0 || ph.counter_base > INT32_MAX - L->G) return EPARA_ERR_SHAPE;
+        for (int32_t q = 0; q < p; ++q)       // counter ranges must not overlap
+            if (ph.counter_base < phases[q].counter_base + phases[q].launch->G &&
+                phases[q].counter_base < ph.counter_base + L->G) return EPARA_ERR_SHAPE;
+        n_counters = std::max(n_counters, ph.counter_base + L->G);
+        if (L->n_tiles > 0) {
+            if (any && L->n_workgroups != n_workgroups) return EPARA_ERR_SHAPE;
+            n_workgroups = L->n_workgroups;
+            any = true;
+        }
+        int gated = 0;
+        for (int32_t g = 0; g < L->G && L->n_tiles > 0; ++g)
+            if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated = 1;
+        if (ph.h_waits && L->n_tiles > 0) {
+            if (p == 0) return EPARA_ERR_SHAPE;
+            if (!ph.d_waits) return EPARA_ERR_NULL;
+            const epara_chain_phase& prev = phases[p - 1];
+            const epara_launch* Lp = prev.launch;
+            std::vector<int64_t> count(static_cast<size_t>(Lp->G), 0);
+            for (int64_t t = 0; t < Lp->n_tiles; ++t) ++count[Lp->h_tiles[t].group];
+            const int prev_esz = prev.out_dtype == EPARA_F32 ? 4 : (prev.out_dtype == EPARA_BF16 ? 2 : 1);
+            const int in_esz = in_dtype == EPARA_F32 ? 4 : (in_dtype == EPARA_BF16 ? 2 : 1);
+            if (prev_esz != in_esz || (in_dtype == EPARA_FP8_E4M3) != (prev.out_dtype == EPARA_FP8_E4M3)) return EPARA_ERR_DTYPE;
+            for (int32_t g = 0; g < L->G; ++g) {
+                const epara_chain_wait& w = ph.h_waits[g];
+                if (w.counter < 0) continue;
+                const int32_t q = w.counter - prev.counter_base;
+                if (q < 0 || q >= Lp->G || w.need != count[q]) return EPARA_ERR_SHAPE;
+                const epara_group_args& a = L->h_args[g];
+                const epara_group_args& b = Lp->h_args[q];
+                if (a.M == 0) continue;
+                if (a.X != b.Y || a.M != b.M || a.K != b.N) return EPARA_ERR_SHAPE;
+            }
+        }
+        chain_phase_dev& d = P.ph[p];
+        d.args = L->d_args; d.tiles = L->d_tiles; d.order = L->d_order;
+        d.waits = (ph.h_waits && L->n_tiles > 0) ? ph.d_waits : nullptr;
+        d.n_slots = L->n_tiles > 0 ? L->n_slots : 0;
+        d.out_dtype = ph.out_dtype; d.gated = gated; d.narrow = narrow; d.counter_base = ph.counter_base;
+    }
+    if (workspace_bytes < epara_chain_workspace_bytes(n_counters)) return EPARA_ERR_CAPACITY;
+    if (!any) return EPARA_OK;
+    P.ws = static_cast<uint32_t*>(d_workspace);
+    P.spin_limit = spin_limit ? spin_limit : (1u << 20);
+    P.n_phases = n_phases;
+    P.n_counters = n_counters;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const void* fn = in_dtype == EPARA_F32 ? reinterpret_cast<const void*>(&grouped_chain_kernel_f32)
+                   : in_dtype == EPARA_BF16 ? reinterpret_cast<const void*>(&grouped_chain_kernel<EPARA_BF16>)
+                                            : reinterpret_cast<const void*>(&grouped_chain_kernel<EPARA_FP8_E4M3>);
+    const int threads = in_dtype == EPARA_F32 ? F32_NT : NT;
+    const size_t dyn = in_dtype == EPARA_F32 ? 0 : LDS_BYTES;
+    (void)hipGetLastError();
+    if (dyn && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) return EPARA_ERR_HIP;
+    // a waiting workgroup must not keep the one it waits for off the GPU: the whole grid has to be resident
+    int dev = 0, per_cu = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, dyn) != hipSuccess) return EPARA_ERR_HIP;
+    if (static_cast<int64_t>(n_workgroups) > static_cast<int64_t>(per_cu) * cus) return EPARA_ERR_SHAPE;
+    const dim3 grid(static_cast<unsigned>(n_workgroups));
+    if (in_dtype == EPARA_F32)
+        hipLaunchKernelGGL(grouped_chain_kernel_f32, grid, dim3(F32_NT), 0, st, P);
+    else if (in_dtype == EPARA_BF16)
+        hipLaunchKernelGGL(grouped_chain_kernel<EPARA_BF16>, grid, dim3(NT), LDS_BYTES, st, P);
+    else
+        hipLaunchKernelGGL(grouped_chain_kernel<EPARA_FP8_E4M3>, grid, dim3(NT), LDS_BYTES, st, P);
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+int32_t epara_chain_status(void* d_workspace, void* stream, int32_t* flag)
+{
+    if (!d_workspace || !flag) return EPARA_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint32_t v = 0;
+    if (hipStreamSynchronize(st) != hipSuccess) return EPARA_ERR_HIP;
+    if (hipMemcpy(&v, d_workspace, 4, hipMemcpyDeviceToHost) != hipSuccess) return EPARA_ERR_HIP;
+    *flag = static_cast<int32_t>(v);
+    if (v) {
+        const uint32_t zero = 0;
+        if (hipMemcpy(d_workspace, &zero, 4, hipMemcpyHostToDevice) != hipSuccess) return EPARA_ERR_HIP;
+    }
+    return EPARA_OK;
 }
 
 }  // extern "C"

@@ -27,8 +27,10 @@ def _bits(a, dtype, scale=None):
 
 
 class StagedMix:
-    def __init__(self, mix, dtype_name=None, device="cuda:0", copies=1, s_h=None, n_workgroups=None, host_bits=None):
-        """copies > 1 stages independent replicas of all weights and activations; pass `copy=i` to run()
+    def __init__(self, mix, dtype_name=None, device="cuda:0", copies=1, s_h=None, n_workgroups=None, host_bits=None,
+                 chained=False):
+        """chained: the launches of a pass run as one kernel (epara_grouped_chain) instead of one after the other.
+        copies > 1 stages independent replicas of all weights and activations; pass `copy=i` to run()
         to rotate through them (keeps a timing loop out of the last-level cache).
         s_h: per-service scales of the hidden activations for the fp8 SwiGLU path (list of floats)."""
         self.mix = mix
@@ -39,6 +41,7 @@ class StagedMix:
             raise ValueError("the fp8 path is staged for SwiGLU FFN mixes only (chained layers would need fp8 outputs)")
         self.out_dtype = B.EPARA_F32 if self.dtype == B.EPARA_F32 else B.EPARA_BF16
         self.copies = copies
+        self.chained = chained
         self.host_bits = []          # per service: dict of the exact inputs handed to the GPU
         self.programs = []           # per copy: list of ("forward", plan, out_dtype) / ("ffn", up, down, h_dtype)
         self.outputs = []            # per copy: list (per launch) of list (per group) of (service, label, tensor)
@@ -126,9 +129,14 @@ class StagedMix:
                 o_h.append((g, "H", H))
                 o_y.append((g, "Y", Y))
             up_args, down_args = B.epara_ffn_swiglu_args(ffn, dt)
-            up = R.LaunchPlan(up_args, dt, self.device, n_workgroups)
-            down = R.LaunchPlan(down_args, dt, self.device, n_workgroups)
-            prog.append(("ffn", up, down, h_dtype))
+            if self.chained:
+                chain = R.ChainPlan([up_args, down_args], [h_dtype, B.EPARA_BF16], [None, np.arange(len(ffn), dtype=np.int32)],
+                                    dt, self.device, n_workgroups)
+                prog.append(("chain", chain))
+            else:
+                up = R.LaunchPlan(up_args, dt, self.device, n_workgroups)
+                down = R.LaunchPlan(down_args, dt, self.device, n_workgroups)
+                prog.append(("ffn", up, down, h_dtype))
             outs += [o_h, o_y]
             self.ffn_desc = ffn
         else:
@@ -143,8 +151,11 @@ class StagedMix:
             else:                                  # a chain: layer l reads layer l-1
                 launches = [[(g, l, "in" if l == 0 else l - 1) for g in range(n_svc)] for l in range(n_layers)]
             produced = {}
+            phase_args, producers, where = [], [], {}
             for launch in launches:
                 args, o = [], []
+                producers.append(np.array([-1 if src == "in" else where[(g, src)] for g, l, src in launch], dtype=np.int32))
+                where = {(g, l): i for i, (g, l, src) in enumerate(launch)}
                 for g, l, src in launch:
                     svc, hb = mix.services[g], self.host_bits[g]
                     lay = hb["layers"][l]
@@ -155,9 +166,15 @@ class StagedMix:
                     args.append(R.group_args(Xin, W[g][l], Y, svc.M, K, N, lay["act"], bias=bias[g][l], scale=scale))
                     produced[(g, l)] = Y
                     o.append((g, "L%d" % l, Y))
-                plan = R.LaunchPlan(np.array(args, dtype=B.GROUP_ARGS), dt, self.device, n_workgroups)
-                prog.append(("forward", plan, self.out_dtype))
+                phase_args.append(np.array(args, dtype=B.GROUP_ARGS))
+                if not self.chained:
+                    plan = R.LaunchPlan(phase_args[-1], dt, self.device, n_workgroups)
+                    prog.append(("forward", plan, self.out_dtype))
                 outs.append(o)
+            if self.chained:
+                producers[0] = None
+                chain = R.ChainPlan(phase_args, [self.out_dtype] * len(phase_args), producers, dt, self.device, n_workgroups)
+                prog.append(("chain", chain))
         self.programs.append(prog)
         self.outputs.append(outs)
 
@@ -172,17 +189,24 @@ class StagedMix:
         for step in self.programs[copy % self.copies]:
             if step[0] == "forward":
                 R.grouped_forward(step[1], step[2], stream)
+            elif step[0] == "chain":
+                R.grouped_chain(step[1], stream)
             else:
                 R.grouped_ffn_swiglu(step[1], step[2], step[3], B.EPARA_BF16, stream)
 
     def n_launches(self):
-        return sum(1 if s[0] == "forward" else 2 for s in self.programs[0])
+        return sum(2 if s[0] == "ffn" else 1 for s in self.programs[0])
 
     def plans(self, copy=0):
+        """The per-launch plans (for a chain: its phases, which carry the same fields)."""
         out = []
         for step in self.programs[copy]:
-            out += [step[1]] if step[0] == "forward" else [step[1], step[2]]
+            out += [step[1]] if step[0] == "forward" else (list(step[1].phases) if step[0] == "chain" else [step[1], step[2]])
         return out
+
+    def chain_status(self, copy=0):
+        """After a chained pass: 0 if every wait ended normally (synchronises)."""
+        return max([R.chain_status(step[1]) for step in self.programs[copy % self.copies] if step[0] == "chain"] or [0])
 
     def results(self, copy=0):
         """After a synchronize: list per launch of (service, label, float64 ndarray of output VALUES)."""

@@ -1,5 +1,7 @@
 """Marshalling between PyTorch device memory and libepara.  PyTorch is used for allocation,
 host<->device copies and streams only; every step of the forward path runs in the library."""
+import ctypes
+import itertools
 import time
 
 import numpy as np
@@ -62,16 +64,28 @@ def group_args(X, W, Y, M, K, N, act, bias=None, W2=None, scale=1.0, scale2=1.0,
     return a
 
 
-def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
-    """Largest per-workgroup cost of a schedule, in the units epara_schedule_tiles balances with."""
+def _loads(groups, classes, n_stream, tiles, order, n_workgroups):
+    """Per-workgroup cost of a schedule, in the units epara_schedule_tiles balances with."""
     if len(tiles) == 0:
-        return 0
+        return np.zeros(n_workgroups, dtype=np.int64)
     g = groups[tiles["group"]]
     stream = tiles["cls"] < n_stream
     units = tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
     cost = np.where(stream, units, 340) * g["K"].astype(np.int64)
     per_slot = np.where(order >= 0, cost[np.maximum(order, 0)], 0).reshape(-1, n_workgroups)
-    return int(per_slot.sum(axis=0).max())
+    return per_slot.sum(axis=0)
+
+
+def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
+    return int(_loads(groups, classes, n_stream, tiles, order, n_workgroups).max())
+
+
+def _group_desc(args):
+    groups = np.zeros(len(args), dtype=B.GROUP_DESC)
+    for f in ("M", "K", "N", "act"):
+        groups[f] = args[f]
+    groups["has_bias"] = (args["bias"] != 0).astype(np.int32)
+    return groups
 
 
 class LaunchPlan:
@@ -119,6 +133,89 @@ class LaunchPlan:
         self.upload_seconds = time.perf_counter() - t0
         self.c = B.Launch(self.args.ctypes.data, self.d_args.data_ptr(), self.tiles.ctypes.data, self.d_tiles.data_ptr(),
                           self.d_order.data_ptr(), len(self.tiles), len(self.order), n_workgroups, G)
+
+
+class _Phase:
+    """One phase of a ChainPlan: the fields of a LaunchPlan, scheduled together with the other phases."""
+
+
+class ChainPlan:
+    """Host plan + device copy of a chain of grouped launches that runs as one kernel (epara_grouped_chain).
+
+    phase_args[p]: GROUP_ARGS array of phase p; out_dtypes[p]: its output dtype; producers[p]: None, or per
+    group of phase p the index of the group of phase p-1 whose output it reads (-1: none)."""
+
+    def __init__(self, phase_args, out_dtypes, producers, in_dtype, device, n_workgroups=None, n_xcd=8, panel_m=1, panel_n=4):
+        _require_gpu()
+        t0 = time.perf_counter()
+        if n_workgroups is None:
+            n_workgroups = n_compute_units(device)
+            n_workgroups -= n_workgroups % n_xcd
+        self.n_workgroups, self.in_dtype, self.out_dtypes = n_workgroups, in_dtype, list(out_dtypes)
+        P = len(phase_args)
+        args = [np.ascontiguousarray(a, dtype=B.GROUP_ARGS) for a in phase_args]
+        groups = [_group_desc(a) for a in args]
+        gated = [bool(len(a)) and bool(np.all(a["act"] == B.EPARA_ACT_SWIGLU)) for a in args]
+        options = []                                  # per phase: the class tables that may be used
+        for p in range(P):
+            both = in_dtype != B.EPARA_F32 and len(args[p]) and int(groups[p]["M"].max()) > 32
+            opts = []
+            for narrow in ((False, True) if both else (False,)):
+                classes, n_stream = B.epara_kernel_classes(in_dtype, gated[p], narrow)
+                _, _, _, tiles = B.epara_plan_groups(groups[p], classes)
+                opts.append((narrow, classes, n_stream, tiles))
+            options.append(opts)
+        best = None
+        for combo in itertools.product(*options):     # keep the tables whose joint schedule finishes first
+            orders = B.epara_schedule_chain([(groups[p], c[1], c[2], c[3]) for p, c in enumerate(combo)],
+                                            n_workgroups, n_xcd, panel_m, panel_n)
+            load = sum(_loads(groups[p], c[1], c[2], c[3], orders[p], n_workgroups) for p, c in enumerate(combo))
+            span = int(load.max()) if P else 0
+            if best is None or span < best[0]:
+                best = (span, combo, orders)
+        self.makespan, combo, orders = best
+        self.phases, base = [], 0
+        for p in range(P):
+            ph = _Phase()
+            ph.args, ph.groups, ph.in_dtype, ph.n_workgroups = args[p], groups[p], in_dtype, n_workgroups
+            ph.narrow, ph.classes, ph.n_stream_classes, ph.tiles = combo[p]
+            ph.order, ph.counter_base = orders[p], base
+            base += len(args[p])
+            ph.waits = None
+            if p > 0 and producers[p] is not None:
+                prev = self.phases[p - 1]
+                ph.waits = B.epara_chain_waits(prev.tiles, len(prev.args), prev.counter_base, producers[p])
+            self.phases.append(ph)
+        self.n_counters = base
+        self.plan_seconds = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        self.c = (B.ChainPhase * P)()
+        self._launches = []
+        for p, ph in enumerate(self.phases):
+            ph.d_args, ph.d_tiles, ph.d_order = _upload(ph.args, device), _upload(ph.tiles, device), _upload(ph.order, device)
+            ph.d_waits = None if ph.waits is None else _upload(ph.waits, device)
+            ph.c = B.Launch(ph.args.ctypes.data, ph.d_args.data_ptr(), ph.tiles.ctypes.data, ph.d_tiles.data_ptr(),
+                            ph.d_order.data_ptr(), len(ph.tiles), len(ph.order), n_workgroups, len(ph.args))
+            self._launches.append(ph.c)
+            self.c[p].launch = ctypes.pointer(ph.c)
+            self.c[p].h_waits = None if ph.waits is None else ph.waits.ctypes.data
+            self.c[p].d_waits = None if ph.waits is None else ph.d_waits.data_ptr()
+            self.c[p].out_dtype, self.c[p].counter_base = int(self.out_dtypes[p]), ph.counter_base
+        self.workspace_bytes = B.epara_chain_workspace_bytes(self.n_counters)
+        self.d_workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+        B.epara_chain_workspace_init(self.d_workspace.data_ptr(), self.workspace_bytes, current_stream_handle())
+        torch.cuda.synchronize(device)
+        self.upload_seconds = time.perf_counter() - t0
+
+
+def grouped_chain(plan, stream=None, spin_limit=0):
+    B.epara_grouped_chain(plan.c, plan.in_dtype, plan.d_workspace.data_ptr(), plan.workspace_bytes,
+                          current_stream_handle() if stream is None else stream, spin_limit)
+
+
+def chain_status(plan, stream=None):
+    """Synchronises; 0 = every wait of the chains run on this plan's workspace ended normally."""
+    return B.epara_chain_status(plan.d_workspace.data_ptr(), current_stream_handle() if stream is None else stream)
 
 
 def grouped_forward(plan, out_dtype, stream=None):

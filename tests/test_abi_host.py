@@ -265,3 +265,130 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
     assert lib.epara_pack_weights(0x1000, 8, 8, 7, 0x2000, 1024, None) == B.EPARA_ERR_DTYPE
     assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2004, 1024, None) == B.EPARA_ERR_ALIGN
     assert B.epara_status_string(B.EPARA_ERR_ALIGN).startswith("pointer")
+
+
+# ---- chains of launches ------------------------------------------------------------------------
+
+def _chains():
+    """(phases, gated flags): consecutive launches of the mixes that form chains, plus adversarial ones."""
+    shapes = mix_group_shapes()
+    wide = ([(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)], 3)
+    gatedt = ([(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], 3)
+    narrow = ([(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)], 3)
+    f32 = ([(P.INT32_MAX, 64, 64)], 0)
+    return [
+        ([(shapes[0], f32, False), (shapes[1], f32, False), (shapes[2], f32, False)]),
+        ([(shapes[3], wide, False), (shapes[4], wide, False)]),
+        ([(shapes[5], wide, False), (shapes[6], wide, False)]),
+        ([(shapes[7], gatedt, True), (shapes[8], narrow, False)]),
+        ([(shapes[7], gatedt, True), (shapes[8], wide, False)]),
+        ([(shapes[9], gatedt, True), (shapes[10], wide, False)]),
+        ([([(0, 8, 8)], wide, False), ([], wide, False)]),
+        ([([(63, 40, 31), (513, 24, 1)], wide, False), ([(63, 31, 77), (513, 1, 300)], narrow, False),
+          ([(63, 77, 5), (7, 300, 64)], wide, False), ([(63, 5, 40)], wide, False)]),
+    ]
+
+
+@pytest.mark.parametrize("chain", _chains())
+def test_chain_scheduler_matches_reference_and_covers_every_tile_once(chain):
+    ref_phases, lib_phases = [], []
+    for groups, (classes, n_stream), gated in chain:
+        _, _, _, tiles = P.plan_groups(groups, classes)
+        ref_phases.append(([g + (gated,) for g in groups], classes, n_stream, tiles))
+        t2 = np.array(tiles, dtype=B.TILE) if tiles else np.zeros(0, dtype=B.TILE)
+        lib_phases.append((_desc(groups, 5 if gated else 0), _classes(classes), n_stream, t2))
+    for W, X, pm, pn in ((256, 8, 1, 4), (8, 8, 2, 2), (48, 4, 3, 5), (1, 1, 1, 1)):
+        ref = P.schedule_chain(ref_phases, W, X, pm, pn)
+        got = B.epara_schedule_chain(lib_phases, W, X, pm, pn)
+        assert [o.tolist() for o in got] == ref
+        # what any valid schedule must satisfy, whatever the rule: every tile of every phase exactly once,
+        # lists without holes, and (streaming-only chains) the greedy bound max <= mean + largest tile
+        total = np.zeros(W, dtype=np.int64)
+        biggest, stream_only = 0, True
+        for (groups, classes, n_stream, tiles), order in zip(ref_phases, ref):
+            o = np.array(order, dtype=np.int64).reshape(-1, W) if order else np.zeros((0, W), dtype=np.int64)
+            assert sorted(o[o >= 0].tolist()) == list(range(len(tiles)))
+            for b in range(W):
+                col = o[:, b]
+                assert np.all(col[: int((col >= 0).sum())] >= 0)
+                for t in col[col >= 0]:
+                    tile = tiles[t]
+                    if tile[5] < n_stream:
+                        g = groups[tile[0]]
+                        c = g[1] * (tile[4] * (2 if g[3] else 1) + classes[tile[5]][1])
+                    else:
+                        c, stream_only = 340 * groups[tile[0]][1], False
+                    total[b] += c
+                    biggest = max(biggest, c)
+        if stream_only and total.sum() > 0:
+            assert total.max() <= total.sum() / W + biggest
+
+
+def test_single_phase_chain_is_the_plain_schedule():
+    groups = [(1000, 64, 1000), (7, 2048, 77), (300, 128, 300), (64, 512, 64)]
+    classes, n_stream = CLASS_TABLES[4]
+    _, _, _, tiles = B.epara_plan_groups(_desc(groups), _classes(classes))
+    a = B.epara_schedule_tiles(_desc(groups), _classes(classes), n_stream, tiles, 48, 4, 3, 5)
+    b = B.epara_schedule_chain([(_desc(groups), _classes(classes), n_stream, tiles)], 48, 4, 3, 5)[0]
+    assert a.tolist() == b.tolist()
+
+
+def test_chain_balances_a_coarse_phase_against_a_fine_one():
+    """Decode FFN shapes: the down phase alone leaves a quarter of the workgroups with a third more work than
+    the others; scheduled together with the up phase the loads even out (the reason for joint scheduling)."""
+    up, down = [(m, 4096, 11008) for m in (1, 8, 32, 64)], [(m, 11008, 4096) for m in (1, 8, 32, 64)]
+    gt, nt = [(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], [(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)]
+    tu, td = P.plan_groups(up, gt)[3], P.plan_groups(down, nt)[3]
+    phases = [([g + (True,) for g in up], gt, 3, tu), ([g + (False,) for g in down], nt, 3, td)]
+
+    def loads(orders):
+        total = np.zeros(256, dtype=np.int64)
+        for (groups, classes, _, tiles), order in zip(phases, orders):
+            for slot, t in enumerate(order):
+                if t >= 0:
+                    g = groups[tiles[t][0]]
+                    total[slot % 256] += g[1] * (tiles[t][4] * (2 if g[3] else 1) + classes[tiles[t][5]][1])
+        return total
+    separate = loads([P.schedule_tiles(*ph, 256, 8, 1, 4) for ph in phases])
+    joint = loads(P.schedule_chain(phases, 256, 8, 1, 4))
+    assert separate.sum() == joint.sum()
+    assert separate.max() / separate.mean() > 1.08
+    assert joint.max() / joint.mean() < 1.03
+
+
+def test_chain_waits_match_reference_and_reject_bad_indices():
+    groups = [(63, 40, 31), (0, 8, 8), (513, 24, 1), (7, 8, 300)]
+    classes, _ = CLASS_TABLES[4]
+    _, _, _, tiles = B.epara_plan_groups(_desc(groups), _classes(classes))
+    producer = [2, -1, 0, 3, 1, 0]
+    w = B.epara_chain_waits(tiles, len(groups), 10, producer)
+    ref = P.chain_waits([tuple(int(v) for v in t) for t in tiles], 10, producer)
+    assert [(int(a["counter"]), int(a["need"])) for a in w] == ref
+    # counted independently: tiles per group from the grid rule
+    per = {g: -(-M // (16 if M <= 16 else 32 if M <= 32 else 64 if M <= 64 else 256)) * -(-N // {16: 32, 32: 64, 64: 128, 256: 256}[16 if M <= 16 else 32 if M <= 32 else 64 if M <= 64 else 256])
+           for g, (M, K, N) in enumerate(groups) if M}
+    assert ref[0] == (12, per[2]) and ref[1] == (-1, 0) and ref[4] == (11, 0) and ref[3] == (13, per[3])
+    assert status_of(B.epara_chain_waits, tiles, len(groups), 0, [4]) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_chain_waits, tiles, len(groups), 0, [-2]) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_chain_waits, tiles, len(groups), -1, [0]) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_chain_waits, tiles, 2, 0, [0]) == B.EPARA_ERR_SHAPE       # a tile of group 2 or 3 is outside
+
+
+def test_chain_entry_point_validates_before_touching_the_device():
+    L = B.lib()
+    assert B.epara_chain_workspace_bytes(0) == 256 and B.epara_chain_workspace_bytes(100) == 512
+    assert B.epara_chain_workspace_bytes(-1) == -1
+    ws = ctypes.c_void_p(4096)
+    assert L.epara_grouped_chain(None, 1, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_NULL
+    phases = (B.ChainPhase * 1)()
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 0, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_SHAPE
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 5, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_SHAPE
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_NULL   # no launch
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ctypes.c_void_p(4100), 256, 0, None) == B.EPARA_ERR_ALIGN
+    empty = B.Launch(None, None, None, None, None, 0, 0, 0, 0)
+    phases[0].launch = ctypes.pointer(empty)
+    phases[0].out_dtype = B.EPARA_BF16
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 16, 0, None) == B.EPARA_ERR_CAPACITY
+    assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_OK          # nothing to run
+    assert L.epara_chain_workspace_init(None, 256, None) == B.EPARA_ERR_NULL
+    assert L.epara_chain_status(None, None, None) == B.EPARA_ERR_NULL
