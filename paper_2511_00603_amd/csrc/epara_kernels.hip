@@ -137,7 +137,26 @@ __device__ __forceinline__ EPARA_GLOBAL T* as_global(void* p) { return (EPARA_GL
 
 __device__ __forceinline__ v4i ld16(gcptr p) { return *reinterpret_cast<const EPARA_GLOBAL v4i*>(p); }
 
+// Output stores.  WT ("write through"): the outputs of a chain are read by other workgroups of the
+// same kernel, possibly on another compute die with its own L2; stored as device-scope atomic
+// (relaxed) stores they go through to memory at once, and the producer's release needs no
+// write-back of its whole L2 -- which costs microseconds per workgroup and tile group.
+template <bool WT, class T>
+__device__ __forceinline__ void put(EPARA_GLOBAL T* p, T v)
+{
+    if constexpr (WT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool WT>
+__device__ __forceinline__ void put(EPARA_GLOBAL v2u* p, v2u v)
+{
+    if constexpr (WT) __hip_atomic_store(reinterpret_cast<EPARA_GLOBAL uint64_t*>(p), __builtin_bit_cast(uint64_t, v),
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+
 // Stores up to four consecutive outputs of one row, starting at column n (a multiple of 4).
+template <bool WT>
 __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, int N, const float* v, int valid, bool vec_ok)
 {
     const size_t e = m * static_cast<size_t>(N) + n;
@@ -149,20 +168,20 @@ __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, 
             v2u pk;                               // round to nearest even in hardware, two values per instruction
             pk[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[0], v[1]}), v2bf));
             pk[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[2], v[3]}), v2bf));
-            *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
+            put<WT>(reinterpret_cast<EPARA_GLOBAL v2u*>(y), pk);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (i < valid) y[i] = static_cast<uint16_t>(f32_to_bf16(v[i]));
+                if (i < valid) put<WT>(y + i, static_cast<uint16_t>(f32_to_bf16(v[i])));
         }
     } else {  // EPARA_FP8_E4M3
         EPARA_GLOBAL uint8_t* y = as_global<uint8_t>(Y) + e;
         if (vec_ok && valid >= 4) {
-            *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32x4_to_e4m3(v[0], v[1], v[2], v[3]);
+            put<WT>(reinterpret_cast<EPARA_GLOBAL uint32_t*>(y), f32x4_to_e4m3(v[0], v[1], v[2], v[3]));
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                if (i < valid) y[i] = static_cast<uint8_t>(f32_to_e4m3(v[i]));
+                if (i < valid) put<WT>(y + i, static_cast<uint8_t>(f32_to_e4m3(v[i])));
         }
     }
 }
@@ -171,7 +190,7 @@ __device__ __forceinline__ void store4(void* Y, int out_dtype, size_t m, int n, 
 // `bias` points at the bias of column n0 (global memory for streaming tiles; panel tiles stage the
 // tile's 256 bias values in LDS first, because a global load inside the store loop would make
 // every iteration wait for all earlier stores: loads and stores share one in-order counter).
-template <int ACT, class BiasPtr>
+template <int ACT, bool WT, class BiasPtr>
 __device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out_dtype, const v4f& a, BiasPtr bias,
                                              int m0, int ml, int rows, int n0, int nl, int cols, bool vec_ok)
 {
@@ -184,10 +203,11 @@ __device__ __forceinline__ void finish_plain(const epara_group_args& ga, int out
         if (bias && i < valid) b = bias[nl + i];
         v[i] = act_fast<ACT>(ga.scale * a[i] + b) * ga.out_inv_scale;
     }
-    store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, valid, vec_ok);
+    store4<WT>(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, valid, vec_ok);
 }
 
 // Epilogue of a gate/up fragment pair (EPARA_ACT_SWIGLU groups).
+template <bool WT>
 __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out_dtype, const v4f& g, const v4f& u,
                                              int m0, int ml, int rows, int n0, int nl, int cols, bool vec_ok)
 {
@@ -195,7 +215,7 @@ __device__ __forceinline__ void finish_gated(const epara_group_args& ga, int out
     float v[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] = act_fast<EPARA_ACT_SILU>(ga.scale * g[i]) * (ga.scale2 * u[i]) * ga.out_inv_scale;
-    store4(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, cols - nl, vec_ok);
+    store4<WT>(ga.Y, out_dtype, static_cast<size_t>(m0 + ml), n0 + nl, ga.N, v, cols - nl, vec_ok);
 }
 
 // ------------------------------------------------------------------ big tiles (LDS + MFMA)
@@ -239,7 +259,7 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-template <int DT, bool GATED>
+template <int DT, bool GATED, bool WT>
 __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dtype,
                                          int m0, int n0, int rows, int cols, char* lds)
 {
@@ -505,9 +525,9 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                         v2u pk;
                         pk[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[0], v[1]}), v2bf));
                         pk[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{v[2], v[3]}), v2bf));
-                        *reinterpret_cast<EPARA_GLOBAL v2u*>(y) = pk;
+                        put<WT>(reinterpret_cast<EPARA_GLOBAL v2u*>(y), pk);
                     } else {
-                        *reinterpret_cast<EPARA_GLOBAL uint32_t*>(y) = f32x4_to_e4m3(v[0], v[1], v[2], v[3]);
+                        put<WT>(reinterpret_cast<EPARA_GLOBAL uint32_t*>(y), f32x4_to_e4m3(v[0], v[1], v[2], v[3]));
                     }
                 }
             }
@@ -529,7 +549,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                 const int row = it * RPI + rr, fmi = row >> 5;
                 const int at = ((hq * 32 + (row & 31)) ^ swz_q) + gq * 64 + fmi * 256 + fq * 512;
                 const v4f gate = stash[at], up = stash[at + 1024];
-                finish_gated(ga, out_dtype, gate, up, m0, wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
+                finish_gated<WT>(ga, out_dtype, gate, up, m0, wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
             }
         }
     } else {
@@ -541,7 +561,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
                 for (int it = 0; it < 64 / RPI; ++it) {
                     const int row = it * RPI + rr, fmi = row >> 5;
                     const v4f a4 = stash[((hq * 32 + (row & 31)) ^ swz_q) + gq * 64 + fmi * 256 + fq * 512];
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, a4, bias_tile, m0,
+                    finish_plain<decltype(tag)::value, WT>(ga, out_dtype, a4, bias_tile, m0,
                                                        wm * 128 + half * 64 + row, rows, n0, nl, cols, vec_ok);
                 }
             }
@@ -682,7 +702,7 @@ __device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int
     }
 }
 
-template <int DT, bool GATED, int MB, int NFR>
+template <int DT, bool GATED, int MB, int NFR, bool WT>
 __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int out_dtype, int n0, int cols,
                                               v4f (&acc)[NFR][MB], int wave, int lane, char* lds)
 {
@@ -715,7 +735,7 @@ __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int ou
                     g += red[((w * NP + pi) * MB + fm) * 64 + lane];
                     u += red[((w * NP + NP / 2 + pi) * MB + fm) * 64 + lane];
                 }
-                finish_gated(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
+                finish_gated<WT>(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
             }
         } else {                                                 // units (column block f, row block fm)
             constexpr int UNITS = NP * MB;
@@ -726,7 +746,7 @@ __device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int ou
                     v4f s0 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int w = 0; w < 4; ++w) s0 += red[((w * NP + fi) * MB + fm) * 64 + lane];
-                    finish_plain<decltype(tag)::value>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
+                    finish_plain<decltype(tag)::value, WT>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
                                                        fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
                 }
             });
@@ -767,11 +787,15 @@ struct chain_ctx {
 __device__ __forceinline__ void chain_flush(chain_ctx& c)
 {
     if (c.pend_n == 0) return;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");           // every wave: its stores of the tiles
+    // The tiles were stored with write-through stores (put<true>): once every wave has seen its stores
+    // complete they are in memory, and the count may follow.  A device-scope release fence would do
+    // the same and also write back the die's whole L2, which is what this path avoids.
+    wait_vmcnt<0>();                                             // this wave's stores are done
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0)
         __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group, static_cast<uint32_t>(c.pend_n),
-                               __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     c.pend_n = 0;
 }
 
@@ -900,7 +924,7 @@ __device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ 
         } else {                                                 // nothing follows: the ring drains
             skinny_drain<DT, MB, NFR, U, 0>(cur, c_last, wave, lane, ring, xring, acc);
         }
-        skinny_finish<DT, GATED, MB, NFR>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
+        skinny_finish<DT, GATED, MB, NFR, CHAIN>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
         if constexpr (CHAIN) chain_done(*chain, tl.group);
         if (slot_next < 0) break;
         slot = slot_next;
@@ -937,7 +961,7 @@ __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict_
         else if (tl.cls == 2) s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
         else {
             const epara_group_args ga = args[tl.group];
-            big_tile<DT, GATED>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
+            big_tile<DT, GATED, CHAIN>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
             if constexpr (CHAIN) chain_done(*chain, tl.group);
             s += stride;
         }
@@ -1026,8 +1050,8 @@ __device__ __forceinline__ void f32_body(const epara_group_args* __restrict__ ar
                     const int col = tx * 4 + j;
                     if (col >= tl.cols) continue;
                     const float b = ga.bias ? as_global<float>(ga.bias)[tl.n0 + col] : 0.f;
-                    Y[static_cast<size_t>(tl.m0 + row) * N + tl.n0 + col] =
-                        act_apply<decltype(tag)::value>(ga.scale * acc[i][j] + b);
+                    put<CHAIN>(Y + static_cast<size_t>(tl.m0 + row) * N + tl.n0 + col,
+                               act_apply<decltype(tag)::value>(ga.scale * acc[i][j] + b));
                 }
             }
         });
@@ -1043,69 +1067,71 @@ __global__ __launch_bounds__(F32_NT) void grouped_kernel_f32(const epara_group_a
 }
 
 // ---- a chain of launches as one kernel: the phases one after the other in every workgroup
-struct chain_phase_dev {
-    const epara_group_args* args;
-    const epara_tile* tiles;
-    const int32_t* order;
-    const epara_chain_wait* waits;
-    long n_slots;
-    int out_dtype, gated, narrow, counter_base;
-};
-struct chain_params {
-    chain_phase_dev ph[EPARA_MAX_CHAIN_PHASES];
+//
+// The tables of every phase are kernel arguments of their own (not fields of a structure in memory):
+// only then does the compiler know them as read-only global memory that nothing in the kernel
+// writes, and fetch tile, order and argument records with scalar loads as in the single-launch
+// kernel -- the streaming pipeline counts its outstanding vector loads and has no room for others.
+struct chain_scalars {
+    long n_slots[EPARA_MAX_CHAIN_PHASES];
+    int out_dtype[EPARA_MAX_CHAIN_PHASES], narrow[EPARA_MAX_CHAIN_PHASES], counter_base[EPARA_MAX_CHAIN_PHASES];
     uint32_t* ws;
     uint32_t spin_limit;
     int n_phases, n_counters;
 };
 
-__device__ __forceinline__ chain_ctx chain_begin(const chain_params& P)
+#define CHAIN_TABLES(i) const epara_group_args* __restrict__ a##i, const epara_tile* __restrict__ t##i, \
+                        const int32_t* __restrict__ o##i, const epara_chain_wait* __restrict__ w##i
+#define CHAIN_PICK(p, x) ((p) == 0 ? x##0 : (p) == 1 ? x##1 : (p) == 2 ? x##2 : x##3)
+
+__device__ __forceinline__ chain_ctx chain_begin(const chain_scalars& S)
 {
     chain_ctx c;
-    c.waits = nullptr; c.ws = P.ws; c.spin_limit = P.spin_limit; c.counter_base = 0;
+    c.waits = nullptr; c.ws = S.ws; c.spin_limit = S.spin_limit; c.counter_base = 0;
     c.pend_group = -1; c.pend_n = 0; c.ok_group = -1;
     return c;
 }
 
-__device__ __forceinline__ void chain_enter_phase(chain_ctx& c, const chain_phase_dev& ph)
+__device__ __forceinline__ void chain_enter_phase(chain_ctx& c, const epara_chain_wait* waits, int counter_base)
 {
     chain_flush(c);                          // counts of the phase before go to that phase's counters
-    c.waits = ph.waits;
-    c.counter_base = ph.counter_base;
+    c.waits = waits;
+    c.counter_base = counter_base;
     c.pend_group = -1;
     c.ok_group = -1;
 }
 
-// One phase as a function of its own: the register allocation of a phase body is then the same as
-// in the single-launch kernel instead of one allocation over both bodies and the loop around them.
-template <int DT, bool GATED>
-__device__ __attribute__((noinline)) void chain_phase_body(const chain_phase_dev ph, char* lds, chain_ctx* c)
-{
-    grouped_body<DT, GATED, true>(ph.args, ph.tiles, ph.order, ph.n_slots, ph.out_dtype, ph.narrow, lds, c);
-}
-
-template <int DT>
-__global__ __launch_bounds__(NT) void grouped_chain_kernel(const chain_params P)
+// FFN: exactly two phases, SwiGLU gate/up then down.  Otherwise: up to four phases without gating.
+template <int DT, bool FFN>
+__global__ __launch_bounds__(NT) void grouped_chain_kernel(CHAIN_TABLES(0), CHAIN_TABLES(1), CHAIN_TABLES(2), CHAIN_TABLES(3),
+                                                           const chain_scalars S)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    chain_ctx c = chain_begin(P);
-    for (int p = 0; p < P.n_phases; ++p) {
-        const chain_phase_dev ph = P.ph[p];
-        chain_enter_phase(c, ph);
-        if (ph.gated) chain_phase_body<DT, true>(ph, lds, &c);
-        else          chain_phase_body<DT, false>(ph, lds, &c);
+    chain_ctx c = chain_begin(S);
+    if constexpr (FFN) {
+        chain_enter_phase(c, nullptr, S.counter_base[0]);
+        grouped_body<DT, true, true>(a0, t0, o0, S.n_slots[0], S.out_dtype[0], S.narrow[0], lds, &c);
+        chain_enter_phase(c, w1, S.counter_base[1]);
+        grouped_body<DT, false, true>(a1, t1, o1, S.n_slots[1], S.out_dtype[1], S.narrow[1], lds, &c);
+    } else {
+        for (int p = 0; p < S.n_phases; ++p) {
+            chain_enter_phase(c, CHAIN_PICK(p, w), S.counter_base[p]);
+            grouped_body<DT, false, true>(CHAIN_PICK(p, a), CHAIN_PICK(p, t), CHAIN_PICK(p, o), S.n_slots[p], S.out_dtype[p],
+                                          S.narrow[p], lds, &c);
+        }
     }
-    chain_exit(c, P.n_counters);
+    chain_exit(c, S.n_counters);
 }
 
-__global__ __launch_bounds__(F32_NT) void grouped_chain_kernel_f32(const chain_params P)
+__global__ __launch_bounds__(F32_NT) void grouped_chain_kernel_f32(CHAIN_TABLES(0), CHAIN_TABLES(1), CHAIN_TABLES(2), CHAIN_TABLES(3),
+                                                                   const chain_scalars S)
 {
-    chain_ctx c = chain_begin(P);
-    for (int p = 0; p < P.n_phases; ++p) {
-        const chain_phase_dev& ph = P.ph[p];
-        chain_enter_phase(c, ph);
-        f32_body<true>(ph.args, ph.tiles, ph.order, ph.n_slots, &c);
+    chain_ctx c = chain_begin(S);
+    for (int p = 0; p < S.n_phases; ++p) {
+        chain_enter_phase(c, CHAIN_PICK(p, w), S.counter_base[p]);
+        f32_body<true>(CHAIN_PICK(p, a), CHAIN_PICK(p, t), CHAIN_PICK(p, o), S.n_slots[p], &c);
     }
-    chain_exit(c, P.n_counters);
+    chain_exit(c, S.n_counters);
 }
 
 __global__ void fill_words_kernel(uint32_t* p, long n, uint32_t v)
@@ -1334,8 +1360,13 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
     if (!phases || !d_workspace) return EPARA_ERR_NULL;
     if (n_phases < 1 || n_phases > EPARA_MAX_CHAIN_PHASES) return EPARA_ERR_SHAPE;
     if (!aligned16(d_workspace)) return EPARA_ERR_ALIGN;
-    chain_params P;
-    std::memset(&P, 0, sizeof P);
+    chain_scalars S;
+    std::memset(&S, 0, sizeof S);
+    const epara_group_args* d_args[EPARA_MAX_CHAIN_PHASES] = {};
+    const epara_tile* d_tiles[EPARA_MAX_CHAIN_PHASES] = {};
+    const int32_t* d_order[EPARA_MAX_CHAIN_PHASES] = {};
+    const epara_chain_wait* d_waits[EPARA_MAX_CHAIN_PHASES] = {};
+    int gated[EPARA_MAX_CHAIN_PHASES] = {};
     int32_t n_counters = 0, n_workgroups = 0;
     bool any = false;
     for (int32_t p = 0; p < n_phases; ++p) {
@@ -1353,9 +1384,8 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
             n_workgroups = L->n_workgroups;
             any = true;
         }
-        int gated = 0;
         for (int32_t g = 0; g < L->G && L->n_tiles > 0; ++g)
-            if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated = 1;
+            if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated[p] = 1;
         if (ph.h_waits && L->n_tiles > 0) {
             if (p == 0) return EPARA_ERR_SHAPE;
             if (!ph.d_waits) return EPARA_ERR_NULL;
@@ -1363,53 +1393,68 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
             const epara_launch* Lp = prev.launch;
             std::vector<int64_t> count(static_cast<size_t>(Lp->G), 0);
             for (int64_t t = 0; t < Lp->n_tiles; ++t) ++count[Lp->h_tiles[t].group];
-            const int prev_esz = prev.out_dtype == EPARA_F32 ? 4 : (prev.out_dtype == EPARA_BF16 ? 2 : 1);
-            const int in_esz = in_dtype == EPARA_F32 ? 4 : (in_dtype == EPARA_BF16 ? 2 : 1);
-            if (prev_esz != in_esz || (in_dtype == EPARA_FP8_E4M3) != (prev.out_dtype == EPARA_FP8_E4M3)) return EPARA_ERR_DTYPE;
+            if (prev.out_dtype != in_dtype) return EPARA_ERR_DTYPE;          // the phase reads what the one before stored
             for (int32_t g = 0; g < L->G; ++g) {
                 const epara_chain_wait& w = ph.h_waits[g];
                 if (w.counter < 0) continue;
                 const int32_t q = w.counter - prev.counter_base;
                 if (q < 0 || q >= Lp->G || w.need != count[q]) return EPARA_ERR_SHAPE;
                 const epara_group_args& a = L->h_args[g];
-                const epara_group_args& b = Lp->h_args[q];
                 if (a.M == 0) continue;
+                if (Lp->n_tiles == 0) return EPARA_ERR_SHAPE;
+                const epara_group_args& b = Lp->h_args[q];
                 if (a.X != b.Y || a.M != b.M || a.K != b.N) return EPARA_ERR_SHAPE;
             }
+            d_waits[p] = ph.d_waits;
         }
-        chain_phase_dev& d = P.ph[p];
-        d.args = L->d_args; d.tiles = L->d_tiles; d.order = L->d_order;
-        d.waits = (ph.h_waits && L->n_tiles > 0) ? ph.d_waits : nullptr;
-        d.n_slots = L->n_tiles > 0 ? L->n_slots : 0;
-        d.out_dtype = ph.out_dtype; d.gated = gated; d.narrow = narrow; d.counter_base = ph.counter_base;
+        d_args[p] = L->d_args; d_tiles[p] = L->d_tiles; d_order[p] = L->d_order;
+        S.n_slots[p] = L->n_tiles > 0 ? L->n_slots : 0;
+        S.out_dtype[p] = ph.out_dtype; S.narrow[p] = narrow; S.counter_base[p] = ph.counter_base;
     }
+    // the kernels exist for chains without gating and for the two phases of a SwiGLU FFN
+    bool ffn = false;
+    for (int32_t p = 0; p < n_phases; ++p) ffn = ffn || gated[p];
+    if (ffn && !(n_phases == 2 && gated[0] && !gated[1])) return EPARA_ERR_DTYPE;
     if (workspace_bytes < epara_chain_workspace_bytes(n_counters)) return EPARA_ERR_CAPACITY;
     if (!any) return EPARA_OK;
-    P.ws = static_cast<uint32_t*>(d_workspace);
-    P.spin_limit = spin_limit ? spin_limit : (1u << 20);
-    P.n_phases = n_phases;
-    P.n_counters = n_counters;
+    S.ws = static_cast<uint32_t*>(d_workspace);
+    S.spin_limit = spin_limit ? spin_limit : (1u << 20);
+    S.n_phases = n_phases;
+    S.n_counters = n_counters;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const void* fn = in_dtype == EPARA_F32 ? reinterpret_cast<const void*>(&grouped_chain_kernel_f32)
-                   : in_dtype == EPARA_BF16 ? reinterpret_cast<const void*>(&grouped_chain_kernel<EPARA_BF16>)
-                                            : reinterpret_cast<const void*>(&grouped_chain_kernel<EPARA_FP8_E4M3>);
+    typedef void (*kernel_t)(const epara_group_args*, const epara_tile*, const int32_t*, const epara_chain_wait*,
+                             const epara_group_args*, const epara_tile*, const int32_t*, const epara_chain_wait*,
+                             const epara_group_args*, const epara_tile*, const int32_t*, const epara_chain_wait*,
+                             const epara_group_args*, const epara_tile*, const int32_t*, const epara_chain_wait*, chain_scalars);
+    kernel_t fn = in_dtype == EPARA_F32 ? grouped_chain_kernel_f32
+                : in_dtype == EPARA_BF16 ? (ffn ? grouped_chain_kernel<EPARA_BF16, true> : grouped_chain_kernel<EPARA_BF16, false>)
+                                         : (ffn ? grouped_chain_kernel<EPARA_FP8_E4M3, true> : grouped_chain_kernel<EPARA_FP8_E4M3, false>);
     const int threads = in_dtype == EPARA_F32 ? F32_NT : NT;
     const size_t dyn = in_dtype == EPARA_F32 ? 0 : LDS_BYTES;
     (void)hipGetLastError();
-    if (dyn && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess) return EPARA_ERR_HIP;
     // a waiting workgroup must not keep the one it waits for off the GPU: the whole grid has to be resident
-    int dev = 0, per_cu = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, dyn) != hipSuccess) return EPARA_ERR_HIP;
-    if (static_cast<int64_t>(n_workgroups) > static_cast<int64_t>(per_cu) * cus) return EPARA_ERR_SHAPE;
-    const dim3 grid(static_cast<unsigned>(n_workgroups));
-    if (in_dtype == EPARA_F32)
-        hipLaunchKernelGGL(grouped_chain_kernel_f32, grid, dim3(F32_NT), 0, st, P);
-    else if (in_dtype == EPARA_BF16)
-        hipLaunchKernelGGL(grouped_chain_kernel<EPARA_BF16>, grid, dim3(NT), LDS_BYTES, st, P);
-    else
-        hipLaunchKernelGGL(grouped_chain_kernel<EPARA_FP8_E4M3>, grid, dim3(NT), LDS_BYTES, st, P);
+    struct limit { int dev; const void* fn; int64_t resident; };
+    static thread_local limit cache[8] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return EPARA_ERR_HIP;
+    int64_t resident = -1;
+    for (const limit& l : cache)
+        if (l.fn == reinterpret_cast<const void*>(fn) && l.dev == dev) resident = l.resident;
+    if (resident < 0) {
+        int per_cu = 0, cus = 0;
+        if (dyn && hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return EPARA_ERR_HIP;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(fn), threads, dyn) != hipSuccess) return EPARA_ERR_HIP;
+        resident = static_cast<int64_t>(per_cu) * cus;
+        static thread_local int next = 0;
+        cache[next++ % 8] = {dev, reinterpret_cast<const void*>(fn), resident};
+    }
+    if (static_cast<int64_t>(n_workgroups) > resident) return EPARA_ERR_SHAPE;
+    hipLaunchKernelGGL(fn, dim3(static_cast<unsigned>(n_workgroups)), dim3(threads), dyn, st,
+                       d_args[0], d_tiles[0], d_order[0], d_waits[0], d_args[1], d_tiles[1], d_order[1], d_waits[1],
+                       d_args[2], d_tiles[2], d_order[2], d_waits[2], d_args[3], d_tiles[3], d_order[3], d_waits[3], S);
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 

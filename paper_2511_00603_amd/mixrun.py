@@ -45,6 +45,7 @@ class StagedMix:
         self.host_bits = []          # per service: dict of the exact inputs handed to the GPU
         self.programs = []           # per copy: list of ("forward", plan, out_dtype) / ("ffn", up, down, h_dtype)
         self.outputs = []            # per copy: list (per launch) of list (per group) of (service, label, tensor)
+        self.inputs = []             # per copy: list (per service) of the device tensor holding X
         self.pack_seconds = 0.0
         self.s_h = s_h
         self._keep = []
@@ -110,7 +111,7 @@ class StagedMix:
 
     def _stage_device(self, n_workgroups):
         mix, dt = self.mix, self.dtype
-        prog, outs = [], []
+        prog, outs, ins = [], [], []
         if mix.services[0].kind == "swiglu":
             ffn = np.zeros(len(mix.services), dtype=B.FFN_DESC)
             o_h, o_y = [], []
@@ -118,6 +119,7 @@ class StagedMix:
             for g, (svc, hb) in enumerate(zip(mix.services, self.host_bits)):
                 d, f = svc.Wgate.shape
                 X = self._dev(hb["X"])
+                ins.append(X)
                 Wg, Wu, Wd = self._packed(hb["Wgate"]), self._packed(hb["Wup"]), self._packed(hb["Wdown"])
                 H, Y = self._empty(svc.M, f, h_dtype), self._empty(svc.M, d, B.EPARA_BF16)
                 rec = ffn[g]
@@ -142,6 +144,7 @@ class StagedMix:
         else:
             n_layers = len(mix.services[0].layers)
             X0 = [self._dev(hb["X"]) for hb in self.host_bits]
+            ins = list(X0)
             W = [[self._packed(l["W"]) for l in hb["layers"]] for hb in self.host_bits]
             bias = [[None if l["b"] is None else self._dev_f32(l["b"]) for l in hb["layers"]] for hb in self.host_bits]
             n_svc = len(mix.services)
@@ -177,6 +180,7 @@ class StagedMix:
                 prog.append(("chain", chain))
         self.programs.append(prog)
         self.outputs.append(outs)
+        self.inputs.append(ins)
 
     def _dev_f32(self, a):
         t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device)

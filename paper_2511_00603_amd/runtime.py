@@ -76,6 +76,38 @@ def _loads(groups, classes, n_stream, tiles, order, n_workgroups):
     return per_slot.sum(axis=0)
 
 
+def _tile_costs(groups, classes, n_stream, tiles):
+    g = groups[tiles["group"]]
+    units = tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
+    return np.where(tiles["cls"] < n_stream, units, 340) * g["K"].astype(np.int64)
+
+
+def _chain_finish(groups, combo, orders, producers, n_workgroups):
+    """When the last workgroup of a chain finishes under the scheduler's cost model, counting the time a
+    tile waits for the group that produces its input (all tiles of that group, wherever they run)."""
+    clock = np.zeros(n_workgroups, dtype=np.int64)
+    ready_prev = None
+    for p, (c, order) in enumerate(zip(combo, orders)):
+        _, classes, n_stream, tiles = c
+        if len(tiles) == 0:
+            ready_prev = np.zeros(len(groups[p]), dtype=np.int64)
+            continue
+        cost = _tile_costs(groups[p], classes, n_stream, tiles)
+        end = np.zeros(len(tiles), dtype=np.int64)
+        for row in order.reshape(-1, n_workgroups):
+            m = row >= 0
+            t = row[m]
+            start = clock[m]
+            if p > 0 and producers[p] is not None and ready_prev is not None:
+                q = np.asarray(producers[p])[tiles["group"][t]]
+                start = np.maximum(start, np.where(q >= 0, ready_prev[np.maximum(q, 0)], 0))
+            clock[m] = start + cost[t]
+            end[t] = clock[m]
+        ready_prev = np.zeros(len(groups[p]), dtype=np.int64)
+        np.maximum.at(ready_prev, tiles["group"], end)
+    return int(clock.max())
+
+
 def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
     return int(_loads(groups, classes, n_stream, tiles, order, n_workgroups).max())
 
@@ -166,11 +198,10 @@ class ChainPlan:
                 opts.append((narrow, classes, n_stream, tiles))
             options.append(opts)
         best = None
-        for combo in itertools.product(*options):     # keep the tables whose joint schedule finishes first
+        for combo in itertools.product(*options):     # keep the tables whose joint schedule finishes first, waits included
             orders = B.epara_schedule_chain([(groups[p], c[1], c[2], c[3]) for p, c in enumerate(combo)],
                                             n_workgroups, n_xcd, panel_m, panel_n)
-            load = sum(_loads(groups[p], c[1], c[2], c[3], orders[p], n_workgroups) for p, c in enumerate(combo))
-            span = int(load.max()) if P else 0
+            span = _chain_finish(groups, combo, orders, producers, n_workgroups)
             if best is None or span < best[0]:
                 best = (span, combo, orders)
         self.makespan, combo, orders = best

@@ -90,6 +90,32 @@ def test_full_size_chain_equals_separate_launches(index, dtype_name):
             assert np.array_equal(x, y)
 
 
+@pytest.mark.parametrize("index,shrink,dtype_name", [SMALL[0], SMALL[1], SMALL[2], SMALL[3], SMALL[5], (4, {}, "bf16")])
+def test_chain_sees_fresh_activations_when_the_inputs_change_between_passes(index, shrink, dtype_name):
+    """The hidden activations live at the same addresses in every pass: a consumer that read a line cached from
+    the pass before, or read ahead of the producer's stores, would reproduce the OLD inputs' values.  The
+    inputs are rescaled in place between passes and every pass is compared with the separate launches."""
+    print("fresh activations", index, shrink, dtype_name, flush=True)
+    mix = make_mix(index, **shrink)
+    ch = StagedMix(mix, dtype_name, U.DEV, chained=True)
+    sep = StagedMix(mix, dtype_name, U.DEV, chained=False, host_bits=ch.host_bits)
+    for factor in (1.0, -0.5, 3.0, 0.125, -2.0):
+        for st in (ch, sep):
+            for X in st.inputs[0]:
+                X.mul_(factor)
+        ch.run()
+        sep.run()
+        torch.cuda.synchronize()
+        assert ch.chain_status() == 0
+        for la, lb in zip(_raw(sep), _raw(ch)):
+            for a, b in zip(la, lb):
+                assert np.array_equal(a, b), "factor %g" % factor
+        # the pass did change the outputs (otherwise this test could not see a stale read)
+        if factor != 1.0:
+            assert not all(np.array_equal(a, b) for la, lb in zip(prev, _raw(ch)) for a, b in zip(la, lb))
+        prev = _raw(ch)
+
+
 def test_device_copies_of_the_chain_plan_are_the_reference_planners():
     from oracle import planner as P
     staged = StagedMix(make_mix(4), "bf16", U.DEV, chained=True)
