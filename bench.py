@@ -109,6 +109,24 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         else:
             k.update(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
         res["kernels"].append(k)
+    # (b2) the same passes captured once into a HIP graph and replayed (no host work per launch)
+    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for c in range(copies):
+                staged.run(copy=c)
+    torch.cuda.synchronize()
+    reps = max(1, steps // copies)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    res["graph_replay_ms_per_step"] = e0.elapsed_time(e1) / (reps * copies)
+    del graph
+
     # (c) the same pass as ONE kernel (epara_grouped_chain): reported beside the launches above, not instead
     del staged
     torch.cuda.empty_cache()
@@ -289,9 +307,9 @@ def main():
             cpu = cpu_baseline(mix)
         if idx == 5 and forming is None:
             forming = time_batch_forming(mix, a.steps, a.warmup)
-        print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%; as one chained kernel %.3f ms" % (
+        print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%; graph replay %.3f ms; as one chained kernel %.3f ms" % (
             mix.name, dtype_name, results[-1]["ms_per_step"], results[-1]["tflops"], results[-1]["requests_per_s"],
-            results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"], results[-1]["chained"]["ms_per_step"]),
+            results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"], results[-1]["graph_replay_ms_per_step"], results[-1]["chained"]["ms_per_step"]),
             file=sys.stderr, flush=True)
 
     head = results[0]
