@@ -285,8 +285,9 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
  *      workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X)  (X = n_xcd), so the
  *      W/X workgroups of one compute die (workgroup b runs on die b mod X) work on neighbouring
  *      tiles and share operands in that die's L2.
- *   2. streaming tiles, longest first: cost = K * (cols * (2 for EPARA_ACT_SWIGLU groups) + BM)
- *      for a streaming tile (weight columns streamed plus activation rows re-read) and 340 * K
+ *   2. streaming tiles, longest first: cost = K * (6 * cols * (2 for EPARA_ACT_SWIGLU groups) + BM)
+ *      for a streaming tile (weight columns streamed from HBM; the activation rows, re-read from L2,
+ *      were measured at about a sixth of that per row) and 2040 * K
  *      for a panel tile; tiles by descending cost (ties: lower tile index) each go to the
  *      workgroup with the smallest accumulated cost (ties: lower workgroup), after that
  *      workgroup's panel tiles.

@@ -224,8 +224,9 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        outermost, and inside a panel the m index runs fastest.  The l-th tile of that sequence
        goes to workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X): the W/X
        tiles that run together on one die are consecutive in the sequence.
-    2. Streaming tiles, longest first.  cost = K * (cols * (2 if gated) + BM) for a streaming
-       tile (weight columns streamed plus activation rows re-read), 340 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
+    2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + BM) for a streaming
+       tile (weight columns streamed from HBM, plus the activation rows re-read from L2 at a sixth of
+       that price), 2040 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
        the workgroup with the smallest accumulated cost (ties: lower workgroup), after that
        workgroup's panel tiles.
     """
@@ -270,13 +271,13 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
                                 x, i = divmod(l % W, per)
                                 b = i * X + x
                                 lists[p][b].append(first[g] + tm * TN + tn)
-                                load[b] += 340 * K
+                                load[b] += 2040 * K
                                 l += 1
         for t, tile in enumerate(tiles):
             if tile[5] < n_stream_classes:
                 g = groups[tile[0]]
                 gated = len(g) > 3 and bool(g[3])
-                stream.append((-(g[1] * (tile[4] * (2 if gated else 1) + classes[tile[5]][1])), p, t))
+                stream.append((-(g[1] * (6 * tile[4] * (2 if gated else 1) + classes[tile[5]][1])), p, t))
     stream.sort()
     heap = [(load[b], b) for b in range(W)]
     heapq.heapify(heap)

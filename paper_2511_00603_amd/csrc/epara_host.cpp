@@ -363,7 +363,7 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                             for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
                                 const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
                                 lists[p][b].push_back(static_cast<int32_t>(first[p][g] + tm * TN + tn));
-                                load[b] += 340 * static_cast<int64_t>(ph.groups[g].K);
+                                load[b] += 2040 * static_cast<int64_t>(ph.groups[g].K);
                                 ++l;
                             }
             }
@@ -378,7 +378,7 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
         for (int64_t t = 0; t < ph.n_tiles; ++t)
             if (ph.tiles[t].cls < ph.n_stream_classes) {
                 const epara_group_desc& d = ph.groups[ph.tiles[t].group];
-                const int64_t units = static_cast<int64_t>(ph.tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + ph.classes[ph.tiles[t].cls].BM;
+                const int64_t units = 6 * static_cast<int64_t>(ph.tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + ph.classes[ph.tiles[t].cls].BM;
                 stream.push_back({units * d.K, p, static_cast<int32_t>(t)});
             }
     }

@@ -780,30 +780,40 @@ struct chain_ctx {
     uint32_t* ws;                    // workspace: header, then the counters
     uint32_t spin_limit;
     int counter_base;                // of the current phase
-    int pend_group, pend_n;          // stored tiles not yet counted
+    int pend_group[2], pend_n[2];    // stored tiles not yet counted, for up to two groups
     int ok_group;                    // the group whose wait was passed last
 };
 
 __device__ __forceinline__ void chain_flush(chain_ctx& c)
 {
-    if (c.pend_n == 0) return;
+    if (c.pend_n[0] == 0 && c.pend_n[1] == 0) return;
     // The tiles were stored with write-through stores (put<true>): once every wave has seen its stores
-    // complete they are in memory, and the count may follow.  A device-scope release fence would do
+    // complete they are in memory, and the counts may follow.  A device-scope release fence would do
     // the same and also write back the die's whole L2, which is what this path avoids.
     wait_vmcnt<0>();                                             // this wave's stores are done
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    if (threadIdx.x == 0)
-        __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group, static_cast<uint32_t>(c.pend_n),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    c.pend_n = 0;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (c.pend_n[i] > 0)
+                __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group[i],
+                                       static_cast<uint32_t>(c.pend_n[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    c.pend_n[0] = c.pend_n[1] = 0;
 }
 
+// A finished tile is counted at once if its group is one of the two being collected; a third group
+// publishes the other two first.  (Publishing drains the wave's loads in flight, so it is done
+// rarely: a workgroup's list holds the tiles of a group together.)
 __device__ __forceinline__ void chain_done(chain_ctx& c, int group)
 {
-    if (c.pend_n > 0 && c.pend_group != group) chain_flush(c);
-    c.pend_group = group;
-    ++c.pend_n;
+    if (c.pend_n[0] > 0 && c.pend_group[0] == group) { ++c.pend_n[0]; return; }
+    if (c.pend_n[1] > 0 && c.pend_group[1] == group) { ++c.pend_n[1]; return; }
+    if (c.pend_n[0] > 0 && c.pend_n[1] > 0) chain_flush(c);
+    const int i = c.pend_n[0] == 0 ? 0 : 1;
+    c.pend_group[i] = group;
+    c.pend_n[i] = 1;
 }
 
 // True if a tile of `group` has to wait (or may have to) before its input can be read.
@@ -812,6 +822,11 @@ __device__ __forceinline__ bool chain_must_wait(const chain_ctx& c, int group)
     return c.waits != nullptr && group != c.ok_group && c.waits[group].counter >= 0 && c.waits[group].need > 0;
 }
 
+// No cache is invalidated after the wait.  A line of the produced tensor can only be in this die's
+// L2 or this unit's L1 if it was read, and inside this kernel it is read only by tiles that have
+// passed this wait, i.e. after all of it was written through to memory; lines cached by an earlier
+// kernel are dropped at the kernel boundary.  (A device-scope acquire would invalidate the die's
+// whole L2 at every wait, and with it the activation rows that the tiles of a group share.)
 __device__ __forceinline__ void chain_wait(chain_ctx& c, int group)
 {
     if (!chain_must_wait(c, group)) { c.ok_group = group; return; }
@@ -819,7 +834,7 @@ __device__ __forceinline__ void chain_wait(chain_ctx& c, int group)
     if (threadIdx.x == 0) {
         const uint32_t* ctr = c.ws + CHAIN_HEADER_WORDS + w.counter;
         uint32_t polls = 0;
-        while (__hip_atomic_load(ctr, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(w.need)) {
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < static_cast<uint32_t>(w.need)) {
             if (++polls >= c.spin_limit) {                       // bounded: report and go on, the kernel always ends
                 __hip_atomic_store(c.ws, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
@@ -829,22 +844,23 @@ __device__ __forceinline__ void chain_wait(chain_ctx& c, int group)
             __builtin_amdgcn_s_sleep(8);
         }
     }
-    __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");           // every wave, before it reads the produced rows
+    __syncthreads();                                             // nobody reads the produced rows before the count was seen
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     c.ok_group = group;
 }
 
-// The last workgroup to leave puts the counters back to zero for the next chain on this workspace.
+// The last workgroup to leave puts the counters back to zero for the next chain on this workspace
+// (the kernel boundary orders these stores before that chain).
 __device__ __forceinline__ void chain_exit(chain_ctx& c, int n_counters)
 {
     chain_flush(c);
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t left = __hip_atomic_fetch_add(c.ws + 1, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t left = __hip_atomic_fetch_add(c.ws + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (left + 1 == gridDim.x) {
             for (int i = 0; i < n_counters; ++i)
                 __hip_atomic_store(c.ws + CHAIN_HEADER_WORDS + i, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(c.ws + 1, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(c.ws + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -1088,7 +1104,7 @@ __device__ __forceinline__ chain_ctx chain_begin(const chain_scalars& S)
 {
     chain_ctx c;
     c.waits = nullptr; c.ws = S.ws; c.spin_limit = S.spin_limit; c.counter_base = 0;
-    c.pend_group = -1; c.pend_n = 0; c.ok_group = -1;
+    c.pend_group[0] = c.pend_group[1] = -1; c.pend_n[0] = c.pend_n[1] = 0; c.ok_group = -1;
     return c;
 }
 
@@ -1097,7 +1113,6 @@ __device__ __forceinline__ void chain_enter_phase(chain_ctx& c, const epara_chai
     chain_flush(c);                          // counts of the phase before go to that phase's counters
     c.waits = waits;
     c.counter_base = counter_base;
-    c.pend_group = -1;
     c.ok_group = -1;
 }
 

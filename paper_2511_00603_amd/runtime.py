@@ -70,16 +70,16 @@ def _loads(groups, classes, n_stream, tiles, order, n_workgroups):
         return np.zeros(n_workgroups, dtype=np.int64)
     g = groups[tiles["group"]]
     stream = tiles["cls"] < n_stream
-    units = tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
-    cost = np.where(stream, units, 340) * g["K"].astype(np.int64)
+    units = 6 * tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
+    cost = np.where(stream, units, 2040) * g["K"].astype(np.int64)
     per_slot = np.where(order >= 0, cost[np.maximum(order, 0)], 0).reshape(-1, n_workgroups)
     return per_slot.sum(axis=0)
 
 
 def _tile_costs(groups, classes, n_stream, tiles):
     g = groups[tiles["group"]]
-    units = tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
-    return np.where(tiles["cls"] < n_stream, units, 340) * g["K"].astype(np.int64)
+    units = 6 * tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
+    return np.where(tiles["cls"] < n_stream, units, 2040) * g["K"].astype(np.int64)
 
 
 def _chain_finish(groups, combo, orders, producers, n_workgroups):
