@@ -71,7 +71,26 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / steps
 
-    # (b) the same launches one by one with an event between them: per-kernel durations
+    # (a2) the same passes captured once into a HIP graph and replayed (no host work per launch)
+    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for c in range(copies):
+                staged.run(copy=c)
+    torch.cuda.synchronize()
+    reps = max(1, steps // copies)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    graph_ms = e0.elapsed_time(e1) / (reps * copies)
+    del graph
+
+    # (b) the same launches one by one with an event between them: per-kernel durations (the last use of
+    # these kernels in the run, so that a kernel trace of this command ends with exactly these passes)
     plans = [staged.plans(c) for c in range(copies)]
     outs = []
     for step in staged.programs[0]:
@@ -92,7 +111,7 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
            "tflops": flops / (ms_per_step * 1e-3) / 1e12, "requests_per_s": mix.requests / (ms_per_step * 1e-3),
            "requests": mix.requests, "rows": mix.rows, "flops": flops, "launches": n_l, "weight_copies": copies,
            "plan_us": plan_us, "plan_upload_us": upload_us, "pack_weights_s": staged.pack_seconds / copies,
-           "stage_s": stage_s, "kernels": []}
+           "stage_s": stage_s, "graph_replay_ms_per_step": graph_ms, "kernels": []}
     for l in range(n_l):
         t = per_launch_ms[l] * 1e-3
         st = stats[l]
@@ -109,24 +128,6 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         else:
             k.update(achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS)
         res["kernels"].append(k)
-    # (b2) the same passes captured once into a HIP graph and replayed (no host work per launch)
-    side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
-    with torch.cuda.stream(side):
-        with torch.cuda.graph(graph, stream=side):
-            for c in range(copies):
-                staged.run(copy=c)
-    torch.cuda.synchronize()
-    reps = max(1, steps // copies)
-    graph.replay()
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(reps):
-        graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    res["graph_replay_ms_per_step"] = e0.elapsed_time(e1) / (reps * copies)
-    del graph
-
     # (c) the same pass as ONE kernel (epara_grouped_chain): reported beside the launches above, not instead
     del staged
     torch.cuda.empty_cache()
