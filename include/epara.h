@@ -260,6 +260,54 @@ int32_t epara_place_services(const int32_t* partial, int32_t n_partial, const in
                              const int32_t* X_dot, int32_t n_xdot, epara_phi_fn phi, void* user,
                              int32_t* theta_out, int32_t cap, int32_t* n_out);
 
+/* ---- host side: the placement objective by event-driven simulation (Sec. 3.3, Sec. 5) -------- */
+
+/* One user request of the period.  32 bytes. */
+typedef struct {
+    int64_t arrival_us;        /* when the user sends it to server `origin` */
+    int64_t slo_us;            /* latency SLO: it must be finished by arrival_us + slo_us */
+    int32_t service;           /* l */
+    int32_t origin;            /* n */
+    int32_t frames;            /* >= 1: it occupies an instance for frames * c_ln microseconds */
+    int32_t reserved;
+} epara_sim_request;
+
+typedef struct {
+    const int64_t* compute_us; /* c_ln, [n_services * n_servers] row-major (service major): the time one frame of
+                                  service l takes on server n, from a lookup table (measured); <= 0: cannot run there */
+    int64_t hop_us;            /* transmission time of one offload hop */
+    int64_t sync_delay_us;     /* t: period and delay of the state synchronisation, > 0 */
+    int32_t n_servers, n_services;
+    int32_t max_offload;       /* offload count at which the handler gives up */
+    int32_t reserved;
+} epara_sim_config;
+
+typedef struct {
+    double  satisfied;         /* phi(Theta): requests served within their SLO */
+    int64_t local, offloaded, timeout, offload_exceeded, insufficient;   /* handler decisions taken */
+} epara_sim_result;
+
+/* phi(Theta) of Eq. "optimal" for the placement list placements[0..n) (id = l * n_servers + n, one
+ * service instance per entry, repeats = replicas), by replaying the period's requests through the
+ * handler of Sec. 3.2 (epara_handle_request) event by event; nothing is executed, computation times
+ * come from the table (Sec. 3.3: c_ln; Sec. 5: lookup tables indexed by GPU and service).  Model:
+ *   - an instance serves one request at a time in the order they were bound to it;
+ *   - "locally sufficient" = the instance of (l, n) that is free first finishes the request by its
+ *     deadline; the request is bound to it at once and counts as satisfied;
+ *   - every sync_delay_us = t, at time j*t, each server publishes per service its completions in
+ *     ((j-1)t, jt] and when its first instance is free; at time `now` the others know snapshot
+ *     J = floor(now / t) - 1 (J < 1: nothing yet, zeros): theoretical goodput = instances * 1e6 / c_lm,
+ *     actual = completions of that window * 1e6 / t, queued = max(0, first free time - J*t);
+ *   - servers a request has visited are never destinations (no loops); a hop takes hop_us;
+ *   - the k-th offloading decision of request r uses draws[r * max_offload + k] in [0, 1).
+ * Events are handled in (time, sequence) order; sequence = request index for arrivals from users,
+ * then in order of creation for offloaded arrivals.  Requests need not be sorted.
+ * Errors: ERR_NULL; ERR_SHAPE for counts <= 0 (servers, services, t), negative counts, ids, frames < 1
+ * or a draw outside [0, 1). */
+int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements, int32_t n_placements,
+                       const epara_sim_request* requests, int64_t n_requests, const double* draws,
+                       epara_sim_result* result);
+
 /* Group planning: the single-GPU part of the allocator's "parallel mode per task" decision.
  *   row_off[g] = sum_{h<g} M_h ; x_off[g] = sum_{h<g} M_h K_h ; y_off[g] = sum_{h<g} M_h N_h
  *   (each G+1 entries; x_off / y_off are element offsets for callers that pack groups

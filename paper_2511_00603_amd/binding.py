@@ -33,6 +33,8 @@ FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "
                      ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
 SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<i8"), ("first_chunk", "<i8"), ("group", "<i4"), ("reserved", "<i4")])
 CHAIN_WAIT = np.dtype([("counter", "<i4"), ("need", "<i4")])
+SIM_REQUEST = np.dtype([("arrival_us", "<i8"), ("slo_us", "<i8"), ("service", "<i4"), ("origin", "<i4"), ("frames", "<i4"), ("reserved", "<i4")])
+assert SIM_REQUEST.itemsize == 32
 EPARA_MAX_CHAIN_PHASES = 4
 assert CHAIN_WAIT.itemsize == 8
 assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
@@ -48,6 +50,22 @@ class Launch(ctypes.Structure):
 
 
 assert ctypes.sizeof(Launch) == 64
+
+
+class SimConfig(ctypes.Structure):
+    """struct epara_sim_config."""
+    _fields_ = [("compute_us", ctypes.c_void_p), ("hop_us", ctypes.c_int64), ("sync_delay_us", ctypes.c_int64),
+                ("n_servers", ctypes.c_int32), ("n_services", ctypes.c_int32), ("max_offload", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class SimResult(ctypes.Structure):
+    """struct epara_sim_result."""
+    _fields_ = [("satisfied", ctypes.c_double), ("local", ctypes.c_int64), ("offloaded", ctypes.c_int64),
+                ("timeout", ctypes.c_int64), ("offload_exceeded", ctypes.c_int64), ("insufficient", ctypes.c_int64)]
+
+
+assert ctypes.sizeof(SimConfig) == 40 and ctypes.sizeof(SimResult) == 48
 
 
 class PhaseSchedule(ctypes.Structure):
@@ -114,6 +132,8 @@ def lib():
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
+        L.epara_simulate.argtypes = [vp, vp, i32, vp, i64, vp, vp]
+        L.epara_simulate.restype = i32
         L.epara_schedule_chain.argtypes = [vp, i32, i32, i32, i32, i32]
         L.epara_chain_waits.argtypes = [vp, i64, i32, i32, vp, i32, vp]
         L.epara_chain_workspace_bytes.argtypes = [i32]
@@ -301,6 +321,21 @@ def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups,
     order = np.zeros(int(n[0]), dtype=np.int32)
     _check(lib().epara_schedule_tiles(*args, _ptr(order), len(order), _ptr(n)), "epara_schedule_tiles")
     return order
+
+
+def epara_simulate(n_servers, n_services, compute_us, hop_us, sync_delay_us, max_offload, placements, requests, draws):
+    """compute_us: [n_services, n_servers]; requests: SIM_REQUEST array; draws: [n_requests, max_offload] in [0, 1).
+    -> dict(satisfied, local, offloaded, timeout, offload_exceeded, insufficient)."""
+    compute_us = np.ascontiguousarray(compute_us, dtype=np.int64).reshape(n_services, n_servers)
+    placements = np.ascontiguousarray(placements, dtype=np.int32)
+    requests = np.ascontiguousarray(requests, dtype=SIM_REQUEST)
+    draws = np.ascontiguousarray(draws, dtype=np.float64).reshape(-1)
+    cfg = SimConfig(_ptr(compute_us), int(hop_us), int(sync_delay_us), int(n_servers), int(n_services), int(max_offload), 0)
+    res = SimResult()
+    _check(lib().epara_simulate(ctypes.addressof(cfg), _ptr(placements) if len(placements) else None, len(placements),
+                                _ptr(requests) if len(requests) else None, len(requests),
+                                _ptr(draws) if len(draws) else None, ctypes.addressof(res)), "epara_simulate")
+    return {k: getattr(res, k) for k, _ in SimResult._fields_}
 
 
 def epara_schedule_chain(phases, n_workgroups, n_xcd=8, panel_m=8, panel_n=4):

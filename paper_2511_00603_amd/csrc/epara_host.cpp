@@ -243,6 +243,111 @@ int64_t epara_inter_request_count(int64_t batch_size, int64_t max_inter_frame_co
     return batch_size / max_inter_frame_count;
 }
 
+int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements, int32_t n_placements,
+                       const epara_sim_request* requests, int64_t n_requests, const double* draws,
+                       epara_sim_result* result)
+{
+    if (!config || !result) return EPARA_ERR_NULL;
+    const int32_t N = config->n_servers, L = config->n_services, max_off = config->max_offload;
+    const int64_t t = config->sync_delay_us;
+    if (N <= 0 || L <= 0 || t <= 0 || max_off < 0 || config->hop_us < 0 || n_placements < 0 || n_requests < 0) return EPARA_ERR_SHAPE;
+    if (!config->compute_us || (n_placements > 0 && !placements) || (n_requests > 0 && !requests)) return EPARA_ERR_NULL;
+    if (n_requests > 0 && max_off > 0 && !draws) return EPARA_ERR_NULL;
+    for (int32_t i = 0; i < n_placements; ++i)
+        if (placements[i] < 0 || placements[i] >= static_cast<int64_t>(L) * N) return EPARA_ERR_SHAPE;
+    for (int64_t r = 0; r < n_requests; ++r) {
+        const epara_sim_request& q = requests[r];
+        if (q.service < 0 || q.service >= L || q.origin < 0 || q.origin >= N || q.frames < 1 || q.slo_us < 0 || q.arrival_us < 0)
+            return EPARA_ERR_SHAPE;
+        for (int32_t k = 0; k < max_off; ++k) {
+            const double u = draws[r * max_off + k];
+            if (!(u >= 0.0 && u < 1.0)) return EPARA_ERR_SHAPE;
+        }
+    }
+
+    struct pool {                                            // the instances of one (service, server)
+        std::vector<int64_t> free;                           // when each instance is free
+        std::vector<std::pair<int64_t, int64_t>> log;        // (decision time, first free time after it)
+        std::vector<std::pair<int64_t, int64_t>> done;       // (window index, completions), ascending windows may repeat
+    };
+    std::vector<pool> pools(static_cast<size_t>(L) * N);
+    for (int32_t i = 0; i < n_placements; ++i) pools[placements[i]].free.push_back(0);
+
+    struct event { int64_t time, seq, request; int32_t server, hops; std::vector<int32_t> path; };
+    auto later = [](const event& a, const event& b) { return a.time != b.time ? a.time > b.time : a.seq > b.seq; };
+    std::priority_queue<event, std::vector<event>, decltype(later)> heap(later);
+    for (int64_t r = 0; r < n_requests; ++r) heap.push({requests[r].arrival_us, r, r, requests[r].origin, 0, {requests[r].origin}});
+    int64_t seq = n_requests;
+
+    epara_sim_result out;
+    std::memset(&out, 0, sizeof out);
+    std::vector<double> theoretical(N), actual(N);
+    std::vector<int64_t> queued(N);
+    while (!heap.empty()) {
+        event e = heap.top();
+        heap.pop();
+        const epara_sim_request& q = requests[e.request];
+        const int32_t l = q.service, n = e.server;
+        const int64_t now = e.time, deadline = q.arrival_us + q.slo_us;
+        pool& here = pools[static_cast<size_t>(l) * N + n];
+        const int64_t c_here = config->compute_us[static_cast<size_t>(l) * N + n];
+        int32_t slot = -1, local_ok = 0;
+        int64_t finish = 0;
+        if (!here.free.empty() && c_here > 0) {
+            slot = 0;
+            for (size_t i = 1; i < here.free.size(); ++i)
+                if (here.free[i] < here.free[slot]) slot = static_cast<int32_t>(i);
+            finish = std::max(now, here.free[slot]) + q.frames * c_here;
+            local_ok = finish <= deadline;
+        }
+        const int64_t J = now / t - 1;
+        for (int32_t m = 0; m < N; ++m) {
+            theoretical[m] = actual[m] = 0.0;
+            queued[m] = 0;
+            const pool& there = pools[static_cast<size_t>(l) * N + m];
+            const int64_t c = config->compute_us[static_cast<size_t>(l) * N + m];
+            if (there.free.empty() || c <= 0 || std::find(e.path.begin(), e.path.end(), m) != e.path.end()) continue;
+            theoretical[m] = static_cast<double>(there.free.size()) * 1e6 / static_cast<double>(c);
+            if (J >= 1) {
+                int64_t completions = 0;
+                for (const auto& d : there.done)
+                    if (d.first == J) completions += d.second;
+                actual[m] = static_cast<double>(completions) * 1e6 / static_cast<double>(t);
+                int64_t first_free = 0;
+                for (const auto& g : there.log)
+                    if (g.first <= J * t) first_free = g.second;
+                queued[m] = std::max<int64_t>(0, first_free - J * t);
+            }
+        }
+        const double u = e.hops < max_off ? draws[e.request * max_off + e.hops] : 0.0;
+        int32_t decision = 0, dest = -1;
+        if (int32_t st = epara_handle_request(now, deadline, local_ok, e.hops, max_off, theoretical.data(), actual.data(),
+                                              queued.data(), N, n, t, q.slo_us, u, &decision, &dest)) return st;
+        switch (decision) {
+        case EPARA_HANDLE_LOCAL: {
+            here.free[slot] = finish;
+            here.log.push_back({now, *std::min_element(here.free.begin(), here.free.end())});
+            here.done.push_back({(finish + t - 1) / t, 1});
+            ++out.local;
+            out.satisfied += 1.0;
+            break;
+        }
+        case EPARA_HANDLE_OFFLOAD: {
+            ++out.offloaded;
+            event f{now + config->hop_us, seq++, e.request, dest, e.hops + 1, e.path};
+            f.path.push_back(dest);
+            heap.push(std::move(f));
+            break;
+        }
+        case EPARA_HANDLE_TIMEOUT: ++out.timeout; break;
+        case EPARA_HANDLE_OFFLOAD_EXCEEDED: ++out.offload_exceeded; break;
+        default: ++out.insufficient; break;
+        }
+    }
+    *result = out;
+    return EPARA_OK;
+}
+
 int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
                           const epara_tile_class* classes, int32_t n_classes,
                           int64_t* row_off, int64_t* x_off, int64_t* y_off,
