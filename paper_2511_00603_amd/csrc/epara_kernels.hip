@@ -259,9 +259,12 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-template <int DT, bool GATED, bool WT>
+// `advance` is called three times, well apart (after the first loads are issued, when the multiply
+// loop starts, when it ends): the caller uses it to fetch the records of its next tile, one
+// dependent scalar load per call, so that their latencies pass under this tile.
+template <int DT, bool GATED, bool WT, class Advance>
 __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dtype,
-                                         int m0, int n0, int rows, int cols, char* lds)
+                                         int m0, int n0, int rows, int cols, char* lds, Advance&& advance)
 {
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
@@ -349,8 +352,10 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     __syncthreads();                       // and nobody still reads it
     if (!GATED) bias_tile[tid] = my_bias;   // zeros when the group has no bias: the epilogue adds it unconditionally
     issue_w(0); issue_w(1); issue_x(0); issue_w(2); issue_w(3); issue_x(1);
+    advance();
     wait_vmcnt<16>();                      // W0, W1, X(0,1) have landed
     __builtin_amdgcn_s_barrier();
+    advance();
     if constexpr (DT == EPARA_BF16) {
         v4i wf[2][4], xf[2][4];
         // Fragment i = 0..7 of step (kt, s2), in the order the next half's MFMAs need them:
@@ -458,6 +463,7 @@ __device__ __forceinline__ void big_tile(const epara_group_args& ga, int out_dty
     }
     wait_vmcnt<0>();
     __syncthreads();                       // every wave is done with the stage buffers
+    advance();
 
     // Epilogue.  The 256 accumulators of a lane sit in the AGPR half of the register file: they can
     // be stored but not computed on there, and they cannot be indexed at run time.  So each wave
@@ -976,10 +982,30 @@ __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict_
         else if (tl.cls == 2 && !narrow) s = skinny_run<DT, GATED, CHAIN, 2, 4, 8, 2>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
         else if (tl.cls == 2) s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
         else {
-            const epara_group_args ga = args[tl.group];
-            big_tile<DT, GATED, CHAIN>(ga, out_dtype, tl.m0, tl.n0, tl.rows, tl.cols, lds);
-            if constexpr (CHAIN) chain_done(*chain, tl.group);
-            s += stride;
+            // A run of panel tiles.  What follows a tile in the workgroup's list is found by three
+            // dependent scalar loads (order -> tile -> group arguments); they are issued one at a time
+            // from inside the tile before, so the next tile starts without waiting for them.
+            epara_tile cur = tl;
+            epara_group_args ga = args[cur.group];
+            for (;;) {
+                if constexpr (CHAIN) chain_wait(*chain, cur.group);
+                const long s1 = s + stride;
+                int t1 = -1, stage = 0;
+                epara_tile nxt = cur;
+                epara_group_args ga1 = ga;
+                auto advance = [&]() {
+                    if (stage == 0)      { t1 = s1 < n_slots ? order[s1] : -1; }
+                    else if (stage == 1) { if (t1 >= 0) nxt = tiles[t1]; }
+                    else                 { if (t1 >= 0 && nxt.cls >= N_STREAM_CLASSES) ga1 = args[nxt.group]; }
+                    ++stage;
+                };
+                big_tile<DT, GATED, CHAIN>(ga, out_dtype, cur.m0, cur.n0, cur.rows, cur.cols, lds, advance);
+                if constexpr (CHAIN) chain_done(*chain, cur.group);
+                s = s1;
+                if (t1 < 0 || nxt.cls < N_STREAM_CLASSES) break;   // idle slot, end of the list or a streaming tile
+                cur = nxt;
+                ga = ga1;
+            }
         }
     }
 }
