@@ -377,7 +377,9 @@ int32_t epara_chain_waits(const epara_tile* producer_tiles, int64_t n_producer_t
  * bf16 / fp8 have two tables: the wide one (narrow = 0) gives batches of 33..64 rows tiles of 128
  * (gated: 64) columns, which halves the activation re-reads; the narrow one (narrow = 1) gives
  * them 64 (gated: 32) columns, for launches with too few columns to keep every workgroup busy
- * with wide tiles.  A launch may use either. */
+ * with wide tiles.  A launch may use either.  fp32: batches of up to 16 rows in 16 x 64 tiles (the sum
+ * over K is formed in four contiguous quarters that are added in order), larger ones in 64 x 64
+ * tiles (K ascending). */
 int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
                              epara_tile_class* classes, int32_t cap, int32_t* n_classes,
                              int32_t* n_stream_classes);

@@ -563,6 +563,7 @@ int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
     int32_t n = 0, ns = 0;
     if (in_dtype == EPARA_F32) {
         if (gated) return EPARA_ERR_DTYPE;
+        table[n++] = {16, 16, 64};          // K split over the four waves of a workgroup
         table[n++] = {INT32_MAX, 64, 64};
     } else if (in_dtype == EPARA_BF16 || in_dtype == EPARA_FP8_E4M3) {
         // weight-streaming classes: the whole batch (1, 2 or 4 blocks of 16 rows) against 2, 4 or 8

@@ -159,7 +159,7 @@ def test_kernel_classes_and_packed_sizes():
     c, ns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
     assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)] and ns == 3
     c, ns = B.epara_kernel_classes(B.EPARA_F32, 0)
-    assert [tuple(int(v) for v in x) for x in c] == [(P.INT32_MAX, 64, 64)] and ns == 0
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 64), (P.INT32_MAX, 64, 64)] and ns == 0
     c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0, narrow=True)
     assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)] and ns == 3
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE

@@ -111,6 +111,25 @@ def test_linearity_in_x(dtype_name):
     assert_close(lhs, rhs, 3 * TOL[dtype_name], "linearity")
 
 
+def test_fp32_small_batches_with_awkward_shapes():
+    """Batches of at most 16 rows take the fp32 path that cuts K into four quarters: K smaller than the number of
+    quarters, K not a multiple of the staging step, ragged column tiles, every activation, next to a group of
+    the 64-row class in the same launch."""
+    rng = np.random.default_rng(21)
+    acts = ["none", "relu", "gelu_erf", "gelu_tanh", "silu"]
+    shapes = [(1, 1, 1), (7, 3, 10), (16, 7, 65), (3, 17, 130), (16, 100, 64), (9, 513, 77), (2, 2048, 5), (40, 33, 70), (16, 64, 128)]
+    specs = [U.rand_spec(rng, M, K, N, acts[i % len(acts)], bias=i % 3 != 0) for i, (M, K, N) in enumerate(shapes)]
+    G = U.Groups(specs, "f32")
+    assert sorted(set(int(c) for c in G.plan.tiles["cls"])) == [0, 1]
+    for (M, K, N), y, yref in zip(shapes, G.run(), G.expected()):
+        assert_close(y, yref, TOL["f32"], "fp32 small %s" % ((M, K, N),))
+    # and the same values whatever the grid size (fixed summation order)
+    y_a = U.Groups(specs, "f32", n_workgroups=8).run()
+    y_b = U.Groups(specs, "f32", n_workgroups=256).run()
+    for a, b in zip(y_a, y_b):
+        assert np.array_equal(a, b)
+
+
 # ---- independence and determinism ------------------------------------------------------------------
 
 def test_group_order_row_order_and_grid_size_do_not_change_a_single_bit():
