@@ -71,7 +71,25 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / steps
 
-    # (a2) the same passes captured once into a HIP graph and replayed (no host work per launch)
+    # (b) the same launches one by one with an event between them: per-kernel durations, right after (a) so
+    # that the chip is in the same state (passes warmup + steps .. warmup + 2 steps - 1 of these kernels in a
+    # kernel trace of this command)
+    plans = [staged.plans(c) for c in range(copies)]
+    outs = []
+    for step in staged.programs[0]:
+        outs += [step[2]] if step[0] == "forward" else [step[3], 1]     # out dtype per launch (1 = bf16)
+    n_l = len(plans[0])
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_l + 1)] for _ in range(steps)]
+    for i in range(steps):
+        evs[i][0].record()
+        for l in range(n_l):
+            R.grouped_forward(plans[i % copies][l], outs[l])
+            evs[i][l + 1].record()
+    torch.cuda.synchronize()
+    samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
+    per_launch_ms = [sum(v) / steps for v in samples]
+
+    # (b2) the same passes captured once into a HIP graph and replayed (no host work per launch)
     side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
@@ -89,29 +107,40 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     graph_ms = e0.elapsed_time(e1) / (reps * copies)
     del graph
 
-    # (b) the same launches one by one with an event between them: per-kernel durations (the last use of
-    # these kernels in the run, so that a kernel trace of this command ends with exactly these passes)
-    plans = [staged.plans(c) for c in range(copies)]
-    outs = []
-    for step in staged.programs[0]:
-        outs += [step[2]] if step[0] == "forward" else [step[3], 1]     # out dtype per launch (1 = bf16)
-    n_l = len(plans[0])
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n_l + 1)] for _ in range(steps)]
-    for i in range(steps):
-        evs[i][0].record()
-        for l in range(n_l):
-            R.grouped_forward(plans[i % copies][l], outs[l])
-            evs[i][l + 1].record()
+    # (b3) consecutive passes on two streams in turn: passes are independent (each works on its own copy of
+    # every buffer), so the start of one fills the compute units that the end of the other leaves idle
+    even = copies if copies % 2 == 0 else copies + 1
+    pair = staged if even == copies else StagedMix(mix, dtype_name, "cuda:0", copies=even, s_h=s_h, host_bits=staged.host_bits)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    def alternate(n):
+        for st in streams:
+            st.wait_stream(torch.cuda.current_stream())
+        for i in range(n):
+            with torch.cuda.stream(streams[i % 2]):
+                pair.run(copy=i)                  # an even number of copies: a stream always meets the same buffers
+        for st in streams:
+            torch.cuda.current_stream().wait_stream(st)
+    alternate(2 * warmup)
     torch.cuda.synchronize()
-    samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
-    per_launch_ms = [sum(v) / steps for v in samples]
+    n2 = 4 * steps
+    t0 = time.perf_counter()
+    alternate(n2)
+    torch.cuda.synchronize()
+    two_stream_ms = (time.perf_counter() - t0) * 1e3 / n2
+    if pair is not staged:
+        del pair
+        torch.cuda.empty_cache()
 
     flops = mix.flops()
     res = {"name": mix.name, "dtype": dtype_name, "ms_per_step": ms_per_step,
            "tflops": flops / (ms_per_step * 1e-3) / 1e12, "requests_per_s": mix.requests / (ms_per_step * 1e-3),
            "requests": mix.requests, "rows": mix.rows, "flops": flops, "launches": n_l, "weight_copies": copies,
            "plan_us": plan_us, "plan_upload_us": upload_us, "pack_weights_s": staged.pack_seconds / copies,
-           "stage_s": stage_s, "graph_replay_ms_per_step": graph_ms, "kernels": []}
+           "stage_s": stage_s, "graph_replay_ms_per_step": graph_ms,
+           "two_streams": {"ms_per_step": two_stream_ms, "tflops": flops / (two_stream_ms * 1e-3) / 1e12,
+                           "requests_per_s": mix.requests / (two_stream_ms * 1e-3), "steps": n2,
+                           "clock": "host wall clock around the submissions, synchronised at both ends"},
+           "kernels": []}
     for l in range(n_l):
         t = per_launch_ms[l] * 1e-3
         st = stats[l]
@@ -308,9 +337,10 @@ def main():
             cpu = cpu_baseline(mix)
         if idx == 5 and forming is None:
             forming = time_batch_forming(mix, a.steps, a.warmup)
-        print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%; graph replay %.3f ms; as one chained kernel %.3f ms" % (
+        print("# %s %s: %.3f ms/step, %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%%; graph replay %.3f ms; passes on two streams %.3f ms; as one chained kernel %.3f ms" % (
             mix.name, dtype_name, results[-1]["ms_per_step"], results[-1]["tflops"], results[-1]["requests_per_s"],
-            results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"], results[-1]["graph_replay_ms_per_step"], results[-1]["chained"]["ms_per_step"]),
+            results[-1]["roofline"]["bound"], 100 * results[-1]["roofline"]["frac"], results[-1]["graph_replay_ms_per_step"], results[-1]["two_streams"]["ms_per_step"],
+            results[-1]["chained"]["ms_per_step"]),
             file=sys.stderr, flush=True)
 
     head = results[0]

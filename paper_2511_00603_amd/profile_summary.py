@@ -1,7 +1,7 @@
 """Turns rocprofv3 CSV output (kernel trace and counter collection of profile_driver runs) into the
 short text summaries kept under profiles/ and into profiles/traffic.json.
 
-    python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt [LAUNCHES [LAST_PASSES]]
+    python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt [LAUNCHES [PASSES [FIRST_PASS]]]
     python -m paper_2511_00603_amd.profile_summary traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
     python -m paper_2511_00603_amd.profile_summary report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
     python -m paper_2511_00603_amd.profile_summary counters OUT WORKLOAD MIX DTYPE    (OUT/{sq,tcc}_counter_collection.csv)
@@ -32,7 +32,7 @@ def _rows(path):
     return list(csv.DictReader(open(path)))
 
 
-def kernels(trace_csv, command, out_txt, launches_per_pass, tail_passes=0):
+def kernels(trace_csv, command, out_txt, launches_per_pass, tail_passes=0, first_pass=None):
     rows = _rows(trace_csv)
     by = {}
     for r in rows:
@@ -44,12 +44,17 @@ def kernels(trace_csv, command, out_txt, launches_per_pass, tail_passes=0):
         L.append("%-78s %6d %12.1f %10.2f %7.2f" % (name[:78], len(d), sum(d), sum(d) / len(d), 100 * sum(d) / total))
     g = [(r["Kernel_Name"], (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3, r) for r in rows if "grouped_kernel" in r["Kernel_Name"]]
     g.sort(key=lambda t: int(t[2]["Start_Timestamp"]))
-    first = max(launches_per_pass, len(g) - tail_passes * launches_per_pass) if tail_passes else launches_per_pass
-    L += ["", "grouped_kernel per launch of a pass (dispatch i -> launch i mod %d; %s):" % (
-        launches_per_pass, ("the last %d passes, i.e. the ones the benchmark times launch by launch" % tail_passes) if tail_passes
-        else "first pass skipped as warm-up")]
+    first, last = launches_per_pass, len(g)
+    what = "first pass skipped as warm-up"
+    if first_pass is not None:
+        first, last = first_pass * launches_per_pass, (first_pass + tail_passes) * launches_per_pass
+        what = "passes %d..%d, the ones the benchmark times launch by launch" % (first_pass, first_pass + tail_passes - 1)
+    elif tail_passes:
+        first = max(launches_per_pass, len(g) - tail_passes * launches_per_pass)
+        what = "the last %d passes" % tail_passes
+    L += ["", "grouped_kernel per launch of a pass (dispatch i -> launch i mod %d; %s):" % (launches_per_pass, what)]
     for l in range(launches_per_pass):
-        d = [t[1] for i, t in enumerate(g) if i % launches_per_pass == l and i >= first]
+        d = [t[1] for i, t in enumerate(g) if i % launches_per_pass == l and first <= i < last]
         if d:
             r = g[l][2]
             L.append("  launch %d  n=%3d  avg %9.2f  median %9.2f  min %9.2f  max %9.2f   grid %s x %s threads, scratch %s B/lane"
@@ -179,6 +184,6 @@ if __name__ == "__main__":
         report(sys.argv[2], sys.argv[3], sys.argv[4], sys.argv[5], int(sys.argv[6]) if len(sys.argv) > 6 else 2)
     elif sys.argv[1] == "kernels":
         kernels(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2,
-                int(sys.argv[6]) if len(sys.argv) > 6 else 0)
+                int(sys.argv[6]) if len(sys.argv) > 6 else 0, int(sys.argv[7]) if len(sys.argv) > 7 else None)
     elif sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2)

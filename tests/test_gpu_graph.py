@@ -53,3 +53,30 @@ def test_graph_replays_equal_the_eager_pass(index, shrink, dtype_name, chained):
         want = _raw(staged)
     if chained:
         assert staged.chain_status() == 0
+
+
+def test_passes_on_two_streams_equal_the_passes_one_after_the_other():
+    """Independent passes (their own copies of every buffer) submitted to two streams in turn overlap on the
+    GPU; each must still produce what it produces alone."""
+    mix = make_mix(4, d=512, ffn=1376)
+    staged = StagedMix(mix, "bf16", U.DEV, copies=2)
+    raw = lambda c: [[t.cpu().view(torch.uint8).numpy().copy() for _, _, t in launch] for launch in staged.outputs[c]]
+    for c in range(2):
+        staged.run(copy=c)
+    torch.cuda.synchronize()
+    want = [raw(0), raw(1)]
+    for c in range(2):
+        for launch in staged.outputs[c]:
+            for _, _, t in launch:
+                t.zero_()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    for i in range(6):
+        with torch.cuda.stream(streams[i % 2]):
+            staged.run(copy=i)
+    torch.cuda.synchronize()
+    for c in range(2):
+        for la, lb in zip(want[c], raw(c)):
+            for a, b in zip(la, lb):
+                assert np.array_equal(a, b)
