@@ -434,8 +434,13 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
  * phase by phase (bit-identical), without the launch boundaries: a workgroup that finishes its
  * share of a phase goes on with the next phase at once, and a tile of group g waits only for the
  * group that produces its input (phase[p].h_waits[g]).  Completion is counted per group in
- * d_workspace (counter counter_base + g of phase p rises by one per stored tile, made visible with
- * device-scope release / acquire); counter ranges of different phases must not overlap.
+ * d_workspace (counter counter_base + g of phase p rises by the tiles a workgroup has stored, after
+ * its stores, which go through to memory, have completed; a workgroup may hold back the counts of up
+ * to two groups until it starts a third or ends the phase); counter ranges of different phases
+ * must not overlap.  The kernels exist for chains without EPARA_ACT_SWIGLU groups (up to
+ * EPARA_MAX_CHAIN_PHASES phases) and for the two phases of a SwiGLU FFN (gate/up, then down);
+ * other mixtures of gated and plain phases -> ERR_DTYPE.  Every phase but the last must store
+ * in_dtype (the next phase reads it) -> ERR_DTYPE.
  * Requirements beyond epara_grouped_forward's, checked before anything is enqueued: every phase has
  * the same n_workgroups, which must not exceed what the GPU keeps resident at once (a waiting
  * workgroup must never keep the one it waits for from running) -> ERR_SHAPE; a wait must name a
