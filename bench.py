@@ -51,7 +51,9 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
 
     esz = {"f32": 4, "bf16": 2, "fp8": 1}[dtype_name]
     footprint = mix.weight_elems() * esz
-    copies = 1 if footprint >= 2 * LLC_BYTES else min(8, -(-2 * LLC_BYTES // max(footprint, 1)))
+    # cold-cache rule: rotate through copies whose total is at least twice the last-level cache, and never
+    # fewer than two unless a single pass already streams six times the cache
+    copies = 1 if footprint >= 6 * LLC_BYTES else max(2, min(8, -(-2 * LLC_BYTES // max(footprint, 1))))
     t0 = time.perf_counter()
     staged = StagedMix(mix, dtype_name, "cuda:0", copies=copies, s_h=s_h)
     stage_s = time.perf_counter() - t0
