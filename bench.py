@@ -105,6 +105,16 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     torch.cuda.synchronize()
     samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
     per_launch_ms = [sum(v) / steps for v in samples]
+    # each launch repeated back to back (on its rotating copies) with events at both ends only: without the
+    # idle microseconds that an event pair around a single short kernel also spans
+    repeated_ms = []
+    for l in range(n_l):
+        e0.record()
+        for i in range(steps):
+            R.grouped_forward(plans[i % copies][l], outs[l])
+        e1.record()
+        torch.cuda.synchronize()
+        repeated_ms.append(e0.elapsed_time(e1) / steps)
 
     # (b2) the same passes captured once into a HIP graph and replayed (no host work per launch)
     side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
@@ -167,6 +177,7 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         t_hbm = st["bytes"] / (HBM_PEAK_GBS * 1e9)
         bound = "mfma" if t_mfma > t_hbm else "hbm"
         k = {"launch": l, "ms": per_launch_ms[l], "ms_median": samples[l][steps // 2], "ms_min": samples[l][0],
+             "ms_repeated": repeated_ms[l],
              "tiles": st["tiles"], "groups": st["groups"],
              "flops": st["flops"], "bytes": st["bytes"], "bound": bound}
         if bound == "mfma":
