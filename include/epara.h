@@ -393,6 +393,12 @@ int32_t epara_ffn_swiglu_args(const epara_ffn_desc* ffn, int32_t G, int32_t in_d
 
 /* ---- device side -------------------------------------------------------------------- */
 
+/* Device workspace that epara_grouped_forward / epara_grouped_ffn_swiglu need for these groups: 0.
+ * Partial sums and transposes live in LDS and nothing is split over K across workgroups, so a launch
+ * uses no device memory beyond its operands and tables (only epara_grouped_chain has a workspace,
+ * epara_chain_workspace_bytes).  -1 for a bad dtype or G < 0. */
+int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype);
+
 /* Bytes of the packed form of a [K,N] weight matrix (fp32: K*N*4, unchanged layout). */
 int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype);
 

@@ -132,6 +132,8 @@ def lib():
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
+        L.epara_workspace_bytes.argtypes = [vp, i32, i32]
+        L.epara_workspace_bytes.restype = i64
         L.epara_simulate.argtypes = [vp, vp, i32, vp, i64, vp, vp]
         L.epara_simulate.restype = i32
         L.epara_schedule_chain.argtypes = [vp, i32, i32, i32, i32, i32]
@@ -321,6 +323,11 @@ def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups,
     order = np.zeros(int(n[0]), dtype=np.int32)
     _check(lib().epara_schedule_tiles(*args, _ptr(order), len(order), _ptr(n)), "epara_schedule_tiles")
     return order
+
+
+def epara_workspace_bytes(groups, in_dtype):
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    return int(lib().epara_workspace_bytes(_ptr(groups), len(groups), int(in_dtype)))
 
 
 def epara_simulate(n_servers, n_services, compute_us, hop_us, sync_delay_us, max_offload, placements, requests, draws):

@@ -554,6 +554,13 @@ int32_t epara_chain_waits(const epara_tile* producer_tiles, int64_t n_producer_t
     return EPARA_OK;
 }
 
+int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype)
+{
+    (void)groups;
+    if (G < 0 || (in_dtype != EPARA_F32 && in_dtype != EPARA_BF16 && in_dtype != EPARA_FP8_E4M3)) return -1;
+    return 0;
+}
+
 int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
                              epara_tile_class* classes, int32_t cap, int32_t* n_classes,
                              int32_t* n_stream_classes)

@@ -164,6 +164,7 @@ def test_kernel_classes_and_packed_sizes():
     assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)] and ns == 3
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
+    assert B.epara_workspace_bytes(_desc([(5, 8, 8)]), B.EPARA_BF16) == 0 and B.epara_workspace_bytes(_desc([]), 9) == -1
     assert B.epara_packed_weight_bytes(4096, 11008, B.EPARA_BF16) == 4096 * 11008 * 2
     assert B.epara_packed_weight_bytes(40, 10, B.EPARA_BF16) == 1 * 2 * 1024
     assert B.epara_packed_weight_bytes(40, 10, B.EPARA_FP8_E4M3) == 1024
