@@ -1,5 +1,5 @@
 """Turns rocprofv3 CSV output (kernel trace and counter collection of profile_driver runs) into the
-short text summaries kept under profiles/ and into profiles/traffic.json.
+short text summaries kept under profiles/ and into profiles/traffic.txt.
 
     python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt [LAUNCHES [PASSES [FIRST_PASS]]]
     python -m paper_2511_00603_amd.profile_summary traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
@@ -20,7 +20,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 KERNEL_SOURCE = os.path.join(HERE, "csrc", "epara_kernels.hip")
-TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.txt")
 COPY_BYTES = 1 << 30
 
 
@@ -107,7 +107,7 @@ def lookup_traffic(workload, launch):
 
 
 def report(out_dir, workload, mix, dtype, launches_per_pass=2):
-    """profiles/grouped_kernel_WORKLOAD.txt and the WORKLOAD entry of profiles/traffic.json from the three
+    """profiles/grouped_kernel_WORKLOAD.txt and the WORKLOAD entry of profiles/traffic.txt from the three
     runs of the profile driver (kernel trace with 8 passes, FETCH_SIZE and WRITE_SIZE with 4 passes each)."""
     drv = "python3 -m paper_2511_00603_amd.profile_driver %s %s" % (mix, dtype)
     txt = os.path.join(ROOT, "profiles", "grouped_kernel_%s.txt" % workload)
@@ -116,7 +116,7 @@ def report(out_dir, workload, mix, dtype, launches_per_pass=2):
     traffic(os.path.join(out_dir, "fetch_counter_collection.csv"), os.path.join(out_dir, "write_counter_collection.csv"),
             workload, launches_per_pass)
     rec = json.load(open(TRAFFIC_JSON))[workload]
-    L = ["", "HBM-side traffic per launch (profiles/traffic.json, kernel source %s), from" % rec["kernel_source_sha256_16"],
+    L = ["", "HBM-side traffic per launch (profiles/traffic.txt, kernel source %s), from" % rec["kernel_source_sha256_16"],
          "  rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- %s 4" % drv,
          "  rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT -o write -- %s 4" % drv,
          "each scaled by what the same counter reads for the 1 GiB copy kernel of the same run (fetch x %.3f, write x %.3f):"
