@@ -200,7 +200,7 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     res["chained"] = {"ms_per_step": e0.elapsed_time(e1) / steps, "launches": chained.n_launches(),
                       "wait_error_flag": max(chained.chain_status(c) for c in range(copies))}
     staged = chained
-    from paper_2511_00603_amd.profile_summary import lookup_traffic
+    from profile_summary import lookup_traffic
     dom = max(res["kernels"], key=lambda k: k["ms"])
     res["roofline"] = {"bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"], "unit": dom["unit"],
                        "frac": dom["frac"], "traffic": lookup_traffic("%s_%s" % (mix.name, dtype_name), dom["launch"]),
@@ -212,11 +212,11 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
 
 
 def measure_peaks():
-    """What this GPU sustains on the library's own probes: streaming read bandwidth, and the bf16 MFMA rate
+    """What this GPU sustains on the benchmark's probes (bench_probes.hip): streaming read bandwidth, and the bf16 MFMA rate
     on all-zero operands and on N(0,1) operands (the matrix clock is power limited and data dependent)."""
     import numpy as np
     import torch
-    from paper_2511_00603_amd import binding as B
+    import bench_probes as P
     from workloads import casts
     dev = "cuda:0"
     stream = torch.cuda.current_stream().cuda_stream
@@ -225,10 +225,10 @@ def measure_peaks():
     nbytes = 2 << 30
     buf = torch.ones(nbytes, dtype=torch.uint8, device=dev)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    B.epara_probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
+    P.probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
     e0.record()
     for _ in range(5):
-        B.epara_probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
+        P.probe_read(buf.data_ptr(), nbytes, sink.data_ptr(), 256, stream)
     e1.record()
     torch.cuda.synchronize()
     out["hbm_read_GBs"] = 5 * nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
@@ -237,9 +237,9 @@ def measure_peaks():
     for name, vals in (("zeros", np.zeros(16384, dtype=np.float32)), ("normal", rng.standard_normal(16384).astype(np.float32))):
         ops = torch.from_numpy(casts.bf16_bits(vals).view(np.int16)).to(dev)
         iters = 20000
-        B.epara_probe_mfma(ops.data_ptr(), 2000, sink.data_ptr(), 256, stream)
+        P.probe_mfma(ops.data_ptr(), 2000, sink.data_ptr(), 256, stream)
         e0.record()
-        B.epara_probe_mfma(ops.data_ptr(), iters, sink.data_ptr(), 256, stream)
+        P.probe_mfma(ops.data_ptr(), iters, sink.data_ptr(), 256, stream)
         e1.record()
         torch.cuda.synchronize()
         out["mfma_bf16_TFLOPs_%s_operands" % name] = 256 * 4 * iters * 16 * 2 * 32 * 32 * 16 / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -1,13 +1,19 @@
-// Measurement helpers of libepara (not part of the forward path): what this GPU sustains, so
-// that roofline fractions can be read against measured ceilings as well as the data-sheet ones.
-//   epara_probe_read   streams a buffer once (every wave reads consecutive 1 KiB chunks)
-//   epara_probe_copy   plain copy kernel of known size (calibrates the HBM traffic counters)
-//   epara_probe_mfma   register-resident 32x32x16 bf16 MFMA loop on caller-provided operand data
-//                      (the sustained matrix rate depends on the operand values: power-limited)
+// Measurement probes of the benchmark (a library of their own, built beside bench.py; not part of
+// libepara): what this GPU sustains, so that roofline fractions can be read against measured
+// ceilings as well as the data-sheet ones.  Every entry point returns 0 or a hipError_t / -1.
+//   probe_read   streams `bytes` (>= 8 KiB, rounded down to 8 KiB per wave step) of d_buf once with
+//                n_workgroups workgroups of 256 threads, 16-byte loads, each wave reading consecutive
+//                1 KiB chunks: the read bandwidth this GPU sustains.  d_sink: 4 writable bytes.
+//   probe_copy   plain copy kernel d_dst[0..bytes) = d_src[0..bytes) (bytes a multiple of 16): a kernel
+//                of known HBM traffic against which profiler byte counters are calibrated.
+//   probe_mfma   register-resident bf16 MFMA loop: every wave of n_workgroups x 256 threads issues
+//                iters x 16 v_mfma_f32_32x32x16_bf16 (16 independent accumulators) on operands taken
+//                from d_operands (8 x 256 x 16 bytes).  The sustained rate depends on the operand
+//                VALUES (clocks are power limited), so the caller passes data distributed like its
+//                workload.  Flops per call = n_workgroups * 4 * iters * 16 * 2*32*32*16.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "epara.h"
 
 namespace {
 
@@ -61,37 +67,37 @@ __global__ __launch_bounds__(256) void mfma_kernel(const v4i* __restrict__ ops, 
 
 extern "C" {
 
-int32_t epara_probe_read(const void* d_buf, int64_t bytes, void* d_sink, int32_t n_workgroups, void* stream)
+int32_t probe_read(const void* d_buf, int64_t bytes, void* d_sink, int32_t n_workgroups, void* stream)
 {
-    if (!d_buf || !d_sink) return EPARA_ERR_NULL;
-    if (bytes < 8192 || n_workgroups <= 0) return EPARA_ERR_SHAPE;
-    if (reinterpret_cast<uintptr_t>(d_buf) & 15u) return EPARA_ERR_ALIGN;
+    if (!d_buf || !d_sink) return -1;
+    if (bytes < 8192 || n_workgroups <= 0) return -1;
+    if (reinterpret_cast<uintptr_t>(d_buf) & 15u) return -1;
     (void)hipGetLastError();
     hipLaunchKernelGGL(read_kernel, dim3(static_cast<unsigned>(n_workgroups)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4i*>(d_buf), static_cast<long>(bytes / 1024), static_cast<int*>(d_sink));
-    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+    return static_cast<int32_t>(hipGetLastError());
 }
 
-int32_t epara_probe_copy(const void* d_src, void* d_dst, int64_t bytes, void* stream)
+int32_t probe_copy(const void* d_src, void* d_dst, int64_t bytes, void* stream)
 {
-    if (!d_src || !d_dst) return EPARA_ERR_NULL;
-    if (bytes < 16) return EPARA_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(d_src) | reinterpret_cast<uintptr_t>(d_dst)) & 15u) return EPARA_ERR_ALIGN;
+    if (!d_src || !d_dst) return -1;
+    if (bytes < 16) return -1;
+    if ((reinterpret_cast<uintptr_t>(d_src) | reinterpret_cast<uintptr_t>(d_dst)) & 15u) return -1;
     (void)hipGetLastError();
     hipLaunchKernelGGL(copy_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4i*>(d_src), static_cast<v4i*>(d_dst), static_cast<long>(bytes / 16));
-    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+    return static_cast<int32_t>(hipGetLastError());
 }
 
-int32_t epara_probe_mfma(const void* d_operands, int32_t iters, void* d_sink, int32_t n_workgroups, void* stream)
+int32_t probe_mfma(const void* d_operands, int32_t iters, void* d_sink, int32_t n_workgroups, void* stream)
 {
-    if (!d_operands || !d_sink) return EPARA_ERR_NULL;
-    if (iters <= 0 || n_workgroups <= 0) return EPARA_ERR_SHAPE;
-    if (reinterpret_cast<uintptr_t>(d_operands) & 15u) return EPARA_ERR_ALIGN;
+    if (!d_operands || !d_sink) return -1;
+    if (iters <= 0 || n_workgroups <= 0) return -1;
+    if (reinterpret_cast<uintptr_t>(d_operands) & 15u) return -1;
     (void)hipGetLastError();
     hipLaunchKernelGGL(mfma_kernel, dim3(static_cast<unsigned>(n_workgroups)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4i*>(d_operands), iters, static_cast<float*>(d_sink));
-    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+    return static_cast<int32_t>(hipGetLastError());
 }
 
 }  // extern "C"

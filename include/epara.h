@@ -404,8 +404,9 @@ int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype);
 
 /* Packs d_W ([K,N] row-major, `dtype`) into d_packed for the bf16 / fp8 kernels:
  * 1 KiB fragments of 16 columns x (64 bytes of K), fragment (nb, ks) at
- * ((nb * ceil(K/KF) + ks) * 1024) bytes, KF = 32 (bf16) or 64 (fp8); inside a fragment the
- * 16-byte chunk (q*16 + r) holds W[ks*KF + q*KF/4 ... +KF/4-1][nb*16 + r]; zero padded.
+ * ((nb * KSP + ks) * 1024) bytes, KSP = ceil(K/KF) rounded up to a multiple of 4, KF = 32 (bf16)
+ * or 64 (fp8); inside a fragment the 16-byte chunk (q*16 + r) holds
+ * W[ks*KF + q*KF/4 ... +KF/4-1][nb*16 + r]; zero padded, the padding stages included.
  * fp32: plain copy.  Enqueues one kernel. */
 int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
                            void* d_packed, int64_t packed_bytes, void* stream);
@@ -495,24 +496,6 @@ int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epar
  * copy h_args is not touched: launch validation does not read the scale fields. */
 int32_t epara_patch_scales(epara_group_args* d_args, int32_t G, const float* d_sx, const float* d_sw,
                            const float* d_sw2, const float* d_sout, void* stream);
-
-/* ---- measurement helpers (not part of the forward path) ------------------------------------- */
-
-/* Streams `bytes` (>= 8 KiB, rounded down to 8 KiB per wave step) of d_buf once with n_workgroups
- * workgroups of 256 threads, 16-byte loads, each wave reading consecutive 1 KiB chunks: the read
- * bandwidth this GPU sustains.  d_sink: 4 writable bytes. */
-int32_t epara_probe_read(const void* d_buf, int64_t bytes, void* d_sink, int32_t n_workgroups, void* stream);
-
-/* Plain copy kernel d_dst[0..bytes) = d_src[0..bytes) (bytes a multiple of 16): a kernel of known HBM
- * traffic against which profiler byte counters are calibrated. */
-int32_t epara_probe_copy(const void* d_src, void* d_dst, int64_t bytes, void* stream);
-
-/* Register-resident bf16 MFMA loop: every wave of n_workgroups x 256 threads issues iters x 16
- * v_mfma_f32_32x32x16_bf16 (16 independent accumulators) on operands taken from d_operands
- * (8 x 256 x 16 bytes).  The sustained rate depends on the operand VALUES (clocks are power
- * limited), so the caller passes data distributed like its workload.  d_sink: 4 writable bytes.
- * Flops per call = n_workgroups * 4 * iters * 16 * 2*32*32*16. */
-int32_t epara_probe_mfma(const void* d_operands, int32_t iters, void* d_sink, int32_t n_workgroups, void* stream);
 
 const char* epara_status_string(int32_t status);
 

@@ -113,7 +113,11 @@ def ffn_swiglu(X, Wgate, Wup, Wdown, s_gate=1.0, s_up=1.0, s_down=1.0, h_scale=N
     fp8 path stores them; then H is returned as the dequantised values s_h * q and
     s_down must already include s_h.
     """
-    H = swiglu_hidden(X, Wgate, Wup, s_gate, s_up)
+    return ffn_swiglu_down(swiglu_hidden(X, Wgate, Wup, s_gate, s_up), Wdown, s_down, h_scale)
+
+
+def ffn_swiglu_down(H, Wdown, s_down=1.0, h_scale=None):
+    """Second half of ffn_swiglu from given hidden activations H (fp64): returns (H as stored, Y)."""
     if h_scale is not None:
         H = e4m3_decode(e4m3_encode(H, h_scale), 1.0)       # codes as values, scale folded in s_down
         Y = dense_forward(H, Wdown, None, "none", s_down)

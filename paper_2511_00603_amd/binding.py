@@ -156,11 +156,6 @@ def lib():
         L.epara_copy_segments.argtypes = [vp, vp, i64, i64, vp]
         L.epara_quantize_segments_e4m3.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
         L.epara_patch_scales.argtypes = [vp, i32, vp, vp, vp, vp, vp]
-        L.epara_probe_read.argtypes = [vp, i64, vp, i32, vp]
-        L.epara_probe_copy.argtypes = [vp, vp, i64, vp]
-        L.epara_probe_mfma.argtypes = [vp, i32, vp, i32, vp]
-        for name in ("epara_probe_read", "epara_probe_copy", "epara_probe_mfma"):
-            getattr(L, name).restype = i32
         for name in ("epara_batch_rows", "epara_plan_groups", "epara_schedule_tiles", "epara_kernel_classes",
                      "epara_ffn_swiglu_args", "epara_pack_weights", "epara_grouped_forward", "epara_grouped_ffn_swiglu",
                      "epara_request_segments", "epara_copy_segments", "epara_quantize_segments_e4m3", "epara_patch_scales"):
@@ -430,15 +425,3 @@ def epara_grouped_forward(launch, in_dtype, out_dtype, stream=0):
 def epara_grouped_ffn_swiglu(up, down, in_dtype, h_dtype, out_dtype, stream=0):
     _check(lib().epara_grouped_ffn_swiglu(ctypes.addressof(up), ctypes.addressof(down), int(in_dtype), int(h_dtype),
                                           int(out_dtype), int(stream) or None), "epara_grouped_ffn_swiglu")
-
-
-def epara_probe_read(d_buf, nbytes, d_sink, n_workgroups, stream=0):
-    _check(lib().epara_probe_read(int(d_buf), int(nbytes), int(d_sink), int(n_workgroups), int(stream) or None), "epara_probe_read")
-
-
-def epara_probe_copy(d_src, d_dst, nbytes, stream=0):
-    _check(lib().epara_probe_copy(int(d_src), int(d_dst), int(nbytes), int(stream) or None), "epara_probe_copy")
-
-
-def epara_probe_mfma(d_operands, iters, d_sink, n_workgroups, stream=0):
-    _check(lib().epara_probe_mfma(int(d_operands), int(iters), int(d_sink), int(n_workgroups), int(stream) or None), "epara_probe_mfma")

@@ -1,0 +1,296 @@
+// Streaming tiles of libepara: small batches against weights streamed from HBM.
+#ifndef EPARA_STREAM_H
+#define EPARA_STREAM_H
+
+#include "epara_device.h"
+
+namespace {
+
+// ------------------------------------------------------------------ skinny tiles (weight streaming)
+
+// Small batches are bandwidth bound: the weights are streamed from HBM exactly once, straight
+// into MFMA operand registers (each load instruction of a wave reads 1 KiB of consecutive packed
+// weights), while the activations are re-read from L2 by every tile, through a small LDS ring per
+// wave (see skinny_setup).  To keep that re-read at half the weight traffic, a tile of streaming
+// class c = 0, 1, 2 pairs MB = 1, 2, 4 blocks of 16 rows (the whole batch) with NFR = 2, 4, 8
+// weight column blocks: 32 / 64 / 128 output columns, or for gated groups NFR/2 gate blocks and
+// the matching NFR/2 up blocks (16 / 32 / 64 hidden columns).  K is walked in steps of two packed
+// fragments (128 bytes of every activation row, so a row's cache line is used whole); wave w takes
+// the steps p = w, w+4, ....  The four partial sums meet in LDS and are added in wave order: the
+// result does not depend on timing.
+//
+// Consecutive tiles of one class that a workgroup owns are processed as one software-pipelined
+// stream: a ring of U slots per wave (weights in registers, activations in LDS) stays full across
+// tile boundaries, so the loads of the next tile are in flight while this tile is reduced and
+// stored; the last tile of a run drains the ring.  Every tile is padded to a whole number of U
+// steps; padding steps, rows past the batch and column blocks past N re-load a valid address and
+// are not multiplied / not stored.  The scheduling barriers keep the compiler from sinking the
+// prefetch loads down to their first use.
+template <int NFR>
+struct skinny_tile_state {
+    gcptr w[NFR];          // uniform: start of each weight column block's fragment stream
+    const char* x;         // uniform: activations of the group
+    uint32_t xoff[8];      // per lane, per direct-load instruction j < 2 MB: byte offset of my row + my chunk's 16 c
+    int KS, K;             // fragments along K, K
+    int n_chunks;          // chunks of U steps per wave
+};
+
+// Activations of a step (two fragments = 128 bytes of K for MB x 16 rows) go through a per-wave LDS
+// slot: direct-load instruction j covers rows 8j .. 8j+7 whole (8 x 128 bytes, eight cache lines),
+// where loading MFMA operands straight from memory touches 16 half lines per instruction - the
+// lines, not the bytes, are what the re-read of the activations costs next to the weight stream.
+// Lane l of instruction j writes LDS chunk s = l%8 of row 8j + l/8 and fetches the global chunk
+// c = s ^ ((row/2)%8); operand reads (16 rows x one chunk per quarter wave) then fall into 16
+// different bank groups.
+template <int DT, bool GATED, int MB, int NFR, int U>
+__device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const epara_group_args& ga, int n0, int lane)
+{
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const int K = ga.K, N = ga.N;
+    const int KS = (K + KF - 1) / KF;
+    const int NB = (N + 15) >> 4;
+    st.K = K;
+    st.KS = KS;
+    const int steps = (KS + 1) >> 1;                             // two fragments per step
+    st.n_chunks = (((steps + 3) >> 2) + U - 1) / U;
+#pragma unroll
+    for (int f = 0; f < NFR; ++f) {
+        // gated: fragments 0 .. NFR/2-1 are gate blocks, the rest the same blocks of the up matrix
+        const int rel = GATED ? (f % (NFR / 2)) : f;
+        const int nb = min((n0 >> 4) + rel, NB - 1);             // a block past N only feeds unstored columns
+        gcptr base = as_global<char>((GATED && f >= NFR / 2) ? ga.W2 : ga.W);
+        st.w[f] = base + static_cast<size_t>(nb) * ((KS + 3) & ~3) * 1024;   // blocks are padded to a multiple of four stages
+    }
+    st.x = static_cast<const char*>(ga.X);
+#pragma unroll
+    for (int j = 0; j < 2 * MB; ++j) {
+        const int row = 8 * j + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        st.xoff[j] = static_cast<uint32_t>(min(row, ga.M - 1)) * static_cast<uint32_t>(K * ESZ) + c * 16;
+    }
+}
+
+// One ring slot: weight fragments ks = 2p and 2p+1 of NFR column blocks (the activations of the
+// step sit in the wave's LDS slot of the same index).
+template <int NFR>
+struct skinny_slot { v4i w[2][NFR]; };
+
+template <int DT, int MB, int NFR>
+__device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, int i, int wave, int lane, skinny_slot<NFR>& sl,
+                                            char* xslot_generic)
+{
+    ldsptr xslot = (ldsptr)xslot_generic;
+    constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
+    constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
+    const int p = wave + 4 * i;                                  // step: fragments 2p and 2p+1
+    // activations first: loads complete in issue order, so once the weights of this slot are in
+    // their registers the slot's LDS image is complete too
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(st.x), 0, -1, 0x00020000);
+    if ((2 * p + 2) * KF <= st.K) {                              // both fragments lie inside K
+#pragma unroll
+        for (int j = 0; j < 2 * MB; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(xslot + j * 1024), 16,
+                                                     static_cast<int>(st.xoff[j]), p * 128, 0, 0);
+    } else {
+        // ragged or padding step: a fragment past the last one repeats the last, a chunk past K
+        // falls back to chunk 0 of its fragment (the packed weights are zero there)
+#pragma unroll
+        for (int j = 0; j < 2 * MB; ++j) {
+            const int c = (lane & 7) ^ ((4 * j + (lane >> 4)) & 7);
+            const int ks = min(2 * p + (c >> 2), st.KS - 1);
+            const int cc = (ks * KF + (c & 3) * EPC < st.K) ? (c & 3) : 0;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(xslot + j * 1024), 16,
+                                                     static_cast<int>(st.xoff[j]) - c * 16 + ks * 64 + cc * 16, 0, 0, 0);
+        }
+    }
+    const uint32_t lane16 = lane * 16;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int ks = min(2 * p + e, st.KS - 1);                // padding repeats the last fragment
+#pragma unroll
+        for (int f = 0; f < NFR; ++f) sl.w[e][f] = ld16(st.w[f] + static_cast<size_t>(ks) * 1024 + lane16);
+    }
+}
+
+template <int DT, int MB, int NFR, int AFTER>
+__device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int i, int wave, int lane, const skinny_slot<NFR>& sl,
+                                           char* xslot_generic, v4f (&acc)[NFR][MB])
+{
+    ldsptr xslot = (ldsptr)xslot_generic;
+    // every load issued after this slot's belongs to one of the AFTER slots filled since
+    wait_vmcnt<AFTER * (2 * NFR + 2 * MB)>();
+    __builtin_amdgcn_sched_barrier(0);
+    const int r = lane & 15, q = lane >> 4;
+    v4i x[2][MB];
+#pragma unroll
+    for (int e = 0; e < 2; ++e)
+#pragma unroll
+        for (int fm = 0; fm < MB; ++fm)
+            x[e][fm] = *reinterpret_cast<lds_v4i>(xslot + (fm * 16 + r) * 128 + (((e * 4 + q) ^ ((r >> 1) & 7)) << 4));
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        if (2 * (wave + 4 * i) + e < st.KS) {
+#pragma unroll
+            for (int f = 0; f < NFR; ++f)
+#pragma unroll
+                for (int fm = 0; fm < MB; ++fm) mma<DT>(acc[f][fm], sl.w[e][f], x[e][fm]);
+        }
+    }
+}
+
+template <int DT, bool GATED, int MB, int NFR, bool WT>
+__device__ __forceinline__ void skinny_finish(const epara_group_args& ga, int out_dtype, int n0, int cols,
+                                              v4f (&acc)[NFR][MB], int wave, int lane, char* lds)
+{
+    const int r = lane & 15, q = lane >> 4;
+    // red[wave][block of the pass][fm][lane]: at most 64 KiB, so the widest tile takes two passes
+    constexpr int PASSES = (NFR * MB * 4096 + RING_LDS_OFFSET - 1) / RING_LDS_OFFSET;
+    constexpr int NP = NFR / PASSES;                             // column blocks per pass
+    v4f* red = reinterpret_cast<v4f*>(lds);
+    const bool vec_ok = (ga.N & 3) == 0;
+    const int M = ga.M;
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        __syncthreads();                                         // the previous sums have been read
+#pragma unroll
+        for (int fi = 0; fi < NP; ++fi) {
+            // gated: a pass holds NP/2 gate blocks and the matching up blocks
+            const int f = GATED ? (fi < NP / 2 ? pass * (NP / 2) + fi : NFR / 2 + pass * (NP / 2) + fi - NP / 2) : pass * NP + fi;
+#pragma unroll
+            for (int fm = 0; fm < MB; ++fm) red[((wave * NP + fi) * MB + fm) * 64 + lane] = acc[f][fm];
+        }
+        __syncthreads();
+        if constexpr (GATED) {                                   // units (hidden column block p, row block fm)
+            constexpr int UNITS = (NP / 2) * MB;
+            for (int unit = wave; unit < UNITS; unit += 4) {
+                const int pi = unit / MB, fm = unit % MB, p = pass * (NP / 2) + pi;
+                if (fm * 16 >= M || p * 16 >= cols) continue;
+                v4f g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    g += red[((w * NP + pi) * MB + fm) * 64 + lane];
+                    u += red[((w * NP + NP / 2 + pi) * MB + fm) * 64 + lane];
+                }
+                finish_gated<WT>(ga, out_dtype, g, u, 0, fm * 16 + r, M, n0, p * 16 + 4 * q, cols, vec_ok);
+            }
+        } else {                                                 // units (column block f, row block fm)
+            constexpr int UNITS = NP * MB;
+            with_act(ga.act, [&](auto tag) {
+                for (int unit = wave; unit < UNITS; unit += 4) {
+                    const int fi = unit / MB, fm = unit % MB, f = pass * NP + fi;
+                    if (fm * 16 >= M || f * 16 >= cols) continue;
+                    v4f s0 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) s0 += red[((w * NP + fi) * MB + fm) * 64 + lane];
+                    finish_plain<decltype(tag)::value, WT>(ga, out_dtype, s0, ga.bias ? as_global<float>(ga.bias) + n0 : nullptr, 0,
+                                                       fm * 16 + r, M, n0, f * 16 + 4 * q, cols, vec_ok);
+                }
+            });
+        }
+    }
+}
+
+// The last chunk of a run: slot I has U - 1 - I slots issued after it and nothing is refilled.
+template <int DT, int MB, int NFR, int U, int I>
+__device__ __forceinline__ void skinny_drain(const skinny_tile_state<NFR>& st, int c, int wave, int lane, const skinny_slot<NFR> (&ring)[U],
+                                             char* xring, v4f (&acc)[NFR][MB])
+{
+    if constexpr (I < U) {
+        skinny_mma<DT, MB, NFR, U - 1 - I>(st, c * U + I, wave, lane, ring[I], xring + I * (MB * 2048), acc);
+        __builtin_amdgcn_sched_barrier(0);
+        skinny_drain<DT, MB, NFR, U, I + 1>(st, c, wave, lane, ring, xring, acc);
+    }
+}
+
+// Processes slot `slot` and every following slot of this workgroup that holds a tile of the same
+// streaming class.  Returns the first slot it did not process.
+template <int DT, bool GATED, bool CHAIN, int CLS, int MB, int NFR, int U>
+__device__ __forceinline__ long skinny_run(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
+                                           const int32_t* __restrict__ order, long slot, long n_slots, long stride,
+                                           int out_dtype, char* lds, chain_ctx* chain)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    epara_tile tl = tiles[order[slot]];
+    epara_group_args ga = args[tl.group];
+    skinny_tile_state<NFR> cur, nxt;
+    skinny_setup<DT, GATED, MB, NFR, U>(cur, ga, tl.n0, lane);
+    skinny_slot<NFR> ring[U];
+    constexpr int XSLOT_BYTES = MB * 2048;
+    char* xring = lds + RING_LDS_OFFSET + wave * (U * XSLOT_BYTES);
+    static_assert(RING_LDS_OFFSET + 4 * U * XSLOT_BYTES <= LDS_BYTES, "activation rings do not fit");
+    // The rings overlay whatever used this part of the LDS before (a panel tile's epilogue, the
+    // rings of another streaming class: a run ends with every slot consumed, nothing in flight).
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) skinny_load<DT, MB, NFR>(cur, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
+    __builtin_amdgcn_sched_barrier(0);
+
+    for (;;) {
+        // What follows this tile in the workgroup's list (a list has no holes, so an idle slot ends
+        // it) is found by three dependent scalar loads: order -> tile -> group arguments.  Each
+        // link is issued after one chunk of the tile and read after the next, so that its latency
+        // passes while the wave waits for weights anyway instead of stopping the stream.
+        int t_next = -1, stage = 0;
+        bool have_next = false;
+        epara_tile tl_next = tl;
+        epara_group_args ga_next = ga;
+        auto advance = [&]() {
+            if (stage == 0)      { const long s1 = slot + stride; t_next = s1 < n_slots ? order[s1] : -1; }
+            else if (stage == 1) { if (t_next >= 0) tl_next = tiles[t_next]; }
+            else {
+                have_next = t_next >= 0 && tl_next.cls == CLS;
+                // in a chain the run ends before a tile that may have to wait for its input
+                if constexpr (CHAIN) have_next = have_next && (tl_next.group == tl.group || !chain_must_wait(*chain, tl_next.group));
+                if (have_next) ga_next = args[tl_next.group];
+            }
+            ++stage;
+        };
+        v4f acc[NFR][MB];
+#pragma unroll
+        for (int f = 0; f < NFR; ++f)
+#pragma unroll
+            for (int fm = 0; fm < MB; ++fm) acc[f][fm] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c + 1 < cur.n_chunks; ++c) {             // refill from this tile
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                skinny_mma<DT, MB, NFR, U - 1>(cur, c * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                skinny_load<DT, MB, NFR>(cur, (c + 1) * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (stage < 3) advance();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        while (stage < 3) advance();                             // short tiles: the rest of the chain at once
+        const long slot_next = have_next ? slot + stride : -1L;
+        const int c_last = cur.n_chunks - 1;
+        if (have_next) {                                         // last chunk: refill from the next tile
+            skinny_setup<DT, GATED, MB, NFR, U>(nxt, ga_next, tl_next.n0, lane);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                skinny_mma<DT, MB, NFR, U - 1>(cur, c_last * U + u, wave, lane, ring[u], xring + u * XSLOT_BYTES, acc);
+                __builtin_amdgcn_sched_barrier(0);
+                skinny_load<DT, MB, NFR>(nxt, u, wave, lane, ring[u], xring + u * XSLOT_BYTES);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {                                                 // nothing follows: the ring drains
+            skinny_drain<DT, MB, NFR, U, 0>(cur, c_last, wave, lane, ring, xring, acc);
+        }
+        skinny_finish<DT, GATED, MB, NFR, CHAIN>(ga, out_dtype, tl.n0, tl.cols, acc, wave, lane, lds);
+        if constexpr (CHAIN) chain_done(*chain, tl.group);
+        if (slot_next < 0) break;
+        slot = slot_next;
+        tl = tl_next;
+        ga = ga_next;
+        cur = nxt;
+    }
+    // first slot after this run: the next non-idle slot of this workgroup or the end
+    for (slot += stride; slot < n_slots && order[slot] < 0; slot += stride) {}
+    return slot;
+}
+
+}  // namespace
+
+#endif

@@ -1,17 +1,21 @@
 """Small driver for rocprofv3 runs: a few passes of one synthetic mix, then the plain copy kernel
 of known size whose HBM traffic calibrates the byte counters.
 
-    rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- python3 -m paper_2511_00603_amd.profile_driver 5 bf16 6
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 -m paper_2511_00603_amd.profile_driver 5 bf16 3
+    rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- python3 profile_driver.py 5 bf16 6
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 profile_driver.py 5 bf16 3
 """
 import sys
 
 import torch
 
-from workloads import make_mix
+import os
 
-from . import binding as B
-from .mixrun import StagedMix
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+import bench_probes as P
+from paper_2511_00603_amd import binding as B
+from paper_2511_00603_amd.mixrun import StagedMix
+from workloads import make_mix
 
 COPY_BYTES = 1 << 30
 
@@ -20,7 +24,7 @@ def batch_forming(mix, steps):
     """Gather, gather + dynamic E4M3 quantisation and scatter of the mix's requests (bf16 rows), `steps` times."""
     import numpy as np
     from workloads import casts
-    from . import runtime as R
+    from paper_2511_00603_amd import runtime as R
     dev = "cuda:0"
     reqs, batches, codes = [], [], []
     for svc in mix.services:
@@ -64,7 +68,7 @@ def main():
     src = torch.ones(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
     dst = torch.zeros(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
     for _ in range(2):
-        B.epara_probe_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream)
+        P.probe_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     print("profile_driver: mix %d %s, %d passes, copy probe %d bytes" % (idx, dtype or mix.dtype, steps, COPY_BYTES))
 

@@ -1,10 +1,10 @@
 """Turns rocprofv3 CSV output (kernel trace and counter collection of profile_driver runs) into the
 short text summaries kept under profiles/ and into profiles/traffic.txt.
 
-    python -m paper_2511_00603_amd.profile_summary kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt [LAUNCHES [PASSES [FIRST_PASS]]]
-    python -m paper_2511_00603_amd.profile_summary traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
-    python -m paper_2511_00603_amd.profile_summary report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
-    python -m paper_2511_00603_amd.profile_summary counters OUT WORKLOAD MIX DTYPE    (OUT/{sq,tcc}_counter_collection.csv)
+    python profile_summary.py kernels OUT/run_kernel_trace.csv "command" profiles/NAME.txt [LAUNCHES [PASSES [FIRST_PASS]]]
+    python profile_summary.py traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
+    python profile_summary.py report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
+    python profile_summary.py counters OUT WORKLOAD MIX DTYPE    (OUT/{sq,tcc}_counter_collection.csv)
 
 Per-launch figures: the launches of one pass alternate (launch 0, launch 1, ...), so dispatch i of
 grouped_kernel belongs to launch i mod L.  HBM traffic of a launch = counter value (KiB) x 1024 x
@@ -17,15 +17,15 @@ import os
 import statistics
 import sys
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-ROOT = os.path.dirname(HERE)
-KERNEL_SOURCE = os.path.join(HERE, "csrc", "epara_kernels.hip")
+ROOT = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(ROOT, "paper_2511_00603_amd", "csrc")
+KERNEL_SOURCES = [os.path.join(CSRC, f) for f in ("epara_device.h", "epara_panel.h", "epara_stream.h", "epara_grouped.h")]
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.txt")
 COPY_BYTES = 1 << 30
 
 
 def kernel_source_hash():
-    return hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:16]
+    return hashlib.sha256(b"".join(open(f, "rb").read() for f in KERNEL_SOURCES)).hexdigest()[:16]
 
 
 def _rows(path):
@@ -109,7 +109,7 @@ def lookup_traffic(workload, launch):
 def report(out_dir, workload, mix, dtype, launches_per_pass=2):
     """profiles/grouped_kernel_WORKLOAD.txt and the WORKLOAD entry of profiles/traffic.txt from the three
     runs of the profile driver (kernel trace with 8 passes, FETCH_SIZE and WRITE_SIZE with 4 passes each)."""
-    drv = "python3 -m paper_2511_00603_amd.profile_driver %s %s" % (mix, dtype)
+    drv = "python3 profile_driver.py %s %s" % (mix, dtype)
     txt = os.path.join(ROOT, "profiles", "grouped_kernel_%s.txt" % workload)
     kernels(os.path.join(out_dir, "run_kernel_trace.csv"),
             "rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- %s 8" % drv, txt, launches_per_pass)
@@ -153,7 +153,7 @@ def _per_launch(path, launches_per_pass):
 
 def counters(out_dir, workload, mix, dtype, launches_per_pass=2):
     """profiles/counters_WORKLOAD.txt: clocks, matrix-core busy share, LDS bank conflicts and L2 hit rate per launch."""
-    drv = "python3 -m paper_2511_00603_amd.profile_driver %s %s 4" % (mix, dtype)
+    drv = "python3 profile_driver.py %s %s 4" % (mix, dtype)
     sq = _per_launch(os.path.join(out_dir, "sq_counter_collection.csv"), launches_per_pass)
     tcc = _per_launch(os.path.join(out_dir, "tcc_counter_collection.csv"), launches_per_pass)
     L = ["rocprofv3 counter summary of grouped_kernel, per launch of a pass (medians over passes, first pass skipped)",

@@ -45,8 +45,8 @@ class Groups:
             X, W, b, act = sp["X"], sp["W"], sp.get("b"), sp.get("act", "none")
             M, K = X.shape
             N = W.shape[1]
-            sx = casts.e4m3_scale(X) if dtype_name == "fp8" else 1.0
-            sw = casts.e4m3_scale(W) if dtype_name == "fp8" else 1.0
+            sx = sp.get("s_x", casts.e4m3_scale(X)) if dtype_name == "fp8" else 1.0     # per-tensor scales: amax / 448
+            sw = sp.get("s_w", casts.e4m3_scale(W)) if dtype_name == "fp8" else 1.0     # unless the case fixes them
             xb, wb = to_bits(X, dtype_name, sx), to_bits(W, dtype_name, sw)
             self.bits.append({"X": xb, "W": wb, "b": b, "act": act, "s": sx * sw})
             dX = R.device_tensor_from_bits(xb, dt, DEV) if M else None

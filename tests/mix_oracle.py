@@ -17,11 +17,12 @@ def decode(bits, dtype_name, scale=1.0):
     return ref.e4m3_decode(bits, scale)
 
 
-def expected(mix, host_bits, dtype_name, rows=None, h_scales=None):
+def expected(mix, host_bits, dtype_name, rows=None, h_scales=None, calibrated=None):
     """-> list per launch of list of (service, label, Yref) in the launch/group order of StagedMix.
 
     rows: optional list (per service) of row index arrays; only those rows are evaluated.
-    h_scales: per-service s_h for the fp8 SwiGLU path.
+    h_scales: per-service s_h for the fp8 SwiGLU path; or pass an empty list as `calibrated`: s_h of every
+    service is then taken from the oracle's hidden activations (amax / 448) and appended to that list.
     """
     fp8 = dtype_name == "fp8"
     launches = []
@@ -34,8 +35,12 @@ def expected(mix, host_bits, dtype_name, rows=None, h_scales=None):
             X = decode(hb["X"][sel(g)], dtype_name)             # codes as values; scales applied below
             Wg, Wu, Wd = (decode(hb[k], dtype_name) for k in ("Wgate", "Wup", "Wdown"))
             if fp8:
-                sx, sg, su, sd, sh = hb["s_x"], hb["s_wgate"], hb["s_wup"], hb["s_wdown"], h_scales[g]
-                H, Y = ref.ffn_swiglu(X, Wg, Wu, Wd, s_gate=sx * sg, s_up=sx * su, s_down=sh * sd, h_scale=sh)
+                sx, sg, su, sd = hb["s_x"], hb["s_wgate"], hb["s_wup"], hb["s_wdown"]
+                H = ref.swiglu_hidden(X, Wg, Wu, sx * sg, sx * su)
+                if calibrated is not None:                      # static scale from the oracle's own hidden activations
+                    calibrated.append(float(np.abs(H).max()) / 448.0)
+                sh = calibrated[g] if calibrated is not None else h_scales[g]
+                H, Y = ref.ffn_swiglu_down(H, Wd, s_down=sh * sd, h_scale=sh)
             else:
                 H, Y = ref.ffn_swiglu(X, Wg, Wu, Wd)
             hs.append((g, "H", H))

@@ -166,8 +166,9 @@ def test_kernel_classes_and_packed_sizes():
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
     assert B.epara_workspace_bytes(_desc([(5, 8, 8)]), B.EPARA_BF16) == 0 and B.epara_workspace_bytes(_desc([]), 9) == -1
     assert B.epara_packed_weight_bytes(4096, 11008, B.EPARA_BF16) == 4096 * 11008 * 2
-    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_BF16) == 1 * 2 * 1024
-    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_FP8_E4M3) == 1024
+    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_BF16) == 1 * 4 * 1024          # 2 stages of K, padded to 4
+    assert B.epara_packed_weight_bytes(40, 10, B.EPARA_FP8_E4M3) == 4 * 1024
+    assert B.epara_packed_weight_bytes(160, 17, B.EPARA_BF16) == 2 * 8 * 1024        # 5 stages -> 8, 2 column blocks
     assert B.epara_packed_weight_bytes(3, 5, B.EPARA_F32) == 60
     assert B.epara_packed_weight_bytes(0, 5, B.EPARA_BF16) == -1 and B.epara_packed_weight_bytes(3, 5, 9) == -1
 
@@ -264,7 +265,7 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
     assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2000, 16, None) == B.EPARA_ERR_CAPACITY
     assert lib.epara_pack_weights(0x1000, 0, 8, B.EPARA_BF16, 0x2000, 1024, None) == B.EPARA_ERR_SHAPE
     assert lib.epara_pack_weights(0x1000, 8, 8, 7, 0x2000, 1024, None) == B.EPARA_ERR_DTYPE
-    assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2004, 1024, None) == B.EPARA_ERR_ALIGN
+    assert lib.epara_pack_weights(0x1000, 8, 8, B.EPARA_BF16, 0x2004, 4096, None) == B.EPARA_ERR_ALIGN
     assert B.epara_status_string(B.EPARA_ERR_ALIGN).startswith("pointer")
 
 
