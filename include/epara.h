@@ -16,9 +16,10 @@
  *   - plain C ABI; every entry point returns an epara_status (0 = EPARA_OK) unless noted;
  *     nothing aborts on bad input.
  *   - "h_" / "d_" prefixes say whether a pointer is host or device memory.
- *   - the caller owns every buffer and the stream; the library allocates no device memory,
- *     never synchronises and keeps no mutable global state.  Launch functions only
- *     enqueue work on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *   - the caller owns every buffer and the stream; the library allocates no device memory
+ *     and keeps no mutable global state.  Launch functions only enqueue work on `stream` (a
+ *     hipStream_t passed as void*; NULL = default stream) and never synchronise; the one call
+ *     that waits for the stream and copies to the host is epara_chain_status.
  *   - X_g and Y_g are dense row-major ([M,K] and [M,N]); device pointers must be 16-byte
  *     aligned and K*sizeof(element) must be a multiple of 16, and at most 8 MiB, for bf16/fp8
  *     inputs (ERR_ALIGN / ERR_SHAPE otherwise).
@@ -308,7 +309,8 @@ int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements
                        const epara_sim_request* requests, int64_t n_requests, const double* draws,
                        epara_sim_result* result);
 
-/* Group planning: the single-GPU part of the allocator's "parallel mode per task" decision.
+/* Group planning (Sec. 3.1: the allocator decides the parallel mode of each task; BS / MF fix the
+ * rows of a service's batch, MT puts the services on one GPU): the single-GPU part of that decision.
  *   row_off[g] = sum_{h<g} M_h ; x_off[g] = sum_{h<g} M_h K_h ; y_off[g] = sum_{h<g} M_h N_h
  *   (each G+1 entries; x_off / y_off are element offsets for callers that pack groups
  *   back to back), tile class of g = first class with M_g <= max_M, and the canonical tile
@@ -411,7 +413,10 @@ int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype);
 int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
                            void* d_packed, int64_t packed_bytes, void* stream);
 
-/* Y_g = act_g(s_g X_g W_g + b_g) for all groups of the launch, in one persistent kernel
+/* The MT operator of Sec. 3.1 on one GPU (several services with their own weights share it; here
+ * they share a launch), over batches formed by BS / MF; the weights are already resident (Sec. 3.3
+ * pre-placement, epara_pack_weights).
+ * Y_g = act_g(s_g X_g W_g + b_g) for all groups of the launch, in one persistent kernel
  * that walks the device tile table in the scheduled order; bias, activation, SwiGLU gating
  * and the output cast are fused in the epilogue.  Accumulation is fp32 in a fixed order
  * (bit-reproducible, independent of n_workgroups).
@@ -421,7 +426,9 @@ int32_t epara_pack_weights(const void* d_W, int32_t K, int32_t N, int32_t dtype,
 int32_t epara_grouped_forward(const epara_launch* launch, int32_t in_dtype, int32_t out_dtype,
                               void* stream);
 
-/* Y_g = (SiLU(X_g Wgate_g) * (X_g Wup_g)) Wdown_g for all services: phase `up` (gated
+/* Two dependent grouped launches of the same batches (Sec. 3.1: a batch crosses its service's layers
+ * as a whole; MT across the services):
+ * Y_g = (SiLU(X_g Wgate_g) * (X_g Wup_g)) Wdown_g for all services: phase `up` (gated
  * launch writing H in h_dtype) then phase `down` (reading H), enqueued back to back on
  * `stream`.  in_dtype BF16: h_dtype = out_dtype = BF16.  in_dtype FP8_E4M3: h_dtype =
  * FP8_E4M3 (codes sat(RNE(h / s_h))), out_dtype = BF16. */
@@ -452,7 +459,11 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
  * the same n_workgroups, which must not exceed what the GPU keeps resident at once (a waiting
  * workgroup must never keep the one it waits for from running) -> ERR_SHAPE; a wait must name a
  * counter of the phase before, with need = that group's tile count, and the waiting group's X must
- * be that group's Y with matching shape -> ERR_SHAPE; workspace too small -> ERR_CAPACITY.
+ * be that group's Y with matching shape -> ERR_SHAPE; a tensor that is waited for must own its cache
+ * lines (consumers invalidate nothing after a wait, so a line it shared with another tensor of the
+ * chain could be cached before it was written): it must start on a 128-byte boundary, and no other
+ * tensor of the chain (X, Y, weights, bias of any group) may overlap the rest of its last 128-byte
+ * line -> ERR_ALIGN; workspace too small -> ERR_CAPACITY.
  * A wait polls at most spin_limit times (0 = the default, some seconds); if it runs out the kernel
  * sets the error flag, goes on without the data and still terminates, and the outputs of the chain
  * are invalid: read the flag with epara_chain_status.  Two chains that use one workspace must not

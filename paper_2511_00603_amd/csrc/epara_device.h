@@ -249,9 +249,12 @@ __device__ __forceinline__ void chain_flush(chain_ctx& c)
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            if (c.pend_n[i] > 0)
-                __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group[i],
-                                       static_cast<uint32_t>(c.pend_n[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (c.pend_n[i] > 0) {
+                // the returned value is asked for so that the wave can wait for the add itself (chain_exit)
+                const uint32_t before = __hip_atomic_fetch_add(c.ws + CHAIN_HEADER_WORDS + c.counter_base + c.pend_group[i],
+                                                               static_cast<uint32_t>(c.pend_n[i]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("" :: "v"(before));
+            }
     }
     c.pend_n[0] = c.pend_n[1] = 0;
 }
@@ -307,8 +310,11 @@ __device__ __forceinline__ void chain_wait(chain_ctx& c, int group)
 __device__ __forceinline__ void chain_exit(chain_ctx& c, int n_counters)
 {
     chain_flush(c);
+    wait_vmcnt<0>();                                             // my counter adds have been performed (they return a value)
     __syncthreads();
     if (threadIdx.x == 0) {
+        // nothing of this workgroup is still on its way to a counter when it is counted as gone, so the
+        // zeroing below cannot be overtaken by a late add
         const uint32_t left = __hip_atomic_fetch_add(c.ws + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (left + 1 == gridDim.x) {
             for (int i = 0; i < n_counters; ++i)

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "epara.h"
@@ -16,6 +17,7 @@ constexpr int N_STREAM_CLASSES = 3;
 constexpr int CHAIN_HEADER_WORDS = 4;     // error flag, exit count (the kernels use the same layout)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t dtype_bytes(int32_t dtype) { return dtype == EPARA_F32 ? 4 : (dtype == EPARA_BF16 ? 2 : 1); }
 
 // Every tile must be exactly what epara_plan_groups produces from one of the kernel class tables.
 int32_t check_tiles(const epara_launch* L, int32_t in_dtype, int narrow)
@@ -184,12 +186,13 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
     return e == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 
-int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
-                            void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream)
+// n_counters_out: when given, only validates and reports the number of counters the chain needs.
+static int32_t chain_impl(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                          void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream, int32_t* n_counters_out)
 {
-    if (!phases || !d_workspace) return EPARA_ERR_NULL;
+    if (!phases || (!d_workspace && !n_counters_out)) return EPARA_ERR_NULL;
     if (n_phases < 1 || n_phases > EPARA_MAX_CHAIN_PHASES) return EPARA_ERR_SHAPE;
-    if (!aligned16(d_workspace)) return EPARA_ERR_ALIGN;
+    if (d_workspace && !aligned16(d_workspace)) return EPARA_ERR_ALIGN;
     epara_chain_scalars S;
     std::memset(&S, 0, sizeof S);
     const epara_group_args* d_args[EPARA_MAX_CHAIN_PHASES] = {};
@@ -199,6 +202,8 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
     int gated[EPARA_MAX_CHAIN_PHASES] = {};
     int32_t n_counters = 0, n_workgroups = 0;
     bool any = false;
+    struct span { uintptr_t at; int64_t bytes; };
+    std::vector<span> produced;               // the tensors some group waits for
     for (int32_t p = 0; p < n_phases; ++p) {
         const epara_chain_phase& ph = phases[p];
         const epara_launch* L = ph.launch;
@@ -234,6 +239,7 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
                 if (Lp->n_tiles == 0) return EPARA_ERR_SHAPE;
                 const epara_group_args& b = Lp->h_args[q];
                 if (a.X != b.Y || a.M != b.M || a.K != b.N) return EPARA_ERR_SHAPE;
+                produced.push_back({reinterpret_cast<uintptr_t>(b.Y), static_cast<int64_t>(b.M) * b.N * dtype_bytes(prev.out_dtype)});
             }
             d_waits[p] = ph.d_waits;
         }
@@ -241,10 +247,36 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
         S.n_slots[p] = L->n_tiles > 0 ? L->n_slots : 0;
         S.out_dtype[p] = ph.out_dtype; S.narrow[p] = narrow; S.counter_base[p] = ph.counter_base;
     }
+    // A produced tensor must own its cache lines: a consumer invalidates nothing after its wait, so a line
+    // that also holds bytes of another tensor of the chain could be cached (by a read of that tensor)
+    // before the produced tensor was written.  It must start on a line and nothing else may begin in
+    // the rest of its last line.
+    for (const span& y : produced) {
+        if (y.at % 128 != 0) return EPARA_ERR_ALIGN;
+        const uintptr_t end = y.at + static_cast<uintptr_t>(y.bytes), line_end = (end + 127) / 128 * 128;
+        for (int32_t p = 0; p < n_phases; ++p) {
+            const epara_launch* L = phases[p].launch;
+            for (int32_t g = 0; g < L->G && L->n_tiles > 0; ++g) {
+                const epara_group_args& a = L->h_args[g];
+                if (a.M == 0) continue;
+                const span others[5] = {
+                    {reinterpret_cast<uintptr_t>(a.X), static_cast<int64_t>(a.M) * a.K * dtype_bytes(in_dtype)},
+                    {reinterpret_cast<uintptr_t>(a.Y), static_cast<int64_t>(a.M) * a.N * dtype_bytes(phases[p].out_dtype)},
+                    {reinterpret_cast<uintptr_t>(a.W), epara_packed_weight_bytes(a.K, a.N, in_dtype)},
+                    {reinterpret_cast<uintptr_t>(a.W2), a.W2 ? epara_packed_weight_bytes(a.K, a.N, in_dtype) : 0},
+                    {reinterpret_cast<uintptr_t>(a.bias), a.bias ? static_cast<int64_t>(a.N) * 4 : 0}};
+                for (const span& o : others) {
+                    if (o.bytes <= 0 || o.at == y.at) continue;
+                    if (o.at < line_end && o.at + static_cast<uintptr_t>(o.bytes) > end) return EPARA_ERR_ALIGN;
+                }
+            }
+        }
+    }
     // the kernels exist for chains without gating and for the two phases of a SwiGLU FFN
     bool ffn = false;
     for (int32_t p = 0; p < n_phases; ++p) ffn = ffn || gated[p];
     if (ffn && !(n_phases == 2 && gated[0] && !gated[1])) return EPARA_ERR_DTYPE;
+    if (n_counters_out) { *n_counters_out = n_counters; return EPARA_OK; }
     if (workspace_bytes < epara_chain_workspace_bytes(n_counters)) return EPARA_ERR_CAPACITY;
     if (!any) return EPARA_OK;
     S.ws = static_cast<uint32_t*>(d_workspace);
@@ -275,6 +307,12 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
     }
     if (static_cast<int64_t>(n_workgroups) > resident) return EPARA_ERR_SHAPE;
     return fn(T, S, static_cast<unsigned>(n_workgroups), st, nullptr) == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                            void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream)
+{
+    return chain_impl(phases, n_phases, in_dtype, d_workspace, workspace_bytes, spin_limit, stream, nullptr);
 }
 
 int32_t epara_chain_status(void* d_workspace, void* stream, int32_t* flag)

@@ -16,8 +16,9 @@ namespace {
 // weight column blocks: 32 / 64 / 128 output columns, or for gated groups NFR/2 gate blocks and
 // the matching NFR/2 up blocks (16 / 32 / 64 hidden columns).  K is walked in steps of two packed
 // fragments (128 bytes of every activation row, so a row's cache line is used whole); wave w takes
-// the steps p = w, w+4, ....  The four partial sums meet in LDS and are added in wave order: the
-// result does not depend on timing.
+// a contiguous quarter of the steps (a wave then reads one sequential stream per column block, which
+// the memory system serves faster than four waves interleaving 2-KiB pieces).  The four partial sums
+// meet in LDS and are added in wave order: the result does not depend on timing.
 //
 // Consecutive tiles of one class that a workgroup owns are processed as one software-pipelined
 // stream: a ring of U slots per wave (weights in registers, activations in LDS) stays full across
@@ -33,6 +34,7 @@ struct skinny_tile_state {
     uint32_t xoff[8];      // per lane, per direct-load instruction j < 2 MB: byte offset of my row + my chunk's 16 c
     int KS, K;             // fragments along K, K
     int n_chunks;          // chunks of U steps per wave
+    int spw;               // steps per wave: wave w owns the steps w * spw .. (w + 1) * spw - 1
 };
 
 // Activations of a step (two fragments = 128 bytes of K for MB x 16 rows) go through a per-wave LDS
@@ -53,7 +55,8 @@ __device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const e
     st.K = K;
     st.KS = KS;
     const int steps = (KS + 1) >> 1;                             // two fragments per step
-    st.n_chunks = (((steps + 3) >> 2) + U - 1) / U;
+    st.spw = (steps + 3) >> 2;
+    st.n_chunks = (st.spw + U - 1) / U;
 #pragma unroll
     for (int f = 0; f < NFR; ++f) {
         // gated: fragments 0 .. NFR/2-1 are gate blocks, the rest the same blocks of the up matrix
@@ -83,7 +86,7 @@ __device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, in
     ldsptr xslot = (ldsptr)xslot_generic;
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
-    const int p = wave + 4 * i;                                  // step: fragments 2p and 2p+1
+    const int p = wave * st.spw + min(i, st.spw - 1);            // step: fragments 2p and 2p+1 (padding repeats the last step)
     // activations first: loads complete in issue order, so once the weights of this slot are in
     // their registers the slot's LDS image is complete too
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(st.x), 0, -1, 0x00020000);
@@ -130,7 +133,7 @@ __device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int
             x[e][fm] = *reinterpret_cast<lds_v4i>(xslot + (fm * 16 + r) * 128 + (((e * 4 + q) ^ ((r >> 1) & 7)) << 4));
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-        if (2 * (wave + 4 * i) + e < st.KS) {
+        if (i < st.spw && 2 * (wave * st.spw + i) + e < st.KS) {
 #pragma unroll
             for (int f = 0; f < NFR; ++f)
 #pragma unroll

@@ -395,3 +395,42 @@ def test_chain_entry_point_validates_before_touching_the_device():
     assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_OK          # nothing to run
     assert L.epara_chain_workspace_init(None, 256, None) == B.EPARA_ERR_NULL
     assert L.epara_chain_status(None, None, None) == B.EPARA_ERR_NULL
+
+
+def test_chain_rejects_produced_tensors_that_do_not_own_their_cache_lines():
+    """A consumer invalidates nothing after its wait, so a tensor that is waited for must start on a 128-byte
+    line and nothing else of the chain may overlap the rest of its last line.  Host-side validation only:
+    every case is rejected before anything is enqueued (K = N = 72 bf16, M = 3 is 432 bytes, as when groups
+    are packed back to back with the planner's y_off)."""
+    L = B.lib()
+
+    def chain(y_a, y_b, x_b_of):
+        a0 = np.zeros(2, dtype=B.GROUP_ARGS)                  # phase 0: two groups that write Y_A, Y_B
+        a1 = np.zeros(2, dtype=B.GROUP_ARGS)                  # phase 1: each reads one of them
+        for g, y in enumerate((y_a, y_b)):
+            a0[g]["X"], a0[g]["W"], a0[g]["Y"] = 0x100000 + 0x1000 * g, 0x200000 + 0x10000 * g, y
+            a0[g]["M"], a0[g]["K"], a0[g]["N"], a0[g]["scale"] = 3, 72, 72, 1.0
+            a1[g]["X"], a1[g]["W"], a1[g]["Y"] = x_b_of[g], 0x300000 + 0x10000 * g, 0x400000 + 0x1000 * g
+            a1[g]["M"], a1[g]["K"], a1[g]["N"], a1[g]["scale"] = 3, 72, 72, 1.0
+        classes, _ = B.epara_kernel_classes(B.EPARA_BF16, False)
+        keep, phases = [], (B.ChainPhase * 2)()
+        for p, a in enumerate((a0, a1)):
+            d = np.zeros(2, dtype=B.GROUP_DESC)
+            for f in ("M", "K", "N"):
+                d[f] = a[f]
+            _, _, _, tiles = B.epara_plan_groups(d, classes)
+            launch = _host_launch(a, tiles, 8 * len(tiles), 8)
+            keep += [a, tiles, launch]
+            phases[p].launch = ctypes.pointer(launch)
+            phases[p].out_dtype, phases[p].counter_base = B.EPARA_BF16, 2 * p
+        waits = B.epara_chain_waits(keep[1], 2, 0, [0, 1])
+        keep.append(waits)
+        phases[1].h_waits, phases[1].d_waits = waits.ctypes.data, 0x5000
+        return L.epara_grouped_chain(ctypes.addressof(phases), 2, B.EPARA_BF16, ctypes.c_void_p(0x6000), 16, 0, None), keep
+
+    # Y_B begins in the last line of Y_A (432 bytes after it): rejected; so is a produced tensor that starts off a line
+    assert chain(0x500000, 0x500000 + 432, [0x500000, 0x500000 + 432])[0] == B.EPARA_ERR_ALIGN
+    assert chain(0x500000 + 64, 0x510000, [0x500000 + 64, 0x510000])[0] == B.EPARA_ERR_ALIGN
+    # tensors on lines of their own pass this check and reach the next one (the workspace given here is too
+    # small on purpose, so that nothing is ever enqueued with these made-up addresses)
+    assert chain(0x500000, 0x510000, [0x500000, 0x510000])[0] == B.EPARA_ERR_CAPACITY
