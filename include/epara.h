@@ -17,7 +17,8 @@
  *     nothing aborts on bad input.
  *   - "h_" / "d_" prefixes say whether a pointer is host or device memory.
  *   - the caller owns every buffer and the stream; the library allocates no device memory
- *     and keeps no mutable global state.  Launch functions only enqueue work on `stream` (a
+ *     and keeps no mutable global state (one exception, stated there: the scratch array of
+ *     epara_grouped_chain_static).  Launch functions only enqueue work on `stream` (a
  *     hipStream_t passed as void*; NULL = default stream) and never synchronise; the one call
  *     that waits for the stream and copies to the host is epara_chain_status.
  *   - X_g and Y_g are dense row-major ([M,K] and [M,N]); device pointers must be 16-byte
@@ -470,6 +471,21 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
  * overlap in time. */
 int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
                             void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream);
+
+/* epara_grouped_chain for callers that cannot allocate device memory or bring a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same chain, the
+ * same kernels and results, with the completion counters in a device array that is part of the
+ * library (EPARA_STATIC_CHAIN_COUNTERS counters, 16 KiB; every GPU the library runs on holds its copy
+ * until the process ends).  Enqueues, on `stream`: a small kernel that zeroes the header and the
+ * counters the chain uses (the array keeps what the last call left), the chain kernel, and, if d_flag
+ * is given, a kernel that copies the error flag (0 = every wait ended normally) to *d_flag (device
+ * memory of the caller, 4-byte aligned).  Calls no allocation routine and never synchronises.
+ * Errors as for epara_grouped_chain; a chain with more than EPARA_STATIC_CHAIN_COUNTERS counters
+ * (the sum of G over its phases) -> ERR_CAPACITY.  Every call on a GPU shares that GPU's array: two
+ * calls that overlap in time on one GPU (different streams) race and their results are undefined. */
+#define EPARA_STATIC_CHAIN_COUNTERS 4092
+int32_t epara_grouped_chain_static(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                                   uint32_t spin_limit, int32_t* d_flag, void* stream);
 
 /* Waits for `stream`, then *flag = the workspace's error flag (0 = every wait of every chain since
  * the last call ended normally) and clears it. */

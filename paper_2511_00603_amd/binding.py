@@ -36,6 +36,7 @@ CHAIN_WAIT = np.dtype([("counter", "<i4"), ("need", "<i4")])
 SIM_REQUEST = np.dtype([("arrival_us", "<i8"), ("slo_us", "<i8"), ("service", "<i4"), ("origin", "<i4"), ("frames", "<i4"), ("reserved", "<i4")])
 assert SIM_REQUEST.itemsize == 32
 EPARA_MAX_CHAIN_PHASES = 4
+EPARA_STATIC_CHAIN_COUNTERS = 4092
 assert CHAIN_WAIT.itemsize == 8
 assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
 assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
@@ -143,8 +144,9 @@ def lib():
         L.epara_chain_workspace_init.argtypes = [vp, i64, vp]
         L.epara_grouped_chain.argtypes = [vp, i32, i32, vp, i64, ctypes.c_uint32, vp]
         L.epara_chain_status.argtypes = [vp, vp, vp]
+        L.epara_grouped_chain_static.argtypes = [vp, i32, i32, ctypes.c_uint32, vp, vp]
         for name in ("epara_schedule_chain", "epara_chain_waits", "epara_chain_workspace_init", "epara_grouped_chain",
-                     "epara_chain_status"):
+                     "epara_chain_status", "epara_grouped_chain_static"):
             getattr(L, name).restype = i32
         L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
         L.epara_packed_weight_bytes.argtypes = [i32, i32, i32]
@@ -382,6 +384,12 @@ def epara_grouped_chain(phases, in_dtype, d_workspace, workspace_bytes, stream, 
     """phases: a ctypes array of ChainPhase (kept alive by the caller)."""
     _check(lib().epara_grouped_chain(ctypes.addressof(phases), len(phases), int(in_dtype), int(d_workspace),
                                      int(workspace_bytes), int(spin_limit), stream), "epara_grouped_chain")
+
+
+def epara_grouped_chain_static(phases, in_dtype, stream, spin_limit=0, d_flag=0):
+    """The chain on the library's own scratch array (no workspace argument).  d_flag: device address of an int32 or 0."""
+    _check(lib().epara_grouped_chain_static(ctypes.addressof(phases), len(phases), int(in_dtype), int(spin_limit),
+                                            int(d_flag) or None, stream), "epara_grouped_chain_static")
 
 
 def epara_chain_status(d_workspace, stream):

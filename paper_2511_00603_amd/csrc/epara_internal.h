@@ -40,6 +40,7 @@ EPARA_HIDDEN hipError_t epara_chain_fp8_ffn(const epara_chain_tables&, const epa
 EPARA_HIDDEN hipError_t epara_chain_f32(const epara_chain_tables&, const epara_chain_scalars&, unsigned grid, hipStream_t, int64_t* resident);
 
 EPARA_HIDDEN hipError_t epara_enqueue_fill_words(uint32_t* p, long n, uint32_t v, hipStream_t);
+EPARA_HIDDEN hipError_t epara_enqueue_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t);
 EPARA_HIDDEN hipError_t epara_enqueue_pack(int esz, const char* W, int K, int N, char* out, long n_chunks, hipStream_t);
 
 #endif

@@ -36,6 +36,8 @@ __global__ void fill_words_kernel(uint32_t* p, long n, uint32_t v)
     for (long i = static_cast<long>(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += static_cast<long>(gridDim.x) * blockDim.x) p[i] = v;
 }
 
+__global__ void copy_word_kernel(const uint32_t* src, uint32_t* dst) { *dst = *src; }
+
 // One 16-byte chunk of the packed weights per thread.
 template <int ESZ>
 __global__ void pack_kernel(const char* __restrict__ W, int K, int N, char* __restrict__ out, long n_chunks)
@@ -94,6 +96,12 @@ hipError_t epara_chain_f32(const epara_chain_tables& T, const epara_chain_scalar
 hipError_t epara_enqueue_fill_words(uint32_t* p, long n, uint32_t v, hipStream_t stream)
 {
     hipLaunchKernelGGL(fill_words_kernel, dim3(static_cast<unsigned>(n < 65536 ? (n + 255) / 256 : 256)), dim3(256), 0, stream, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t epara_enqueue_copy_word(const uint32_t* src, uint32_t* dst, hipStream_t stream)
+{
+    hipLaunchKernelGGL(copy_word_kernel, dim3(1), dim3(1), 0, stream, src, dst);
     return hipGetLastError();
 }
 

@@ -315,6 +315,49 @@ int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, i
     return chain_impl(phases, n_phases, in_dtype, d_workspace, workspace_bytes, spin_limit, stream, nullptr);
 }
 
+// ---- the same chain on the library's own scratch (for callers that cannot allocate)
+//
+// The completion counters live in a file-scope device array.  Its name is only a host-side stand-in:
+// the address of each GPU's own copy is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) uint32_t scratch[CHAIN_HEADER_WORDS + EPARA_STATIC_CHAIN_COUNTERS];
+
+static int32_t scratch_address(uint32_t** out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static uint32_t* address[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return EPARA_ERR_HIP;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return EPARA_ERR_HIP;
+        address[dev] = static_cast<uint32_t*>(p);
+    }
+    *out = address[dev];
+    return EPARA_OK;
+}
+
+int32_t epara_grouped_chain_static(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
+                                   uint32_t spin_limit, int32_t* d_flag, void* stream)
+{
+    int32_t n_counters = 0;
+    if (int32_t st = chain_impl(phases, n_phases, in_dtype, nullptr, 0, spin_limit, stream, &n_counters)) return st;
+    if (n_counters > EPARA_STATIC_CHAIN_COUNTERS) return EPARA_ERR_CAPACITY;
+    if (d_flag && (reinterpret_cast<uintptr_t>(d_flag) & 3u)) return EPARA_ERR_ALIGN;
+    uint32_t* ws = nullptr;
+    if (int32_t st = scratch_address(&ws)) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();
+    // the array keeps what the last call left (an error flag of a wait that ran out): start from zero
+    const long words = CHAIN_HEADER_WORDS + n_counters;
+    if (epara_enqueue_fill_words(ws, words, 0u, hs) != hipSuccess) return EPARA_ERR_HIP;
+    if (int32_t st = chain_impl(phases, n_phases, in_dtype, ws, epara_chain_workspace_bytes(EPARA_STATIC_CHAIN_COUNTERS), spin_limit, stream, nullptr))
+        return st;
+    if (d_flag && epara_enqueue_copy_word(ws, reinterpret_cast<uint32_t*>(d_flag), hs) != hipSuccess) return EPARA_ERR_HIP;
+    return EPARA_OK;
+}
+
 int32_t epara_chain_status(void* d_workspace, void* stream, int32_t* flag)
 {
     if (!d_workspace || !flag) return EPARA_ERR_NULL;

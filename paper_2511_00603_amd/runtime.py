@@ -244,6 +244,12 @@ def grouped_chain(plan, stream=None, spin_limit=0):
                           current_stream_handle() if stream is None else stream, spin_limit)
 
 
+def grouped_chain_static(plan, stream=None, spin_limit=0, d_flag=None):
+    """The same chain with the counters in the library's own scratch array (nothing is allocated)."""
+    B.epara_grouped_chain_static(plan.c, plan.in_dtype, current_stream_handle() if stream is None else stream, spin_limit,
+                                 0 if d_flag is None else d_flag.data_ptr())
+
+
 def chain_status(plan, stream=None):
     """Synchronises; 0 = every wait of the chains run on this plan's workspace ended normally."""
     return B.epara_chain_status(plan.d_workspace.data_ptr(), current_stream_handle() if stream is None else stream)
