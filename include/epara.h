@@ -271,7 +271,7 @@ typedef struct {
     int32_t service;           /* l */
     int32_t origin;            /* n */
     int32_t frames;            /* >= 1: it occupies an instance for frames * c_ln microseconds */
-    int32_t reserved;
+    int32_t fps_milli;         /* 0: latency-sensitive; > 0: frequency-sensitive, 1000 * the frame rate its SLO asks for */
 } epara_sim_request;
 
 typedef struct {
@@ -285,9 +285,19 @@ typedef struct {
 } epara_sim_config;
 
 typedef struct {
-    double  satisfied;         /* phi(Theta): requests served within their SLO */
+    double  satisfied;         /* phi(Theta): requests served within their SLO; frames of frequency-sensitive requests
+                                  count in proportion to the achieved rate (Sec. 3.3) */
     int64_t local, offloaded, timeout, offload_exceeded, insufficient;   /* handler decisions taken */
 } epara_sim_result;
+
+/* The lookup table c_ln of Sec. 3.3 / Sec. 5 from measured passes: service l was measured on the
+ * reference GPU at ms_per_pass[l] milliseconds for a pass that serves requests_per_pass[l] requests
+ * (what bench.py reports per mix), and server n runs at server_speed[n] times the reference GPU's
+ * speed (1 = the same GPU; <= 0: it cannot run services).  compute_us[l * n_servers + n] =
+ * ceil(1000 * ms_per_pass[l] / requests_per_pass[l] / server_speed[n]), at least 1; 0 where the server
+ * cannot run it.  ERR_NULL; ERR_SHAPE for counts < 0, a time <= 0 or a request count <= 0. */
+int32_t epara_compute_table(const double* ms_per_pass, const int32_t* requests_per_pass, int32_t n_services,
+                            const double* server_speed, int32_t n_servers, int64_t* compute_us);
 
 /* phi(Theta) of Eq. "optimal" for the placement list placements[0..n) (id = l * n_servers + n, one
  * service instance per entry, repeats = replicas), by replaying the period's requests through the
@@ -295,7 +305,11 @@ typedef struct {
  * come from the table (Sec. 3.3: c_ln; Sec. 5: lookup tables indexed by GPU and service).  Model:
  *   - an instance serves one request at a time in the order they were bound to it;
  *   - "locally sufficient" = the instance of (l, n) that is free first finishes the request by its
- *     deadline; the request is bound to it at once and counts as satisfied;
+ *     deadline; the request is bound to it at once and counts as one satisfied request;
+ *   - a frequency-sensitive request (fps_milli > 0) is a stream of `frames` frames, each counting as a
+ *     request (Sec. 3.3: 120 frames wanted at 60 fps, served at 30 fps, count 120 * 30 / 60 = 60): it is
+ *     locally sufficient wherever an instance of (l, n) exists, is bound to the one that is free first, and
+ *     adds frames * min(1, achieved / required) with achieved = frames * 1e6 / (finish - arrival_us) per second;
  *   - every sync_delay_us = t, at time j*t, each server publishes per service its completions in
  *     ((j-1)t, jt] and when its first instance is free; at time `now` the others know snapshot
  *     J = floor(now / t) - 1 (J < 1: nothing yet, zeros): theoretical goodput = instances * 1e6 / c_lm,
@@ -305,7 +319,7 @@ typedef struct {
  * Events are handled in (time, sequence) order; sequence = request index for arrivals from users,
  * then in order of creation for offloaded arrivals.  Requests need not be sorted.
  * Errors: ERR_NULL; ERR_SHAPE for counts <= 0 (servers, services, t), negative counts, ids, frames < 1
- * or a draw outside [0, 1). */
+ * a negative fps_milli or a draw outside [0, 1). */
 int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements, int32_t n_placements,
                        const epara_sim_request* requests, int64_t n_requests, const double* draws,
                        epara_sim_result* result);

@@ -33,7 +33,7 @@ FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "
                      ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
 SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<i8"), ("first_chunk", "<i8"), ("group", "<i4"), ("reserved", "<i4")])
 CHAIN_WAIT = np.dtype([("counter", "<i4"), ("need", "<i4")])
-SIM_REQUEST = np.dtype([("arrival_us", "<i8"), ("slo_us", "<i8"), ("service", "<i4"), ("origin", "<i4"), ("frames", "<i4"), ("reserved", "<i4")])
+SIM_REQUEST = np.dtype([("arrival_us", "<i8"), ("slo_us", "<i8"), ("service", "<i4"), ("origin", "<i4"), ("frames", "<i4"), ("fps_milli", "<i4")])
 assert SIM_REQUEST.itemsize == 32
 EPARA_MAX_CHAIN_PHASES = 4
 EPARA_STATIC_CHAIN_COUNTERS = 4092
@@ -148,6 +148,8 @@ def lib():
         for name in ("epara_schedule_chain", "epara_chain_waits", "epara_chain_workspace_init", "epara_grouped_chain",
                      "epara_chain_status", "epara_grouped_chain_static"):
             getattr(L, name).restype = i32
+        L.epara_compute_table.argtypes = [vp, vp, i32, vp, i32, vp]
+        L.epara_compute_table.restype = i32
         L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
         L.epara_packed_weight_bytes.argtypes = [i32, i32, i32]
         L.epara_packed_weight_bytes.restype = i64
@@ -325,6 +327,23 @@ def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups,
 def epara_workspace_bytes(groups, in_dtype):
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
     return int(lib().epara_workspace_bytes(_ptr(groups), len(groups), int(in_dtype)))
+
+
+def epara_compute_table(ms_per_pass, requests_per_pass, server_speed):
+    """c_ln [n_services, n_servers] in microseconds per request from measured passes (see the header)."""
+    ms = np.ascontiguousarray(ms_per_pass, dtype=np.float64)
+    rq = np.ascontiguousarray(requests_per_pass, dtype=np.int32)
+    sp = np.ascontiguousarray(server_speed, dtype=np.float64)
+    out = np.zeros((len(ms), len(sp)), dtype=np.int64)
+    _check(lib().epara_compute_table(_ptr(ms) if len(ms) else None, _ptr(rq) if len(rq) else None, len(ms),
+                                     _ptr(sp) if len(sp) else None, len(sp), _ptr(out) if out.size else None), "epara_compute_table")
+    return out
+
+
+def compute_table_from_bench_line(line, mix_keys, server_speed):
+    """The same from one JSON line of bench.py: service l is the mix named mix_keys[l] (a key of line["mixes"])."""
+    mixes = line["mixes"]
+    return epara_compute_table([mixes[k]["ms_per_step"] for k in mix_keys], [mixes[k]["requests"] for k in mix_keys], server_speed)
 
 
 def epara_simulate(n_servers, n_services, compute_us, hop_us, sync_delay_us, max_offload, placements, requests, draws):

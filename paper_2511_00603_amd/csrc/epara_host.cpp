@@ -243,6 +243,28 @@ int64_t epara_inter_request_count(int64_t batch_size, int64_t max_inter_frame_co
     return batch_size / max_inter_frame_count;
 }
 
+int32_t epara_compute_table(const double* ms_per_pass, const int32_t* requests_per_pass, int32_t n_services,
+                            const double* server_speed, int32_t n_servers, int64_t* compute_us)
+{
+    if (n_services < 0 || n_servers < 0) return EPARA_ERR_SHAPE;
+    if (n_services == 0 || n_servers == 0) return EPARA_OK;
+    if (!ms_per_pass || !requests_per_pass || !server_speed || !compute_us) return EPARA_ERR_NULL;
+    for (int32_t l = 0; l < n_services; ++l)
+        if (!(ms_per_pass[l] > 0.0) || requests_per_pass[l] <= 0) return EPARA_ERR_SHAPE;
+    for (int32_t l = 0; l < n_services; ++l)
+        for (int32_t n = 0; n < n_servers; ++n) {
+            int64_t us = 0;
+            if (server_speed[n] > 0.0) {
+                const double exact = 1000.0 * ms_per_pass[l] / static_cast<double>(requests_per_pass[l]) / server_speed[n];
+                us = static_cast<int64_t>(exact);
+                if (static_cast<double>(us) < exact) ++us;
+                if (us < 1) us = 1;
+            }
+            compute_us[static_cast<size_t>(l) * n_servers + n] = us;
+        }
+    return EPARA_OK;
+}
+
 int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements, int32_t n_placements,
                        const epara_sim_request* requests, int64_t n_requests, const double* draws,
                        epara_sim_result* result)
@@ -257,7 +279,7 @@ int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements
         if (placements[i] < 0 || placements[i] >= static_cast<int64_t>(L) * N) return EPARA_ERR_SHAPE;
     for (int64_t r = 0; r < n_requests; ++r) {
         const epara_sim_request& q = requests[r];
-        if (q.service < 0 || q.service >= L || q.origin < 0 || q.origin >= N || q.frames < 1 || q.slo_us < 0 || q.arrival_us < 0)
+        if (q.service < 0 || q.service >= L || q.origin < 0 || q.origin >= N || q.frames < 1 || q.slo_us < 0 || q.arrival_us < 0 || q.fps_milli < 0)
             return EPARA_ERR_SHAPE;
         for (int32_t k = 0; k < max_off; ++k) {
             const double u = draws[r * max_off + k];
@@ -298,7 +320,7 @@ int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements
             for (size_t i = 1; i < here.free.size(); ++i)
                 if (here.free[i] < here.free[slot]) slot = static_cast<int32_t>(i);
             finish = std::max(now, here.free[slot]) + q.frames * c_here;
-            local_ok = finish <= deadline;
+            local_ok = finish <= deadline || q.fps_milli > 0;    // a stream is taken at whatever rate the instance gives
         }
         const int64_t J = now / t - 1;
         for (int32_t m = 0; m < N; ++m) {
@@ -329,7 +351,13 @@ int32_t epara_simulate(const epara_sim_config* config, const int32_t* placements
             here.log.push_back({now, *std::min_element(here.free.begin(), here.free.end())});
             here.done.push_back({(finish + t - 1) / t, 1});
             ++out.local;
-            out.satisfied += 1.0;
+            if (q.fps_milli > 0) {                               // frames count, in proportion to the achieved rate
+                const double achieved = static_cast<double>(q.frames) * 1e6 / static_cast<double>(finish - q.arrival_us);
+                const double share = achieved / (static_cast<double>(q.fps_milli) / 1000.0);
+                out.satisfied += static_cast<double>(q.frames) * (share < 1.0 ? share : 1.0);
+            } else {
+                out.satisfied += 1.0;
+            }
             break;
         }
         case EPARA_HANDLE_OFFLOAD: {

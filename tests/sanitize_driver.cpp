@@ -116,7 +116,7 @@ int main()
         epara_sim_config cfg = {c, 300, 2000, S, L, 2, 0};
         std::vector<epara_sim_request> reqs(400);
         std::vector<double> draws(reqs.size() * 2);
-        for (auto& q : reqs) { q.arrival_us = rnd(0, 200000); q.slo_us = rnd(1000, 20000); q.service = rnd(0, L - 1); q.origin = rnd(0, S - 1); q.frames = rnd(1, 3); q.reserved = 0; }
+        for (auto& q : reqs) { q.arrival_us = rnd(0, 200000); q.slo_us = rnd(1000, 20000); q.service = rnd(0, L - 1); q.origin = rnd(0, S - 1); q.frames = rnd(1, 3); q.fps_milli = rnd(0, 2) == 0 ? rnd(1000, 60000) : 0; }
         for (auto& u : draws) u = unit();
         int32_t placements[10];
         for (auto& p : placements) p = rnd(0, L * S - 1);

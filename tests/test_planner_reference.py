@@ -152,7 +152,18 @@ def test_paper_worked_numbers():
         elif name == "inter_request_count":
             assert P.inter_request_count(*a) == int(expect)
         elif name == "satisfied_frames":
-            assert a[0] * a[1] // a[2] == int(expect)
+            # through the reference simulation and the library: one stream of a[0] frames that wants a[2] fps on an
+            # instance that delivers a[1] fps (1e6 / a[1] us per frame, rounded to whole microseconds)
+            from oracle import simulator as S
+            from paper_2511_00603_amd import binding as B
+            frames, achieved, wanted = a
+            c = [[round(1e6 / achieved)]]
+            ref = S.simulate(1, 1, c, 0, 10 ** 6, 0, [0], [(0, 0, 0, 10 ** 9, frames, 1000 * wanted)], [[]])
+            req = np.zeros(1, dtype=B.SIM_REQUEST)
+            req[0]["slo_us"], req[0]["frames"], req[0]["fps_milli"] = 10 ** 9, frames, 1000 * wanted
+            got = B.epara_simulate(1, 1, c, 0, 10 ** 6, 0, [0], req, np.zeros((1, 0)))
+            assert got == ref and ref["local"] == 1
+            assert abs(ref["satisfied"] - int(expect)) < 1e-3 * int(expect)
         else:
             raise AssertionError(name)
         seen += 1

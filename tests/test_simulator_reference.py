@@ -13,8 +13,10 @@ from paper_2511_00603_amd import binding as B
 
 def _requests(rows):
     a = np.zeros(len(rows), dtype=B.SIM_REQUEST)
-    for i, (t, l, n, slo, frames) in enumerate(rows):
+    for i, row in enumerate(rows):
+        t, l, n, slo, frames = row[:5]
         a[i]["arrival_us"], a[i]["service"], a[i]["origin"], a[i]["slo_us"], a[i]["frames"] = t, l, n, slo, frames
+        a[i]["fps_milli"] = row[5] if len(row) > 5 else 0
     return a
 
 
@@ -26,6 +28,23 @@ def both(N, L, c, hop, t, max_off, placements, rows, draws):
 
 
 # ---- hand-worked timelines ---------------------------------------------------------------------
+
+def test_frequency_sensitive_streams_count_frames_in_proportion_to_the_achieved_rate():
+    """Sec. 3.3: a stream of 120 frames that wants 80 fps on an instance that needs 25 ms per frame (40 fps) counts
+    120 * 40 / 80 = 60; the same stream queued behind another one is served later, hence slower still; a stream
+    that gets at least its rate counts every frame and no more."""
+    c = [[25000]]
+    r = both(1, 1, c, 0, 10 ** 6, 1, [0], [(0, 0, 0, 10 ** 9, 120, 80000)], [[0.5]])
+    assert r == dict(satisfied=60.0, local=1, offloaded=0, timeout=0, offload_exceeded=0, insufficient=0)
+    # a second stream arrives at the same time and waits for the first: 120 frames in 6 s = 20 fps -> 30 more
+    r = both(1, 1, c, 0, 10 ** 6, 1, [0], [(0, 0, 0, 10 ** 9, 120, 80000), (0, 0, 0, 10 ** 9, 120, 80000)], [[0.5]] * 2)
+    assert r["satisfied"] == 60.0 + 30.0 and r["local"] == 2
+    # asked for 30 fps, gets 40: all 120 frames count, capped; a latency-sensitive request next to it counts one
+    r = both(1, 1, c, 0, 10 ** 6, 1, [0, 0], [(0, 0, 0, 10 ** 9, 120, 30000), (0, 0, 0, 10 ** 9, 3, 0)], [[0.5]] * 2)
+    assert r["satisfied"] == 121.0
+    # a stream is refused only where no instance exists at all (and nobody else has one)
+    r = both(2, 1, [[25000, 25000]], 0, 10 ** 6, 1, [], [(0, 0, 0, 10 ** 9, 10, 1000)], [[0.5]])
+    assert r["satisfied"] == 0.0 and r["insufficient"] == 1
 
 def test_one_instance_serves_in_order_and_refuses_what_would_be_late():
     c = [[10]]
@@ -179,3 +198,48 @@ def test_placement_algorithms_over_the_simulated_objective():
     assert phi_ref(want) <= best
     assert phi_ref(want) >= best / 3                        # greedy on a monotone objective: far from arbitrary
     assert phi_ref(want) > phi_ref([])
+
+
+def test_compute_table_from_measured_passes_and_placement_over_it():
+    """The lookup table c_ln (Sec. 3.3, Sec. 5 "Settings") built from a benchmark line's per-mix pass times, then
+    Alg. 1 placing those services over the simulated objective: library pair = reference pair."""
+    line = {"mixes": {"vit_b16_bf16_bf16": {"ms_per_step": 0.306, "requests": 75},          # the shape of bench.py's line
+                      "llm_decode_bf16_bf16": {"ms_per_step": 0.221, "requests": 105},
+                      "llm_prefill_bf16": {"ms_per_step": 2.816, "requests": 9}}}
+    keys = ["vit_b16_bf16_bf16", "llm_decode_bf16_bf16", "llm_prefill_bf16"]
+    speed = [1.0, 0.5, 0.0]                                  # this GPU, one half as fast, a server without a GPU
+    c = B.compute_table_from_bench_line(line, keys, speed)
+    # by hand: microseconds per request, rounded up; twice that on the slower server; 0 = cannot run
+    assert c.tolist() == [[5, 9, 0], [3, 5, 0], [313, 626, 0]]
+    assert c[0][0] == -(-306 // 75) and c[2][0] == -(-2816 // 9)
+    assert status_of_table([0.0], [1], [1.0]) == B.EPARA_ERR_SHAPE and status_of_table([1.0], [0], [1.0]) == B.EPARA_ERR_SHAPE
+    rng = np.random.default_rng(77)
+    N, Lsvc = 3, 3
+    rows = sorted((int(rng.integers(0, 3000)), int(rng.integers(0, Lsvc)), int(rng.integers(0, N)), int(rng.integers(300, 1500)), 1)
+                  for _ in range(120))
+    draws = rng.random((len(rows), 2))
+    table = c.tolist()
+
+    def feasible(theta):
+        return all(sum(1 for p in theta if p % N == n) <= 2 for n in range(N))
+
+    def phi_ref(theta):
+        return S.simulate(N, Lsvc, table, 20, 500, 2, list(theta), rows, draws.tolist())["satisfied"] if feasible(theta) else -1.0
+
+    def phi_lib(theta):
+        return B.epara_simulate(N, Lsvc, c, 20, 500, 2, list(theta), _requests(rows), draws)["satisfied"] if feasible(theta) else -1.0
+
+    X = [l * N + n for l in range(Lsvc) for n in range(N) if table[l][n] > 0]
+    want = P.place_services([], X, [], phi_ref)
+    got = B.epara_place_services([], X, [], phi_lib)
+    assert list(got) == list(want) and len(want) > 0
+    assert all(p % N != 2 for p in want)                     # nothing lands on the server that cannot run it
+    assert phi_ref(want) > phi_ref([])
+
+
+def status_of_table(ms, rq, speed):
+    try:
+        B.epara_compute_table(ms, rq, speed)
+    except B.EparaError as e:
+        return e.status
+    return B.EPARA_OK
