@@ -339,6 +339,16 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
                           int64_t* row_off, int64_t* x_off, int64_t* y_off,
                           epara_tile* tiles, int64_t tiles_cap, int64_t* n_tiles);
 
+/* The scheduler's cost model, in one place.  A streaming tile costs
+ *     K * (EPARA_COST_PER_COLUMN * cols * (2 for EPARA_ACT_SWIGLU groups) + EPARA_COST_PER_ROW * BM for classes with BM >= 32)
+ * (weight columns streamed from HBM; activation rows re-read from L2 through the LDS: workgroups of the
+ * decode mix that stream the same 1.41 MB of weights take 62 / 72 / 83 us with tiles of the 16- / 32- /
+ * 64-row class, i.e. a row of the larger classes costs a third of a weight column and the rows of the
+ * 16-row class disappear under the weight stream); a panel tile costs EPARA_COST_PANEL * K. */
+#define EPARA_COST_PER_COLUMN 6
+#define EPARA_COST_PER_ROW 2
+#define EPARA_COST_PANEL 2040
+
 /* Visit order of the persistent workgroups.  Workgroup b of W = n_workgroups visits slots
  * b, b + W, b + 2W, ...; order[slot] is a tile index or -1 (idle).  Every workgroup gets a list
  * of tiles; slot j*W + b holds the j-th entry of workgroup b's list; *n_slots = W * (longest list).
@@ -350,10 +360,8 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
  *      workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X)  (X = n_xcd), so the
  *      W/X workgroups of one compute die (workgroup b runs on die b mod X) work on neighbouring
  *      tiles and share operands in that die's L2.
- *   2. streaming tiles, longest first: cost = K * (6 * cols * (2 for EPARA_ACT_SWIGLU groups) + BM)
- *      for a streaming tile (weight columns streamed from HBM; the activation rows, re-read from L2,
- *      were measured at about a sixth of that per row) and 2040 * K
- *      for a panel tile; tiles by descending cost (ties: lower tile index) each go to the
+ *   2. streaming tiles, longest first: costs as defined above (EPARA_COST_*); tiles by descending
+ *      cost (ties: lower tile index) each go to the
  *      workgroup with the smallest accumulated cost (ties: lower workgroup), after that
  *      workgroup's panel tiles.
  * order may be NULL to query *n_slots.  W must be a positive multiple of X;
@@ -379,6 +387,55 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
  * written) if an order array is too small. */
 int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                              int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n);
+
+/* What epara_plan_launch decided and how large its outputs are. */
+typedef struct {
+    epara_tile_class classes[4];      /* the class table the launch was cut with */
+    int32_t n_classes, n_stream_classes;
+    int32_t narrow;                   /* 1: the narrow table (see epara_kernel_classes) */
+    int32_t gated;                    /* 1: every group is EPARA_ACT_SWIGLU */
+    int64_t n_tiles, n_slots;
+    int64_t makespan;                 /* cost of the most loaded workgroup under the cost model */
+} epara_launch_plan;
+
+/* The whole planning decision of one launch (Sec. 3.1: the parallel mode of each task): picks the class
+ * table -- the wide one, or the narrow one when some batch has more than 32 rows and the narrow
+ * table's schedule has the smaller makespan under the cost model (ties: wide) -- then plans
+ * (epara_plan_groups) and schedules (epara_schedule_tiles) with it.  The groups must be all
+ * EPARA_ACT_SWIGLU or none (ERR_DTYPE).  *plan is always written (sizes included); tiles / order are
+ * written when given and large enough, else ERR_CAPACITY (give NULL and 0 to ask for the sizes only;
+ * that returns EPARA_OK).  row_off / x_off / y_off may be NULL.  Other errors as for the two calls. */
+int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_dtype,
+                          int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
+                          int64_t* row_off, int64_t* x_off, int64_t* y_off,
+                          epara_tile* tiles, int64_t tiles_cap, int32_t* order, int64_t order_cap,
+                          epara_launch_plan* plan);
+
+/* One phase of epara_plan_chain: in: groups, G, producer (per group the group of the phase before whose
+ * output it reads, or -1; NULL: the phase waits for nothing); out: tiles, order, waits (G entries; may
+ * be NULL when producer is), counter_base, plan. */
+typedef struct {
+    const epara_group_desc* groups;
+    const int32_t*          producer;
+    epara_tile*             tiles;
+    int32_t*                order;
+    epara_chain_wait*       waits;
+    int64_t tiles_cap, order_cap;
+    int32_t G;
+    int32_t counter_base;             /* out: the sum of G over the phases before */
+    epara_launch_plan plan;           /* out */
+} epara_chain_plan_phase;
+
+/* The planning decision of a chain (epara_grouped_chain): for every phase the wide or the narrow table
+ * (phases with a batch of more than 32 rows have the choice), taken jointly: every combination is
+ * scheduled with epara_schedule_chain and replayed under the cost model -- a workgroup walks its
+ * lists phase after phase, a tile starts when its workgroup is free and, if its group waits, when the
+ * last tile of the producing group has ended -- and the combination whose last workgroup finishes first
+ * is kept (ties: the earlier combination, wide before narrow, first phase varying slowest).  Then tiles,
+ * orders, waits (epara_chain_waits) and counter bases are written as for epara_plan_launch; all sizes
+ * are always written, ERR_CAPACITY if an array that was given is too small. */
+int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32_t in_dtype,
+                         int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n, int64_t* finish);
 
 /* The waits of one phase of a chain: producer[g] = the group of the phase before whose output Y is
  * group g's input X, or -1.  waits[g] = { counter_base + producer[g], number of tiles of that group

@@ -224,9 +224,9 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        outermost, and inside a panel the m index runs fastest.  The l-th tile of that sequence
        goes to workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X): the W/X
        tiles that run together on one die are consecutive in the sequence.
-    2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + BM) for a streaming
-       tile (weight columns streamed from HBM, plus the activation rows re-read from L2 at a sixth of
-       that price), 2040 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
+    2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + (2 * BM if BM >= 32 else 0))
+       for a streaming tile (weight columns streamed from HBM, plus the activation rows re-read from L2
+       at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
        the workgroup with the smallest accumulated cost (ties: lower workgroup), after that
        workgroup's panel tiles.
     """
@@ -277,7 +277,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
             if tile[5] < n_stream_classes:
                 g = groups[tile[0]]
                 gated = len(g) > 3 and bool(g[3])
-                stream.append((-(g[1] * (6 * tile[4] * (2 if gated else 1) + classes[tile[5]][1])), p, t))
+                stream.append((-(g[1] * (6 * tile[4] * (2 if gated else 1) + (2 * classes[tile[5]][1] if classes[tile[5]][1] >= 32 else 0))), p, t))
     stream.sort()
     heap = [(load[b], b) for b in range(W)]
     heapq.heapify(heap)

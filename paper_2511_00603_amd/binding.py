@@ -42,6 +42,23 @@ assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize
 assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
 
 
+class LaunchPlanInfo(ctypes.Structure):
+    """struct epara_launch_plan."""
+    _fields_ = [("classes", ctypes.c_int32 * 12), ("n_classes", ctypes.c_int32), ("n_stream_classes", ctypes.c_int32),
+                ("narrow", ctypes.c_int32), ("gated", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
+                ("makespan", ctypes.c_int64)]
+
+    def class_table(self):
+        return np.array(list(self.classes), dtype=np.int32)[: 3 * self.n_classes].view(TILE_CLASS).copy()
+
+
+class ChainPlanPhase(ctypes.Structure):
+    """struct epara_chain_plan_phase."""
+    _fields_ = [("groups", ctypes.c_void_p), ("producer", ctypes.c_void_p), ("tiles", ctypes.c_void_p), ("order", ctypes.c_void_p),
+                ("waits", ctypes.c_void_p), ("tiles_cap", ctypes.c_int64), ("order_cap", ctypes.c_int64), ("G", ctypes.c_int32),
+                ("counter_base", ctypes.c_int32), ("plan", LaunchPlanInfo)]
+
+
 class Launch(ctypes.Structure):
     """struct epara_launch."""
     _fields_ = [("h_args", ctypes.c_void_p), ("d_args", ctypes.c_void_p),
@@ -148,6 +165,10 @@ def lib():
         for name in ("epara_schedule_chain", "epara_chain_waits", "epara_chain_workspace_init", "epara_grouped_chain",
                      "epara_chain_status", "epara_grouped_chain_static"):
             getattr(L, name).restype = i32
+        L.epara_plan_launch.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i64, vp]
+        L.epara_plan_launch.restype = i32
+        L.epara_plan_chain.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp]
+        L.epara_plan_chain.restype = i32
         L.epara_compute_table.argtypes = [vp, vp, i32, vp, i32, vp]
         L.epara_compute_table.restype = i32
         L.epara_ffn_swiglu_args.argtypes = [vp, i32, i32, vp, vp]
@@ -327,6 +348,54 @@ def epara_schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups,
 def epara_workspace_bytes(groups, in_dtype):
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
     return int(lib().epara_workspace_bytes(_ptr(groups), len(groups), int(in_dtype)))
+
+
+def epara_plan_launch(groups, in_dtype, n_workgroups, n_xcd=8, panel_m=1, panel_n=4):
+    """-> (info: LaunchPlanInfo, row_off, x_off, y_off, tiles, order): the library's whole planning decision of a launch."""
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    G = len(groups)
+    gp = _ptr(groups) if G else None
+    info = LaunchPlanInfo()
+    _check(lib().epara_plan_launch(gp, G, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, None, None, None, None, 0, None, 0,
+                                   ctypes.addressof(info)), "epara_plan_launch")
+    row_off, x_off, y_off = (np.zeros(G + 1, dtype=np.int64) for _ in range(3))
+    tiles, order = np.zeros(info.n_tiles, dtype=TILE), np.zeros(info.n_slots, dtype=np.int32)
+    _check(lib().epara_plan_launch(gp, G, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, _ptr(row_off), _ptr(x_off), _ptr(y_off),
+                                   _ptr(tiles) if len(tiles) else None, len(tiles), _ptr(order) if len(order) else None, len(order),
+                                   ctypes.addressof(info)), "epara_plan_launch")
+    return info, row_off, x_off, y_off, tiles, order
+
+
+def epara_plan_chain(phase_groups, producers, in_dtype, n_workgroups, n_xcd=8, panel_m=1, panel_n=4):
+    """phase_groups[p]: GROUP_DESC array; producers[p]: None or int array (per group: the producing group of phase p-1, -1: none).
+    -> (finish, list per phase of dict(info, tiles, order, waits, counter_base))."""
+    P = len(phase_groups)
+    arr = (ChainPlanPhase * P)()
+    keep = []
+    for p in range(P):
+        g = np.ascontiguousarray(phase_groups[p], dtype=GROUP_DESC)
+        pr = None if producers[p] is None else np.ascontiguousarray(producers[p], dtype=np.int32)
+        keep.append((g, pr))
+        arr[p].groups, arr[p].G = (_ptr(g) if len(g) else None), len(g)
+        arr[p].producer = None if pr is None or not len(pr) else _ptr(pr)
+    finish = ctypes.c_int64(0)
+    _check(lib().epara_plan_chain(ctypes.addressof(arr), P, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, ctypes.byref(finish)),
+           "epara_plan_chain")
+    out = []
+    for p in range(P):
+        tiles, order = np.zeros(arr[p].plan.n_tiles, dtype=TILE), np.zeros(arr[p].plan.n_slots, dtype=np.int32)
+        waits = None if keep[p][1] is None else np.zeros(len(keep[p][0]), dtype=CHAIN_WAIT)
+        out.append({"tiles": tiles, "order": order, "waits": waits})
+        arr[p].tiles, arr[p].tiles_cap = (_ptr(tiles) if len(tiles) else None), len(tiles)
+        arr[p].order, arr[p].order_cap = (_ptr(order) if len(order) else None), len(order)
+        arr[p].waits = None if waits is None or not len(waits) else _ptr(waits)
+    _check(lib().epara_plan_chain(ctypes.addressof(arr), P, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, ctypes.byref(finish)),
+           "epara_plan_chain")
+    for p in range(P):
+        info = LaunchPlanInfo()
+        ctypes.memmove(ctypes.addressof(info), ctypes.addressof(arr[p].plan), ctypes.sizeof(info))
+        out[p]["info"], out[p]["counter_base"] = info, int(arr[p].counter_base)
+    return int(finish.value), out
 
 
 def epara_compute_table(ms_per_pass, requests_per_pass, server_speed):

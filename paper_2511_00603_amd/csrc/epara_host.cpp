@@ -19,6 +19,16 @@ namespace {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// The cost model of the scheduler (the constants are the header's).
+inline int64_t tile_cost(const epara_group_desc& d, const epara_tile& tl, const epara_tile_class* classes, int32_t n_stream_classes)
+{
+    if (tl.cls >= n_stream_classes) return static_cast<int64_t>(EPARA_COST_PANEL) * d.K;
+    const int64_t BM = classes[tl.cls].BM;
+    const int64_t units = static_cast<int64_t>(EPARA_COST_PER_COLUMN) * tl.cols * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) +
+                          (BM >= 32 ? EPARA_COST_PER_ROW * BM : 0);
+    return units * d.K;
+}
+
 int32_t check_classes(const epara_tile_class* classes, int32_t n_classes)
 {
     if (!classes) return EPARA_ERR_NULL;
@@ -496,7 +506,7 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                             for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
                                 const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
                                 lists[p][b].push_back(static_cast<int32_t>(first[p][g] + tm * TN + tn));
-                                load[b] += 2040 * static_cast<int64_t>(ph.groups[g].K);
+                                load[b] += static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[g].K;
                                 ++l;
                             }
             }
@@ -510,9 +520,7 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
         const epara_phase_schedule& ph = phases[p];
         for (int64_t t = 0; t < ph.n_tiles; ++t)
             if (ph.tiles[t].cls < ph.n_stream_classes) {
-                const epara_group_desc& d = ph.groups[ph.tiles[t].group];
-                const int64_t units = 6 * static_cast<int64_t>(ph.tiles[t].cols) * (d.act == EPARA_ACT_SWIGLU ? 2 : 1) + ph.classes[ph.tiles[t].cls].BM;
-                stream.push_back({units * d.K, p, static_cast<int32_t>(t)});
+                stream.push_back({tile_cost(ph.groups[ph.tiles[t].group], ph.tiles[t], ph.classes, ph.n_stream_classes), p, static_cast<int32_t>(t)});
             }
     }
     std::stable_sort(stream.begin(), stream.end(), [](const item& a, const item& b) { return a.cost > b.cost; });
@@ -557,6 +565,179 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
     ph.G = G; ph.n_classes = n_classes; ph.n_stream_classes = n_stream_classes;
     const int32_t st = epara_schedule_chain(&ph, 1, n_workgroups, n_xcd, panel_m, panel_n);
     if (st == EPARA_OK || st == EPARA_ERR_CAPACITY) *n_slots = ph.n_slots;
+    return st;
+}
+
+namespace {
+
+// One candidate of a phase: a class table and the canonical tiles it gives.
+struct phase_option {
+    epara_tile_class classes[4];
+    int32_t n_classes = 0, n_stream = 0, narrow = 0;
+    std::vector<epara_tile> tiles;
+};
+
+int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
+{
+    int32_t n_gated = 0, n_live = 0;
+    for (int32_t g = 0; g < G; ++g)
+        if (groups[g].M > 0) { ++n_live; n_gated += groups[g].act == EPARA_ACT_SWIGLU; }
+    if (n_gated != 0 && n_gated != n_live) return EPARA_ERR_DTYPE;
+    *gated = n_gated > 0;
+    return EPARA_OK;
+}
+
+int32_t phase_options(const epara_group_desc* groups, int32_t G, int32_t in_dtype, std::vector<phase_option>& out)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (G > 0 && !groups) return EPARA_ERR_NULL;
+    int32_t gated = 0;
+    if (int32_t st = gated_of(groups, G, &gated)) return st;
+    int32_t max_M = 0;
+    for (int32_t g = 0; g < G; ++g) max_M = std::max(max_M, groups[g].M);
+    const int n_opt = (in_dtype != EPARA_F32 && max_M > 32) ? 2 : 1;
+    out.resize(static_cast<size_t>(n_opt));
+    for (int narrow = 0; narrow < n_opt; ++narrow) {
+        phase_option& o = out[narrow];
+        o.narrow = narrow;
+        if (int32_t st = epara_kernel_classes(in_dtype, gated, narrow, o.classes, 4, &o.n_classes, &o.n_stream)) return st;
+        int64_t n = 0;
+        if (int32_t st = epara_plan_groups(groups, G, o.classes, o.n_classes, nullptr, nullptr, nullptr, nullptr, 0, &n)) return st;
+        o.tiles.resize(static_cast<size_t>(n));
+        if (int32_t st = epara_plan_groups(groups, G, o.classes, o.n_classes, nullptr, nullptr, nullptr, o.tiles.data(), n, &n)) return st;
+    }
+    return EPARA_OK;
+}
+
+void fill_plan(epara_launch_plan& plan, const phase_option& o, int32_t gated, int64_t n_slots, int64_t makespan)
+{
+    std::memset(&plan, 0, sizeof plan);
+    std::memcpy(plan.classes, o.classes, sizeof(epara_tile_class) * o.n_classes);
+    plan.n_classes = o.n_classes; plan.n_stream_classes = o.n_stream; plan.narrow = o.narrow; plan.gated = gated;
+    plan.n_tiles = static_cast<int64_t>(o.tiles.size()); plan.n_slots = n_slots; plan.makespan = makespan;
+}
+
+}  // namespace
+
+int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32_t in_dtype,
+                         int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n, int64_t* finish)
+{
+    if (n_phases < 1 || n_phases > EPARA_MAX_CHAIN_PHASES) return EPARA_ERR_SHAPE;
+    if (!phases) return EPARA_ERR_NULL;
+    if (n_workgroups <= 0 || n_xcd <= 0 || n_workgroups % n_xcd != 0 || panel_m <= 0 || panel_n <= 0) return EPARA_ERR_SHAPE;
+    const int64_t W = n_workgroups;
+    std::vector<std::vector<phase_option>> options(static_cast<size_t>(n_phases));
+    std::vector<int32_t> gated(static_cast<size_t>(n_phases), 0);
+    for (int32_t p = 0; p < n_phases; ++p) {
+        if (int32_t st = phase_options(phases[p].groups, phases[p].G, in_dtype, options[p])) return st;
+        gated_of(phases[p].groups, phases[p].G, &gated[p]);
+        if (phases[p].producer) {
+            if (p == 0) return EPARA_ERR_SHAPE;
+            for (int32_t g = 0; g < phases[p].G; ++g)
+                if (phases[p].producer[g] < -1 || phases[p].producer[g] >= phases[p - 1].G) return EPARA_ERR_SHAPE;
+        }
+    }
+    // every combination, first phase varying slowest, wide before narrow
+    int64_t best_finish = -1;
+    std::vector<int> best_pick;
+    std::vector<std::vector<int32_t>> best_order;
+    std::vector<int> pick(static_cast<size_t>(n_phases), 0);
+    for (;;) {
+        std::vector<epara_phase_schedule> sched(static_cast<size_t>(n_phases));
+        std::vector<std::vector<int32_t>> order(static_cast<size_t>(n_phases));
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int32_t p = 0; p < n_phases; ++p) {
+                const phase_option& o = options[p][pick[p]];
+                epara_phase_schedule& ph = sched[p];
+                if (pass == 0) {
+                    std::memset(&ph, 0, sizeof ph);
+                    ph.groups = phases[p].groups; ph.classes = o.classes; ph.tiles = o.tiles.data();
+                    ph.n_tiles = static_cast<int64_t>(o.tiles.size());
+                    ph.G = phases[p].G; ph.n_classes = o.n_classes; ph.n_stream_classes = o.n_stream;
+                } else {
+                    order[p].assign(static_cast<size_t>(ph.n_slots), -1);
+                    ph.order = order[p].data(); ph.order_cap = ph.n_slots;
+                }
+            }
+            if (int32_t st = epara_schedule_chain(sched.data(), n_phases, n_workgroups, n_xcd, panel_m, panel_n)) return st;
+        }
+        // replay under the cost model, waits included
+        std::vector<int64_t> clock(static_cast<size_t>(W), 0), ready_prev;
+        for (int32_t p = 0; p < n_phases; ++p) {
+            const phase_option& o = options[p][pick[p]];
+            std::vector<int64_t> ready(static_cast<size_t>(phases[p].G), 0);
+            const int64_t rows = sched[p].n_slots / W;
+            for (int64_t j = 0; j < rows; ++j)
+                for (int64_t b = 0; b < W; ++b) {
+                    const int32_t t = order[p][static_cast<size_t>(j * W + b)];
+                    if (t < 0) continue;
+                    const epara_tile& tl = o.tiles[t];
+                    int64_t start = clock[b];
+                    if (p > 0 && phases[p].producer && phases[p].producer[tl.group] >= 0)
+                        start = std::max(start, ready_prev[phases[p].producer[tl.group]]);
+                    clock[b] = start + tile_cost(phases[p].groups[tl.group], tl, o.classes, o.n_stream);
+                    ready[tl.group] = std::max(ready[tl.group], clock[b]);
+                }
+            ready_prev.swap(ready);
+        }
+        const int64_t fin = *std::max_element(clock.begin(), clock.end());
+        if (best_finish < 0 || fin < best_finish) { best_finish = fin; best_pick = pick; best_order = order; }
+        int32_t p = n_phases - 1;
+        while (p >= 0 && ++pick[p] == static_cast<int>(options[p].size())) pick[p--] = 0;
+        if (p < 0) break;
+    }
+    if (finish) *finish = best_finish;
+    int32_t status = EPARA_OK, base = 0;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        const phase_option& o = options[p][best_pick[p]];
+        epara_chain_plan_phase& ph = phases[p];
+        // a phase's own makespan: its workgroups' costs in this phase alone
+        std::vector<int64_t> load(static_cast<size_t>(W), 0);
+        for (size_t i = 0; i < best_order[p].size(); ++i)
+            if (best_order[p][i] >= 0) {
+                const epara_tile& tl = o.tiles[best_order[p][i]];
+                load[i % W] += tile_cost(ph.groups[tl.group], tl, o.classes, o.n_stream);
+            }
+        fill_plan(ph.plan, o, gated[p], static_cast<int64_t>(best_order[p].size()), *std::max_element(load.begin(), load.end()));
+        ph.counter_base = base;
+        base += ph.G;
+        if (ph.tiles) {
+            if (ph.tiles_cap < ph.plan.n_tiles) status = EPARA_ERR_CAPACITY;
+            else std::copy(o.tiles.begin(), o.tiles.end(), ph.tiles);
+        }
+        if (ph.order) {
+            if (ph.order_cap < ph.plan.n_slots) status = EPARA_ERR_CAPACITY;
+            else std::copy(best_order[p].begin(), best_order[p].end(), ph.order);
+        }
+    }
+    if (status != EPARA_OK) return status;
+    for (int32_t p = 1; p < n_phases; ++p) {
+        epara_chain_plan_phase& ph = phases[p];
+        if (!ph.producer || !ph.waits) continue;
+        const phase_option& prev = options[p - 1][best_pick[p - 1]];
+        if (int32_t st = epara_chain_waits(prev.tiles.data(), static_cast<int64_t>(prev.tiles.size()), phases[p - 1].G,
+                                           phases[p - 1].counter_base, ph.producer, ph.G, ph.waits)) return st;
+    }
+    return EPARA_OK;
+}
+
+int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_dtype,
+                          int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
+                          int64_t* row_off, int64_t* x_off, int64_t* y_off,
+                          epara_tile* tiles, int64_t tiles_cap, int32_t* order, int64_t order_cap,
+                          epara_launch_plan* plan)
+{
+    if (!plan) return EPARA_ERR_NULL;
+    epara_chain_plan_phase ph;
+    std::memset(&ph, 0, sizeof ph);
+    ph.groups = groups; ph.G = G; ph.tiles = tiles; ph.tiles_cap = tiles_cap; ph.order = order; ph.order_cap = order_cap;
+    const int32_t st = epara_plan_chain(&ph, 1, in_dtype, n_workgroups, n_xcd, panel_m, panel_n, nullptr);
+    if (st != EPARA_OK && st != EPARA_ERR_CAPACITY) return st;
+    *plan = ph.plan;
+    if (row_off || x_off || y_off) {
+        int64_t n = 0;
+        if (int32_t s2 = epara_plan_groups(groups, G, plan->classes, plan->n_classes, row_off, x_off, y_off, nullptr, 0, &n)) return s2;
+    }
     return st;
 }
 

@@ -1,7 +1,6 @@
 """Marshalling between PyTorch device memory and libepara.  PyTorch is used for allocation,
 host<->device copies and streams only; every step of the forward path runs in the library."""
 import ctypes
-import itertools
 import time
 
 import numpy as np
@@ -64,54 +63,6 @@ def group_args(X, W, Y, M, K, N, act, bias=None, W2=None, scale=1.0, scale2=1.0,
     return a
 
 
-def _loads(groups, classes, n_stream, tiles, order, n_workgroups):
-    """Per-workgroup cost of a schedule, in the units epara_schedule_tiles balances with."""
-    if len(tiles) == 0:
-        return np.zeros(n_workgroups, dtype=np.int64)
-    g = groups[tiles["group"]]
-    stream = tiles["cls"] < n_stream
-    units = 6 * tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
-    cost = np.where(stream, units, 2040) * g["K"].astype(np.int64)
-    per_slot = np.where(order >= 0, cost[np.maximum(order, 0)], 0).reshape(-1, n_workgroups)
-    return per_slot.sum(axis=0)
-
-
-def _tile_costs(groups, classes, n_stream, tiles):
-    g = groups[tiles["group"]]
-    units = 6 * tiles["cols"].astype(np.int64) * np.where(g["act"] == B.EPARA_ACT_SWIGLU, 2, 1) + classes["BM"][tiles["cls"]]
-    return np.where(tiles["cls"] < n_stream, units, 2040) * g["K"].astype(np.int64)
-
-
-def _chain_finish(groups, combo, orders, producers, n_workgroups):
-    """When the last workgroup of a chain finishes under the scheduler's cost model, counting the time a
-    tile waits for the group that produces its input (all tiles of that group, wherever they run)."""
-    clock = np.zeros(n_workgroups, dtype=np.int64)
-    ready_prev = None
-    for p, (c, order) in enumerate(zip(combo, orders)):
-        _, classes, n_stream, tiles = c
-        if len(tiles) == 0:
-            ready_prev = np.zeros(len(groups[p]), dtype=np.int64)
-            continue
-        cost = _tile_costs(groups[p], classes, n_stream, tiles)
-        end = np.zeros(len(tiles), dtype=np.int64)
-        for row in order.reshape(-1, n_workgroups):
-            m = row >= 0
-            t = row[m]
-            start = clock[m]
-            if p > 0 and producers[p] is not None and ready_prev is not None:
-                q = np.asarray(producers[p])[tiles["group"][t]]
-                start = np.maximum(start, np.where(q >= 0, ready_prev[np.maximum(q, 0)], 0))
-            clock[m] = start + cost[t]
-            end[t] = clock[m]
-        ready_prev = np.zeros(len(groups[p]), dtype=np.int64)
-        np.maximum.at(ready_prev, tiles["group"], end)
-    return int(clock.max())
-
-
-def _makespan(groups, classes, n_stream, tiles, order, n_workgroups):
-    return int(_loads(groups, classes, n_stream, tiles, order, n_workgroups).max())
-
-
 def _group_desc(args):
     groups = np.zeros(len(args), dtype=B.GROUP_DESC)
     for f in ("M", "K", "N", "act"):
@@ -121,41 +72,25 @@ def _group_desc(args):
 
 
 class LaunchPlan:
-    """Host plan + its device copy for one grouped launch (epara_launch)."""
+    """Host plan + its device copy for one grouped launch (epara_launch).  The plan itself -- class table, tiles,
+    visit order -- is the library's (epara_plan_launch); this class only keeps the arrays and uploads them."""
 
     def __init__(self, args, in_dtype, device, n_workgroups=None, n_xcd=8, panel_m=1, panel_n=4):
         # panel 1 x 4: panel tiles are visited strip by strip (4 tile columns), row by row, so the 32
         # tiles that run together on one die are 8 whole rows of a strip wherever a strip begins
-        # (with 8 x 4 panels a group whose rows are not a multiple of 8 tiles shifts every later
-        # panel across two dies, and each die then fetches more rows and columns than 8 + 4).
         _require_gpu()
         t0 = time.perf_counter()
         self.args = np.ascontiguousarray(args, dtype=B.GROUP_ARGS)
         G = len(self.args)
-        gated = bool(G) and bool(np.all(self.args["act"] == B.EPARA_ACT_SWIGLU))
-        if G and not gated and np.any(self.args["act"] == B.EPARA_ACT_SWIGLU):
-            raise ValueError("a launch is either all SwiGLU groups or none")
         self.in_dtype = in_dtype
-        self.groups = np.zeros(G, dtype=B.GROUP_DESC)
-        for f in ("M", "K", "N", "act"):
-            self.groups[f] = self.args[f]
-        self.groups["has_bias"] = (self.args["bias"] != 0).astype(np.int32)
+        self.groups = _group_desc(self.args)
         if n_workgroups is None:
             n_workgroups = n_compute_units(device)
             n_workgroups -= n_workgroups % n_xcd
         self.n_workgroups = n_workgroups
-        # two class tables exist for small batches (wide / narrow tiles): keep the one whose
-        # schedule finishes first under the scheduler's own cost model
-        best = None
-        for narrow in ((False, True) if (in_dtype != B.EPARA_F32 and G and int(self.groups["M"].max()) > 32) else (False,)):
-            classes, n_stream = B.epara_kernel_classes(in_dtype, gated, narrow)
-            row_off, x_off, y_off, tiles = B.epara_plan_groups(self.groups, classes)
-            order = B.epara_schedule_tiles(self.groups, classes, n_stream, tiles, n_workgroups, n_xcd, panel_m, panel_n)
-            span = _makespan(self.groups, classes, n_stream, tiles, order, n_workgroups)
-            if best is None or span < best[0]:
-                best = (span, narrow, classes, n_stream, row_off, x_off, y_off, tiles, order)
-        (self.makespan, self.narrow, self.classes, self.n_stream_classes, self.row_off, self.x_off, self.y_off,
-         self.tiles, self.order) = best
+        info, self.row_off, self.x_off, self.y_off, self.tiles, self.order = B.epara_plan_launch(
+            self.groups, in_dtype, n_workgroups, n_xcd, panel_m, panel_n)
+        self.makespan, self.narrow, self.classes, self.n_stream_classes = info.makespan, bool(info.narrow), info.class_table(), info.n_stream_classes
         self.plan_seconds = time.perf_counter() - t0
         t0 = time.perf_counter()
         self.d_args = _upload(self.args, device)
@@ -172,7 +107,8 @@ class _Phase:
 
 
 class ChainPlan:
-    """Host plan + device copy of a chain of grouped launches that runs as one kernel (epara_grouped_chain).
+    """Host plan + device copy of a chain of grouped launches that runs as one kernel (epara_grouped_chain); planned
+    by the library (epara_plan_chain).
 
     phase_args[p]: GROUP_ARGS array of phase p; out_dtypes[p]: its output dtype; producers[p]: None, or per
     group of phase p the index of the group of phase p-1 whose output it reads (-1: none)."""
@@ -187,37 +123,17 @@ class ChainPlan:
         P = len(phase_args)
         args = [np.ascontiguousarray(a, dtype=B.GROUP_ARGS) for a in phase_args]
         groups = [_group_desc(a) for a in args]
-        gated = [bool(len(a)) and bool(np.all(a["act"] == B.EPARA_ACT_SWIGLU)) for a in args]
-        options = []                                  # per phase: the class tables that may be used
-        for p in range(P):
-            both = in_dtype != B.EPARA_F32 and len(args[p]) and int(groups[p]["M"].max()) > 32
-            opts = []
-            for narrow in ((False, True) if both else (False,)):
-                classes, n_stream = B.epara_kernel_classes(in_dtype, gated[p], narrow)
-                _, _, _, tiles = B.epara_plan_groups(groups[p], classes)
-                opts.append((narrow, classes, n_stream, tiles))
-            options.append(opts)
-        best = None
-        for combo in itertools.product(*options):     # keep the tables whose joint schedule finishes first, waits included
-            orders = B.epara_schedule_chain([(groups[p], c[1], c[2], c[3]) for p, c in enumerate(combo)],
-                                            n_workgroups, n_xcd, panel_m, panel_n)
-            span = _chain_finish(groups, combo, orders, producers, n_workgroups)
-            if best is None or span < best[0]:
-                best = (span, combo, orders)
-        self.makespan, combo, orders = best
-        self.phases, base = [], 0
+        self.makespan, planned = B.epara_plan_chain(groups, [None if p == 0 else producers[p] for p in range(P)], in_dtype,
+                                                    n_workgroups, n_xcd, panel_m, panel_n)
+        self.phases = []
         for p in range(P):
             ph = _Phase()
             ph.args, ph.groups, ph.in_dtype, ph.n_workgroups = args[p], groups[p], in_dtype, n_workgroups
-            ph.narrow, ph.classes, ph.n_stream_classes, ph.tiles = combo[p]
-            ph.order, ph.counter_base = orders[p], base
-            base += len(args[p])
-            ph.waits = None
-            if p > 0 and producers[p] is not None:
-                prev = self.phases[p - 1]
-                ph.waits = B.epara_chain_waits(prev.tiles, len(prev.args), prev.counter_base, producers[p])
+            info = planned[p]["info"]
+            ph.narrow, ph.classes, ph.n_stream_classes = bool(info.narrow), info.class_table(), info.n_stream_classes
+            ph.tiles, ph.order, ph.waits, ph.counter_base = planned[p]["tiles"], planned[p]["order"], planned[p]["waits"], planned[p]["counter_base"]
             self.phases.append(ph)
-        self.n_counters = base
+        self.n_counters = sum(len(a) for a in args)
         self.plan_seconds = time.perf_counter() - t0
         t0 = time.perf_counter()
         self.c = (B.ChainPhase * P)()

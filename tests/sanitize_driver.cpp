@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "epara.h"
@@ -73,6 +74,60 @@ int main()
         for (auto& q : producer) q = G ? rnd(-1, G - 1) : -1;
         std::vector<epara_chain_wait> waits(static_cast<size_t>(G));
         CHECK(epara_chain_waits(tiles.data(), n_tiles, G, 3, producer.data(), G, waits.data()) == EPARA_OK);
+    }
+    // ---- the whole planning decision from C alone: the decode and prefill FFN launches, singly and as chains;
+    // every tile of the chosen plan exactly once in the order, every group covered by its tiles
+    {
+        const int32_t rows4[4] = {1, 8, 32, 64}, rows5[2] = {4692, 3500};
+        for (int mix = 4; mix <= 5; ++mix) {
+            const int32_t G = mix == 4 ? 4 : 2, d = mix == 4 ? 4096 : 5120, f = mix == 4 ? 11008 : 13824;
+            std::vector<epara_group_desc> up(G), down(G);
+            for (int32_t g = 0; g < G; ++g) {
+                const int32_t M = mix == 4 ? rows4[g] : rows5[g];
+                up[g] = {M, d, f, EPARA_ACT_SWIGLU, 0, 0};
+                down[g] = {M, f, d, EPARA_ACT_NONE, 0, 0};
+            }
+            for (int which = 0; which < 2; ++which) {
+                const std::vector<epara_group_desc>& groups = which ? down : up;
+                epara_launch_plan plan;
+                CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, nullptr, nullptr, nullptr, nullptr, 0, nullptr, 0, &plan) == EPARA_OK);
+                std::vector<epara_tile> tiles(static_cast<size_t>(plan.n_tiles));
+                std::vector<int32_t> order(static_cast<size_t>(plan.n_slots));
+                std::vector<int64_t> row_off(G + 1);
+                CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, row_off.data(), nullptr, nullptr, tiles.data(), plan.n_tiles - 1,
+                                        order.data(), plan.n_slots, &plan) == EPARA_ERR_CAPACITY);
+                CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, row_off.data(), nullptr, nullptr, tiles.data(), plan.n_tiles,
+                                        order.data(), plan.n_slots, &plan) == EPARA_OK);
+                CHECK(plan.gated == (which ? 0 : 1) && plan.n_classes == 4 && plan.makespan > 0);
+                std::vector<int64_t> area(static_cast<size_t>(G), 0);
+                for (const epara_tile& t : tiles) { CHECK(t.rows >= 1 && t.cols >= 1 && t.m0 + t.rows <= groups[t.group].M && t.n0 + t.cols <= groups[t.group].N); area[t.group] += static_cast<int64_t>(t.rows) * t.cols; }
+                for (int32_t g = 0; g < G; ++g) CHECK(area[g] == static_cast<int64_t>(groups[g].M) * groups[g].N);
+                std::vector<char> seen(tiles.size(), 0);
+                for (int32_t t : order) if (t >= 0) { CHECK(static_cast<size_t>(t) < tiles.size() && !seen[t]); seen[t] = 1; }
+                for (char c : seen) CHECK(c);
+            }
+            const int32_t producer[4] = {0, 1, 2, 3};
+            epara_chain_plan_phase ph[2];
+            std::memset(ph, 0, sizeof ph);
+            ph[0].groups = up.data(); ph[0].G = G; ph[1].groups = down.data(); ph[1].G = G; ph[1].producer = producer;
+            int64_t finish = 0;
+            CHECK(epara_plan_chain(ph, 2, EPARA_BF16, 256, 8, 1, 4, &finish) == EPARA_OK && finish > 0);
+            std::vector<epara_tile> ct[2];
+            std::vector<int32_t> co[2];
+            std::vector<epara_chain_wait> waits(static_cast<size_t>(G));
+            for (int p = 0; p < 2; ++p) {
+                ct[p].resize(static_cast<size_t>(ph[p].plan.n_tiles)); co[p].resize(static_cast<size_t>(ph[p].plan.n_slots));
+                ph[p].tiles = ct[p].data(); ph[p].tiles_cap = ph[p].plan.n_tiles; ph[p].order = co[p].data(); ph[p].order_cap = ph[p].plan.n_slots;
+            }
+            ph[1].waits = waits.data();
+            CHECK(epara_plan_chain(ph, 2, EPARA_BF16, 256, 8, 1, 4, &finish) == EPARA_OK);
+            CHECK(ph[0].counter_base == 0 && ph[1].counter_base == G);
+            for (int32_t g = 0; g < G; ++g) {
+                int32_t n = 0;
+                for (const epara_tile& t : ct[0]) n += t.group == g;
+                CHECK(waits[g].counter == g && waits[g].need == n);
+            }
+        }
     }
     // ---- batch accounting, segments, dealer
     {

@@ -317,7 +317,7 @@ def test_chain_scheduler_matches_reference_and_covers_every_tile_once(chain):
                     tile = tiles[t]
                     if tile[5] < n_stream:
                         g = groups[tile[0]]
-                        c = g[1] * (6 * tile[4] * (2 if g[3] else 1) + classes[tile[5]][1])
+                        c = g[1] * (6 * tile[4] * (2 if g[3] else 1) + (2 * classes[tile[5]][1] if classes[tile[5]][1] >= 32 else 0))
                     else:
                         c, stream_only = 2040 * groups[tile[0]][1], False
                     total[b] += c
@@ -349,7 +349,7 @@ def test_chain_balances_a_coarse_phase_against_a_fine_one():
             for slot, t in enumerate(order):
                 if t >= 0:
                     g = groups[tiles[t][0]]
-                    total[slot % 256] += g[1] * (6 * tiles[t][4] * (2 if g[3] else 1) + classes[tiles[t][5]][1])
+                    total[slot % 256] += g[1] * (6 * tiles[t][4] * (2 if g[3] else 1) + (2 * classes[tiles[t][5]][1] if classes[tiles[t][5]][1] >= 32 else 0))
         return total
     # separate launches: a launch boundary is a barrier, the maxima of the phases add up
     alone = [loads([ph], [P.schedule_tiles(*ph, 256, 8, 1, 4)]) for ph in phases]
@@ -434,3 +434,94 @@ def test_chain_rejects_produced_tensors_that_do_not_own_their_cache_lines():
     # tensors on lines of their own pass this check and reach the next one (the workspace given here is too
     # small on purpose, so that nothing is ever enqueued with these made-up addresses)
     assert chain(0x500000, 0x510000, [0x500000, 0x510000])[0] == B.EPARA_ERR_CAPACITY
+
+
+def _launches_by_mix():
+    s = mix_group_shapes()          # launches in mix order: 3 of mix 1, 2 of mix 2, 2 of mix 3, 2 of mix 4, 2 of mix 5
+    return {1: [(s[0], False), (s[1], False), (s[2], False)], 2: [(s[3], False), (s[4], False)], 3: [(s[5], False), (s[6], False)],
+            4: [(s[7], True), (s[8], False)], 5: [(s[9], True), (s[10], False)]}
+
+
+LAUNCHES = _launches_by_mix()
+
+
+def _ref_cost(group, tile, classes, n_stream, gated):
+    if tile[5] >= n_stream:
+        return 2040 * group[1]
+    bm = classes[tile[5]][1]
+    return group[1] * (6 * tile[4] * (2 if gated else 1) + (2 * bm if bm >= 32 else 0))
+
+
+@pytest.mark.parametrize("index,dtype", [(4, B.EPARA_BF16), (5, B.EPARA_BF16), (3, B.EPARA_BF16), (2, B.EPARA_BF16), (1, B.EPARA_F32), (4, B.EPARA_FP8_E4M3)])
+def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(index, dtype):
+    """epara_plan_launch on the launches of the benchmark mixes (shapes only).  What any plan must satisfy: the
+    tiles partition every group, the order holds every tile once, lists have no holes.  The choice between the
+    wide and the narrow table and the integers of the chosen plan are also compared with the reference planner
+    run on both tables under the cost model of the header (a transcription check: the same rule typed twice)."""
+    W = 256
+    for groups, gated in LAUNCHES[index]:
+        info, row_off, x_off, y_off, tiles, order = B.epara_plan_launch(_desc(groups, 5 if gated else 0), dtype, W, 8, 1, 4)
+        classes = [tuple(int(v) for v in c) for c in info.class_table()]
+        # validity
+        cover = {g: np.zeros((M, N), dtype=np.int32) for g, (M, K, N) in enumerate(groups) if M}
+        for t in tiles:
+            cover[int(t["group"])][t["m0"]: t["m0"] + t["rows"], t["n0"]: t["n0"] + t["cols"]] += 1
+        assert all(np.all(c == 1) for c in cover.values())
+        o = order.reshape(-1, W)
+        assert sorted(o[o >= 0].tolist()) == list(range(len(tiles)))
+        for b in range(W):
+            col = o[:, b]
+            assert np.all(col[: int((col >= 0).sum())] >= 0)
+        assert row_off[-1] == sum(g[0] for g in groups)
+        # the choice
+        best = None
+        big = dtype != B.EPARA_F32 and max(g[0] for g in groups) > 32
+        for narrow in ((0, 1) if big else (0,)):
+            cls, n_stream = B.epara_kernel_classes(dtype, gated, bool(narrow))
+            cls = [tuple(int(v) for v in c) for c in cls]
+            _, _, _, rt = P.plan_groups(groups, cls)
+            ro = P.schedule_tiles([g + (gated,) for g in groups], cls, n_stream, rt, W, 8, 1, 4)
+            loads = [sum(_ref_cost(groups[rt[t][0]], rt[t], cls, n_stream, gated) for t in ro[b::W] if t >= 0) for b in range(W)]
+            if best is None or max(loads) < best[0]:
+                best = (max(loads), narrow, cls, rt, ro)
+        assert (info.makespan, info.narrow, classes) == best[:3]
+        assert [tuple(int(v) for v in t) for t in tiles] == best[3] and order.tolist() == best[4]
+
+
+def test_plan_chain_picks_tables_jointly_and_writes_waits():
+    """epara_plan_chain on the decode FFN (gate/up then down): both phases may take either table; whatever it
+    picks, the plan is valid, the waits are those of epara_chain_waits, and no other combination finishes
+    earlier under the replay the header describes (run here by the reference scheduler)."""
+    W = 256
+    up, down = [(m, 4096, 11008) for m in (1, 8, 32, 64)], [(m, 11008, 4096) for m in (1, 8, 32, 64)]
+    finish, phases = B.epara_plan_chain([_desc(up, 5), _desc(down, 0)], [None, [0, 1, 2, 3]], B.EPARA_BF16, W, 8, 1, 4)
+    assert [ph["counter_base"] for ph in phases] == [0, 4]
+    want = B.epara_chain_waits(phases[0]["tiles"], 4, 0, [0, 1, 2, 3])
+    assert phases[1]["waits"].tolist() == want.tolist() and phases[0]["waits"] is None
+    for ph, groups in zip(phases, (up, down)):
+        o = ph["order"].reshape(-1, W)
+        assert sorted(o[o >= 0].tolist()) == list(range(len(ph["tiles"])))
+
+    def replay(picks):
+        ref_phases = []
+        for groups, gated, narrow in ((up, True, picks[0]), (down, False, picks[1])):
+            cls, n_stream = B.epara_kernel_classes(B.EPARA_BF16, gated, bool(narrow))
+            cls = [tuple(int(v) for v in c) for c in cls]
+            ref_phases.append(([g + (gated,) for g in groups], cls, n_stream, P.plan_groups(groups, cls)[3]))
+        orders = P.schedule_chain(ref_phases, W, 8, 1, 4)
+        clock, ready_prev = [0] * W, None
+        for p, ((groups, cls, n_stream, tiles), order) in enumerate(zip(ref_phases, orders)):
+            ready = [0] * len(groups)
+            for slot, t in enumerate(order):
+                if t < 0:
+                    continue
+                b, g = slot % W, tiles[t][0]
+                start = max(clock[b], ready_prev[g]) if p else clock[b]
+                clock[b] = start + _ref_cost(groups[g], tiles[t], cls, n_stream, groups[g][3])
+                ready[g] = max(ready[g], clock[b])
+            ready_prev = ready
+        return max(clock)
+
+    all_finishes = {picks: replay(picks) for picks in ((0, 0), (0, 1), (1, 0), (1, 1))}
+    assert finish == min(all_finishes.values())
+    assert all_finishes[(int(phases[0]["info"].narrow), int(phases[1]["info"].narrow))] == finish

@@ -99,12 +99,12 @@ def test_streaming_tiles_are_balanced_longest_first():
     assert len(tiles) == 128 + 128 + 64 + 32
     W = 256
     order = P.schedule_tiles(groups, classes, 3, tiles, W, 8, 8, 4)
-    cost = lambda t: 11008 * (6 * tiles[t][4] + classes[tiles[t][5]][1])     # weight columns, and activation rows at a sixth
+    cost = lambda t: 11008 * (6 * tiles[t][4] + (2 * classes[tiles[t][5]][1] if classes[tiles[t][5]][1] >= 32 else 0))     # weight columns, and activation rows at a third
     loads = [sum(cost(t) for t in order[b::W] if t >= 0) for b in range(W)]
     total = sum(cost(t) for t in range(len(tiles)))
     # greedy longest-first never exceeds the mean by more than one largest tile
-    assert max(loads) <= total / W + 11008 * (6 * 128 + 64)
-    assert max(loads) == 11008 * (6 * 128 + 64)             # a wide tile is all its owner gets
+    assert max(loads) <= total / W + 11008 * (6 * 128 + 128)
+    assert max(loads) == 11008 * (6 * 128 + 128)             # a wide tile is all its owner gets
     # the widest tiles are visited first by whoever owns them
     firsts = [tiles[order[b]][4] for b in range(W)]
     assert sorted(firsts, reverse=True)[:32] == [128] * 32
@@ -112,12 +112,13 @@ def test_streaming_tiles_are_balanced_longest_first():
     narrow = classes[:2] + [(64, 64, 64)] + classes[3:]
     _, _, _, t2 = P.plan_groups(groups, narrow)
     o2 = P.schedule_tiles(groups, narrow, 3, t2, W, 8, 8, 4)
-    loads2 = [sum(11008 * (6 * t2[t][4] + narrow[t2[t][5]][1]) for t in o2[b::W] if t >= 0) for b in range(W)]
-    assert max(loads2) <= 11008 * (6 * 64 + 64 + 6 * 32 + 16) and max(loads2) < 0.6 * max(loads)
+    rows = lambda bm: 2 * bm if bm >= 32 else 0
+    loads2 = [sum(11008 * (6 * t2[t][4] + rows(narrow[t2[t][5]][1])) for t in o2[b::W] if t >= 0) for b in range(W)]
+    assert max(loads2) <= 11008 * (6 * 64 + 128 + 6 * 32) and max(loads2) < 0.6 * max(loads)
     # gated groups stream two weight matrices: the column part of the cost doubles, the row part does not
     o2 = P.schedule_tiles([g + (True,) for g in groups], classes, 3, tiles, W, 8, 8, 4)
-    gcost = lambda t: 11008 * (12 * tiles[t][4] + classes[tiles[t][5]][1])
-    assert max(sum(gcost(t) for t in o2[b::W] if t >= 0) for b in range(W)) == 11008 * (12 * 128 + 64)
+    gcost = lambda t: 11008 * (12 * tiles[t][4] + rows(classes[tiles[t][5]][1]))
+    assert max(sum(gcost(t) for t in o2[b::W] if t >= 0) for b in range(W)) == 11008 * (12 * 128 + 128)
 
 
 def test_schedule_keeps_a_die_on_one_panel():
