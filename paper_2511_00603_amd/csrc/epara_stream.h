@@ -35,6 +35,7 @@ struct skinny_tile_state {
     int KS, K;             // fragments along K, K
     int n_chunks;          // chunks of U steps per wave
     int spw;               // steps per wave: wave w owns the steps w * spw .. (w + 1) * spw - 1
+    int rot;               // where in its range a wave starts (it wraps around): differs from tile to tile
 };
 
 // Activations of a step (two fragments = 128 bytes of K for MB x 16 rows) go through a per-wave LDS
@@ -57,6 +58,11 @@ __device__ __forceinline__ void skinny_setup(skinny_tile_state<NFR>& st, const e
     const int steps = (KS + 1) >> 1;                             // two fragments per step
     st.spw = (steps + 3) >> 2;
     st.n_chunks = (st.spw + U - 1) / U;
+    // Tiles of one group that run at the same time would otherwise ask for the same activation lines (and
+    // the same DRAM pages of their column blocks) at the same moment.  The start depends on the 128-column
+    // span of the output only (every streaming class cuts a span into whole tiles), so a result is still a
+    // function of the operands alone, whatever the class table and the grid.
+    st.rot = static_cast<int>((static_cast<uint32_t>(n0 >> 7) * 2654435761u >> 12) % static_cast<uint32_t>(st.spw));
 #pragma unroll
     for (int f = 0; f < NFR; ++f) {
         // gated: fragments 0 .. NFR/2-1 are gate blocks, the rest the same blocks of the up matrix
@@ -86,7 +92,9 @@ __device__ __forceinline__ void skinny_load(const skinny_tile_state<NFR>& st, in
     ldsptr xslot = (ldsptr)xslot_generic;
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ, KF = 4 * EPC;
-    const int p = wave * st.spw + min(i, st.spw - 1);            // step: fragments 2p and 2p+1 (padding repeats the last step)
+    int pi = min(i, st.spw - 1) + st.rot;                        // padding repeats the last step
+    if (pi >= st.spw) pi -= st.spw;
+    const int p = wave * st.spw + pi;                            // step: fragments 2p and 2p+1
     // activations first: loads complete in issue order, so once the weights of this slot are in
     // their registers the slot's LDS image is complete too
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(st.x), 0, -1, 0x00020000);
@@ -133,7 +141,9 @@ __device__ __forceinline__ void skinny_mma(const skinny_tile_state<NFR>& st, int
             x[e][fm] = *reinterpret_cast<lds_v4i>(xslot + (fm * 16 + r) * 128 + (((e * 4 + q) ^ ((r >> 1) & 7)) << 4));
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-        if (i < st.spw && 2 * (wave * st.spw + i) + e < st.KS) {
+        int pi = i + st.rot;
+        if (pi >= st.spw) pi -= st.spw;
+        if (i < st.spw && 2 * (wave * st.spw + pi) + e < st.KS) {
 #pragma unroll
             for (int f = 0; f < NFR; ++f)
 #pragma unroll
