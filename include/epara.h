@@ -63,8 +63,10 @@ typedef enum { EPARA_CAT_LATENCY = 0, EPARA_CAT_FREQUENCY = 1 } epara_category;
 
 typedef struct { int32_t M, K, N; int32_t act; int32_t has_bias; int32_t category; } epara_group_desc;
 
-/* A group with M <= max_M (first such class wins) is cut into BM x BN output tiles. */
-typedef struct { int32_t max_M; int32_t BM, BN; } epara_tile_class;
+/* A group with M <= max_M (first such class wins) is cut into BM x BN output tiles.  split_K: 0, or the K
+ * from which a single launch visits a weight-streaming tile of this class in two parts of K (see
+ * "Splitting K" below); ignored for the other classes. */
+typedef struct { int32_t max_M; int32_t BM, BN; int32_t split_K; } epara_tile_class;
 
 /* One output tile: rows [m0, m0+rows) x columns [n0, n0+cols) of group `group`. 24 bytes. */
 typedef struct { int32_t group, m0, n0, rows, cols, cls; } epara_tile;
@@ -82,7 +84,7 @@ typedef struct {
     float scale;               /* s = s_x * s_w   (fp8 per-tensor scales; 1 otherwise) */
     float scale2;              /* s2 = s_x * s_w2 (EPARA_ACT_SWIGLU) */
     float out_inv_scale;       /* fp8 output: stored code = sat(RNE(y * out_inv_scale)); else 1 */
-    int32_t reserved;
+    int32_t reserved;          /* split_base[g] of epara_split_layout when the launch has split tiles, else ignored */
 } epara_group_args;
 
 /* Everything one launch needs.  h_* copies let the library validate shapes before it
@@ -97,6 +99,10 @@ typedef struct {
     int64_t n_slots;
     int32_t n_workgroups;             /* the value the order was built for; becomes the grid size */
     int32_t G;
+    void*   d_workspace;              /* device, 256-byte aligned, zeroed once (epara_workspace_init); NULL if n_split_tiles = 0 */
+    int64_t workspace_bytes;
+    int32_t n_split_tiles;            /* streaming tiles whose K is split over several visits (epara_split_layout) */
+    int32_t reserved;
 } epara_launch;
 
 /* ---- chains of launches in one kernel -----------------------------------------------------
@@ -348,9 +354,46 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
 #define EPARA_COST_PER_COLUMN 6
 #define EPARA_COST_PER_ROW 2
 #define EPARA_COST_PANEL 2040
+#define EPARA_COST_PARTIAL 24
+
+/* Splitting K.  A streaming tile of a class with BM >= 32 streams its weights while re-reading BM activation
+ * rows per weight column, which is cheapest with wide tiles; wide tiles of a long K are too coarse to balance,
+ * so the scheduler can cut their K instead: a tile of a streaming class with split_K > 0 and K >= split_K is
+ * visited P = EPARA_SPLIT_PARTS times, each visit multiplying one contiguous part of K (part j of P covers the
+ * steps floor(S j / P) .. floor(S (j+1) / P) - 1 of the S = ceil(K / step) steps of 128 bytes of K).  The visits
+ * leave their sums in a device workspace; a workgroup counts its visits at the tiles' counters when its list
+ * ends, and whoever counts last at a tile adds the parts in index order (a fixed order: the result does not
+ * depend on timing or on the grid) and runs the epilogue.  An entry of the visit order then is
+ * tile | part << 24 | (P - 1) << 28  (P = 1: just the tile; the format leaves room for up to
+ * EPARA_SPLIT_MAX_PARTS).  Only single launches are split (epara_schedule_tiles); the phases of a chain are not.
+ * Every visit costs a few microseconds of its own (another start of the weight stream, the sums' trip through
+ * memory).  Measured on the decode mix: two parts pay for bf16 from K = 8192 on (EPARA_SPLIT_K_BF16, what
+ * epara_kernel_classes puts into the 32- and 64-row classes); four parts, a shorter K, or fp8 (half the bytes
+ * per visit) do not, so the fp8 tables carry split_K = 0. */
+#define EPARA_SPLIT_PARTS 2
+#define EPARA_SPLIT_K_BF16 8192
+#define EPARA_SPLIT_MAX_PARTS 4
+#define EPARA_SPLIT_STRIDE 32768      /* bytes of partial sums per (split tile, part) */
+#define EPARA_ORDER_ENTRY(tile, part, parts) ((int32_t)((tile) | ((part) << 24) | (((parts) - 1) << 28)))
+#define EPARA_ORDER_TILE(entry) ((entry) & 0xFFFFFF)
+
+/* Where the split tiles of a launch meet: split_base[g] (G entries) = index of the first split tile of
+ * group g among all split tiles of the launch (its tiles follow in n0 order), or -1 if the tiles of g are
+ * not split; *n_split_tiles = their number; *workspace_bytes = 256-aligned(4 * n_split_tiles) counters +
+ * n_split_tiles * EPARA_SPLIT_MAX_PARTS * EPARA_SPLIT_STRIDE bytes of partial sums (0 if nothing is split).
+ * The caller writes split_base[g] into epara_group_args.reserved, sets epara_launch.n_split_tiles and
+ * provides the workspace, zeroed once with epara_workspace_init (a launch leaves its counters zero).
+ * More than 2^24 tiles -> ERR_SHAPE. */
+int32_t epara_split_layout(const epara_group_desc* groups, int32_t G,
+                           const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
+                           int32_t* split_base, int32_t* n_split_tiles, int64_t* workspace_bytes);
+
+/* Zeroes a launch workspace (one small kernel on `stream`). */
+int32_t epara_workspace_init(void* d_workspace, int64_t bytes, void* stream);
 
 /* Visit order of the persistent workgroups.  Workgroup b of W = n_workgroups visits slots
- * b, b + W, b + 2W, ...; order[slot] is a tile index or -1 (idle).  Every workgroup gets a list
+ * b, b + W, b + 2W, ...; order[slot] is a tile index (with the part of K in its upper bits when the tile
+ * is split) or -1 (idle).  Every workgroup gets a list
  * of tiles; slot j*W + b holds the j-th entry of workgroup b's list; *n_slots = W * (longest list).
  * The first n_stream_classes classes of the table are weight-streaming classes (small batches,
  * bandwidth bound), the others are panel classes (matrix-core bound).
@@ -360,8 +403,10 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
  *      workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X)  (X = n_xcd), so the
  *      W/X workgroups of one compute die (workgroup b runs on die b mod X) work on neighbouring
  *      tiles and share operands in that die's L2.
- *   2. streaming tiles, longest first: costs as defined above (EPARA_COST_*); tiles by descending
- *      cost (ties: lower tile index) each go to the
+ *   2. streaming tiles, longest first: costs as defined above (EPARA_COST_*); a tile that is split (see
+ *      "Splitting K") gives P items, each of cost / P + EPARA_COST_PARTIAL * BM * cols (* 2 for
+ *      EPARA_ACT_SWIGLU groups; the partial sums it writes and the last visit reads); items by descending
+ *      cost (ties: lower tile index, then lower part) each go to the
  *      workgroup with the smallest accumulated cost (ties: lower workgroup), after that
  *      workgroup's panel tiles.
  * order may be NULL to query *n_slots.  W must be a positive multiple of X;
@@ -396,6 +441,8 @@ typedef struct {
     int32_t gated;                    /* 1: every group is EPARA_ACT_SWIGLU */
     int64_t n_tiles, n_slots;
     int64_t makespan;                 /* cost of the most loaded workgroup under the cost model */
+    int64_t workspace_bytes;          /* of epara_split_layout for the chosen table */
+    int32_t n_split_tiles, reserved;
 } epara_launch_plan;
 
 /* The whole planning decision of one launch (Sec. 3.1: the parallel mode of each task): picks the class
@@ -404,12 +451,13 @@ typedef struct {
  * (epara_plan_groups) and schedules (epara_schedule_tiles) with it.  The groups must be all
  * EPARA_ACT_SWIGLU or none (ERR_DTYPE).  *plan is always written (sizes included); tiles / order are
  * written when given and large enough, else ERR_CAPACITY (give NULL and 0 to ask for the sizes only;
- * that returns EPARA_OK).  row_off / x_off / y_off may be NULL.  Other errors as for the two calls. */
+ * that returns EPARA_OK).  row_off / x_off / y_off and split_base (G entries, epara_split_layout) may be NULL.
+ * Other errors as for the two calls. */
 int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_dtype,
                           int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
                           int64_t* row_off, int64_t* x_off, int64_t* y_off,
                           epara_tile* tiles, int64_t tiles_cap, int32_t* order, int64_t order_cap,
-                          epara_launch_plan* plan);
+                          int32_t* split_base, epara_launch_plan* plan);
 
 /* One phase of epara_plan_chain: in: groups, G, producer (per group the group of the phase before whose
  * output it reads, or -1; NULL: the phase waits for nothing); out: tiles, order, waits (G entries; may
@@ -467,10 +515,10 @@ int32_t epara_ffn_swiglu_args(const epara_ffn_desc* ffn, int32_t G, int32_t in_d
 
 /* ---- device side -------------------------------------------------------------------- */
 
-/* Device workspace that epara_grouped_forward / epara_grouped_ffn_swiglu need for these groups: 0.
- * Partial sums and transposes live in LDS and nothing is split over K across workgroups, so a launch
- * uses no device memory beyond its operands and tables (only epara_grouped_chain has a workspace,
- * epara_chain_workspace_bytes).  -1 for a bad dtype or G < 0. */
+/* An upper bound of the device workspace a launch of these groups needs, whichever class table the plan
+ * picks (epara_plan_launch reports the exact size): the larger of epara_split_layout over the two tables;
+ * 0 when no tile would be split (fp32 launches, batches of at most 16 rows, short K).  -1 for a bad
+ * dtype, G < 0 or a mixture of EPARA_ACT_SWIGLU and other groups. */
 int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype);
 
 /* Bytes of the packed form of a [K,N] weight matrix (fp32: K*N*4, unchanged layout). */

@@ -176,20 +176,21 @@ def place_services(partial, X, X_dot, phi):
 
 
 def pick_class(M, classes):
-    for c, (max_M, _bm, _bn) in enumerate(classes):
-        if M <= max_M:
+    for c, cl in enumerate(classes):
+        if M <= cl[0]:
             return c
     raise ValueError("no tile class admits M=%d" % M)
 
 
 def plan_groups(groups, classes):
-    """groups: list of (M, K, N); classes: list of (max_M, BM, BN) with increasing max_M.
+    """groups: list of (M, K, N); classes: list of (max_M, BM, BN) or (max_M, BM, BN, split_K) with increasing max_M.
 
     Returns (row_off, x_off, y_off, tiles) with tiles a list of 6-tuples.
     """
     prev = -1
-    for max_M, bm, bn in classes:
-        if bm <= 0 or bn <= 0 or max_M <= prev:
+    for cl in classes:
+        max_M, bm, bn = cl[:3]
+        if bm <= 0 or bn <= 0 or max_M <= prev or (len(cl) > 3 and cl[3] < 0):
             raise ValueError("bad tile class table")
         prev = max_M
     row_off, x_off, y_off, tiles = [0], [0], [0], []
@@ -202,11 +203,40 @@ def plan_groups(groups, classes):
         if M == 0:
             continue
         c = pick_class(M, classes)
-        _, bm, bn = classes[c]
+        bm, bn = classes[c][1], classes[c][2]
         for m0 in range(0, M, bm):
             for n0 in range(0, N, bn):
                 tiles.append((g, m0, n0, min(bm, M - m0), min(bn, N - n0), c))
     return row_off, x_off, y_off, tiles
+
+
+def split_parts(K, cls):
+    """Visits a streaming tile of class cls = (max_M, BM, BN[, split_K]) is cut into: two when the class names a
+    K (split_K > 0) and the group's K reaches it (see schedule_tiles)."""
+    return 2 if len(cls) > 3 and cls[3] > 0 and K >= cls[3] else 1
+
+
+def order_entry(tile, part, parts):
+    return tile | (part << 24) | ((parts - 1) << 28)
+
+
+def order_decode(entry):
+    """-> (tile, part, parts) of a non-negative entry of a visit order."""
+    return entry & 0xFFFFFF, (entry >> 24) & 15, ((entry >> 28) & 7) + 1
+
+
+def split_layout(groups, classes, n_stream_classes):
+    """-> (split_base per group, number of split tiles, workspace bytes): see epara_split_layout in the header."""
+    base, n = [], 0
+    for M, K, N in (g[:3] for g in groups):
+        b = -1
+        if M > 0:
+            c = next(i for i, cl in enumerate(classes) if M <= cl[0])
+            if c < n_stream_classes and split_parts(K, classes[c]) > 1:
+                b = n
+                n += -(-M // classes[c][1]) * -(-N // classes[c][2])
+        base.append(b)
+    return base, n, (0 if n == 0 else (n * 4 + 255) // 256 * 256 + n * 4 * 32768)
 
 
 def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
@@ -226,9 +256,11 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        tiles that run together on one die are consecutive in the sequence.
     2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + (2 * BM if BM >= 32 else 0))
        for a streaming tile (weight columns streamed from HBM, plus the activation rows re-read from L2
-       at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  Tiles by descending cost (ties: lower tile index) each go to
-       the workgroup with the smallest accumulated cost (ties: lower workgroup), after that
-       workgroup's panel tiles.
+       at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  In a single launch a
+       streaming tile of a class (max_M, BM, BN, split_K) with split_K > 0 and K >= split_K is visited in P = 2 parts of K, each an
+       item of cost // P + 24 * BM * cols (* 2 if gated) whose order entry is tile | part << 24 | (P - 1) << 28.
+       Items by descending cost (ties: lower tile index, then lower part) each go to the workgroup with the
+       smallest accumulated cost (ties: lower workgroup), after that workgroup's panel tiles.
     """
     return schedule_chain([(groups, classes, n_stream_classes, tiles)], n_workgroups, n_xcd, panel_m, panel_n)[0]
 
@@ -260,7 +292,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
         panel_classes = sorted(range(n_stream_classes, len(classes)), key=lambda c: (-classes[c][1] * classes[c][2], c))
         for c in panel_classes:
             members = sorted({t[0] for t in tiles if t[5] == c}, key=lambda g: (-groups[g][1], g))
-            _, bm, bn = classes[c]
+            bm, bn = classes[c][1], classes[c][2]
             for g in members:
                 M, K, N = groups[g][:3]
                 TM, TN = -(-M // bm), -(-N // bn)
@@ -277,17 +309,24 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
             if tile[5] < n_stream_classes:
                 g = groups[tile[0]]
                 gated = len(g) > 3 and bool(g[3])
-                stream.append((-(g[1] * (6 * tile[4] * (2 if gated else 1) + (2 * classes[tile[5]][1] if classes[tile[5]][1] >= 32 else 0))), p, t))
+                bm = classes[tile[5]][1]
+                cost = g[1] * (6 * tile[4] * (2 if gated else 1) + (2 * bm if bm >= 32 else 0))
+                parts = split_parts(g[1], classes[tile[5]]) if len(phases) == 1 else 1
+                if parts == 1:
+                    stream.append((-cost, p, t, 0, t))
+                else:                                            # a split tile: one item per part of K
+                    each = cost // parts + 24 * bm * tile[4] * (2 if gated else 1)
+                    stream += [(-each, p, t, j, order_entry(t, j, parts)) for j in range(parts)]
     stream.sort()
     heap = [(load[b], b) for b in range(W)]
     heapq.heapify(heap)
-    for negcost, p, t in stream:
+    for negcost, p, _, _, entry in stream:
         ld, b = heapq.heappop(heap)
-        lists[p][b].append(t)
+        lists[p][b].append(entry)
         heapq.heappush(heap, (ld - negcost, b))
     orders = []
     for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
-        assert sum(len(v) for v in lists[p]) == len(tiles)
+        assert sum(len(v) for v in lists[p]) >= len(tiles)
         longest = max(len(v) for v in lists[p])
         order = [-1] * (longest * W)
         for b in range(W):

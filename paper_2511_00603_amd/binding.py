@@ -23,7 +23,7 @@ DTYPE_BYTES = {EPARA_F32: 4, EPARA_BF16: 2, EPARA_FP8_E4M3: 1}
 
 # ---- struct layouts ----------------------------------------------------------------------
 GROUP_DESC = np.dtype([("M", "<i4"), ("K", "<i4"), ("N", "<i4"), ("act", "<i4"), ("has_bias", "<i4"), ("category", "<i4")])
-TILE_CLASS = np.dtype([("max_M", "<i4"), ("BM", "<i4"), ("BN", "<i4")])
+TILE_CLASS = np.dtype([("max_M", "<i4"), ("BM", "<i4"), ("BN", "<i4"), ("split_K", "<i4")])
 TILE = np.dtype([("group", "<i4"), ("m0", "<i4"), ("n0", "<i4"), ("rows", "<i4"), ("cols", "<i4"), ("cls", "<i4")])
 GROUP_ARGS = np.dtype([("X", "<u8"), ("W", "<u8"), ("W2", "<u8"), ("bias", "<u8"), ("Y", "<u8"),
                        ("M", "<i4"), ("K", "<i4"), ("N", "<i4"), ("act", "<i4"),
@@ -38,18 +38,19 @@ assert SIM_REQUEST.itemsize == 32
 EPARA_MAX_CHAIN_PHASES = 4
 EPARA_STATIC_CHAIN_COUNTERS = 4092
 assert CHAIN_WAIT.itemsize == 8
-assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 12 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
+assert GROUP_DESC.itemsize == 24 and TILE_CLASS.itemsize == 16 and TILE.itemsize == 24 and SEGMENT.itemsize == 40
 assert GROUP_ARGS.itemsize == 72 and FFN_DESC.itemsize == 80
 
 
 class LaunchPlanInfo(ctypes.Structure):
     """struct epara_launch_plan."""
-    _fields_ = [("classes", ctypes.c_int32 * 12), ("n_classes", ctypes.c_int32), ("n_stream_classes", ctypes.c_int32),
+    _fields_ = [("classes", ctypes.c_int32 * 16), ("n_classes", ctypes.c_int32), ("n_stream_classes", ctypes.c_int32),
                 ("narrow", ctypes.c_int32), ("gated", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
-                ("makespan", ctypes.c_int64)]
+                ("makespan", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64), ("n_split_tiles", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
     def class_table(self):
-        return np.array(list(self.classes), dtype=np.int32)[: 3 * self.n_classes].view(TILE_CLASS).copy()
+        return np.array(list(self.classes), dtype=np.int32)[: 4 * self.n_classes].view(TILE_CLASS).copy()
 
 
 class ChainPlanPhase(ctypes.Structure):
@@ -64,10 +65,12 @@ class Launch(ctypes.Structure):
     _fields_ = [("h_args", ctypes.c_void_p), ("d_args", ctypes.c_void_p),
                 ("h_tiles", ctypes.c_void_p), ("d_tiles", ctypes.c_void_p), ("d_order", ctypes.c_void_p),
                 ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
-                ("n_workgroups", ctypes.c_int32), ("G", ctypes.c_int32)]
+                ("n_workgroups", ctypes.c_int32), ("G", ctypes.c_int32),
+                ("d_workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64), ("n_split_tiles", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
-assert ctypes.sizeof(Launch) == 64
+assert ctypes.sizeof(Launch) == 88
 
 
 class SimConfig(ctypes.Structure):
@@ -165,7 +168,13 @@ def lib():
         for name in ("epara_schedule_chain", "epara_chain_waits", "epara_chain_workspace_init", "epara_grouped_chain",
                      "epara_chain_status", "epara_grouped_chain_static"):
             getattr(L, name).restype = i32
-        L.epara_plan_launch.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i64, vp]
+        L.epara_plan_launch.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, i64, vp, i64, vp, vp]
+        L.epara_split_layout.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
+        L.epara_split_layout.restype = i32
+        L.epara_workspace_init.argtypes = [vp, i64, vp]
+        L.epara_workspace_init.restype = i32
+        L.epara_workspace_bytes.argtypes = [vp, i32, i32]
+        L.epara_workspace_bytes.restype = i64
         L.epara_plan_launch.restype = i32
         L.epara_plan_chain.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp]
         L.epara_plan_chain.restype = i32
@@ -351,19 +360,40 @@ def epara_workspace_bytes(groups, in_dtype):
 
 
 def epara_plan_launch(groups, in_dtype, n_workgroups, n_xcd=8, panel_m=1, panel_n=4):
-    """-> (info: LaunchPlanInfo, row_off, x_off, y_off, tiles, order): the library's whole planning decision of a launch."""
+    """-> (info: LaunchPlanInfo, row_off, x_off, y_off, tiles, order, split_base): the library's whole planning decision of a launch."""
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
     G = len(groups)
     gp = _ptr(groups) if G else None
     info = LaunchPlanInfo()
     _check(lib().epara_plan_launch(gp, G, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, None, None, None, None, 0, None, 0,
-                                   ctypes.addressof(info)), "epara_plan_launch")
+                                   None, ctypes.addressof(info)), "epara_plan_launch")
     row_off, x_off, y_off = (np.zeros(G + 1, dtype=np.int64) for _ in range(3))
     tiles, order = np.zeros(info.n_tiles, dtype=TILE), np.zeros(info.n_slots, dtype=np.int32)
+    split_base = np.full(G, -1, dtype=np.int32)
     _check(lib().epara_plan_launch(gp, G, int(in_dtype), n_workgroups, n_xcd, panel_m, panel_n, _ptr(row_off), _ptr(x_off), _ptr(y_off),
                                    _ptr(tiles) if len(tiles) else None, len(tiles), _ptr(order) if len(order) else None, len(order),
-                                   ctypes.addressof(info)), "epara_plan_launch")
-    return info, row_off, x_off, y_off, tiles, order
+                                   _ptr(split_base) if G else None, ctypes.addressof(info)), "epara_plan_launch")
+    return info, row_off, x_off, y_off, tiles, order, split_base
+
+
+def epara_split_layout(groups, classes, n_stream_classes):
+    """-> (split_base [G], n_split_tiles, workspace_bytes)."""
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
+    base = np.full(len(groups), -1, dtype=np.int32)
+    n, nbytes = ctypes.c_int32(0), ctypes.c_int64(0)
+    _check(lib().epara_split_layout(_ptr(groups) if len(groups) else None, len(groups), _ptr(classes), len(classes), int(n_stream_classes),
+                                    _ptr(base) if len(base) else None, ctypes.byref(n), ctypes.byref(nbytes)), "epara_split_layout")
+    return base, int(n.value), int(nbytes.value)
+
+
+def epara_workspace_bytes(groups, in_dtype):
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    return int(lib().epara_workspace_bytes(_ptr(groups) if len(groups) else None, len(groups), int(in_dtype)))
+
+
+def epara_workspace_init(d_workspace, nbytes, stream=0):
+    _check(lib().epara_workspace_init(int(d_workspace), int(nbytes), int(stream) or None), "epara_workspace_init")
 
 
 def epara_plan_chain(phase_groups, producers, in_dtype, n_workgroups, n_xcd=8, panel_m=1, panel_n=4):

@@ -326,6 +326,36 @@ __device__ __forceinline__ void chain_exit(chain_ctx& c, int n_counters)
 
 constexpr int N_STREAM_CLASSES = 3;
 
+// An entry of the visit order: bits 0..23 the tile, bits 24..27 which part of K this visit multiplies,
+// bits 28..30 the number of parts minus one (0: the whole K, the common case); negative: idle.
+__device__ __forceinline__ int order_tile(int o)  { return o & 0xFFFFFF; }
+__device__ __forceinline__ int order_part(int o)  { return (o >> 24) & 15; }
+__device__ __forceinline__ int order_parts(int o) { return ((o >> 28) & 7) + 1; }
+
+// Streaming tiles whose K is split over several visits (possibly of different workgroups) meet in a
+// device workspace: one arrival counter per split tile, then, 256-byte aligned, SPLIT_MAX_PARTS x
+// SPLIT_STRIDE bytes of partial sums per split tile.  The visit that arrives last adds the parts in index order and
+// runs the epilogue, so the result does not depend on who that is.
+constexpr int SPLIT_STRIDE = EPARA_SPLIT_STRIDE, SPLIT_MAX_PARTS = EPARA_SPLIT_MAX_PARTS;
+struct split_ctx { uint32_t* ws; int n_split; };
+__device__ __forceinline__ char* split_partials(const split_ctx& sp) { return reinterpret_cast<char*>(sp.ws) + ((sp.n_split * 4 + 255) & ~255); }
+__device__ __forceinline__ void split_put(char* at, const v4f& v)     // through to memory: another die reads it
+{
+    typedef unsigned long long u64;
+    const u64 lo = (static_cast<u64>(__float_as_uint(v[1])) << 32) | __float_as_uint(v[0]);
+    const u64 hi = (static_cast<u64>(__float_as_uint(v[3])) << 32) | __float_as_uint(v[2]);
+    __hip_atomic_store(reinterpret_cast<u64*>(at), lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<u64*>(at) + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ v4f split_get(const char* at)
+{
+    typedef unsigned long long u64;
+    const u64 lo = __hip_atomic_load(reinterpret_cast<const u64*>(at), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u64 hi = __hip_atomic_load(reinterpret_cast<const u64*>(at) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v4f{__uint_as_float(static_cast<uint32_t>(lo)), __uint_as_float(static_cast<uint32_t>(lo >> 32)),
+               __uint_as_float(static_cast<uint32_t>(hi)), __uint_as_float(static_cast<uint32_t>(hi >> 32))};
+}
+
 }  // namespace
 
 #endif

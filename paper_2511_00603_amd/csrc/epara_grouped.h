@@ -18,41 +18,99 @@ namespace {
 // Streaming classes: (row blocks, weight column blocks, ring depth) = (1, 2, 4), (2, 4, 3) and
 // (4, 8, 2) or, in a launch planned with the narrow table, (4, 4, 3).  PANEL_ONLY: the launch holds
 // no streaming tile (checked on the host), so the kernel carries no code for them.
+// Counts the workgroup's visits to split tiles at the tiles' counters (one atomic instruction for all of
+// them) and finishes the tiles at which it arrived last.  Every partial sum of the workgroup is in memory
+// before the count says so; whoever finishes a tile puts its counter back to zero for the next launch.
+template <int DT, bool GATED>
+__device__ __forceinline__ void split_flush(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
+                                            int out_dtype, int narrow, char* lds, const split_ctx* sp, split_pending& pend)
+{
+    if (pend.count == 0) return;
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    wait_vmcnt<0>();
+    __syncthreads();
+    __attribute__((address_space(3))) uint32_t* box = (__attribute__((address_space(3))) uint32_t*)(ldsptr)lds;
+    if (wave == 0) {
+        const bool mine = lane < pend.count;
+        uint32_t before = 0;
+        if (mine) before = __hip_atomic_fetch_add(sp->ws + (pend.slots & 0xFFFFFFF), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long last = __ballot(mine && before == (static_cast<uint32_t>(pend.slots) >> 28));
+        if (lane == 0) { box[0] = static_cast<uint32_t>(last); box[1] = static_cast<uint32_t>(last >> 32); }
+    }
+    __syncthreads();
+    unsigned long long last = (static_cast<unsigned long long>(box[1]) << 32) | box[0];
+    last = (static_cast<unsigned long long>(__builtin_amdgcn_readfirstlane(static_cast<int>(last >> 32))) << 32) |
+           static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(last)));
+    __syncthreads();                                             // the box's place in LDS is free again
+    while (last) {
+        const int i = __builtin_ctzll(last);
+        last &= last - 1;
+        const int entry = __builtin_amdgcn_readlane(pend.entries, i);
+        const int info = __builtin_amdgcn_readlane(pend.slots, i);
+        const int slot = info & 0xFFFFFFF, nparts = (static_cast<uint32_t>(info) >> 28) + 1;
+        const epara_tile tl = tiles[order_tile(entry)];
+        const epara_group_args ga = args[tl.group];
+        if (tl.cls == 1)                 split_finish<DT, GATED, 2, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+        else if (tl.cls == 2 && !narrow) split_finish<DT, GATED, 4, 8>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+        else if (tl.cls == 2)            split_finish<DT, GATED, 4, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+        if (tid == 0) __hip_atomic_store(sp->ws + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();                                         // the next tile's parts land where these were read
+    }
+    pend.count = 0;
+}
+
 template <int DT, bool GATED, bool CHAIN, bool PANEL_ONLY>
 __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
                                              const int32_t* __restrict__ order, long n_slots, int out_dtype, int narrow, char* lds,
-                                             chain_ctx* chain = nullptr)
+                                             chain_ctx* chain = nullptr, const split_ctx* sp = nullptr)
 {
     const long stride = gridDim.x;
     long s = blockIdx.x;
+    split_pending pend = {0, 0, 0};
+    run_next nx = {};
     while (s < n_slots) {
-        const int t = order[s];
-        if (t < 0) { s += stride; continue; }
-        const epara_tile tl = tiles[t];
+        int t;
+        epara_tile tl;
+        const bool known = nx.known;                             // the run before has read this slot already
+        if (known) { t = nx.entry; tl = nx.tl; }
+        else {
+            t = order[s];
+            if (t < 0) { s += stride; continue; }
+            tl = tiles[order_tile(t)];
+        }
+        nx.known = false;
         if constexpr (CHAIN) chain_wait(*chain, tl.group);
         if constexpr (!PANEL_ONLY) {
-            if (tl.cls == 0)      { s = skinny_run<DT, GATED, CHAIN, 0, 1, 2, 4>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain); continue; }
-            else if (tl.cls == 1) { s = skinny_run<DT, GATED, CHAIN, 1, 2, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain); continue; }
-            else if (tl.cls == 2 && !narrow) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 8, 2>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain); continue; }
-            else if (tl.cls == 2) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain); continue; }
+            if constexpr (!CHAIN && DT == EPARA_BF16) { if (pend.count >= 63) split_flush<DT, GATED>(args, tiles, out_dtype, narrow, lds, sp, pend); }
+            const epara_group_args ga0 = nx.ga;
+            if (tl.cls == 0)      { s = skinny_run<DT, GATED, CHAIN, 0, 1, 2, 4>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
+            else if (tl.cls == 1) { s = skinny_run<DT, GATED, CHAIN, 1, 2, 4, 3>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
+            else if (tl.cls == 2 && !narrow) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 8, 2>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
+            else if (tl.cls == 2) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
         }
         s = panel_run<DT, GATED, CHAIN, CHAIN>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
+        nx = run_next{};                                         // nothing is carried across a panel run
     }
+    if constexpr (!PANEL_ONLY && !CHAIN && DT == EPARA_BF16) split_flush<DT, GATED>(args, tiles, out_dtype, narrow, lds, sp, pend);
 }
 
 template <int DT, bool GATED, bool PANEL_ONLY>
 __global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
                                                      const epara_tile* __restrict__ tiles,
                                                      const int32_t* __restrict__ order,
-                                                     long n_slots, int out_dtype, int narrow)
+                                                     long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    grouped_body<DT, GATED, false, PANEL_ONLY>(args, tiles, order, n_slots, out_dtype, narrow, lds);
+    const split_ctx sp = {split_ws, n_split};
+    grouped_body<DT, GATED, false, PANEL_ONLY>(args, tiles, order, n_slots, out_dtype, narrow, lds, nullptr, &sp);
 }
 
 template <int DT, bool GATED>
 hipError_t enqueue_grouped(int panel_only, unsigned grid, hipStream_t stream, const epara_group_args* args, const epara_tile* tiles,
-                           const int32_t* order, long n_slots, int out_dtype, int narrow)
+                           const int32_t* order, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split)
 {
     static const hipError_t attr0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<DT, GATED, false>),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -61,9 +119,9 @@ hipError_t enqueue_grouped(int panel_only, unsigned grid, hipStream_t stream, co
     if (attr0 != hipSuccess) return attr0;
     if (attr1 != hipSuccess) return attr1;
     if (panel_only)
-        hipLaunchKernelGGL((grouped_kernel<DT, GATED, true>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow);
+        hipLaunchKernelGGL((grouped_kernel<DT, GATED, true>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split);
     else
-        hipLaunchKernelGGL((grouped_kernel<DT, GATED, false>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow);
+        hipLaunchKernelGGL((grouped_kernel<DT, GATED, false>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split);
     return hipGetLastError();
 }
 

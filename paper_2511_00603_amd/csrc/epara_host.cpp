@@ -34,7 +34,7 @@ int32_t check_classes(const epara_tile_class* classes, int32_t n_classes)
     if (!classes) return EPARA_ERR_NULL;
     if (n_classes <= 0) return EPARA_ERR_SHAPE;
     for (int32_t c = 0; c < n_classes; ++c) {
-        if (classes[c].BM <= 0 || classes[c].BN <= 0) return EPARA_ERR_SHAPE;
+        if (classes[c].BM <= 0 || classes[c].BN <= 0 || classes[c].split_K < 0) return EPARA_ERR_SHAPE;
         if (c > 0 && classes[c].max_M <= classes[c - 1].max_M) return EPARA_ERR_SHAPE;
     }
     return EPARA_OK;
@@ -45,6 +45,26 @@ int32_t class_of(int32_t M, const epara_tile_class* classes, int32_t n_classes)
     for (int32_t c = 0; c < n_classes; ++c)
         if (M <= classes[c].max_M) return c;
     return -1;
+}
+
+int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
+{
+    int32_t n_gated = 0, n_live = 0;
+    for (int32_t g = 0; g < G; ++g)
+        if (groups[g].M > 0) { ++n_live; n_gated += groups[g].act == EPARA_ACT_SWIGLU; }
+    if (n_gated != 0 && n_gated != n_live) return EPARA_ERR_DTYPE;
+    *gated = n_gated > 0;
+    return EPARA_OK;
+}
+
+
+inline int32_t split_parts(const epara_group_desc& d, const epara_tile_class& c) { return c.split_K > 0 && d.K >= c.split_K ? EPARA_SPLIT_PARTS : 1; }
+
+// Cost of one of the `parts` visits of a tile whose whole cost is `cost`: its share of K plus the partial result it leaves.
+inline int64_t visit_cost(int64_t cost, int32_t parts, const epara_group_desc& d, const epara_tile& t, const epara_tile_class& c)
+{
+    if (parts == 1) return cost;
+    return cost / parts + static_cast<int64_t>(EPARA_COST_PARTIAL) * c.BM * t.cols * (d.act == EPARA_ACT_SWIGLU ? 2 : 1);
 }
 
 }  // namespace
@@ -520,7 +540,14 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
         const epara_phase_schedule& ph = phases[p];
         for (int64_t t = 0; t < ph.n_tiles; ++t)
             if (ph.tiles[t].cls < ph.n_stream_classes) {
-                stream.push_back({tile_cost(ph.groups[ph.tiles[t].group], ph.tiles[t], ph.classes, ph.n_stream_classes), p, static_cast<int32_t>(t)});
+                const epara_group_desc& d = ph.groups[ph.tiles[t].group];
+                const epara_tile_class& c = ph.classes[ph.tiles[t].cls];
+                const int64_t cost = tile_cost(d, ph.tiles[t], ph.classes, ph.n_stream_classes);
+                const int32_t parts = n_phases == 1 ? split_parts(d, c) : 1;       // the phases of a chain are not split
+                if (parts == 1) { stream.push_back({cost, p, static_cast<int32_t>(t)}); continue; }
+                if (ph.n_tiles > 0xFFFFFF) return EPARA_ERR_SHAPE;
+                const int64_t each = visit_cost(cost, parts, d, ph.tiles[t], c);
+                for (int32_t j = 0; j < parts; ++j) stream.push_back({each, p, EPARA_ORDER_ENTRY(static_cast<int32_t>(t), j, parts)});
             }
     }
     std::stable_sort(stream.begin(), stream.end(), [](const item& a, const item& b) { return a.cost > b.cost; });
@@ -539,7 +566,7 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
         epara_phase_schedule& ph = phases[p];
         size_t longest = 0, total = 0;
         for (const auto& v : lists[p]) { longest = std::max(longest, v.size()); total += v.size(); }
-        if (static_cast<int64_t>(total) != ph.n_tiles) return EPARA_ERR_SHAPE;
+        if (static_cast<int64_t>(total) < ph.n_tiles) return EPARA_ERR_SHAPE;
         ph.n_slots = static_cast<int64_t>(longest) * W;
         if (!ph.order) continue;
         if (ph.order_cap < ph.n_slots) { status = EPARA_ERR_CAPACITY; continue; }
@@ -576,16 +603,6 @@ struct phase_option {
     int32_t n_classes = 0, n_stream = 0, narrow = 0;
     std::vector<epara_tile> tiles;
 };
-
-int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
-{
-    int32_t n_gated = 0, n_live = 0;
-    for (int32_t g = 0; g < G; ++g)
-        if (groups[g].M > 0) { ++n_live; n_gated += groups[g].act == EPARA_ACT_SWIGLU; }
-    if (n_gated != 0 && n_gated != n_live) return EPARA_ERR_DTYPE;
-    *gated = n_gated > 0;
-    return EPARA_OK;
-}
 
 int32_t phase_options(const epara_group_desc* groups, int32_t G, int32_t in_dtype, std::vector<phase_option>& out)
 {
@@ -669,13 +686,14 @@ int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32
             const int64_t rows = sched[p].n_slots / W;
             for (int64_t j = 0; j < rows; ++j)
                 for (int64_t b = 0; b < W; ++b) {
-                    const int32_t t = order[p][static_cast<size_t>(j * W + b)];
-                    if (t < 0) continue;
-                    const epara_tile& tl = o.tiles[t];
+                    const int32_t e = order[p][static_cast<size_t>(j * W + b)];
+                    if (e < 0) continue;
+                    const epara_tile& tl = o.tiles[EPARA_ORDER_TILE(e)];
                     int64_t start = clock[b];
                     if (p > 0 && phases[p].producer && phases[p].producer[tl.group] >= 0)
                         start = std::max(start, ready_prev[phases[p].producer[tl.group]]);
-                    clock[b] = start + tile_cost(phases[p].groups[tl.group], tl, o.classes, o.n_stream);
+                    clock[b] = start + visit_cost(tile_cost(phases[p].groups[tl.group], tl, o.classes, o.n_stream), (e >> 28) + 1,
+                                                  phases[p].groups[tl.group], tl, o.classes[tl.cls]);
                     ready[tl.group] = std::max(ready[tl.group], clock[b]);
                 }
             ready_prev.swap(ready);
@@ -695,8 +713,10 @@ int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32
         std::vector<int64_t> load(static_cast<size_t>(W), 0);
         for (size_t i = 0; i < best_order[p].size(); ++i)
             if (best_order[p][i] >= 0) {
-                const epara_tile& tl = o.tiles[best_order[p][i]];
-                load[i % W] += tile_cost(ph.groups[tl.group], tl, o.classes, o.n_stream);
+                const int32_t e = best_order[p][i];
+                const epara_tile& tl = o.tiles[EPARA_ORDER_TILE(e)];
+                load[i % W] += visit_cost(tile_cost(ph.groups[tl.group], tl, o.classes, o.n_stream), (e >> 28) + 1, ph.groups[tl.group], tl,
+                                          o.classes[tl.cls]);
             }
         fill_plan(ph.plan, o, gated[p], static_cast<int64_t>(best_order[p].size()), *std::max_element(load.begin(), load.end()));
         ph.counter_base = base;
@@ -725,7 +745,7 @@ int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_
                           int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
                           int64_t* row_off, int64_t* x_off, int64_t* y_off,
                           epara_tile* tiles, int64_t tiles_cap, int32_t* order, int64_t order_cap,
-                          epara_launch_plan* plan)
+                          int32_t* split_base, epara_launch_plan* plan)
 {
     if (!plan) return EPARA_ERR_NULL;
     epara_chain_plan_phase ph;
@@ -734,6 +754,8 @@ int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_
     const int32_t st = epara_plan_chain(&ph, 1, in_dtype, n_workgroups, n_xcd, panel_m, panel_n, nullptr);
     if (st != EPARA_OK && st != EPARA_ERR_CAPACITY) return st;
     *plan = ph.plan;
+    if (int32_t s3 = epara_split_layout(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, split_base,
+                                        &plan->n_split_tiles, &plan->workspace_bytes)) return s3;
     if (row_off || x_off || y_off) {
         int64_t n = 0;
         if (int32_t s2 = epara_plan_groups(groups, G, plan->classes, plan->n_classes, row_off, x_off, y_off, nullptr, 0, &n)) return s2;
@@ -763,11 +785,52 @@ int32_t epara_chain_waits(const epara_tile* producer_tiles, int64_t n_producer_t
     return EPARA_OK;
 }
 
+int32_t epara_split_layout(const epara_group_desc* groups, int32_t G,
+                           const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
+                           int32_t* split_base, int32_t* n_split_tiles, int64_t* workspace_bytes)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (!n_split_tiles || !workspace_bytes || (G > 0 && !groups)) return EPARA_ERR_NULL;
+    if (int32_t st = check_classes(classes, n_classes)) return st;
+    if (n_stream_classes < 0 || n_stream_classes > n_classes) return EPARA_ERR_SHAPE;
+    int64_t n = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_group_desc& d = groups[g];
+        if (d.M < 0 || d.K <= 0 || d.N <= 0) return EPARA_ERR_SHAPE;
+        int32_t base = -1;
+        if (d.M > 0) {
+            const int32_t c = class_of(d.M, classes, n_classes);
+            if (c < 0) return EPARA_ERR_SHAPE;
+            if (c < n_stream_classes && split_parts(d, classes[c]) > 1) {
+                base = static_cast<int32_t>(n);
+                n += ceil_div(d.M, classes[c].BM) * ceil_div(d.N, classes[c].BN);
+            }
+        }
+        if (split_base) split_base[g] = base;
+    }
+    if (n > 0xFFFFFF) return EPARA_ERR_SHAPE;
+    *n_split_tiles = static_cast<int32_t>(n);
+    *workspace_bytes = n == 0 ? 0 : (n * 4 + 255) / 256 * 256 + n * EPARA_SPLIT_MAX_PARTS * static_cast<int64_t>(EPARA_SPLIT_STRIDE);
+    return EPARA_OK;
+}
+
 int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype)
 {
-    (void)groups;
     if (G < 0 || (in_dtype != EPARA_F32 && in_dtype != EPARA_BF16 && in_dtype != EPARA_FP8_E4M3)) return -1;
-    return 0;
+    if (G > 0 && !groups) return -1;
+    if (in_dtype == EPARA_F32) return 0;
+    int32_t gated = 0;
+    if (gated_of(groups, G, &gated) != EPARA_OK) return -1;
+    int64_t worst = 0;
+    for (int narrow = 0; narrow < 2; ++narrow) {
+        epara_tile_class classes[4];
+        int32_t nc = 0, ns = 0, n_split = 0;
+        int64_t bytes = 0;
+        if (epara_kernel_classes(in_dtype, gated, narrow, classes, 4, &nc, &ns) != EPARA_OK) return -1;
+        if (epara_split_layout(groups, G, classes, nc, ns, nullptr, &n_split, &bytes) != EPARA_OK) return -1;
+        worst = std::max(worst, bytes);
+    }
+    return worst;
 }
 
 int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
@@ -779,16 +842,17 @@ int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
     int32_t n = 0, ns = 0;
     if (in_dtype == EPARA_F32) {
         if (gated) return EPARA_ERR_DTYPE;
-        table[n++] = {16, 16, 64};          // K split over the four waves of a workgroup
-        table[n++] = {INT32_MAX, 64, 64};
+        table[n++] = {16, 16, 64, 0};       // K split over the four waves of a workgroup
+        table[n++] = {INT32_MAX, 64, 64, 0};
     } else if (in_dtype == EPARA_BF16 || in_dtype == EPARA_FP8_E4M3) {
         // weight-streaming classes: the whole batch (1, 2 or 4 blocks of 16 rows) against 2, 4 or 8
         // weight column blocks, so that activations re-read per weight byte stay constant
-        table[n++] = {16, 16, gated ? 16 : 32};
-        table[n++] = {32, 32, gated ? 32 : 64};
-        table[n++] = {64, 64, (gated ? 64 : 128) >> (narrow ? 1 : 0)};
+        const int32_t split_K = in_dtype == EPARA_BF16 ? EPARA_SPLIT_K_BF16 : 0;   // where two visits pay (measured)
+        table[n++] = {16, 16, gated ? 16 : 32, 0};
+        table[n++] = {32, 32, gated ? 32 : 64, split_K};
+        table[n++] = {64, 64, (gated ? 64 : 128) >> (narrow ? 1 : 0), split_K};
         ns = 3;
-        table[n++] = {INT32_MAX, 256, gated ? 128 : 256};  // LDS-tiled MFMA class
+        table[n++] = {INT32_MAX, 256, gated ? 128 : 256, 0};  // LDS-tiled MFMA class
     } else {
         return EPARA_ERR_DTYPE;
     }

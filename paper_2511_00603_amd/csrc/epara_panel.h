@@ -58,7 +58,9 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
     constexpr int KF = 4 * EPC;     // K elements per stage
-    const int tid = threadIdx.x, lane = tid & 63;
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));                               // what is derived from it is computed per run (see skinny_run)
+    const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r32 = lane & 31, h = lane >> 5;
     ldsptr l3 = (ldsptr)lds;
@@ -72,7 +74,7 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
         w.slot += stride;
         int t = w.slot < n_slots ? order[w.slot] : -1;
         if (t >= 0) {
-            const epara_tile tl = tiles[t];
+            const epara_tile tl = tiles[order_tile(t)];          // (an entry of a streaming tile may name a part of K)
             bool ok = tl.cls >= N_STREAM_CLASSES;
             if constexpr (CHAIN) {
                 if (ok && chain->waits != nullptr && tl.group != group) {
@@ -84,7 +86,7 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
         }
         w.t = t;
     };
-    const panel_walker first = {slot0, order[slot0], tiles[order[slot0]]};
+    const panel_walker first = {slot0, order[slot0], tiles[order_tile(order[slot0])]};
 
     // ---- activation loader: wave w fetches rows 64 w + 8 j + lane / 8 with instruction j = 0..7 of a pair;
     // lane l writes LDS slot l % 8 of its row and fetches the global chunk that belongs there.

@@ -88,18 +88,26 @@ class LaunchPlan:
             n_workgroups = n_compute_units(device)
             n_workgroups -= n_workgroups % n_xcd
         self.n_workgroups = n_workgroups
-        info, self.row_off, self.x_off, self.y_off, self.tiles, self.order = B.epara_plan_launch(
+        info, self.row_off, self.x_off, self.y_off, self.tiles, self.order, split_base = B.epara_plan_launch(
             self.groups, in_dtype, n_workgroups, n_xcd, panel_m, panel_n)
+        self.n_split_tiles, self.workspace_bytes = int(info.n_split_tiles), int(info.workspace_bytes)
+        if self.n_split_tiles:                               # where each group's split tiles meet in the workspace
+            self.args["reserved"] = split_base
         self.makespan, self.narrow, self.classes, self.n_stream_classes = info.makespan, bool(info.narrow), info.class_table(), info.n_stream_classes
         self.plan_seconds = time.perf_counter() - t0
         t0 = time.perf_counter()
         self.d_args = _upload(self.args, device)
         self.d_tiles = _upload(self.tiles, device)
         self.d_order = _upload(self.order, device)
+        self.d_workspace = None
+        if self.n_split_tiles:
+            self.d_workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+            B.epara_workspace_init(self.d_workspace.data_ptr(), self.workspace_bytes, current_stream_handle())
         torch.cuda.synchronize(device)
         self.upload_seconds = time.perf_counter() - t0
         self.c = B.Launch(self.args.ctypes.data, self.d_args.data_ptr(), self.tiles.ctypes.data, self.d_tiles.data_ptr(),
-                          self.d_order.data_ptr(), len(self.tiles), len(self.order), n_workgroups, G)
+                          self.d_order.data_ptr(), len(self.tiles), len(self.order), n_workgroups, G,
+                          None if self.d_workspace is None else self.d_workspace.data_ptr(), self.workspace_bytes, self.n_split_tiles, 0)
 
 
 class _Phase:
@@ -142,7 +150,7 @@ class ChainPlan:
             ph.d_args, ph.d_tiles, ph.d_order = _upload(ph.args, device), _upload(ph.tiles, device), _upload(ph.order, device)
             ph.d_waits = None if ph.waits is None else _upload(ph.waits, device)
             ph.c = B.Launch(ph.args.ctypes.data, ph.d_args.data_ptr(), ph.tiles.ctypes.data, ph.d_tiles.data_ptr(),
-                            ph.d_order.data_ptr(), len(ph.tiles), len(ph.order), n_workgroups, len(ph.args))
+                            ph.d_order.data_ptr(), len(ph.tiles), len(ph.order), n_workgroups, len(ph.args), None, 0, 0, 0)
             self._launches.append(ph.c)
             self.c[p].launch = ctypes.pointer(ph.c)
             self.c[p].h_waits = None if ph.waits is None else ph.waits.ctypes.data

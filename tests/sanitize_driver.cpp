@@ -90,21 +90,34 @@ int main()
             for (int which = 0; which < 2; ++which) {
                 const std::vector<epara_group_desc>& groups = which ? down : up;
                 epara_launch_plan plan;
-                CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, nullptr, nullptr, nullptr, nullptr, 0, nullptr, 0, &plan) == EPARA_OK);
+                CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, nullptr, nullptr, nullptr, nullptr, 0, nullptr, 0, nullptr, &plan) == EPARA_OK);
                 std::vector<epara_tile> tiles(static_cast<size_t>(plan.n_tiles));
                 std::vector<int32_t> order(static_cast<size_t>(plan.n_slots));
                 std::vector<int64_t> row_off(G + 1);
+                std::vector<int32_t> split_base(static_cast<size_t>(G));
                 CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, row_off.data(), nullptr, nullptr, tiles.data(), plan.n_tiles - 1,
-                                        order.data(), plan.n_slots, &plan) == EPARA_ERR_CAPACITY);
+                                        order.data(), plan.n_slots, split_base.data(), &plan) == EPARA_ERR_CAPACITY);
                 CHECK(epara_plan_launch(groups.data(), G, EPARA_BF16, 256, 8, 1, 4, row_off.data(), nullptr, nullptr, tiles.data(), plan.n_tiles,
-                                        order.data(), plan.n_slots, &plan) == EPARA_OK);
+                                        order.data(), plan.n_slots, split_base.data(), &plan) == EPARA_OK);
                 CHECK(plan.gated == (which ? 0 : 1) && plan.n_classes == 4 && plan.makespan > 0);
                 std::vector<int64_t> area(static_cast<size_t>(G), 0);
                 for (const epara_tile& t : tiles) { CHECK(t.rows >= 1 && t.cols >= 1 && t.m0 + t.rows <= groups[t.group].M && t.n0 + t.cols <= groups[t.group].N); area[t.group] += static_cast<int64_t>(t.rows) * t.cols; }
                 for (int32_t g = 0; g < G; ++g) CHECK(area[g] == static_cast<int64_t>(groups[g].M) * groups[g].N);
-                std::vector<char> seen(tiles.size(), 0);
-                for (int32_t t : order) if (t >= 0) { CHECK(static_cast<size_t>(t) < tiles.size() && !seen[t]); seen[t] = 1; }
-                for (char c : seen) CHECK(c);
+                std::vector<int32_t> seen(tiles.size(), 0), parts(tiles.size(), 0);   // bit j of seen[t]: part j of tile t was visited
+                for (int32_t e : order) if (e >= 0) {
+                    const int32_t t = EPARA_ORDER_TILE(e), j = (e >> 24) & 15, n = (e >> 28) + 1;
+                    CHECK(static_cast<size_t>(t) < tiles.size() && j < n && !(seen[t] >> j & 1) && (parts[t] == 0 || parts[t] == n));
+                    seen[t] |= 1 << j; parts[t] = n;
+                }
+                int32_t n_split = 0;
+                for (size_t t = 0; t < tiles.size(); ++t) {
+                    const epara_tile_class& c = plan.classes[tiles[t].cls];
+                    const int32_t want = tiles[t].cls < plan.n_stream_classes && c.split_K > 0 && groups[tiles[t].group].K >= c.split_K ? EPARA_SPLIT_PARTS : 1;
+                    CHECK(parts[t] == want && seen[t] == (1 << want) - 1);
+                    n_split += want > 1;
+                }
+                CHECK(plan.n_split_tiles == n_split && (n_split == 0) == (plan.workspace_bytes == 0));
+                CHECK(epara_workspace_bytes(groups.data(), G, EPARA_BF16) >= plan.workspace_bytes);
             }
             const int32_t producer[4] = {0, 1, 2, 3};
             epara_chain_plan_phase ph[2];

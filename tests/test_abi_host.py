@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_header_layout():
     assert B.GROUP_ARGS.itemsize == 72 and B.TILE.itemsize == 24 and B.FFN_DESC.itemsize == 80
-    assert ctypes.sizeof(B.Launch) == 64
+    assert ctypes.sizeof(B.Launch) == 88
 
 
 def _desc(groups, act=0):
@@ -38,8 +38,9 @@ def _desc(groups, act=0):
 
 def _classes(cl):
     c = np.zeros(len(cl), dtype=B.TILE_CLASS)
-    for i, (mm, bm, bn) in enumerate(cl):
-        c[i]["max_M"], c[i]["BM"], c[i]["BN"] = mm, bm, bn
+    for i, row in enumerate(cl):
+        c[i]["max_M"], c[i]["BM"], c[i]["BN"] = row[:3]
+        c[i]["split_K"] = row[3] if len(row) > 3 else 0
     return c
 
 
@@ -67,7 +68,8 @@ ADVERSARIAL = [
 CLASS_TABLES = [([(64, 64, 32), (P.INT32_MAX, 256, 256)], 1), ([(64, 64, 32), (P.INT32_MAX, 256, 128)], 0),
                 ([(P.INT32_MAX, 64, 64)], 0), ([(16, 16, 64), (64, 64, 64), (512, 128, 128), (P.INT32_MAX, 256, 256)], 2),
                 ([(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)], 3),
-                ([(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], 4)]
+                ([(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], 4),
+                ([(16, 16, 32, 0), (32, 32, 64, 512), (64, 64, 128, 128), (P.INT32_MAX, 256, 256, 0)], 3)]
 
 
 @pytest.mark.parametrize("groups", mix_group_shapes() + ADVERSARIAL)
@@ -155,13 +157,13 @@ def test_batch_accounting_and_paper_numbers():
 
 def test_kernel_classes_and_packed_sizes():
     c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)] and ns == 3
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 128, 8192), (P.INT32_MAX, 256, 256, 0)] and ns == 3
     c, ns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)] and ns == 3
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 16, 0), (32, 32, 32, 0), (64, 64, 64, 0), (P.INT32_MAX, 256, 128, 0)] and ns == 3   # fp8 tiles are not split
     c, ns = B.epara_kernel_classes(B.EPARA_F32, 0)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 64), (P.INT32_MAX, 64, 64)] and ns == 0
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 64, 0), (P.INT32_MAX, 64, 64, 0)] and ns == 0
     c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0, narrow=True)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32), (32, 32, 64), (64, 64, 64), (P.INT32_MAX, 256, 256)] and ns == 3
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 64, 8192), (P.INT32_MAX, 256, 256, 0)] and ns == 3
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
     assert B.epara_workspace_bytes(_desc([(5, 8, 8)]), B.EPARA_BF16) == 0 and B.epara_workspace_bytes(_desc([]), 9) == -1
@@ -196,7 +198,7 @@ def _host_launch(args, tiles, order_len, W=8):
     """A Launch whose device pointers are fake but non-NULL: only the host-side validation is exercised,
     and every case below must be rejected before anything is enqueued."""
     L = B.Launch(args.ctypes.data, 0x1000, tiles.ctypes.data if len(tiles) else None, 0x2000, 0x3000,
-                 len(tiles), order_len, W, len(args))
+                 len(tiles), order_len, W, len(args), None, 0, 0, 0)
     return L
 
 
@@ -250,12 +252,12 @@ def test_launch_validation_rejects_bad_arguments_without_a_gpu():
     assert fwd(_host_launch(a, bad, 8)) == B.EPARA_ERR_SHAPE
     # nothing to do is fine and touches nothing: no tiles, G = 0
     empty = np.zeros(0, dtype=B.GROUP_ARGS)
-    assert fwd(B.Launch(None, None, None, None, None, 0, 0, 8, 0)) == B.EPARA_OK
+    assert fwd(B.Launch(None, None, None, None, None, 0, 0, 8, 0, None, 0, 0, 0)) == B.EPARA_OK
     z = mk(M=0)
-    assert fwd(B.Launch(z.ctypes.data, None, None, None, None, 0, 0, 8, 1)) == B.EPARA_OK
+    assert fwd(B.Launch(z.ctypes.data, None, None, None, None, 0, 0, 8, 1, None, 0, 0, 0)) == B.EPARA_OK
     # ffn wrapper: dtype rules and phase consistency
     ffn = lambda u, d, i, h, o: lib.epara_grouped_ffn_swiglu(ctypes.addressof(u), ctypes.addressof(d), i, h, o, None)
-    e = B.Launch(None, None, None, None, None, 0, 0, 8, 0)
+    e = B.Launch(None, None, None, None, None, 0, 0, 8, 0, None, 0, 0, 0)
     assert ffn(e, e, B.EPARA_BF16, B.EPARA_BF16, B.EPARA_BF16) == B.EPARA_OK
     assert ffn(e, e, B.EPARA_BF16, B.EPARA_FP8_E4M3, B.EPARA_BF16) == B.EPARA_ERR_DTYPE
     assert ffn(e, e, B.EPARA_F32, B.EPARA_F32, B.EPARA_F32) == B.EPARA_ERR_DTYPE
@@ -336,9 +338,10 @@ def test_single_phase_chain_is_the_plain_schedule():
 
 
 def test_chain_balances_a_coarse_phase_against_a_fine_one():
-    """Decode FFN shapes with the wide table in the down phase: alone, its 32 widest tiles are all their
-    owners get and twice the mean; scheduled together with the up phase the loads even out."""
-    up, down = [(m, 4096, 11008) for m in (1, 8, 32, 64)], [(m, 11008, 4096) for m in (1, 8, 32, 64)]
+    """Decode-like FFN shapes (K short enough that no tile is split) with the wide table in the down phase: alone,
+    its 32 widest tiles are all their owners get and twice the mean; scheduled together with the up phase the
+    loads even out."""
+    up, down = [(m, 4000, 4096) for m in (1, 8, 32, 64)], [(m, 4000, 4096) for m in (1, 8, 32, 64)]
     gt, nt = [(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], [(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)]
     tu, td = P.plan_groups(up, gt)[3], P.plan_groups(down, nt)[3]
     phases = [([g + (True,) for g in up], gt, 3, tu), ([g + (False,) for g in down], nt, 3, td)]
@@ -388,7 +391,7 @@ def test_chain_entry_point_validates_before_touching_the_device():
     assert L.epara_grouped_chain(ctypes.addressof(phases), 5, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_SHAPE
     assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 256, 0, None) == B.EPARA_ERR_NULL   # no launch
     assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ctypes.c_void_p(4100), 256, 0, None) == B.EPARA_ERR_ALIGN
-    empty = B.Launch(None, None, None, None, None, 0, 0, 0, 0)
+    empty = B.Launch(None, None, None, None, None, 0, 0, 0, 0, None, 0, 0, 0)
     phases[0].launch = ctypes.pointer(empty)
     phases[0].out_dtype = B.EPARA_BF16
     assert L.epara_grouped_chain(ctypes.addressof(phases), 1, B.EPARA_BF16, ws, 16, 0, None) == B.EPARA_ERR_CAPACITY
@@ -445,11 +448,26 @@ def _launches_by_mix():
 LAUNCHES = _launches_by_mix()
 
 
-def _ref_cost(group, tile, classes, n_stream, gated):
+def _ref_cost(group, tile, classes, n_stream, gated, parts=1):
     if tile[5] >= n_stream:
         return 2040 * group[1]
     bm = classes[tile[5]][1]
-    return group[1] * (6 * tile[4] * (2 if gated else 1) + (2 * bm if bm >= 32 else 0))
+    whole = group[1] * (6 * tile[4] * (2 if gated else 1) + (2 * bm if bm >= 32 else 0))
+    return whole if parts == 1 else whole // parts + 24 * bm * tile[4] * (2 if gated else 1)
+
+
+def _visits(order, tiles, groups, classes, n_stream):
+    """Checks that a visit order holds every tile the right number of times, each part once, and returns the decoded entries."""
+    seen = {}
+    for e in order:
+        if e >= 0:
+            t, part, parts = P.order_decode(int(e))
+            seen.setdefault(t, []).append((part, parts))
+    assert sorted(seen) == list(range(len(tiles)))
+    for t, v in seen.items():
+        tile = tiles[t]
+        want = P.split_parts(groups[tile[0]][1], classes[tile[5]]) if tile[5] < n_stream else 1
+        assert sorted(v) == [(j, want) for j in range(want)]
 
 
 @pytest.mark.parametrize("index,dtype", [(4, B.EPARA_BF16), (5, B.EPARA_BF16), (3, B.EPARA_BF16), (2, B.EPARA_BF16), (1, B.EPARA_F32), (4, B.EPARA_FP8_E4M3)])
@@ -460,7 +478,7 @@ def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(inde
     run on both tables under the cost model of the header (a transcription check: the same rule typed twice)."""
     W = 256
     for groups, gated in LAUNCHES[index]:
-        info, row_off, x_off, y_off, tiles, order = B.epara_plan_launch(_desc(groups, 5 if gated else 0), dtype, W, 8, 1, 4)
+        info, row_off, x_off, y_off, tiles, order, split_base = B.epara_plan_launch(_desc(groups, 5 if gated else 0), dtype, W, 8, 1, 4)
         classes = [tuple(int(v) for v in c) for c in info.class_table()]
         # validity
         cover = {g: np.zeros((M, N), dtype=np.int32) for g, (M, K, N) in enumerate(groups) if M}
@@ -468,7 +486,8 @@ def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(inde
             cover[int(t["group"])][t["m0"]: t["m0"] + t["rows"], t["n0"]: t["n0"] + t["cols"]] += 1
         assert all(np.all(c == 1) for c in cover.values())
         o = order.reshape(-1, W)
-        assert sorted(o[o >= 0].tolist()) == list(range(len(tiles)))
+        _visits(order.tolist(), [tuple(int(v) for v in t) for t in tiles], groups, classes, info.n_stream_classes)
+        assert (split_base.tolist(), info.n_split_tiles, info.workspace_bytes) == P.split_layout(groups, classes, info.n_stream_classes)
         for b in range(W):
             col = o[:, b]
             assert np.all(col[: int((col >= 0).sum())] >= 0)
@@ -481,7 +500,8 @@ def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(inde
             cls = [tuple(int(v) for v in c) for c in cls]
             _, _, _, rt = P.plan_groups(groups, cls)
             ro = P.schedule_tiles([g + (gated,) for g in groups], cls, n_stream, rt, W, 8, 1, 4)
-            loads = [sum(_ref_cost(groups[rt[t][0]], rt[t], cls, n_stream, gated) for t in ro[b::W] if t >= 0) for b in range(W)]
+            dec = [P.order_decode(e) if e >= 0 else None for e in ro]
+            loads = [sum(_ref_cost(groups[rt[d[0]][0]], rt[d[0]], cls, n_stream, gated, d[2]) for d in dec[b::W] if d) for b in range(W)]
             if best is None or max(loads) < best[0]:
                 best = (max(loads), narrow, cls, rt, ro)
         assert (info.makespan, info.narrow, classes) == best[:3]

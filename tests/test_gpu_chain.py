@@ -1,7 +1,8 @@
 """GPU tests of chains of launches run as one kernel (epara_grouped_chain).
 
 A chain computes the same tiles with the same arithmetic as the launches called one after the other, so its
-outputs must equal theirs bit for bit (the separate launches are held to the oracle by test_gpu_parity);
+outputs must equal theirs bit for bit wherever the launches do not cut a tile's K into parts (the separate
+launches are held to the oracle by test_gpu_parity);
 small chains are also compared with the CPU oracle directly.  A wait that cannot be met is forced from the
 host with a poll limit of one: the kernel must still end and report it.
 """
@@ -52,6 +53,20 @@ def _raw(staged):
             for launch in staged.outputs[0]]
 
 
+def _assert_same(mix, dtype_name, sep_raw, sep_vals, ch, cut, what=""):
+    """Chain against launches.  Bit for bit, except (cut = True: the full-size decode launches) for the services
+    whose tiles the single launches visit in parts of K and add in index order, which a chain does not: the same
+    products in another order of addition.  Those are held to the parity tolerance; a stored E4M3 value may
+    land on the neighbouring code (an eighth apart)."""
+    for la, lb, va, vb in zip(sep_raw, _raw(ch), sep_vals, ch.results()):
+        for x, y, (g, label, p), (_, _, q) in zip(la, lb, va, vb):
+            if not cut or mix.services[g].M <= 16:
+                assert np.array_equal(x, y), what
+            else:
+                stored_fp8 = dtype_name == "fp8" and label == "H"
+                assert_close(q, p, 0.13 if stored_fp8 else TOL[dtype_name], "chain against launches, %s svc %d %s %s" % (mix.name, g, label, what))
+
+
 @pytest.mark.parametrize("index,shrink,dtype_name", SMALL)
 @pytest.mark.parametrize("n_workgroups", [None, 8, 64])
 def test_chain_equals_separate_launches_bit_for_bit(index, shrink, dtype_name, n_workgroups):
@@ -80,14 +95,12 @@ def test_full_size_chain_equals_separate_launches(index, dtype_name):
     print("full-size chain", index, dtype_name, flush=True)
     mix = make_mix(index)
     sep = _run(mix, dtype_name, False)
-    a = _raw(sep)
+    a, vals = _raw(sep), sep.results()
     bits = sep.host_bits
     del sep
     torch.cuda.empty_cache()
     ch = _run(mix, dtype_name, True, host_bits=bits, passes=2)
-    for la, lb in zip(a, _raw(ch)):
-        for x, y in zip(la, lb):
-            assert np.array_equal(x, y)
+    _assert_same(mix, dtype_name, a, vals, ch, index == 4)
 
 
 @pytest.mark.parametrize("index,shrink,dtype_name", [SMALL[0], SMALL[1], SMALL[2], SMALL[3], SMALL[5], (4, {}, "bf16")])
@@ -107,9 +120,7 @@ def test_chain_sees_fresh_activations_when_the_inputs_change_between_passes(inde
         sep.run()
         torch.cuda.synchronize()
         assert ch.chain_status() == 0
-        for la, lb in zip(_raw(sep), _raw(ch)):
-            for a, b in zip(la, lb):
-                assert np.array_equal(a, b), "factor %g" % factor
+        _assert_same(mix, dtype_name, _raw(sep), sep.results(), ch, index == 4 and not shrink, "factor %g" % factor)
         # the pass did change the outputs (otherwise this test could not see a stale read)
         if factor != 1.0:
             assert not all(np.array_equal(a, b) for la, lb in zip(prev, _raw(ch)) for a, b in zip(la, lb))

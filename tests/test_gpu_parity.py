@@ -84,6 +84,46 @@ def test_small_integers_are_bit_exact(dtype_name):
         assert np.array_equal(y, yref), (dtype_name, M, K, N, np.argwhere(y != yref)[:5])
 
 
+def test_long_k_tiles_visited_in_parts(dtype_name="bf16"):
+    """Batches of 17 to 64 rows with K >= 8192 (bf16; fp8 tiles are not split): the launch visits each tile in two
+    parts of K whose sums meet in the workspace.  Integer-valued operands make every order of addition exact, so the result must be
+    the oracle's bit for bit: ragged K (a part boundary inside a fragment pair, a last fragment cut short),
+    ragged rows and columns, next to groups that are not split; twice, on grids of different sizes (who arrives
+    last changes), and three times in a row on one plan (the arrival counters return to zero)."""
+    rng = np.random.default_rng(17)
+    shapes = [(40, 8208, 200), (64, 11024, 136), (17, 8192, 70), (8, 8192, 40), (33, 12304, 24), (64, 4080, 130), (20, 16384, 16)]
+    acts = ["relu", "none", "relu", "none", "none", "relu", "none"]
+    specs = []
+    for (M, K, N), act in zip(shapes, acts):
+        X = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        W = rng.integers(-3, 4, (K, N)).astype(np.float32)
+        b = rng.integers(-8, 9, N).astype(np.float32)
+        specs.append({"X": X, "W": W, "b": b, "act": act, "s_x": 0.125, "s_w": 0.25})
+    for W_ in (None, 24):
+        G = U.Groups(specs, dtype_name, n_workgroups=W_)
+        assert G.plan.n_split_tiles > 0
+        parts = {int(e >> 28) + 1 for e in G.plan.order if e >= 0}
+        assert parts == {1, 2}
+        want = [ref.bf16_decode(ref.bf16_encode(y)) for y in G.expected()]
+        for rep in range(3):
+            for (M, K, N), y, yref in zip(shapes, G.run(), want):
+                assert np.array_equal(y, yref), (dtype_name, W_, rep, M, K, N, np.argwhere(y != yref)[:5])
+        if dtype_name == "bf16":
+            # new activations at the same addresses: the parts that come back from the workspace must be this
+            # launch's (the visit that adds them may run on another compute die than the ones that wrote them)
+            for i, sp in enumerate(specs):
+                G.keep[3 * i].mul_(-2.0)
+                G.bits[i]["X"] = casts.bf16_bits(-2.0 * sp["X"])
+            want = [ref.bf16_decode(ref.bf16_encode(y)) for y in G.expected()]
+            for (M, K, N), y, yref in zip(shapes, G.run(), want):
+                assert np.array_equal(y, yref), ("rescaled", W_, M, K, N, np.argwhere(y != yref)[:5])
+    # real values: against the oracle at the usual tolerance
+    specs = [U.rand_spec(rng, M, K, N, act, bias=True) for (M, K, N), act in zip(shapes, ["gelu_erf", "silu", "none", "relu", "gelu_tanh", "none", "relu"])]
+    G = U.Groups(specs, dtype_name)
+    for (M, K, N), y, yref in zip(shapes, G.run(), G.expected()):
+        assert_close(y, yref, TOL[dtype_name], "split K %s" % ((M, K, N),))
+
+
 def test_identity_zero_and_ones_weights_bf16():
     rng = np.random.default_rng(12)
     X = rng.standard_normal((37, 64)).astype(np.float32)

@@ -92,19 +92,19 @@ def test_schedule_is_a_permutation_with_idle_padding(W, X):
 
 
 def test_streaming_tiles_are_balanced_longest_first():
-    # decode-like launch: three streaming classes, every tile of a group costs cols * K
+    # decode-like launch with a K too short to be split: three streaming classes, every tile of a group costs cols * K
     classes = [(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)]
-    groups = [(1, 11008, 4096), (8, 11008, 4096), (32, 11008, 4096), (64, 11008, 4096)]
+    groups = [(1, 2048, 4096), (8, 2048, 4096), (32, 2048, 4096), (64, 2048, 4096)]
     _, _, _, tiles = P.plan_groups(groups, classes)
     assert len(tiles) == 128 + 128 + 64 + 32
     W = 256
     order = P.schedule_tiles(groups, classes, 3, tiles, W, 8, 8, 4)
-    cost = lambda t: 11008 * (6 * tiles[t][4] + (2 * classes[tiles[t][5]][1] if classes[tiles[t][5]][1] >= 32 else 0))     # weight columns, and activation rows at a third
+    cost = lambda t: 2048 * (6 * tiles[t][4] + (2 * classes[tiles[t][5]][1] if classes[tiles[t][5]][1] >= 32 else 0))     # weight columns, and activation rows at a third
     loads = [sum(cost(t) for t in order[b::W] if t >= 0) for b in range(W)]
     total = sum(cost(t) for t in range(len(tiles)))
     # greedy longest-first never exceeds the mean by more than one largest tile
-    assert max(loads) <= total / W + 11008 * (6 * 128 + 128)
-    assert max(loads) == 11008 * (6 * 128 + 128)             # a wide tile is all its owner gets
+    assert max(loads) <= total / W + 2048 * (6 * 128 + 128)
+    assert max(loads) == 2048 * (6 * 128 + 128)             # a wide tile is all its owner gets
     # the widest tiles are visited first by whoever owns them
     firsts = [tiles[order[b]][4] for b in range(W)]
     assert sorted(firsts, reverse=True)[:32] == [128] * 32
@@ -113,12 +113,49 @@ def test_streaming_tiles_are_balanced_longest_first():
     _, _, _, t2 = P.plan_groups(groups, narrow)
     o2 = P.schedule_tiles(groups, narrow, 3, t2, W, 8, 8, 4)
     rows = lambda bm: 2 * bm if bm >= 32 else 0
-    loads2 = [sum(11008 * (6 * t2[t][4] + rows(narrow[t2[t][5]][1])) for t in o2[b::W] if t >= 0) for b in range(W)]
-    assert max(loads2) <= 11008 * (6 * 64 + 128 + 6 * 32) and max(loads2) < 0.6 * max(loads)
+    loads2 = [sum(2048 * (6 * t2[t][4] + rows(narrow[t2[t][5]][1])) for t in o2[b::W] if t >= 0) for b in range(W)]
+    assert max(loads2) <= 2048 * (6 * 64 + 128 + 6 * 32) and max(loads2) < 0.6 * max(loads)
     # gated groups stream two weight matrices: the column part of the cost doubles, the row part does not
     o2 = P.schedule_tiles([g + (True,) for g in groups], classes, 3, tiles, W, 8, 8, 4)
-    gcost = lambda t: 11008 * (12 * tiles[t][4] + rows(classes[tiles[t][5]][1]))
-    assert max(sum(gcost(t) for t in o2[b::W] if t >= 0) for b in range(W)) == 11008 * (12 * 128 + 128)
+    gcost = lambda t: 2048 * (12 * tiles[t][4] + rows(classes[tiles[t][5]][1]))
+    assert max(sum(gcost(t) for t in o2[b::W] if t >= 0) for b in range(W)) == 2048 * (12 * 128 + 128)
+
+
+def test_long_k_streaming_tiles_are_visited_in_parts():
+    """A single launch cuts the K of the 32- and 64-row classes' tiles in two when K >= 8192: every part once,
+    items longest first, and the widest tile no longer sets the makespan."""
+    classes = [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 128, 8192), (P.INT32_MAX, 256, 256, 0)]
+    assert [P.split_parts(K, cl) for K, cl in ((4096, classes[1]), (8191, classes[2]), (8192, classes[1]), (11008, classes[2]),
+                                               (11008, classes[0]), (1 << 20, (64, 64, 64)), (1 << 20, (64, 64, 64, 1 << 20)))] == \
+        [1, 1, 2, 2, 1, 1, 2]
+    for K, parts in ((11008, 2), (8192, 2)):
+        groups = [(1, K, 4096), (8, K, 4096), (32, K, 4096), (64, K, 4096)]
+        _, _, _, tiles = P.plan_groups(groups, classes)
+        W = 256
+        order = P.schedule_tiles(groups, classes, 3, tiles, W, 8, 8, 4)
+        seen = {}
+        for e in order:
+            if e >= 0:
+                t, j, n = P.order_decode(e)
+                assert P.order_entry(t, j, n) == e
+                seen.setdefault(t, []).append((j, n))
+        assert sorted(seen) == list(range(len(tiles)))
+        for t, v in seen.items():
+            want = parts if tiles[t][5] >= 1 else 1
+            assert sorted(v) == [(j, want) for j in range(want)]
+        whole = lambda t: K * (6 * tiles[t][4] + (2 * classes[tiles[t][5]][1] if classes[tiles[t][5]][1] >= 32 else 0))
+        def item(e):
+            t, _, n = P.order_decode(e)
+            return whole(t) if n == 1 else whole(t) // n + 24 * classes[tiles[t][5]][1] * tiles[t][4]
+        loads = [sum(item(e) for e in order[b::W] if e >= 0) for b in range(W)]
+        biggest = max(item(e) for e in order if e >= 0)
+        assert max(loads) <= sum(loads) / W + biggest
+        assert max(loads) < 0.8 * K * (6 * 128 + 128)       # an unsplit wide tile alone costs that
+        # a chain of launches does not split
+        o2 = P.schedule_chain([(groups, classes, 3, tiles), (groups, classes, 3, tiles)], W, 8, 8, 4)
+        assert all(e < (1 << 24) for o in o2 for e in o)
+    base, n, nbytes = P.split_layout([(64, 11008, 4096), (8, 11008, 4096), (0, 11008, 4096), (32, 8192, 100), (200, 11008, 4096), (40, 8191, 512)], classes, 3)
+    assert base == [0, -1, -1, 32, -1, -1] and n == 32 + 2 and nbytes == 256 + 34 * 4 * 32768
 
 
 def test_schedule_keeps_a_die_on_one_panel():

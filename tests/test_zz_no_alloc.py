@@ -84,7 +84,7 @@ def test_static_scratch_chain_rejects_more_counters_than_the_array_holds():
     G = B.EPARA_STATIC_CHAIN_COUNTERS + 1
     args = np.zeros(G, dtype=B.GROUP_ARGS)
     args["K"], args["N"] = 8, 8                              # M = 0 everywhere: nothing to launch, only the counter count matters
-    launch = B.Launch(args.ctypes.data, None, None, None, None, 0, 0, 8, G)
+    launch = B.Launch(args.ctypes.data, None, None, None, None, 0, 0, 8, G, None, 0, 0, 0)
     phases = (B.ChainPhase * 1)()
     phases[0].launch = ctypes.pointer(launch)
     phases[0].out_dtype, phases[0].counter_base = B.EPARA_BF16, 0
