@@ -115,6 +115,8 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     torch.cuda.synchronize()
     samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
     per_launch_ms = [sum(v) / steps for v in samples]
+    # where these passes sit among the grouped_kernel dispatches of a kernel trace of this command
+    trace_first_pass = warmup + 2 * steps + (1 + steps + copies if copies > 1 else 0)
     # each launch repeated back to back (on its rotating copies) with events at both ends only: without the
     # idle microseconds that an event pair around a single short kernel also spans
     repeated_ms = []
@@ -199,6 +201,8 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     # the whole pass against the same ceilings: time the roofline allows for all launches / time taken
     t_roof = sum(max(st["flops"] / (MFMA_PEAK_TFLOPS[dtype_name] * 1e12) if dtype_name in MFMA_PEAK_TFLOPS else 0.0,
                      st["bytes"] / (HBM_PEAK_GBS * 1e9)) for st in stats)
+    res["kernel_trace"] = {"first_pass": trace_first_pass, "passes": steps, "launches_per_pass": n_l,
+                           "what": "passes first_pass .. first_pass + passes - 1 of this mix's grouped_kernel dispatches are the ones timed launch by launch"}
     res["pass_roofline"] = {"frac": t_roof / (ms_per_step * 1e-3), "roofline_ms": t_roof * 1e3,
                             "algorithmic_bytes": sum(st["bytes"] for st in stats), "algorithmic_flops": sum(st["flops"] for st in stats),
                             "GBs": sum(st["bytes"] for st in stats) / (ms_per_step * 1e-3) / 1e9,

@@ -565,7 +565,8 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
 
 /* The n_phases (1..EPARA_MAX_CHAIN_PHASES) launches of a chain in ONE persistent kernel of
  * n_workgroups workgroups: the same tiles, arithmetic and results as epara_grouped_forward called
- * phase by phase (bit-identical), without the launch boundaries: a workgroup that finishes its
+ * phase by phase (bit-identical, except that the phases of a chain are never visited in parts of K, see
+ * "Splitting K"), without the launch boundaries: a workgroup that finishes its
  * share of a phase goes on with the next phase at once, and a tile of group g waits only for the
  * group that produces its input (phase[p].h_waits[g]).  Completion is counted per group in
  * d_workspace (counter counter_base + g of phase p rises by the tiles a workgroup has stored, after
@@ -587,7 +588,11 @@ int32_t epara_chain_workspace_init(void* d_workspace, int64_t bytes, void* strea
  * A wait polls at most spin_limit times (0 = the default, some seconds); if it runs out the kernel
  * sets the error flag, goes on without the data and still terminates, and the outputs of the chain
  * are invalid: read the flag with epara_chain_status.  Two chains that use one workspace must not
- * overlap in time. */
+ * overlap in time.
+ * Meant for passes of long (panel-class) tiles submitted once; for passes of short weight-streaming tiles
+ * (decode-sized batches, small models) separate launches are faster on this GPU, because every dependency
+ * costs a poll, a drained pipeline and a fresh start of the weight stream, more than the launch boundary
+ * it removes. */
 int32_t epara_grouped_chain(const epara_chain_phase* phases, int32_t n_phases, int32_t in_dtype,
                             void* d_workspace, int64_t workspace_bytes, uint32_t spin_limit, void* stream);
 
