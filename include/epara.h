@@ -399,10 +399,13 @@ int32_t epara_workspace_init(void* d_workspace, int64_t bytes, void* stream);
  * bandwidth bound), the others are panel classes (matrix-core bound).
  *   1. panel tiles: classes by descending BM*BN (ties: lower class), inside a class groups by
  *      descending K (ties: lower group), inside a group panels of panel_m x panel_n tiles,
- *      n-panel outermost, m fastest inside a panel.  The l-th tile of that sequence goes to
- *      workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X)  (X = n_xcd), so the
- *      W/X workgroups of one compute die (workgroup b runs on die b mod X) work on neighbouring
- *      tiles and share operands in that die's L2.
+ *      n-panel outermost, m fastest inside a panel.  Each tile of that sequence goes to the workgroup
+ *      with the smallest accumulated cost (EPARA_COST_PANEL * K per panel tile); among equally loaded
+ *      workgroups the smallest die-major rank wins, rank r standing for workgroup (r mod (W/X)) * X +
+ *      r div (W/X)  (X = n_xcd).  Tiles of equal cost therefore go round robin, the l-th to rank l mod W,
+ *      so that the W/X workgroups of one compute die (workgroup b runs on die b mod X) work on
+ *      neighbouring tiles and share operands in that die's L2; where K differs between the groups of a
+ *      launch, a workgroup that got a long tile gets fewer of the short ones.
  *   2. streaming tiles, longest first: costs as defined above (EPARA_COST_*); a tile that is split (see
  *      "Splitting K") gives P items, each of cost / P + EPARA_COST_PARTIAL * BM * cols (* 2 for
  *      EPARA_ACT_SWIGLU groups; the partial sums it writes and the last visit reads); items by descending
@@ -422,8 +425,8 @@ int32_t epara_schedule_tiles(const epara_group_desc* groups, int32_t G,
  * list of phase p+1 follows its list of phase p).  The rule of epara_schedule_tiles with the
  * workgroup loads shared by all phases, so that a workgroup with much work in one phase gets less in
  * another:
- *   1. panel tiles phase by phase, each phase's sequence as in epara_schedule_tiles; the position l
- *      of the round-robin is not reset between phases.
+ *   1. panel tiles phase by phase, each phase's sequence as in epara_schedule_tiles, on the loads
+ *      accumulated over the phases before.
  *   2. the streaming tiles of ALL phases together, by descending cost (ties: earlier phase, then
  *      lower tile index), each onto the workgroup with the smallest accumulated cost (ties: lower
  *      workgroup); it joins that workgroup's list of its own phase, after the panel tiles.

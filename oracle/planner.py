@@ -251,9 +251,12 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
     1. Panel tiles.  Classes by descending BM*BN (ties: lower class first); inside a class the
        groups by descending K (ties: lower group first); inside a group the tile grid TM x TN
        is cut into panels of panel_m x panel_n tiles, panels taken with the n-panel index
-       outermost, and inside a panel the m index runs fastest.  The l-th tile of that sequence
-       goes to workgroup i*X + x with w = l mod W, x = w div (W/X), i = w mod (W/X): the W/X
-       tiles that run together on one die are consecutive in the sequence.
+       outermost, and inside a panel the m index runs fastest.  Each tile of that sequence goes to the
+       workgroup with the smallest accumulated cost (a panel tile costs 2040 * K); among equally loaded
+       workgroups the one of smallest die-major rank, rank r standing for workgroup (r mod (W/X)) * X + r div (W/X).
+       Tiles of equal cost therefore go round robin, the l-th to rank l mod W, and the W/X tiles that run
+       together on one die are consecutive in the sequence; a workgroup that got a long-K tile gets fewer
+       of the short ones.
     2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + (2 * BM if BM >= 32 else 0))
        for a streaming tile (weight columns streamed from HBM, plus the activation rows re-read from L2
        at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  In a single launch a
@@ -269,8 +272,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
     """Visit orders of a chain of launches run by one kernel, phase after phase in every workgroup.
 
     phases: list of (groups, classes, n_stream_classes, tiles).  The rule of schedule_tiles with the
-    workgroup loads shared by all phases: step 1 phase by phase without resetting the round-robin
-    position l; step 2 once over the streaming tiles of all phases (ties of equal cost: earlier
+    workgroup loads shared by all phases: step 1 phase by phase on the accumulated loads; step 2 once over the streaming tiles of all phases (ties of equal cost: earlier
     phase, then lower tile index), each tile joining its workgroup's list of its own phase.
     Returns one order per phase (W * longest list of that phase entries).
     """
@@ -281,7 +283,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
     per = W // X
     lists = [[[] for _ in range(W)] for _ in phases]
     load = [0] * W
-    l = 0
+    rank_heap = [(0, r) for r in range(W)]                   # (load, die-major rank); rank r = workgroup (r mod per) * X + r div per
     stream = []
     for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
         if not 0 <= n_stream_classes <= len(classes):
@@ -300,11 +302,12 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
                     for pm in range(0, TM, panel_m):
                         for tn in range(pn, min(pn + panel_n, TN)):
                             for tm in range(pm, min(pm + panel_m, TM)):
-                                x, i = divmod(l % W, per)
+                                _, r = heapq.heappop(rank_heap)
+                                x, i = divmod(r, per)
                                 b = i * X + x
                                 lists[p][b].append(first[g] + tm * TN + tn)
                                 load[b] += 2040 * K
-                                l += 1
+                                heapq.heappush(rank_heap, (load[b], r))
         for t, tile in enumerate(tiles):
             if tile[5] < n_stream_classes:
                 g = groups[tile[0]]

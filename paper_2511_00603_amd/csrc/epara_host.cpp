@@ -501,8 +501,12 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                                                           std::vector<std::vector<int32_t>>(static_cast<size_t>(W)));
     std::vector<int64_t> load(static_cast<size_t>(W), 0);
 
-    // 1. panel tiles, phase after phase; the round-robin position carries over
-    int64_t l = 0;
+    // 1. panel tiles, phase after phase, each to the least loaded workgroup; among equally loaded ones the
+    // die-major rank decides (rank r = workgroup (r mod per_die) * X + r div per_die), so that tiles of equal
+    // cost go round robin and the per_die tiles that run together on one die are consecutive in the sequence
+    typedef std::pair<int64_t, int64_t> ranked;                 // (load, rank): smallest first
+    std::priority_queue<ranked, std::vector<ranked>, std::greater<ranked>> panel_heap;
+    for (int64_t r = 0; r < W; ++r) panel_heap.push({0, r});
     std::vector<int32_t> class_order, members;
     for (int32_t p = 0; p < n_phases; ++p) {
         const epara_phase_schedule& ph = phases[p];
@@ -524,10 +528,12 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                     for (int64_t pm = 0; pm < TM; pm += panel_m)
                         for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
                             for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
-                                const int64_t w = l % W, x = w / per_die, i = w % per_die, b = i * X + x;
+                                const ranked top = panel_heap.top();
+                                panel_heap.pop();
+                                const int64_t x = top.second / per_die, i = top.second % per_die, b = i * X + x;
                                 lists[p][b].push_back(static_cast<int32_t>(first[p][g] + tm * TN + tn));
                                 load[b] += static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[g].K;
-                                ++l;
+                                panel_heap.push({load[b], top.second});
                             }
             }
         }

@@ -4,7 +4,7 @@ libepara.  Used by the parity tests, the smoke check and the benchmark.
 A pass is the sequence of grouped launches that serves every service of the mix once:
   mix 1  three launches (layer 1, 2, 3 of both MLPs)
   mix 2  two launches   (all FFN-up groups with GELU, then all FFN-down groups)
-  mix 3  two launches   (QKV + FFN-up groups of every service, then FFN-down groups)
+  mix 3  two launches   (FFN-up groups of every service, then their QKV and FFN-down groups)
   mix 4, 5  one grouped SwiGLU FFN call (gate/up launch, down launch)
 Inputs are rounded once on the host (workloads.casts) and the exact bits are kept in
 `host_bits` so that a checker can be given the same values.
@@ -149,8 +149,10 @@ class StagedMix:
             bias = [[None if l["b"] is None else self._dev_f32(l["b"]) for l in hb["layers"]] for hb in self.host_bits]
             n_svc = len(mix.services)
             if mix.services[0].kind == "vit":      # layers: 0 = QKV (from X), 1 = FFN up (from X), 2 = FFN down (from 1)
-                launches = [[(g, 0, "in") for g in range(n_svc)] + [(g, 1, "in") for g in range(n_svc)],
-                            [(g, 2, 1) for g in range(n_svc)]]
+                # QKV depends on nothing but X, so it shares a launch with FFN down: the few long-K tiles of
+                # FFN down alone would leave a quarter of the workgroups idle, the scheduler fills them with QKV tiles
+                launches = [[(g, 1, "in") for g in range(n_svc)],
+                            [(g, 0, "in") for g in range(n_svc)] + [(g, 2, 1) for g in range(n_svc)]]
             else:                                  # a chain: layer l reads layer l-1
                 launches = [[(g, l, "in" if l == 0 else l - 1) for g in range(n_svc)] for l in range(n_layers)]
             produced = {}

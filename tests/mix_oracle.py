@@ -61,7 +61,7 @@ def expected(mix, host_bits, dtype_name, rows=None, h_scales=None, calibrated=No
                 cur = ref.dense_forward(cur, W[l], L[l]["b"], L[l]["act"])
                 outs[(g, l)] = cur
     if kind == "vit":
-        order = [[(g, 0) for g in range(n)] + [(g, 1) for g in range(n)], [(g, 2) for g in range(n)]]
+        order = [[(g, 1) for g in range(n)], [(g, 0) for g in range(n)] + [(g, 2) for g in range(n)]]
     else:
         order = [[(g, l) for g in range(n)] for l in range(len(host_bits[0]["layers"]))]
     for launch in order:

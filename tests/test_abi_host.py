@@ -53,7 +53,7 @@ def mix_group_shapes():
     rows = [6, 4, 9, 11, 5, 7, 7, 8, 8, 4, 14, 7, 4, 4, 6, 8]
     out += [[(r, k, 4 * k) for r, k in zip(rows, d)], [(r, 4 * k, k) for r, k in zip(rows, d)]]
     M3 = [197 * i for i in [32, 16, 1, 8, 4, 4, 2, 8]]
-    out += [[(m, 768, 2304) for m in M3] + [(m, 768, 3072) for m in M3], [(m, 3072, 768) for m in M3]]
+    out += [[(m, 768, 3072) for m in M3], [(m, 768, 2304) for m in M3] + [(m, 3072, 768) for m in M3]]
     out += [[(m, 4096, 11008) for m in (1, 8, 32, 64)], [(m, 11008, 4096) for m in (1, 8, 32, 64)]]
     out += [[(4692, 5120, 13824), (3500, 5120, 13824)], [(4692, 13824, 5120), (3500, 13824, 5120)]]
     return out

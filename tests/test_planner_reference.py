@@ -158,6 +158,42 @@ def test_long_k_streaming_tiles_are_visited_in_parts():
     assert base == [0, -1, -1, 32, -1, -1] and n == 32 + 2 and nbytes == 256 + 34 * 4 * 32768
 
 
+def test_panel_tiles_of_unequal_k_are_balanced_and_equal_ones_go_round_robin():
+    classes = [(64, 64, 32), (P.INT32_MAX, 256, 256)]
+    # equal cost: the l-th tile of the sequence goes to die-major rank l mod W, i.e. workgroup (r mod W/X) * X + r div W/X
+    groups = [(700, 64, 900), (300, 64, 300), (1000, 64, 513)]
+    _, _, _, tiles = P.plan_groups(groups, classes)
+    W, X = 24, 4
+    order = P.schedule_tiles(groups, classes, 1, tiles, W, X, 1, 1)
+    # panels of 1 x 1: inside a group the n index outermost, the m index fastest; equal K keeps the groups in order
+    by_group = {g: [t for t in range(len(tiles)) if tiles[t][0] == g] for g in range(3)}
+    want = []
+    for g in range(3):
+        TN = -(-groups[g][2] // 256); TM = -(-groups[g][0] // 256)
+        want += [by_group[g][tm * TN + tn] for tn in range(TN) for tm in range(TM)]
+    got = {}
+    for slot, t in enumerate(order):
+        if t >= 0:
+            got.setdefault(slot % W, []).append(t)
+    for l, t in enumerate(want):
+        r = l % W
+        b = (r % (W // X)) * X + r // (W // X)
+        assert got[b][l // W] == t
+    # unequal K: the long tiles first, one per workgroup; the short ones fill up the others, and no workgroup
+    # exceeds the mean by more than one short tile... nor falls short of it by more than one long one
+    groups = [(256 * 5, 3072, 256 * 3), (256 * 9, 768, 256 * 7)]
+    _, _, _, tiles = P.plan_groups(groups, classes)
+    W = 32
+    order = P.schedule_tiles(groups, classes, 1, tiles, W, 8, 1, 4)
+    loads = [sum(2040 * groups[tiles[t][0]][1] for t in order[b::W] if t >= 0) for b in range(W)]
+    assert sum(loads) == 2040 * (15 * 3072 + 63 * 768)
+    assert max(loads) <= sum(loads) / W + 2040 * 768 and min(loads) >= sum(loads) / W - 2040 * 3072
+    rr = [0] * W                                              # plain round robin over the same sequence, for comparison
+    for l in range(15 + 63):
+        rr[l % W] += 2040 * (3072 if l < 15 else 768)
+    assert max(loads) < max(rr)
+
+
 def test_schedule_keeps_a_die_on_one_panel():
     # one group whose grid is a whole number of 8x4 panels: the 32 tiles that run together on one
     # die (slots congruent mod 8 within a round of 256) are exactly one panel
