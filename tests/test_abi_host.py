@@ -545,3 +545,23 @@ def test_plan_chain_picks_tables_jointly_and_writes_waits():
     all_finishes = {picks: replay(picks) for picks in ((0, 0), (0, 1), (1, 0), (1, 1))}
     assert finish == min(all_finishes.values())
     assert all_finishes[(int(phases[0]["info"].narrow), int(phases[1]["info"].narrow))] == finish
+
+
+def test_fast_gelu_constants_hold_their_stated_error():
+    """The 16- and 8-bit epilogues take the erf form of GELU as z / (1 + 2^(z p(min(z^2, 64)))) with three fitted
+    coefficients; the kernel source states |error| < 2.6e-5.  Read the coefficients from the source, evaluate the
+    same expression in fp32 and compare with the oracle's GELU over [-20, 20]."""
+    import os
+    import re
+    from oracle import reference as ref
+    src = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2511_00603_amd", "csrc", "epara_device.h")).read()
+    m = re.search(r"const float u = z \* \((-?[0-9.e-]+)f \+ z2 \* \((-?[0-9.e-]+)f \+ z2 \* (-?[0-9.e-]+)f\)\);", src)
+    assert m, "the expression of the fast GELU has changed: update this test with it"
+    k0, k1, k2 = (np.float32(v) for v in m.groups())
+    z = np.linspace(-20, 20, 200001).astype(np.float32)
+    z2 = np.minimum(z * z, np.float32(64))
+    u = (z * (k0 + z2 * (k1 + z2 * k2))).astype(np.float32)
+    with np.errstate(over="ignore"):
+        got = (z / (np.float32(1) + np.exp2(u))).astype(np.float32)
+    want = ref.dense_forward(z.astype(np.float64).reshape(-1, 1), np.ones((1, 1)), None, "gelu_erf")[:, 0]
+    assert np.all(np.isfinite(got)) and float(np.max(np.abs(got - want))) < 2.6e-5
