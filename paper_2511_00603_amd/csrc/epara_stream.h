@@ -246,8 +246,12 @@ __device__ __forceinline__ bool skinny_finish(const epara_group_args& ga, int ou
     if constexpr (CAN_SPLIT) {
         const int nparts = order_parts(entry);
         if (nparts > 1) {
+            // An order that asks for parts without a workspace, or for more parts than a slot holds, is not one
+            // the library's planner writes (the host cannot see the device copy of the order): the visit is
+            // dropped rather than let it write through a null or past its slot.
             // the tile's slot = the group's first slot + its column tile; quad index = (pass, unit[, gate / up])
             const int slot = ga.reserved + n0 / S::BN;
+            if (sp->ws == nullptr || nparts > SPLIT_MAX_PARTS || ga.reserved < 0 || slot >= sp->n_split) return false;
             char* mine = split_partials(*sp) + (static_cast<size_t>(slot) * SPLIT_MAX_PARTS + order_part(entry)) * SPLIT_STRIDE + lane * 16;
 #pragma unroll
             for (int pass = 0; pass < PASSES; ++pass) {

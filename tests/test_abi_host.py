@@ -565,3 +565,43 @@ def test_fast_gelu_constants_hold_their_stated_error():
         got = (z / (np.float32(1) + np.exp2(u))).astype(np.float32)
     want = ref.dense_forward(z.astype(np.float64).reshape(-1, 1), np.ones((1, 1)), None, "gelu_erf")[:, 0]
     assert np.all(np.isfinite(got)) and float(np.max(np.abs(got - want))) < 2.6e-5
+
+
+def test_split_launch_validation_without_a_gpu():
+    """A launch whose tiles are visited in parts must bring the layout the library computes and a workspace that holds it;
+    every case is rejected on the host, before anything is enqueued."""
+    from paper_2511_00603_amd.runtime import group_args
+    lib = B.lib()
+
+    class T:
+        def __init__(self, p): self.p = p
+        def data_ptr(self): return self.p
+    groups = [(64, 11008, 4096), (8, 11008, 4096), (32, 8192, 256)]
+    g = _desc(groups)
+    info, _, _, _, tiles, order, base = B.epara_plan_launch(g, B.EPARA_BF16, 256)
+    assert info.n_split_tiles > 0 and info.workspace_bytes == 256 * -(-info.n_split_tiles * 4 // 256) + info.n_split_tiles * 4 * 32768
+    assert base.tolist()[1] == -1 and base.tolist()[0] == 0 and base.tolist()[2] > 0
+    assert B.epara_workspace_bytes(g, B.EPARA_BF16) >= info.workspace_bytes and B.epara_workspace_bytes(g, B.EPARA_FP8_E4M3) == 0
+    args = np.array([group_args(T(0x100000), T(0x200000), T(0x300000), M, K, N, "none") for M, K, N in groups], dtype=B.GROUP_ARGS)
+    args["reserved"] = base
+
+    def launch(ws=0x7000000, ws_bytes=None, n_split=None, a=args):
+        return B.Launch(a.ctypes.data, 0x1000, tiles.ctypes.data, 0x2000, 0x3000, len(tiles), len(order), 256, len(a),
+                        ws, info.workspace_bytes if ws_bytes is None else ws_bytes, info.n_split_tiles if n_split is None else n_split, 0)
+    fwd = lambda L, i=B.EPARA_BF16: lib.epara_grouped_forward(ctypes.addressof(L), i, B.EPARA_BF16, None)
+    assert fwd(launch(ws=None)) == B.EPARA_ERR_NULL
+    assert fwd(launch(ws=0x7000010)) == B.EPARA_ERR_ALIGN
+    assert fwd(launch(ws_bytes=info.workspace_bytes - 1)) == B.EPARA_ERR_CAPACITY
+    assert fwd(launch(n_split=info.n_split_tiles - 1)) == B.EPARA_ERR_SHAPE
+    assert fwd(launch(n_split=-1)) == B.EPARA_ERR_SHAPE
+    bad = args.copy(); bad["reserved"][2] = 0
+    assert fwd(launch(a=bad)) == B.EPARA_ERR_SHAPE                                   # a group's slots are not where the layout puts them
+    assert fwd(launch(), B.EPARA_FP8_E4M3) in (B.EPARA_ERR_SHAPE, B.EPARA_ERR_ALIGN)   # fp8 launches have no split tiles
+    # a chain takes no launch with split tiles
+    ph = (B.ChainPhase * 1)()
+    L = launch()
+    ph[0].launch, ph[0].out_dtype = ctypes.pointer(L), B.EPARA_BF16
+    assert lib.epara_grouped_chain(ph, 1, B.EPARA_BF16, ctypes.c_void_p(0x9000000), 1 << 20, 0, None) == B.EPARA_ERR_SHAPE
+    # the workspace's own entry point
+    assert lib.epara_workspace_init(None, 256, None) == B.EPARA_ERR_NULL
+    assert lib.epara_workspace_init(ctypes.c_void_p(0x7000004), 256, None) == B.EPARA_ERR_ALIGN
