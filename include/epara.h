@@ -64,8 +64,8 @@ typedef enum { EPARA_CAT_LATENCY = 0, EPARA_CAT_FREQUENCY = 1 } epara_category;
 typedef struct { int32_t M, K, N; int32_t act; int32_t has_bias; int32_t category; } epara_group_desc;
 
 /* A group with M <= max_M (first such class wins) is cut into BM x BN output tiles.  split_K: 0, or the K
- * from which a single launch visits a weight-streaming tile of this class in two parts of K (see
- * "Splitting K" below); ignored for the other classes. */
+ * from which a single launch may visit a tile of this class in parts of K (see "Splitting K" below): a
+ * weight-streaming tile in two, the panel tiles of a launch's last round in two to four. */
 typedef struct { int32_t max_M; int32_t BM, BN; int32_t split_K; } epara_tile_class;
 
 /* One output tile: rows [m0, m0+rows) x columns [n0, n0+cols) of group `group`. 24 bytes. */
@@ -99,10 +99,10 @@ typedef struct {
     int64_t n_slots;
     int32_t n_workgroups;             /* the value the order was built for; becomes the grid size */
     int32_t G;
-    void*   d_workspace;              /* device, 256-byte aligned, zeroed once (epara_workspace_init); NULL if n_split_tiles = 0 */
-    int64_t workspace_bytes;
+    void*   d_workspace;              /* device, 256-byte aligned, zeroed once (epara_workspace_init); NULL if nothing is split */
+    int64_t workspace_bytes;          /* at least epara_split_workspace_bytes(n_split_tiles, n_panel_split_tiles) */
     int32_t n_split_tiles;            /* streaming tiles whose K is split over several visits (epara_split_layout) */
-    int32_t reserved;
+    int32_t n_panel_split_tiles;      /* panel tiles, the last ones of the tile table, likewise (epara_panel_split) */
 } epara_launch;
 
 /* ---- chains of launches in one kernel -----------------------------------------------------
@@ -373,7 +373,32 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
 #define EPARA_SPLIT_PARTS 2
 #define EPARA_SPLIT_K_BF16 8192
 #define EPARA_SPLIT_MAX_PARTS 4
-#define EPARA_SPLIT_STRIDE 32768      /* bytes of partial sums per (split tile, part) */
+#define EPARA_SPLIT_STRIDE 32768      /* bytes of partial sums per (split streaming tile, part) */
+
+/* Panel tiles can be split the same way, for another reason: a launch of n equal panel tiles on W workgroups
+ * ends with a round of m = n mod W tiles that leaves W - m workgroups idle for a whole tile.  When the launch
+ * holds nothing but panel tiles of one class with split_K > 0 and one K >= split_K, of groups without
+ * EPARA_ACT_SWIGLU (a down projection; epara_kernel_classes sets EPARA_PANEL_SPLIT_K for the plain bf16
+ * panel class, 0 for the gated one, for fp8, whose visits are half as long, and for fp32),
+ * those m tiles -- the last m of the canonical table -- are visited in P parts of K instead, P in 2 ..
+ * EPARA_SPLIT_MAX_PARTS chosen to minimise  ceil(m P / W) * (cost / P + EPARA_COST_PANEL_PARTIAL)  and only if
+ * that is below 0.9 * cost (the smallest such P on ties); part j of P covers the units floor(U j / P) ..
+ * floor(U (j+1) / P) - 1 of the U = ceil(ceil(K / stage) / 4) units of four 64-byte stages.
+ * A visit leaves its 256 x 256 fp32 sums (EPARA_PANEL_SPLIT_STRIDE bytes) in the workspace, behind the streaming
+ * tiles' slots; counting and the addition in index order work as for streaming tiles.  epara_panel_split states
+ * the decision; it depends on the grid size. */
+#define EPARA_PANEL_SPLIT_STRIDE 262144   /* bytes of partial sums per (split panel tile, part) */
+#define EPARA_PANEL_SPLIT_K 1024          /* every part then holds whole units of four stages, bf16 or fp8 */
+#define EPARA_COST_PANEL_PARTIAL 1020000  /* a part's trip through memory, in cost units (about 500 elements of K) */
+int32_t epara_panel_split(const epara_group_desc* groups, int32_t G,
+                          const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
+                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts);
+
+/* Bytes of the workspace of a launch with n_split_tiles split streaming tiles and n_panel_split_tiles split
+ * panel tiles: 4 bytes of counter per split tile, rounded up to 256, then EPARA_SPLIT_MAX_PARTS parts of
+ * EPARA_SPLIT_STRIDE bytes per streaming tile, then EPARA_SPLIT_MAX_PARTS parts of EPARA_PANEL_SPLIT_STRIDE bytes
+ * per panel tile; 0 if both counts are 0, -1 if one is negative. */
+int64_t epara_split_workspace_bytes(int32_t n_split_tiles, int32_t n_panel_split_tiles);
 #define EPARA_ORDER_ENTRY(tile, part, parts) ((int32_t)((tile) | ((part) << 24) | (((parts) - 1) << 28)))
 #define EPARA_ORDER_TILE(entry) ((entry) & 0xFFFFFF)
 
@@ -444,8 +469,8 @@ typedef struct {
     int32_t gated;                    /* 1: every group is EPARA_ACT_SWIGLU */
     int64_t n_tiles, n_slots;
     int64_t makespan;                 /* cost of the most loaded workgroup under the cost model */
-    int64_t workspace_bytes;          /* of epara_split_layout for the chosen table */
-    int32_t n_split_tiles, reserved;
+    int64_t workspace_bytes;          /* epara_split_workspace_bytes of the two counts below */
+    int32_t n_split_tiles, n_panel_split_tiles;
 } epara_launch_plan;
 
 /* The whole planning decision of one launch (Sec. 3.1: the parallel mode of each task): picks the class
@@ -518,11 +543,11 @@ int32_t epara_ffn_swiglu_args(const epara_ffn_desc* ffn, int32_t G, int32_t in_d
 
 /* ---- device side -------------------------------------------------------------------- */
 
-/* An upper bound of the device workspace a launch of these groups needs, whichever class table the plan
- * picks (epara_plan_launch reports the exact size): the larger of epara_split_layout over the two tables;
- * 0 when no tile would be split (fp32 launches, batches of at most 16 rows, short K).  -1 for a bad
- * dtype, G < 0 or a mixture of EPARA_ACT_SWIGLU and other groups. */
-int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype);
+/* An upper bound of the device workspace a launch of these groups on n_workgroups workgroups needs, whichever
+ * class table the plan picks (epara_plan_launch reports the exact size): the larger of the two tables' needs;
+ * 0 when no tile would be split (fp32 launches, batches of at most 16 rows, short K, full last rounds).  -1 for
+ * a bad dtype, G < 0, n_workgroups <= 0 or a mixture of EPARA_ACT_SWIGLU and other groups. */
+int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype, int32_t n_workgroups);
 
 /* Bytes of the packed form of a [K,N] weight matrix (fp32: K*N*4, unchanged layout). */
 int64_t epara_packed_weight_bytes(int32_t K, int32_t N, int32_t dtype);

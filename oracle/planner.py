@@ -239,6 +239,46 @@ def split_layout(groups, classes, n_stream_classes):
     return base, n, (0 if n == 0 else (n * 4 + 255) // 256 * 256 + n * 4 * 32768)
 
 
+def split_workspace_bytes(n_split_tiles, n_panel_split_tiles):
+    """Counters (4 bytes per split tile, rounded up to 256), then 4 parts of 32 KiB per streaming tile, then 4 parts
+    of 256 KiB per panel tile."""
+    n = n_split_tiles + n_panel_split_tiles
+    return 0 if n == 0 else (n * 4 + 255) // 256 * 256 + n_split_tiles * 4 * 32768 + n_panel_split_tiles * 4 * 262144
+
+
+def panel_split(groups, classes, n_stream_classes, n_workgroups):
+    """-> (m, P): the last m tiles of the tile table are visited in P parts of K (m = 0: none).  Only for a launch
+    of panel tiles alone, all of one class that names a split_K and of one K >= split_K, no gated group: with n
+    tiles on W workgroups the last round holds m = n mod W of them; P in 2..4 minimises
+    ceil(m P / W) * (cost // P + 1020000), cost = 2040 K, and must bring it below 9 cost // 10 (smallest P on ties)."""
+    W = n_workgroups
+    cls = K = None
+    n = 0
+    for g in groups:
+        M, Kg, N = g[:3]
+        if M <= 0:
+            continue
+        c = pick_class(M, classes)
+        cl = classes[c]
+        if c < n_stream_classes or (len(g) > 3 and g[3]):
+            return 0, 1
+        if cls is not None and (c != cls or Kg != K):
+            return 0, 1
+        if len(cl) < 4 or cl[3] <= 0 or Kg < cl[3]:
+            return 0, 1
+        cls, K = c, Kg
+        n += -(-M // cl[1]) * -(-N // cl[2])
+    if cls is None or n % W == 0:
+        return 0, 1
+    m, cost = n % W, 2040 * K
+    best, parts = cost * 9 // 10, 1
+    for P in (2, 3, 4):
+        t = -(-m * P // W) * (cost // P + 1020000)
+        if t < best:
+            best, parts = t, P
+    return (m, parts) if parts > 1 else (0, 1)
+
+
 def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
     """Visit order of the persistent workgroups.
 
@@ -256,7 +296,9 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        workgroups the one of smallest die-major rank, rank r standing for workgroup (r mod (W/X)) * X + r div (W/X).
        Tiles of equal cost therefore go round robin, the l-th to rank l mod W, and the W/X tiles that run
        together on one die are consecutive in the sequence; a workgroup that got a long-K tile gets fewer
-       of the short ones.
+       of the short ones.  In a single launch the last m tiles of the table may be left out of this sequence
+       and visited in P parts of K instead (panel_split): their parts follow, tile by tile and part by part,
+       each an item of cost 2040 * K // P + 1020000 under the same rule, entry tile | part << 24 | (P - 1) << 28.
     2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + (2 * BM if BM >= 32 else 0))
        for a streaming tile (weight columns streamed from HBM, plus the activation rows re-read from L2
        at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  In a single launch a
@@ -285,6 +327,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
     load = [0] * W
     rank_heap = [(0, r) for r in range(W)]                   # (load, die-major rank); rank r = workgroup (r mod per) * X + r div per
     stream = []
+    n_panel_split, panel_parts = panel_split(*phases[0][:3], W) if len(phases) == 1 else (0, 1)
     for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
         if not 0 <= n_stream_classes <= len(classes):
             raise ValueError("bad number of streaming classes")
@@ -302,12 +345,24 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
                     for pm in range(0, TM, panel_m):
                         for tn in range(pn, min(pn + panel_n, TN)):
                             for tm in range(pm, min(pm + panel_m, TM)):
+                                t = first[g] + tm * TN + tn
+                                if t >= len(tiles) - n_panel_split:      # visited in parts, after the whole tiles
+                                    continue
                                 _, r = heapq.heappop(rank_heap)
                                 x, i = divmod(r, per)
                                 b = i * X + x
-                                lists[p][b].append(first[g] + tm * TN + tn)
+                                lists[p][b].append(t)
                                 load[b] += 2040 * K
                                 heapq.heappush(rank_heap, (load[b], r))
+        for t in range(len(tiles) - n_panel_split, len(tiles)):    # the parts: tile by tile, part by part, same rule
+            each = 2040 * groups[tiles[t][0]][1] // panel_parts + 1020000
+            for j in range(panel_parts):
+                _, r = heapq.heappop(rank_heap)
+                x, i = divmod(r, per)
+                b = i * X + x
+                lists[p][b].append(order_entry(t, j, panel_parts))
+                load[b] += each
+                heapq.heappush(rank_heap, (load[b], r))
         for t, tile in enumerate(tiles):
             if tile[5] < n_stream_classes:
                 g = groups[tile[0]]

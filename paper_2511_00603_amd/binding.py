@@ -47,7 +47,7 @@ class LaunchPlanInfo(ctypes.Structure):
     _fields_ = [("classes", ctypes.c_int32 * 16), ("n_classes", ctypes.c_int32), ("n_stream_classes", ctypes.c_int32),
                 ("narrow", ctypes.c_int32), ("gated", ctypes.c_int32), ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
                 ("makespan", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64), ("n_split_tiles", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("n_panel_split_tiles", ctypes.c_int32)]
 
     def class_table(self):
         return np.array(list(self.classes), dtype=np.int32)[: 4 * self.n_classes].view(TILE_CLASS).copy()
@@ -67,7 +67,7 @@ class Launch(ctypes.Structure):
                 ("n_tiles", ctypes.c_int64), ("n_slots", ctypes.c_int64),
                 ("n_workgroups", ctypes.c_int32), ("G", ctypes.c_int32),
                 ("d_workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64), ("n_split_tiles", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("n_panel_split_tiles", ctypes.c_int32)]
 
 
 assert ctypes.sizeof(Launch) == 88
@@ -153,8 +153,12 @@ def lib():
         L.epara_plan_groups.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, i64, vp]
         L.epara_schedule_tiles.argtypes = [vp, i32, vp, i32, i32, vp, i64, i32, i32, i32, i32, vp, i64, vp]
         L.epara_kernel_classes.argtypes = [i32, i32, i32, vp, i32, vp, vp]
-        L.epara_workspace_bytes.argtypes = [vp, i32, i32]
+        L.epara_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.epara_workspace_bytes.restype = i64
+        L.epara_split_workspace_bytes.argtypes = [i32, i32]
+        L.epara_split_workspace_bytes.restype = i64
+        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+        L.epara_panel_split.restype = i32
         L.epara_simulate.argtypes = [vp, vp, i32, vp, i64, vp, vp]
         L.epara_simulate.restype = i32
         L.epara_schedule_chain.argtypes = [vp, i32, i32, i32, i32, i32]
@@ -173,8 +177,12 @@ def lib():
         L.epara_split_layout.restype = i32
         L.epara_workspace_init.argtypes = [vp, i64, vp]
         L.epara_workspace_init.restype = i32
-        L.epara_workspace_bytes.argtypes = [vp, i32, i32]
+        L.epara_workspace_bytes.argtypes = [vp, i32, i32, i32]
         L.epara_workspace_bytes.restype = i64
+        L.epara_split_workspace_bytes.argtypes = [i32, i32]
+        L.epara_split_workspace_bytes.restype = i64
+        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+        L.epara_panel_split.restype = i32
         L.epara_plan_launch.restype = i32
         L.epara_plan_chain.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp]
         L.epara_plan_chain.restype = i32
@@ -387,9 +395,23 @@ def epara_split_layout(groups, classes, n_stream_classes):
     return base, int(n.value), int(nbytes.value)
 
 
-def epara_workspace_bytes(groups, in_dtype):
+def epara_workspace_bytes(groups, in_dtype, n_workgroups=256):
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
-    return int(lib().epara_workspace_bytes(_ptr(groups) if len(groups) else None, len(groups), int(in_dtype)))
+    return int(lib().epara_workspace_bytes(_ptr(groups) if len(groups) else None, len(groups), int(in_dtype), int(n_workgroups)))
+
+
+def epara_split_workspace_bytes(n_split_tiles, n_panel_split_tiles):
+    return int(lib().epara_split_workspace_bytes(int(n_split_tiles), int(n_panel_split_tiles)))
+
+
+def epara_panel_split(groups, classes, n_stream_classes, n_workgroups):
+    """-> (number of panel tiles, the last of the tile table, visited in parts of K; parts)."""
+    groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
+    classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
+    n, parts = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().epara_panel_split(_ptr(groups) if len(groups) else None, len(groups), _ptr(classes), len(classes), int(n_stream_classes),
+                                   int(n_workgroups), ctypes.byref(n), ctypes.byref(parts)), "epara_panel_split")
+    return int(n.value), int(parts.value)
 
 
 def epara_workspace_init(d_workspace, nbytes, stream=0):

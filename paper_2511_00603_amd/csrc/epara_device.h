@@ -339,8 +339,18 @@ __device__ __forceinline__ int order_parts(int o) { return ((o >> 28) & 7) + 1; 
 // SPLIT_STRIDE bytes of partial sums per split tile.  The visit that arrives last adds the parts in index order and
 // runs the epilogue, so the result does not depend on who that is.
 constexpr int SPLIT_STRIDE = EPARA_SPLIT_STRIDE, SPLIT_MAX_PARTS = EPARA_SPLIT_MAX_PARTS;
-struct split_ctx { uint32_t* ws; int n_split; };
-__device__ __forceinline__ char* split_partials(const split_ctx& sp) { return reinterpret_cast<char*>(sp.ws) + ((sp.n_split * 4 + 255) & ~255); }
+constexpr int PANEL_SPLIT_STRIDE = EPARA_PANEL_SPLIT_STRIDE;
+// n_split streaming tiles, then n_panel panel tiles (the tiles first_panel ... of the tile table): counters in that
+// order, then the streaming tiles' partial sums, then the panel tiles'.
+struct split_ctx { uint32_t* ws; int n_split; int n_panel; int first_panel; };
+__device__ __forceinline__ char* split_partials(const split_ctx& sp)
+{
+    return reinterpret_cast<char*>(sp.ws) + (((sp.n_split + sp.n_panel) * 4 + 255) & ~255);
+}
+__device__ __forceinline__ char* panel_partials(const split_ctx& sp)
+{
+    return split_partials(sp) + static_cast<size_t>(sp.n_split) * SPLIT_MAX_PARTS * SPLIT_STRIDE;
+}
 __device__ __forceinline__ void split_put(char* at, const v4f& v)     // through to memory: another die reads it
 {
     typedef unsigned long long u64;
@@ -348,6 +358,16 @@ __device__ __forceinline__ void split_put(char* at, const v4f& v)     // through
     const u64 hi = (static_cast<u64>(__float_as_uint(v[3])) << 32) | __float_as_uint(v[2]);
     __hip_atomic_store(reinterpret_cast<u64*>(at), lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(reinterpret_cast<u64*>(at) + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The same store as one 16-byte instruction (the compiler has no 16-byte atomic store to offer): whole 256-byte row
+// pieces leave a quarter wave at once.  Nothing is returned, so only the explicit wait before a visit is counted
+// has to know about it; loads and stores complete in issue order, which keeps every other wait conservative.
+// A store of more than 8 bytes reads its data registers a cycle after it issues, and the compiler's hazard
+// check does not look inside an asm statement: the wait state that keeps the next instruction from
+// overwriting them is part of the statement.
+__device__ __forceinline__ void split_put16(char* at, const v4f& v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(at), "v"(v) : "memory");
 }
 __device__ __forceinline__ v4f split_get(const char* at)
 {
@@ -357,6 +377,16 @@ __device__ __forceinline__ v4f split_get(const char* at)
     return v4f{__uint_as_float(static_cast<uint32_t>(lo)), __uint_as_float(static_cast<uint32_t>(lo >> 32)),
                __uint_as_float(static_cast<uint32_t>(hi)), __uint_as_float(static_cast<uint32_t>(hi >> 32))};
 }
+
+// The visits a workgroup has made to tiles whose K is split, not yet counted at the tiles' counters: lane i
+// of `slots` / `entries` holds the i-th (the same in every wave).  Counting is put off to the end of the
+// workgroup's list, where one atomic instruction does it for all of them and nothing waits for it in the
+// middle of a weight stream.
+struct split_pending {
+    int count;
+    int slots;             // the tile's workspace slot | (parts - 1) << 28
+    int entries;           // the visit's entry of the order
+};
 
 }  // namespace
 

@@ -21,7 +21,7 @@ namespace {
 // Counts the workgroup's visits to split tiles at the tiles' counters (one atomic instruction for all of
 // them) and finishes the tiles at which it arrived last.  Every partial sum of the workgroup is in memory
 // before the count says so; whoever finishes a tile puts its counter back to zero for the next launch.
-template <int DT, bool GATED>
+template <int DT, bool GATED, bool PANEL_ONLY>
 __device__ __forceinline__ void split_flush(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
                                             int out_dtype, int narrow, char* lds, const split_ctx* sp, split_pending& pend)
 {
@@ -53,9 +53,13 @@ __device__ __forceinline__ void split_flush(const epara_group_args* __restrict__
         const int slot = info & 0xFFFFFFF, nparts = (static_cast<uint32_t>(info) >> 28) + 1;
         const epara_tile tl = tiles[order_tile(entry)];
         const epara_group_args ga = args[tl.group];
-        if (tl.cls == 1)                 split_finish<DT, GATED, 2, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
-        else if (tl.cls == 2 && !narrow) split_finish<DT, GATED, 4, 8>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
-        else if (tl.cls == 2)            split_finish<DT, GATED, 4, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+        if (tl.cls >= N_STREAM_CLASSES) {
+            if constexpr (!GATED) panel_split_finish<DT>(ga, tl, out_dtype, slot - sp->n_split, nparts, tid, sp, lds);
+        } else if constexpr (!PANEL_ONLY) {
+            if (tl.cls == 1)                 split_finish<DT, GATED, 2, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+            else if (tl.cls == 2 && !narrow) split_finish<DT, GATED, 4, 8>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+            else if (tl.cls == 2)            split_finish<DT, GATED, 4, 4>(ga, out_dtype, tl.n0, tl.cols, slot, nparts, wave, lane, lds, sp);
+        }
         if (tid == 0) __hip_atomic_store(sp->ws + slot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();                                         // the next tile's parts land where these were read
     }
@@ -67,6 +71,8 @@ __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict_
                                              const int32_t* __restrict__ order, long n_slots, int out_dtype, int narrow, char* lds,
                                              chain_ctx* chain = nullptr, const split_ctx* sp = nullptr)
 {
+    // which kernels can meet tiles visited in parts of K: bf16 only, streaming tiles and plain panel tiles of single launches
+    constexpr bool HAS_SPLIT = !CHAIN && DT == EPARA_BF16 && (!PANEL_ONLY || !GATED);
     const long stride = gridDim.x;
     long s = blockIdx.x;
     split_pending pend = {0, 0, 0};
@@ -83,34 +89,34 @@ __device__ __forceinline__ void grouped_body(const epara_group_args* __restrict_
         }
         nx.known = false;
         if constexpr (CHAIN) chain_wait(*chain, tl.group);
+        if constexpr (HAS_SPLIT) { if (pend.count >= 63) split_flush<DT, GATED, PANEL_ONLY>(args, tiles, out_dtype, narrow, lds, sp, pend); }
         if constexpr (!PANEL_ONLY) {
-            if constexpr (!CHAIN && DT == EPARA_BF16) { if (pend.count >= 63) split_flush<DT, GATED>(args, tiles, out_dtype, narrow, lds, sp, pend); }
             const epara_group_args ga0 = nx.ga;
             if (tl.cls == 0)      { s = skinny_run<DT, GATED, CHAIN, 0, 1, 2, 4>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
             else if (tl.cls == 1) { s = skinny_run<DT, GATED, CHAIN, 1, 2, 4, 3>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
             else if (tl.cls == 2 && !narrow) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 8, 2>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
             else if (tl.cls == 2) { s = skinny_run<DT, GATED, CHAIN, 2, 4, 4, 3>(args, tiles, order, s, t, tl, ga0, known, n_slots, stride, out_dtype, lds, chain, sp, &pend, nx); continue; }
         }
-        s = panel_run<DT, GATED, CHAIN, CHAIN>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain);
+        s = panel_run<DT, GATED, CHAIN, CHAIN>(args, tiles, order, s, n_slots, stride, out_dtype, lds, chain, sp, &pend);
         nx = run_next{};                                         // nothing is carried across a panel run
     }
-    if constexpr (!PANEL_ONLY && !CHAIN && DT == EPARA_BF16) split_flush<DT, GATED>(args, tiles, out_dtype, narrow, lds, sp, pend);
+    if constexpr (HAS_SPLIT) split_flush<DT, GATED, PANEL_ONLY>(args, tiles, out_dtype, narrow, lds, sp, pend);
 }
 
 template <int DT, bool GATED, bool PANEL_ONLY>
 __global__ __launch_bounds__(NT) void grouped_kernel(const epara_group_args* __restrict__ args,
                                                      const epara_tile* __restrict__ tiles,
                                                      const int32_t* __restrict__ order,
-                                                     long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split)
+                                                     long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const split_ctx sp = {split_ws, n_split};
+    const split_ctx sp = {split_ws, n_split, n_panel_split, first_panel_split};
     grouped_body<DT, GATED, false, PANEL_ONLY>(args, tiles, order, n_slots, out_dtype, narrow, lds, nullptr, &sp);
 }
 
 template <int DT, bool GATED>
 hipError_t enqueue_grouped(int panel_only, unsigned grid, hipStream_t stream, const epara_group_args* args, const epara_tile* tiles,
-                           const int32_t* order, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split)
+                           const int32_t* order, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split)
 {
     static const hipError_t attr0 = hipFuncSetAttribute(reinterpret_cast<const void*>(&grouped_kernel<DT, GATED, false>),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -119,9 +125,9 @@ hipError_t enqueue_grouped(int panel_only, unsigned grid, hipStream_t stream, co
     if (attr0 != hipSuccess) return attr0;
     if (attr1 != hipSuccess) return attr1;
     if (panel_only)
-        hipLaunchKernelGGL((grouped_kernel<DT, GATED, true>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split);
+        hipLaunchKernelGGL((grouped_kernel<DT, GATED, true>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split, n_panel_split, first_panel_split);
     else
-        hipLaunchKernelGGL((grouped_kernel<DT, GATED, false>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split);
+        hipLaunchKernelGGL((grouped_kernel<DT, GATED, false>), dim3(grid), dim3(NT), LDS_BYTES, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split, n_panel_split, first_panel_split);
     return hipGetLastError();
 }
 

@@ -29,6 +29,22 @@ inline int64_t tile_cost(const epara_group_desc& d, const epara_tile& tl, const 
     return units * d.K;
 }
 
+// Whether the last round of a launch of equal panel tiles is worth cutting along K, and into how many parts
+// (see "Splitting K" in the header).  n_panel: all tiles of the launch, every one a panel tile of cost `cost`
+// (the class's split_K keeps K long enough for every part to hold whole units of four K stages).  Returns the number of tiles to split (0: none) and the parts.
+inline int32_t panel_split_choice(int64_t n_panel, int64_t W, int64_t cost, int32_t* parts)
+{
+    *parts = 1;
+    const int64_t m = n_panel % W;
+    if (n_panel == 0 || m == 0) return 0;
+    int64_t best = cost * 9 / 10;                                // must beat 0.9 of a whole tile
+    for (int32_t P = 2; P <= EPARA_SPLIT_MAX_PARTS; ++P) {
+        const int64_t t = ((m * P + W - 1) / W) * (cost / P + EPARA_COST_PANEL_PARTIAL);
+        if (t < best) { best = t; *parts = P; }
+    }
+    return *parts > 1 ? static_cast<int32_t>(m) : 0;
+}
+
 int32_t check_classes(const epara_tile_class* classes, int32_t n_classes)
 {
     if (!classes) return EPARA_ERR_NULL;
@@ -47,6 +63,27 @@ int32_t class_of(int32_t M, const epara_tile_class* classes, int32_t n_classes)
     return -1;
 }
 
+// The panel split of a launch (validated groups and classes): tiles to split, parts.
+int32_t panel_split_of(const epara_group_desc* groups, int32_t G, const epara_tile_class* classes, int32_t n_classes,
+                       int32_t n_stream_classes, int64_t W, int32_t* parts)
+{
+    *parts = 1;
+    int32_t cls = -1, K = 0;
+    int64_t n = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_group_desc& d = groups[g];
+        if (d.M <= 0) continue;
+        const int32_t c = class_of(d.M, classes, n_classes);
+        if (c < n_stream_classes || d.act == EPARA_ACT_SWIGLU) return 0;
+        if (cls >= 0 && (c != cls || d.K != K)) return 0;
+        if (classes[c].split_K <= 0 || d.K < classes[c].split_K) return 0;
+        cls = c; K = d.K;
+        n += ceil_div(d.M, classes[c].BM) * ceil_div(d.N, classes[c].BN);
+    }
+    if (cls < 0 || n > 0xFFFFFF) return 0;
+    return panel_split_choice(n, W, static_cast<int64_t>(EPARA_COST_PANEL) * K, parts);
+}
+
 int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
 {
     int32_t n_gated = 0, n_live = 0;
@@ -61,9 +98,10 @@ int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
 inline int32_t split_parts(const epara_group_desc& d, const epara_tile_class& c) { return c.split_K > 0 && d.K >= c.split_K ? EPARA_SPLIT_PARTS : 1; }
 
 // Cost of one of the `parts` visits of a tile whose whole cost is `cost`: its share of K plus the partial result it leaves.
-inline int64_t visit_cost(int64_t cost, int32_t parts, const epara_group_desc& d, const epara_tile& t, const epara_tile_class& c)
+inline int64_t visit_cost(int64_t cost, int32_t parts, const epara_group_desc& d, const epara_tile& t, const epara_tile_class& c, bool panel = false)
 {
     if (parts == 1) return cost;
+    if (panel) return cost / parts + EPARA_COST_PANEL_PARTIAL;
     return cost / parts + static_cast<int64_t>(EPARA_COST_PARTIAL) * c.BM * t.cols * (d.act == EPARA_ACT_SWIGLU ? 2 : 1);
 }
 
@@ -508,6 +546,10 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
     std::priority_queue<ranked, std::vector<ranked>, std::greater<ranked>> panel_heap;
     for (int64_t r = 0; r < W; ++r) panel_heap.push({0, r});
     std::vector<int32_t> class_order, members;
+    // a single launch of equal panel tiles may visit the tiles of its last round in parts of K
+    int32_t panel_parts = 1;
+    const int64_t n_panel_split = n_phases == 1 ? panel_split_of(phases[0].groups, phases[0].G, phases[0].classes, phases[0].n_classes,
+                                                                 phases[0].n_stream_classes, W, &panel_parts) : 0;
     for (int32_t p = 0; p < n_phases; ++p) {
         const epara_phase_schedule& ph = phases[p];
         class_order.clear();
@@ -528,13 +570,30 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
                     for (int64_t pm = 0; pm < TM; pm += panel_m)
                         for (int64_t tn = pn; tn < std::min<int64_t>(pn + panel_n, TN); ++tn)
                             for (int64_t tm = pm; tm < std::min<int64_t>(pm + panel_m, TM); ++tm) {
+                                const int64_t tile = first[p][g] + tm * TN + tn;
+                                if (tile >= ph.n_tiles - n_panel_split) continue;      // visited in parts, after the whole tiles
                                 const ranked top = panel_heap.top();
                                 panel_heap.pop();
                                 const int64_t x = top.second / per_die, i = top.second % per_die, b = i * X + x;
-                                lists[p][b].push_back(static_cast<int32_t>(first[p][g] + tm * TN + tn));
+                                lists[p][b].push_back(static_cast<int32_t>(tile));
                                 load[b] += static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[g].K;
                                 panel_heap.push({load[b], top.second});
                             }
+            }
+        }
+    }
+
+    if (n_panel_split > 0) {                                     // the parts: tile by tile, part by part, same rule
+        const epara_phase_schedule& ph = phases[0];
+        for (int64_t tile = ph.n_tiles - n_panel_split; tile < ph.n_tiles; ++tile) {
+            const int64_t each = static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[ph.tiles[tile].group].K / panel_parts + EPARA_COST_PANEL_PARTIAL;
+            for (int32_t j = 0; j < panel_parts; ++j) {
+                const ranked top = panel_heap.top();
+                panel_heap.pop();
+                const int64_t x = top.second / per_die, i = top.second % per_die, b = i * X + x;
+                lists[0][b].push_back(EPARA_ORDER_ENTRY(static_cast<int32_t>(tile), j, panel_parts));
+                load[b] += each;
+                panel_heap.push({load[b], top.second});
             }
         }
     }
@@ -699,7 +758,7 @@ int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32
                     if (p > 0 && phases[p].producer && phases[p].producer[tl.group] >= 0)
                         start = std::max(start, ready_prev[phases[p].producer[tl.group]]);
                     clock[b] = start + visit_cost(tile_cost(phases[p].groups[tl.group], tl, o.classes, o.n_stream), (e >> 28) + 1,
-                                                  phases[p].groups[tl.group], tl, o.classes[tl.cls]);
+                                                  phases[p].groups[tl.group], tl, o.classes[tl.cls], tl.cls >= o.n_stream);
                     ready[tl.group] = std::max(ready[tl.group], clock[b]);
                 }
             ready_prev.swap(ready);
@@ -722,7 +781,7 @@ int32_t epara_plan_chain(epara_chain_plan_phase* phases, int32_t n_phases, int32
                 const int32_t e = best_order[p][i];
                 const epara_tile& tl = o.tiles[EPARA_ORDER_TILE(e)];
                 load[i % W] += visit_cost(tile_cost(ph.groups[tl.group], tl, o.classes, o.n_stream), (e >> 28) + 1, ph.groups[tl.group], tl,
-                                          o.classes[tl.cls]);
+                                          o.classes[tl.cls], tl.cls >= o.n_stream);
             }
         fill_plan(ph.plan, o, gated[p], static_cast<int64_t>(best_order[p].size()), *std::max_element(load.begin(), load.end()));
         ph.counter_base = base;
@@ -762,6 +821,9 @@ int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_
     *plan = ph.plan;
     if (int32_t s3 = epara_split_layout(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, split_base,
                                         &plan->n_split_tiles, &plan->workspace_bytes)) return s3;
+    int32_t panel_parts = 1;
+    plan->n_panel_split_tiles = panel_split_of(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, n_workgroups, &panel_parts);
+    plan->workspace_bytes = epara_split_workspace_bytes(plan->n_split_tiles, plan->n_panel_split_tiles);
     if (row_off || x_off || y_off) {
         int64_t n = 0;
         if (int32_t s2 = epara_plan_groups(groups, G, plan->classes, plan->n_classes, row_off, x_off, y_off, nullptr, 0, &n)) return s2;
@@ -816,13 +878,38 @@ int32_t epara_split_layout(const epara_group_desc* groups, int32_t G,
     }
     if (n > 0xFFFFFF) return EPARA_ERR_SHAPE;
     *n_split_tiles = static_cast<int32_t>(n);
-    *workspace_bytes = n == 0 ? 0 : (n * 4 + 255) / 256 * 256 + n * EPARA_SPLIT_MAX_PARTS * static_cast<int64_t>(EPARA_SPLIT_STRIDE);
+    *workspace_bytes = epara_split_workspace_bytes(static_cast<int32_t>(n), 0);
     return EPARA_OK;
 }
 
-int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype)
+int64_t epara_split_workspace_bytes(int32_t n_split_tiles, int32_t n_panel_split_tiles)
 {
-    if (G < 0 || (in_dtype != EPARA_F32 && in_dtype != EPARA_BF16 && in_dtype != EPARA_FP8_E4M3)) return -1;
+    if (n_split_tiles < 0 || n_panel_split_tiles < 0) return -1;
+    const int64_t n = static_cast<int64_t>(n_split_tiles) + n_panel_split_tiles;
+    if (n == 0) return 0;
+    return (n * 4 + 255) / 256 * 256 + static_cast<int64_t>(n_split_tiles) * EPARA_SPLIT_MAX_PARTS * EPARA_SPLIT_STRIDE +
+           static_cast<int64_t>(n_panel_split_tiles) * EPARA_SPLIT_MAX_PARTS * EPARA_PANEL_SPLIT_STRIDE;
+}
+
+int32_t epara_panel_split(const epara_group_desc* groups, int32_t G,
+                          const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
+                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts)
+{
+    if (G < 0 || n_workgroups <= 0) return EPARA_ERR_SHAPE;
+    if (!n_panel_split_tiles || !parts || (G > 0 && !groups)) return EPARA_ERR_NULL;
+    if (int32_t st = check_classes(classes, n_classes)) return st;
+    if (n_stream_classes < 0 || n_stream_classes > n_classes) return EPARA_ERR_SHAPE;
+    for (int32_t g = 0; g < G; ++g) {
+        if (groups[g].M < 0 || groups[g].K <= 0 || groups[g].N <= 0) return EPARA_ERR_SHAPE;
+        if (groups[g].M > 0 && class_of(groups[g].M, classes, n_classes) < 0) return EPARA_ERR_SHAPE;
+    }
+    *n_panel_split_tiles = panel_split_of(groups, G, classes, n_classes, n_stream_classes, n_workgroups, parts);
+    return EPARA_OK;
+}
+
+int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t in_dtype, int32_t n_workgroups)
+{
+    if (G < 0 || n_workgroups <= 0 || (in_dtype != EPARA_F32 && in_dtype != EPARA_BF16 && in_dtype != EPARA_FP8_E4M3)) return -1;
     if (G > 0 && !groups) return -1;
     if (in_dtype == EPARA_F32) return 0;
     int32_t gated = 0;
@@ -834,7 +921,9 @@ int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t
         int64_t bytes = 0;
         if (epara_kernel_classes(in_dtype, gated, narrow, classes, 4, &nc, &ns) != EPARA_OK) return -1;
         if (epara_split_layout(groups, G, classes, nc, ns, nullptr, &n_split, &bytes) != EPARA_OK) return -1;
-        worst = std::max(worst, bytes);
+        int32_t parts = 1;
+        const int32_t n_panel = panel_split_of(groups, G, classes, nc, ns, n_workgroups, &parts);
+        worst = std::max(worst, epara_split_workspace_bytes(n_split, n_panel));
     }
     return worst;
 }
@@ -858,7 +947,7 @@ int32_t epara_kernel_classes(int32_t in_dtype, int32_t gated, int32_t narrow,
         table[n++] = {32, 32, gated ? 32 : 64, split_K};
         table[n++] = {64, 64, (gated ? 64 : 128) >> (narrow ? 1 : 0), split_K};
         ns = 3;
-        table[n++] = {INT32_MAX, 256, gated ? 128 : 256, 0};  // LDS-tiled MFMA class
+        table[n++] = {INT32_MAX, 256, gated ? 128 : 256, (gated || in_dtype != EPARA_BF16) ? 0 : EPARA_PANEL_SPLIT_K};  // matrix-core class
     } else {
         return EPARA_ERR_DTYPE;
     }

@@ -26,10 +26,10 @@ struct epara_chain_tables {
 };
 
 // One grouped launch; dtype = EPARA_BF16 / EPARA_FP8_E4M3; panel_only: the tile table holds no streaming tile.
-EPARA_HIDDEN hipError_t epara_enqueue_bf16_plain(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split);
-EPARA_HIDDEN hipError_t epara_enqueue_bf16_gated(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split);
-EPARA_HIDDEN hipError_t epara_enqueue_fp8_plain(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split);
-EPARA_HIDDEN hipError_t epara_enqueue_fp8_gated(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split);
+EPARA_HIDDEN hipError_t epara_enqueue_bf16_plain(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split);
+EPARA_HIDDEN hipError_t epara_enqueue_bf16_gated(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split);
+EPARA_HIDDEN hipError_t epara_enqueue_fp8_plain(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split);
+EPARA_HIDDEN hipError_t epara_enqueue_fp8_gated(int panel_only, unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split);
 EPARA_HIDDEN hipError_t epara_enqueue_f32(unsigned grid, hipStream_t, const epara_group_args*, const epara_tile*, const int32_t*, long n_slots);
 
 // Chain kernels.  resident != NULL: no launch, *resident = workgroups of that kernel the current device holds at once.

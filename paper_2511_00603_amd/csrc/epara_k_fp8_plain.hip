@@ -2,7 +2,7 @@
 #include "epara_grouped.h"
 
 hipError_t epara_enqueue_fp8_plain(int panel_only, unsigned grid, hipStream_t stream, const epara_group_args* args, const epara_tile* tiles,
-                            const int32_t* order, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split)
+                            const int32_t* order, long n_slots, int out_dtype, int narrow, uint32_t* split_ws, int n_split, int n_panel_split, int first_panel_split)
 {
-    return enqueue_grouped<EPARA_FP8_E4M3, false>(panel_only, grid, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split);
+    return enqueue_grouped<EPARA_FP8_E4M3, false>(panel_only, grid, stream, args, tiles, order, n_slots, out_dtype, narrow, split_ws, n_split, n_panel_split, first_panel_split);
 }

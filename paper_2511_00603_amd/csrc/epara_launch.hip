@@ -84,27 +84,28 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
     }
     if (last != EPARA_OK) return last;
     if (narrow_out) *narrow_out = narrow;
-    // split tiles: the groups' slots must be the layout's, and the workspace must hold them
-    if (L->n_split_tiles < 0) return EPARA_ERR_SHAPE;
-    if (L->n_split_tiles > 0) {
+    // split tiles: the groups' slots and the counts must be the layout's, and the workspace must hold them
+    if (L->n_split_tiles < 0 || L->n_panel_split_tiles < 0) return EPARA_ERR_SHAPE;
+    if (L->n_split_tiles > 0 || L->n_panel_split_tiles > 0) {
         if (f32) return EPARA_ERR_DTYPE;
         int gated = 0;
         for (int32_t g = 0; g < L->G; ++g)
             if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated = 1;
         epara_tile_class cls[4];
-        int32_t ncls = 0, nstream = 0, n_split = 0;
+        int32_t ncls = 0, nstream = 0, n_split = 0, n_panel = 0, parts = 1;
         int64_t bytes = 0;
         epara_kernel_classes(in_dtype, gated, narrow, cls, 4, &ncls, &nstream);
         std::vector<epara_group_desc> d(static_cast<size_t>(L->G));
         std::vector<int32_t> base(static_cast<size_t>(L->G));
         for (int32_t g = 0; g < L->G; ++g) d[g] = {L->h_args[g].M, L->h_args[g].K, L->h_args[g].N, L->h_args[g].act, 0, 0};
         if (int32_t st = epara_split_layout(d.data(), L->G, cls, ncls, nstream, base.data(), &n_split, &bytes)) return st;
-        if (n_split != L->n_split_tiles) return EPARA_ERR_SHAPE;
+        if (int32_t st = epara_panel_split(d.data(), L->G, cls, ncls, nstream, L->n_workgroups, &n_panel, &parts)) return st;
+        if (n_split != L->n_split_tiles || n_panel != L->n_panel_split_tiles) return EPARA_ERR_SHAPE;
         for (int32_t g = 0; g < L->G; ++g)
             if (base[g] >= 0 && L->h_args[g].reserved != base[g]) return EPARA_ERR_SHAPE;
         if (!L->d_workspace) return EPARA_ERR_NULL;
         if (reinterpret_cast<uintptr_t>(L->d_workspace) % 256 != 0) return EPARA_ERR_ALIGN;
-        if (L->workspace_bytes < bytes) return EPARA_ERR_CAPACITY;
+        if (L->workspace_bytes < epara_split_workspace_bytes(n_split, n_panel)) return EPARA_ERR_CAPACITY;
     }
     return EPARA_OK;
 }
@@ -123,8 +124,8 @@ int32_t enqueue(const epara_launch* L, int32_t in_dtype, int32_t out_dtype, int 
     (void)hipGetLastError();
     hipError_t e;
     if (in_dtype == EPARA_F32)       e = epara_enqueue_f32(grid, stream, L->d_args, L->d_tiles, L->d_order, n_slots);
-    else if (in_dtype == EPARA_BF16) e = (gated ? epara_enqueue_bf16_gated : epara_enqueue_bf16_plain)(panel_only, grid, stream, L->d_args, L->d_tiles, L->d_order, n_slots, out_dtype, narrow, static_cast<uint32_t*>(L->d_workspace), L->n_split_tiles);
-    else                             e = (gated ? epara_enqueue_fp8_gated : epara_enqueue_fp8_plain)(panel_only, grid, stream, L->d_args, L->d_tiles, L->d_order, n_slots, out_dtype, narrow, static_cast<uint32_t*>(L->d_workspace), L->n_split_tiles);
+    else if (in_dtype == EPARA_BF16) e = (gated ? epara_enqueue_bf16_gated : epara_enqueue_bf16_plain)(panel_only, grid, stream, L->d_args, L->d_tiles, L->d_order, n_slots, out_dtype, narrow, static_cast<uint32_t*>(L->d_workspace), L->n_split_tiles, L->n_panel_split_tiles, static_cast<int>(L->n_tiles - L->n_panel_split_tiles));
+    else                             e = (gated ? epara_enqueue_fp8_gated : epara_enqueue_fp8_plain)(panel_only, grid, stream, L->d_args, L->d_tiles, L->d_order, n_slots, out_dtype, narrow, static_cast<uint32_t*>(L->d_workspace), L->n_split_tiles, L->n_panel_split_tiles, static_cast<int>(L->n_tiles - L->n_panel_split_tiles));
     return e == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 
@@ -233,7 +234,7 @@ static int32_t chain_impl(const epara_chain_phase* phases, int32_t n_phases, int
         const epara_launch* L = ph.launch;
         int narrow = 0;
         if (int32_t st = validate_launch(L, in_dtype, ph.out_dtype, &narrow)) return st;
-        if (L->n_split_tiles != 0) return EPARA_ERR_SHAPE;        // the phases of a chain are scheduled without splitting K
+        if (L->n_split_tiles != 0 || L->n_panel_split_tiles != 0) return EPARA_ERR_SHAPE;   // the phases of a chain are scheduled without splitting K
         if (ph.counter_base < 0 || ph.counter_base > INT32_MAX - L->G) return EPARA_ERR_SHAPE;
         for (int32_t q = 0; q < p; ++q)       // counter ranges must not overlap
             if (ph.counter_base < phases[q].counter_base + phases[q].launch->G &&

@@ -48,13 +48,18 @@ static_assert(STASH_LDS_OFFSET + 4 * 8192 <= LDS_BYTES, "operand ring and stash 
 // pairs' worth (8 activation + 8 weight loads per pair).
 constexpr int PANEL_LOADS_PER_PAIR = 16;
 
-struct panel_walker { long slot; int t; epara_tile tl; };
+struct panel_walker { long slot; int t; epara_tile tl; int nsplit; };   // nsplit: visits to parts of tiles so far in the run
 
 template <int DT, bool GATED, bool WT, bool CHAIN>
 __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ args, const epara_tile* __restrict__ tiles,
                                           const int32_t* __restrict__ order, long slot0, long n_slots, long stride,
-                                          int out_dtype, char* lds, chain_ctx* chain)
+                                          int out_dtype, char* lds, chain_ctx* chain, const split_ctx* sp = nullptr,
+                                          split_pending* pend = nullptr)
 {
+    // Tiles of the launch's last round may be visited in parts of K (plain bf16 groups of a single launch only): an
+    // entry of the order then names the part, the three walkers cover that part's units of four stages only,
+    // and the visit leaves its raw sums in the workspace instead of running the epilogue.
+    constexpr bool CAN_SPLIT = !GATED && !CHAIN && !WT && DT == EPARA_BF16;
     constexpr int ESZ = DT == EPARA_BF16 ? 2 : 1;
     constexpr int EPC = 16 / ESZ;   // elements per 16-byte chunk
     constexpr int KF = 4 * EPC;     // K elements per stage
@@ -64,10 +69,23 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r32 = lane & 31, h = lane >> 5;
     ldsptr l3 = (ldsptr)lds;
+    // units (of two pairs = four stages) of K that the visit `entry` of a tile with KD pairs covers: [u0, u1)
+    auto unit_range = [&](int entry, int KD, int& u0, int& u1) {
+        u0 = 0; u1 = KD >> 1;
+        if constexpr (CAN_SPLIT) {
+            const int parts = order_parts(entry);
+            if (parts > 1) {
+                const uint32_t U = static_cast<uint32_t>(KD >> 1), part = static_cast<uint32_t>(order_part(entry));
+                u0 = static_cast<int>(U * part / static_cast<uint32_t>(parts));
+                u1 = static_cast<int>(U * (part + 1) / static_cast<uint32_t>(parts));
+            }
+        }
+    };
 
     // ---- walking the workgroup's list.  Three consumers (activation loader, weight loader, multiply +
     // epilogue) each hold their own position; w_next moves one to the following tile of the run or
     // marks it ended (t < 0; sticky).  In a chain a run ends before a group that waits for its input.
+    const int split_room = CAN_SPLIT ? 63 - pend->count : 0;     // the caller leaves room for at least one
     auto w_next = [&](panel_walker& w) {
         if (w.t < 0) return;
         const int group = w.tl.group;
@@ -82,11 +100,14 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
                     ok = !(cw.counter >= 0 && cw.need > 0);
                 }
             }
+            if constexpr (CAN_SPLIT) {                           // the run ends while the list of uncounted visits has room
+                if (ok && order_parts(t) > 1) ok = w.nsplit++ < split_room;
+            }
             if (ok) w.tl = tl; else t = -1;
         }
         w.t = t;
     };
-    const panel_walker first = {slot0, order[slot0], tiles[order_tile(order[slot0])]};
+    const panel_walker first = {slot0, order[slot0], tiles[order_tile(order[slot0])], (CAN_SPLIT && order_parts(order[slot0]) > 1) ? 1 : 0};
 
     // ---- activation loader: wave w fetches rows 64 w + 8 j + lane / 8 with instruction j = 0..7 of a pair;
     // lane l writes LDS slot l % 8 of its row and fetches the global chunk that belongs there.
@@ -104,8 +125,10 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
         for (int j = 0; j < 8; ++j)
             x_off[j] = static_cast<uint32_t>(min(64 * wave + 8 * j + (lane >> 3), xw.tl.rows - 1)) * static_cast<uint32_t>(K * ESZ) +
                        static_cast<uint32_t>(x_chunk[j & 1] * 16);
-        x_pair = 0;
-        x_KD = ((K + KF - 1) / KF + 3) >> 2 << 1;               // pairs, an even number
+        int u0, u1;
+        unit_range(xw.t, ((K + KF - 1) / KF + 3) >> 2 << 1, u0, u1);   // pairs: an even number
+        x_pair = 2 * u0;                                         // first pair of the visit
+        x_KD = 2 * u1;                                           // one past its last
         x_K = K;
     };
     auto x_issue = [&](int j) {
@@ -149,8 +172,10 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
             wrsrc[fn] = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(base)) +
                                                           static_cast<size_t>(nb0) * KSP * 1024, 0, -1, 0x00020000);
         }
-        w_stage = 0;
-        w_KSP = KSP;
+        int u0, u1;
+        unit_range(ww.t, KSP >> 1, u0, u1);
+        w_stage = 4 * u0;                                        // first stage of the visit
+        w_KSP = 4 * u1;                                          // one past its last
     };
     auto w_issue = [&](int fn, int s2) -> v4i {
         return __builtin_amdgcn_raw_buffer_load_b128(wrsrc[fn], w_off[fn] + s2 * 512, w_stage * 1024, 0);
@@ -296,7 +321,9 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
     for (;;) {
         const epara_group_args ga = args[cw.tl.group];
         const int m0 = cw.tl.m0, n0 = cw.tl.n0, rows = cw.tl.rows, cols = cw.tl.cols, N = ga.N;
-        const int KD = ((ga.K + KF - 1) / KF + 3) >> 2 << 1;    // pairs, an even number
+        int u0, u1;
+        unit_range(cw.t, ((ga.K + KF - 1) / KF + 3) >> 2 << 1, u0, u1);
+        const int KD = 2 * (u1 - u0);                            // pairs of this visit, an even number
         // epilogue layout: QPR lanes share a row of this wave's part of the tile (64 columns; gated: 32), 4 columns each
         constexpr int QPR = GATED ? 8 : 16, RPI = 64 / QPR, WCOLS = 4 * QPR;
         const int q = lane % QPR, rr = lane / QPR;
@@ -326,6 +353,41 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
         // One wave per SIMD cannot overlap this with anybody's MFMAs, so what counts is the number of
         // instructions: a whole tile (the common case) runs fully unrolled with constant LDS offsets, no
         // bounds checks and one uniform pointer; ragged tiles run a compact loop with the checks.
+        if constexpr (CAN_SPLIT) {
+            const int nparts = order_parts(cw.t);
+            if (nparts > 1) {
+                // this visit's raw sums, row-major 256 x 256 fp32, written through to memory; counted when the
+                // workgroup's list ends (an order that names parts the launch has no room for is dropped)
+                const int pslot = order_tile(cw.t) - sp->first_panel;
+                if (sp->ws != nullptr && nparts <= SPLIT_MAX_PARTS && pslot >= 0 && pslot < sp->n_panel) {
+                    char* mine = panel_partials(*sp) + (static_cast<size_t>(pslot) * SPLIT_MAX_PARTS + order_part(cw.t)) * PANEL_SPLIT_STRIDE +
+                                 static_cast<size_t>(wave * 64 + 4 * (lane & 15)) * 4;
+                    auto raw = [&](auto fm_tag) {
+                        constexpr int fm = decltype(fm_tag)::value;
+                        if (fm * 32 >= rows) return;
+                        // the park of the epilogue below (it is defined there): fragment row fm into the stash
+#pragma unroll
+                        for (int fn = 0; fn < 2; ++fn)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                stash[r32 * 16 + ((fn * 8 + 2 * g + h) ^ (r32 & 15))] =
+                                    v4f{acc[fn][fm][4 * g], acc[fn][fm][4 * g + 1], acc[fn][fm][4 * g + 2], acc[fn][fm][4 * g + 3]};
+#pragma unroll
+                        for (int it = 0; it < 8; ++it) {         // 16 lanes share a row: 4 rows per instruction
+                            const int row = it * 4 + (lane >> 4);
+                            split_put16(mine + static_cast<size_t>(fm * 32 + row) * 1024, stash[row * 16 + ((lane & 15) ^ (row & 15))]);
+                        }
+                    };
+                    raw(act_tag<0>{}); raw(act_tag<1>{}); raw(act_tag<2>{}); raw(act_tag<3>{});
+                    raw(act_tag<4>{}); raw(act_tag<5>{}); raw(act_tag<6>{}); raw(act_tag<7>{});
+                    if (lane == pend->count) { pend->slots = (sp->n_split + pslot) | ((nparts - 1) << 28); pend->entries = cw.t; }
+                    ++pend->count;
+                }
+                w_next(cw);
+                if (cw.t < 0) break;
+                continue;
+            }
+        }
         const float sg = ga.scale, s2g = ga.scale2 * ga.out_inv_scale, inv = ga.out_inv_scale;
         // Fragment row fm of this wave into its stash: 32 rows x 16 quads (fragment fn = 0 / 1: quads 0..7 / 8..15;
         // gated: gate / up), quad c of row r at position c ^ (r % 16): the writes (16 rows of one quad per
@@ -424,6 +486,68 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
     if (s < n_slots && order[s] < 0)
         for (s += stride; s < n_slots && order[s] < 0; s += stride) {}
     return s;
+}
+
+// The visit that counted last at a split panel tile: adds the parts (row-major 256 x 256 fp32 each) in index
+// order, whoever wrote them last, and runs the plain epilogue.  Lane l of wave w takes columns 4 l .. 4 l + 3 of the
+// rows w, w + 4, w + 8, ...; the parts come in batches of four rows per wave straight into the LDS (device-scope
+// direct loads, two buffers: the next batch is in flight while this one is added and stored; a wave reads only
+// what it fetched itself, so there is no barrier).
+template <int DT>
+__device__ __forceinline__ void panel_split_finish(const epara_group_args& ga, const epara_tile& tl, int out_dtype, int pslot, int nparts,
+                                                   int tid, const split_ctx* sp, char* lds)
+{
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c4 = 4 * lane;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        panel_partials(*sp) + static_cast<size_t>(pslot) * SPLIT_MAX_PARTS * PANEL_SPLIT_STRIDE, 0, -1, 0x00020000);
+    ldsptr mine = (ldsptr)lds + wave * 16384;                    // two buffers of 64 KiB, 16 KiB per wave in each
+    const bool vec_ok = (ga.N & 3) == 0;
+    float b4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (ga.bias) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if (c4 + i < tl.cols) b4[i] = as_global<float>(ga.bias)[tl.n0 + c4 + i];
+    }
+    const float sg = ga.scale, inv = ga.out_inv_scale;
+    const int n_batches = (tl.rows + 15) >> 4;
+    auto issue = [&](int b) {                                    // 4 rows x nparts loads of 1 KiB
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int row = min(16 * b + 4 * k + wave, tl.rows - 1);
+            for (int pt = 0; pt < nparts; ++pt)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(mine + (b & 1) * 65536 + ((k * SPLIT_MAX_PARTS + pt) << 10)),
+                                                         16, lane * 16, pt * PANEL_SPLIT_STRIDE + row * 1024, 0, 16);   // 16: device scope (sc1)
+        }
+    };
+    auto run = [&](auto act) {
+        constexpr int ACT = decltype(act)::value;
+        issue(0);
+        for (int b = 0; b < n_batches; ++b) {
+            if (b + 1 < n_batches) {
+                issue(b + 1);
+                // everything but the batch just asked for has landed (and the stores before it have left)
+                if (nparts == 2) wait_vmcnt<8>(); else if (nparts == 3) wait_vmcnt<12>(); else wait_vmcnt<16>();
+            } else {
+                wait_vmcnt<0>();
+            }
+            asm volatile("" ::: "memory");
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int row = 16 * b + 4 * k + wave;
+                v4f sum = {0.f, 0.f, 0.f, 0.f};
+                for (int pt = 0; pt < nparts; ++pt)
+                    sum += *reinterpret_cast<const __attribute__((address_space(3))) v4f*>(mine + (b & 1) * 65536 + ((k * SPLIT_MAX_PARTS + pt) << 10) + lane * 16);
+                if (row < tl.rows && c4 < tl.cols) {
+                    float v[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = act_fast<ACT>(sg * sum[i] + b4[i]) * inv;
+                    store4<false>(ga.Y, out_dtype, static_cast<size_t>(tl.m0 + row), tl.n0 + c4, ga.N, v, tl.cols - c4, vec_ok);
+                }
+            }
+            wait_lgkmcnt0();                                     // the sums are in registers before the buffer is filled again
+        }
+    };
+    with_act(ga.act, run);
 }
 
 }  // namespace

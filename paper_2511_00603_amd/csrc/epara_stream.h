@@ -199,16 +199,6 @@ __device__ __forceinline__ void skinny_finish_unit(const epara_group_args& ga, i
     }
 }
 
-// The visits a workgroup has made to tiles whose K is split, not yet counted at the tiles' counters: lane i
-// of `slots` / `entries` holds the i-th (the same in every wave).  Counting is put off to the end of the
-// workgroup's list, where one atomic instruction does it for all of them and nothing waits for it in the
-// middle of a weight stream.
-struct split_pending {
-    int count;
-    int slots;             // the tile's workspace slot | (parts - 1) << 28
-    int entries;           // the visit's entry of the order
-};
-
 // Reduces the four waves' partial sums of a tile in LDS (wave order) and finishes it.  When the tile's K is
 // split over several visits (nparts > 1), the sums of this visit go to the workspace instead and the visit
 // is noted in `pend`.  Returns whether the output tile was stored.

@@ -91,6 +91,7 @@ class LaunchPlan:
         info, self.row_off, self.x_off, self.y_off, self.tiles, self.order, split_base = B.epara_plan_launch(
             self.groups, in_dtype, n_workgroups, n_xcd, panel_m, panel_n)
         self.n_split_tiles, self.workspace_bytes = int(info.n_split_tiles), int(info.workspace_bytes)
+        self.n_panel_split_tiles = int(info.n_panel_split_tiles)
         if self.n_split_tiles:                               # where each group's split tiles meet in the workspace
             self.args["reserved"] = split_base
         self.makespan, self.narrow, self.classes, self.n_stream_classes = info.makespan, bool(info.narrow), info.class_table(), info.n_stream_classes
@@ -100,14 +101,15 @@ class LaunchPlan:
         self.d_tiles = _upload(self.tiles, device)
         self.d_order = _upload(self.order, device)
         self.d_workspace = None
-        if self.n_split_tiles:
+        if self.workspace_bytes:
             self.d_workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
             B.epara_workspace_init(self.d_workspace.data_ptr(), self.workspace_bytes, current_stream_handle())
         torch.cuda.synchronize(device)
         self.upload_seconds = time.perf_counter() - t0
         self.c = B.Launch(self.args.ctypes.data, self.d_args.data_ptr(), self.tiles.ctypes.data, self.d_tiles.data_ptr(),
                           self.d_order.data_ptr(), len(self.tiles), len(self.order), n_workgroups, G,
-                          None if self.d_workspace is None else self.d_workspace.data_ptr(), self.workspace_bytes, self.n_split_tiles, 0)
+                          None if self.d_workspace is None else self.d_workspace.data_ptr(), self.workspace_bytes, self.n_split_tiles,
+                          self.n_panel_split_tiles)
 
 
 class _Phase:

@@ -69,7 +69,8 @@ CLASS_TABLES = [([(64, 64, 32), (P.INT32_MAX, 256, 256)], 1), ([(64, 64, 32), (P
                 ([(P.INT32_MAX, 64, 64)], 0), ([(16, 16, 64), (64, 64, 64), (512, 128, 128), (P.INT32_MAX, 256, 256)], 2),
                 ([(16, 16, 32), (32, 32, 64), (64, 64, 128), (P.INT32_MAX, 256, 256)], 3),
                 ([(16, 16, 16), (32, 32, 32), (64, 64, 64), (P.INT32_MAX, 256, 128)], 4),
-                ([(16, 16, 32, 0), (32, 32, 64, 512), (64, 64, 128, 128), (P.INT32_MAX, 256, 256, 0)], 3)]
+                ([(16, 16, 32, 0), (32, 32, 64, 512), (64, 64, 128, 128), (P.INT32_MAX, 256, 256, 0)], 3),
+                ([(P.INT32_MAX, 64, 64, 8)], 0), ([(64, 64, 32, 0), (P.INT32_MAX, 256, 256, 1024)], 1)]
 
 
 @pytest.mark.parametrize("groups", mix_group_shapes() + ADVERSARIAL)
@@ -157,16 +158,18 @@ def test_batch_accounting_and_paper_numbers():
 
 def test_kernel_classes_and_packed_sizes():
     c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 128, 8192), (P.INT32_MAX, 256, 256, 0)] and ns == 3
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 128, 8192), (P.INT32_MAX, 256, 256, 1024)] and ns == 3
     c, ns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 1)
     assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 16, 0), (32, 32, 32, 0), (64, 64, 64, 0), (P.INT32_MAX, 256, 128, 0)] and ns == 3   # fp8 tiles are not split
     c, ns = B.epara_kernel_classes(B.EPARA_F32, 0)
     assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 64, 0), (P.INT32_MAX, 64, 64, 0)] and ns == 0
     c, ns = B.epara_kernel_classes(B.EPARA_BF16, 0, narrow=True)
-    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 64, 8192), (P.INT32_MAX, 256, 256, 0)] and ns == 3
+    assert [tuple(int(v) for v in x) for x in c] == [(16, 16, 32, 0), (32, 32, 64, 8192), (64, 64, 64, 8192), (P.INT32_MAX, 256, 256, 1024)] and ns == 3
     assert status_of(B.epara_kernel_classes, B.EPARA_F32, 1) == B.EPARA_ERR_DTYPE
     assert status_of(B.epara_kernel_classes, 7, 0) == B.EPARA_ERR_DTYPE
     assert B.epara_workspace_bytes(_desc([(5, 8, 8)]), B.EPARA_BF16) == 0 and B.epara_workspace_bytes(_desc([]), 9) == -1
+    assert B.epara_workspace_bytes(_desc([(5, 8, 8)]), B.EPARA_BF16, 0) == -1 and B.epara_split_workspace_bytes(-1, 0) == -1
+    assert B.epara_split_workspace_bytes(3, 2) == 256 + 3 * 4 * 32768 + 2 * 4 * 262144 and B.epara_split_workspace_bytes(0, 0) == 0
     assert B.epara_packed_weight_bytes(4096, 11008, B.EPARA_BF16) == 4096 * 11008 * 2
     assert B.epara_packed_weight_bytes(40, 10, B.EPARA_BF16) == 1 * 4 * 1024          # 2 stages of K, padded to 4
     assert B.epara_packed_weight_bytes(40, 10, B.EPARA_FP8_E4M3) == 4 * 1024
@@ -450,14 +453,15 @@ LAUNCHES = _launches_by_mix()
 
 def _ref_cost(group, tile, classes, n_stream, gated, parts=1):
     if tile[5] >= n_stream:
-        return 2040 * group[1]
+        return 2040 * group[1] if parts == 1 else 2040 * group[1] // parts + 1020000
     bm = classes[tile[5]][1]
     whole = group[1] * (6 * tile[4] * (2 if gated else 1) + (2 * bm if bm >= 32 else 0))
     return whole if parts == 1 else whole // parts + 24 * bm * tile[4] * (2 if gated else 1)
 
 
-def _visits(order, tiles, groups, classes, n_stream):
-    """Checks that a visit order holds every tile the right number of times, each part once, and returns the decoded entries."""
+def _visits(order, tiles, groups, classes, n_stream, W=256, gated=False):
+    """Checks that a visit order holds every tile the right number of times, each part once."""
+    n_panel, panel_parts = P.panel_split([g + (gated,) for g in groups], classes, n_stream, W)
     seen = {}
     for e in order:
         if e >= 0:
@@ -466,7 +470,7 @@ def _visits(order, tiles, groups, classes, n_stream):
     assert sorted(seen) == list(range(len(tiles)))
     for t, v in seen.items():
         tile = tiles[t]
-        want = P.split_parts(groups[tile[0]][1], classes[tile[5]]) if tile[5] < n_stream else 1
+        want = P.split_parts(groups[tile[0]][1], classes[tile[5]]) if tile[5] < n_stream else (panel_parts if t >= len(tiles) - n_panel else 1)
         assert sorted(v) == [(j, want) for j in range(want)]
 
 
@@ -486,8 +490,14 @@ def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(inde
             cover[int(t["group"])][t["m0"]: t["m0"] + t["rows"], t["n0"]: t["n0"] + t["cols"]] += 1
         assert all(np.all(c == 1) for c in cover.values())
         o = order.reshape(-1, W)
-        _visits(order.tolist(), [tuple(int(v) for v in t) for t in tiles], groups, classes, info.n_stream_classes)
-        assert (split_base.tolist(), info.n_split_tiles, info.workspace_bytes) == P.split_layout(groups, classes, info.n_stream_classes)
+        _visits(order.tolist(), [tuple(int(v) for v in t) for t in tiles], groups, classes, info.n_stream_classes, W, gated)
+        ref_base, ref_n, _ = P.split_layout(groups, classes, info.n_stream_classes)
+        ref_panel, ref_parts = P.panel_split([g + (gated,) for g in groups], classes, info.n_stream_classes, W)
+        assert (split_base.tolist(), info.n_split_tiles, info.n_panel_split_tiles) == (ref_base, ref_n, ref_panel)
+        assert info.workspace_bytes == P.split_workspace_bytes(ref_n, ref_panel) == B.epara_split_workspace_bytes(ref_n, ref_panel)
+        assert B.epara_panel_split(_desc(groups, 5 if gated else 0), _classes(classes), info.n_stream_classes, W) == (ref_panel, ref_parts)
+        if index == 5 and not gated and dtype == B.EPARA_BF16:
+            assert (ref_panel, ref_parts) == (148, 3)            # 660 tiles on 256 workgroups: the last 148 in three parts
         for b in range(W):
             col = o[:, b]
             assert np.all(col[: int((col >= 0).sum())] >= 0)

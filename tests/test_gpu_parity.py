@@ -124,6 +124,44 @@ def test_long_k_tiles_visited_in_parts(dtype_name="bf16"):
         assert_close(y, yref, TOL[dtype_name], "split K %s" % ((M, K, N),))
 
 
+def test_last_round_panel_tiles_visited_in_parts(dtype_name="bf16"):
+    """A bf16 launch of panel tiles alone, all of one K: the tiles of the last, partial round are visited in two to four
+    parts of K whose raw sums meet in the workspace.  Integer-valued operands make every order of addition exact, so
+    the result must be the oracle's bit for bit: ragged rows and columns, a K that is not a multiple of the parts'
+    unit, two grid sizes (two and four parts), three calls in a row on one plan (the counters return to zero), and
+    (bf16) new activations at the same addresses."""
+    rng = np.random.default_rng(19)
+    shapes = [(300, 2064, 500), (600, 2064, 300)]
+    specs = []
+    for (M, K, N), act in zip(shapes, ["relu", "none"]):
+        X = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        W = rng.integers(-3, 4, (K, N)).astype(np.float32)
+        b = rng.integers(-8, 9, N).astype(np.float32)
+        specs.append({"X": X, "W": W, "b": b, "act": act, "s_x": 0.125, "s_w": 0.25})
+    seen = set()
+    for W_ in (8, 24):
+        G = U.Groups(specs, dtype_name, n_workgroups=W_)
+        assert G.plan.n_panel_split_tiles == 10 % W_ and G.plan.n_split_tiles == 0
+        parts = {int(e >> 28) + 1 for e in G.plan.order if e >= 0}
+        seen |= parts
+        want = [ref.bf16_decode(ref.bf16_encode(y)) for y in G.expected()]
+        for rep in range(3):
+            for (M, K, N), y, yref in zip(shapes, G.run(), want):
+                assert np.array_equal(y, yref), (dtype_name, W_, rep, M, K, N, np.argwhere(y != yref)[:5])
+        if dtype_name == "bf16":
+            for i, sp in enumerate(specs):
+                G.keep[3 * i].mul_(-2.0)
+                G.bits[i]["X"] = casts.bf16_bits(-2.0 * sp["X"])
+            want = [ref.bf16_decode(ref.bf16_encode(y)) for y in G.expected()]
+            for (M, K, N), y, yref in zip(shapes, G.run(), want):
+                assert np.array_equal(y, yref), ("rescaled", W_, M, K, N, np.argwhere(y != yref)[:5])
+    assert seen == {1, 2, 4}
+    specs = [U.rand_spec(rng, M, K, N, act, bias=True) for (M, K, N), act in zip(shapes, ["gelu_erf", "silu"])]
+    G = U.Groups(specs, dtype_name, n_workgroups=8)
+    for (M, K, N), y, yref in zip(shapes, G.run(), G.expected()):
+        assert_close(y, yref, TOL[dtype_name], "panel split K %s" % ((M, K, N),))
+
+
 def test_identity_zero_and_ones_weights_bf16():
     rng = np.random.default_rng(12)
     X = rng.standard_normal((37, 64)).astype(np.float32)
