@@ -40,7 +40,10 @@ def launch_stats(staged, mix, dtype_name):
             flops += 2 * M * K * N * nw
             out_esz = 4 if dtype_name == "f32" else (1 if (gated and dtype_name == "fp8") else 2)
             nbytes += K * N * nw * esz + M * K * esz + M * N * out_esz + (N * 4 if int(a["bias"]) else 0)
-        stats.append({"flops": flops, "bytes": nbytes, "tiles": int(len(plan.tiles)), "groups": int(len(plan.args))})
+        stats.append({"flops": flops, "bytes": nbytes, "tiles": int(len(plan.tiles)), "groups": int(len(plan.args)),
+                      # tiles visited in parts of K (weight-streaming tiles / panel tiles of the last round) and their workspace
+                      "split_tiles": int(getattr(plan, "n_split_tiles", 0)), "panel_split_tiles": int(getattr(plan, "n_panel_split_tiles", 0)),
+                      "workspace_bytes": int(getattr(plan, "workspace_bytes", 0))})
     return stats
 
 
@@ -191,7 +194,8 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
         bound = "mfma" if t_mfma > t_hbm else "hbm"
         k = {"launch": l, "ms": per_launch_ms[l], "ms_median": samples[l][steps // 2], "ms_min": samples[l][0],
              "ms_repeated": repeated_ms[l],
-             "tiles": st["tiles"], "groups": st["groups"],
+             "tiles": st["tiles"], "groups": st["groups"], "split_tiles": st["split_tiles"], "panel_split_tiles": st["panel_split_tiles"],
+             "workspace_bytes": st["workspace_bytes"],
              "flops": st["flops"], "bytes": st["bytes"], "bound": bound}
         if bound == "mfma":
             k.update(achieved=tf, peak=peak_tf, unit="TFLOP/s", frac=tf / peak_tf)
