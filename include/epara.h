@@ -404,10 +404,11 @@ int64_t epara_split_workspace_bytes(int32_t n_split_tiles, int32_t n_panel_split
 
 /* Where the split tiles of a launch meet: split_base[g] (G entries) = index of the first split tile of
  * group g among all split tiles of the launch (its tiles follow in n0 order), or -1 if the tiles of g are
- * not split; *n_split_tiles = their number; *workspace_bytes = 256-aligned(4 * n_split_tiles) counters +
- * n_split_tiles * EPARA_SPLIT_MAX_PARTS * EPARA_SPLIT_STRIDE bytes of partial sums (0 if nothing is split).
- * The caller writes split_base[g] into epara_group_args.reserved, sets epara_launch.n_split_tiles and
- * provides the workspace, zeroed once with epara_workspace_init (a launch leaves its counters zero).
+ * not split; *n_split_tiles = their number; *workspace_bytes = epara_split_workspace_bytes(n_split_tiles, 0).
+ * The caller writes split_base[g] into epara_group_args.reserved, sets epara_launch.n_split_tiles (and
+ * n_panel_split_tiles from epara_panel_split) and provides a workspace of
+ * epara_split_workspace_bytes(n_split_tiles, n_panel_split_tiles) bytes, zeroed once with epara_workspace_init
+ * (a launch leaves its counters zero).  epara_plan_launch does all of this.
  * More than 2^24 tiles -> ERR_SHAPE. */
 int32_t epara_split_layout(const epara_group_desc* groups, int32_t G,
                            const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
@@ -480,6 +481,8 @@ typedef struct {
  * EPARA_ACT_SWIGLU or none (ERR_DTYPE).  *plan is always written (sizes included); tiles / order are
  * written when given and large enough, else ERR_CAPACITY (give NULL and 0 to ask for the sizes only;
  * that returns EPARA_OK).  row_off / x_off / y_off and split_base (G entries, epara_split_layout) may be NULL.
+ * plan->n_split_tiles, n_panel_split_tiles and workspace_bytes say what the launch needs for tiles visited in
+ * parts of K ("Splitting K").
  * Other errors as for the two calls. */
 int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_dtype,
                           int32_t n_workgroups, int32_t n_xcd, int32_t panel_m, int32_t panel_n,
