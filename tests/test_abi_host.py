@@ -615,3 +615,29 @@ def test_split_launch_validation_without_a_gpu():
     # the workspace's own entry point
     assert lib.epara_workspace_init(None, 256, None) == B.EPARA_ERR_NULL
     assert lib.epara_workspace_init(ctypes.c_void_p(0x7000004), 256, None) == B.EPARA_ERR_ALIGN
+
+
+def test_panel_split_decision_and_its_error_paths():
+    """epara_panel_split against the reference on the launches of the mixes and on shapes around the rule's edges
+    (a full last round, a K below the class's split_K, gated groups, two different K, a streaming group next to
+    the panel groups), for several grid sizes; then the argument checks."""
+    cls, ns = B.epara_kernel_classes(B.EPARA_BF16, 0)
+    table = [tuple(int(v) for v in c) for c in cls]
+    cases = [g for g, gated in sum(LAUNCHES.values(), []) if not gated] + [
+        [(256 * 16, 2048, 256 * 16)], [(256 * 16, 1023, 256 * 17)], [(256 * 16, 1024, 256 * 17)], [(300, 4096, 300), (300, 2048, 300)],
+        [(300, 4096, 300), (8, 4096, 300)], [(0, 4096, 300)], [], [(100000, 8192, 256)]]
+    for groups in cases:
+        for W in (256, 8, 24, 1):
+            assert B.epara_panel_split(_desc(groups), cls, ns, W) == P.panel_split(groups, table, ns, W), (groups, W)
+    gcls, gns = B.epara_kernel_classes(B.EPARA_BF16, 1)
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120)], 5), gcls, gns, 256) == (0, 1)          # gated groups are not split
+    fcls, fns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 0)
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), fcls, fns, 256) == (0, 1)   # nor fp8 ones
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), cls, ns, 256) == (148, 3)
+    g = _desc([(300, 4096, 300)])
+    assert status_of(B.epara_panel_split, g, cls, ns, 0) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_panel_split, g, cls, 9, 8) == B.EPARA_ERR_SHAPE
+    assert status_of(B.epara_panel_split, _desc([(300, 0, 300)]), cls, ns, 8) == B.EPARA_ERR_SHAPE
+    n, parts = ctypes.c_int32(0), ctypes.c_int32(0)
+    assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, None, ctypes.byref(parts)) == B.EPARA_ERR_NULL
+    assert B.lib().epara_panel_split(None, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts)) == B.EPARA_ERR_NULL
