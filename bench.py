@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}
 LLC_BYTES = 256 << 20
+PREWARM_S = 0.03        # untimed passes before the warm-up steps of a mix (seconds)
 
 
 def launch_stats(staged, mix, dtype_name):
@@ -64,7 +65,15 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     plan_us = sum(p.plan_seconds for p in staged.plans()) * 1e6
     upload_us = sum(p.upload_seconds for p in staged.plans()) * 1e6
 
-    # (a) whole passes, the library's own entry points, events at both ends only
+    # (a) whole passes, the library's own entry points, events at both ends only.  A pass of the small mixes takes a
+    # quarter of a millisecond: W of them do not bring the clocks up from idle, so every mix first runs, untimed, until
+    # PREWARM_S have passed; then the W warm-up passes, then the K timed ones.
+    t_pre, n_pre = time.perf_counter(), 0
+    while time.perf_counter() - t_pre < PREWARM_S:
+        for _ in range(4):
+            staged.run(copy=n_pre)
+            n_pre += 1
+        torch.cuda.synchronize()
     for i in range(warmup):
         staged.run(copy=i)
     torch.cuda.synchronize()
@@ -119,7 +128,7 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
     samples = [sorted(evs[i][l].elapsed_time(evs[i][l + 1]) for i in range(steps)) for l in range(n_l)]
     per_launch_ms = [sum(v) / steps for v in samples]
     # where these passes sit among the grouped_kernel dispatches of a kernel trace of this command
-    trace_first_pass = warmup + 2 * steps + (1 + steps + copies if copies > 1 else 0)
+    trace_first_pass = n_pre + warmup + 2 * steps + (1 + steps + copies if copies > 1 else 0)
     # each launch repeated back to back (on its rotating copies) with events at both ends only: without the
     # idle microseconds that an event pair around a single short kernel also spans
     repeated_ms = []
@@ -178,7 +187,7 @@ def time_mix(mix, dtype_name, steps, warmup, s_h=None):
            "ms_per_step_median": pass_ms[steps // 2], "ms_per_step_min": pass_ms[0],
            "tflops": flops / (ms_per_step * 1e-3) / 1e12, "requests_per_s": mix.requests / (ms_per_step * 1e-3),
            "requests": mix.requests, "rows": mix.rows, "flops": flops, "launches": n_l, "weight_copies": copies,
-           "plan_us": plan_us, "plan_upload_us": upload_us, "pack_weights_s": staged.pack_seconds / copies,
+           "prewarm_passes": n_pre, "plan_us": plan_us, "plan_upload_us": upload_us, "pack_weights_s": staged.pack_seconds / copies,
            "stage_s": stage_s, "warm_cache_ms_per_step": warm_ms, "graph_replay_ms_per_step": graph_ms,
            "two_streams": {"ms_per_step": two_stream_ms, "tflops": flops / (two_stream_ms * 1e-3) / 1e12,
                            "requests_per_s": mix.requests / (two_stream_ms * 1e-3), "steps": n2,
