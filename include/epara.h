@@ -379,20 +379,25 @@ int32_t epara_plan_groups(const epara_group_desc* groups, int32_t G,
  * ends with a round of m = n mod W tiles that leaves W - m workgroups idle for a whole tile.  When the launch
  * holds nothing but panel tiles of one class with split_K > 0 and one K >= split_K, of groups without
  * EPARA_ACT_SWIGLU (a down projection; epara_kernel_classes sets EPARA_PANEL_SPLIT_K for the plain bf16
- * panel class, 0 for the gated one, for fp8, whose visits are half as long, and for fp32),
- * those m tiles -- the last m of the canonical table -- are visited in P parts of K instead, P in 2 ..
- * EPARA_SPLIT_MAX_PARTS chosen to minimise  ceil(m P / W) * (cost / P + EPARA_COST_PANEL_PARTIAL)  and only if
- * that is below 0.9 * cost (the smallest such P on ties); part j of P covers the units floor(U j / P) ..
- * floor(U (j+1) / P) - 1 of the U = ceil(ceil(K / stage) / 4) units of four 64-byte stages.
+ * panel class, 0 for the gated one, for fp8, whose visits are half as long, and for fp32), those m tiles -- the
+ * last m of the canonical table -- are visited in parts of K instead: tile i of them in P_i parts, part j of P
+ * covering the units floor(U j / P) .. floor(U (j+1) / P) - 1 of the U = ceil(ceil(K / stage) / 4) units of four
+ * 64-byte stages.  The P_i are chosen among
+ *   (a) every tile in P parts, P = 2 .. EPARA_SPLIT_MAX_PARTS: time ceil(m P / W) * (cost / P + EPARA_COST_PANEL_PARTIAL);
+ *   (b) k = 1 .. EPARA_SPLIT_MAX_PARTS parts per workgroup, Q = k W parts in all with 2 m <= Q <= m EPARA_SPLIT_MAX_PARTS
+ *       and Q not a multiple of m: the first m - Q mod m tiles in P = floor(Q / m) parts, the others in P + 1; time =
+ *       the most loaded of W level workgroups when the Q parts, the larger ones first, each go to the least loaded;
+ * by the smallest time, in this order on ties, and only below 0.9 * cost (cost = EPARA_COST_PANEL * K).
  * A visit leaves its 256 x 256 fp32 sums (EPARA_PANEL_SPLIT_STRIDE bytes) in the workspace, behind the streaming
  * tiles' slots; counting and the addition in index order work as for streaming tiles.  epara_panel_split states
- * the decision; it depends on the grid size. */
+ * the decision (*parts = P of the first tiles, *n_more = how many of the last tiles get P + 1); it depends on the
+ * grid size. */
 #define EPARA_PANEL_SPLIT_STRIDE 262144   /* bytes of partial sums per (split panel tile, part) */
 #define EPARA_PANEL_SPLIT_K 1024          /* every part then holds whole units of four stages, bf16 or fp8 */
 #define EPARA_COST_PANEL_PARTIAL 1020000  /* a part's trip through memory, in cost units (about 500 elements of K) */
 int32_t epara_panel_split(const epara_group_desc* groups, int32_t G,
                           const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
-                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts);
+                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts, int32_t* n_more);
 
 /* Bytes of the workspace of a launch with n_split_tiles split streaming tiles and n_panel_split_tiles split
  * panel tiles: 4 bytes of counter per split tile, rounded up to 256, then EPARA_SPLIT_MAX_PARTS parts of

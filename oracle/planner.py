@@ -247,10 +247,16 @@ def split_workspace_bytes(n_split_tiles, n_panel_split_tiles):
 
 
 def panel_split(groups, classes, n_stream_classes, n_workgroups):
-    """-> (m, P): the last m tiles of the tile table are visited in P parts of K (m = 0: none).  Only for a launch
-    of panel tiles alone, all of one class that names a split_K and of one K >= split_K, no gated group: with n
-    tiles on W workgroups the last round holds m = n mod W of them; P in 2..4 minimises
-    ceil(m P / W) * (cost // P + 1020000), cost = 2040 K, and must bring it below 9 cost // 10 (smallest P on ties)."""
+    """-> (m, P, n_more): the last m tiles of the tile table are visited in parts of K, the first m - n_more of them in
+    P parts, the others in P + 1 (m = 0: none).  Only for a launch of panel tiles alone, all of one class that names
+    a split_K and of one K >= split_K, no gated group: with n tiles on W workgroups the last round holds m = n mod W
+    of them.  Candidates, cost = 2040 K, a part of a tile cut in P costs cost // P + 1020000:
+      (a) every tile in P = 2, 3, 4 parts: time -(-m P // W) parts one after the other;
+      (b) k = 1..4 parts per workgroup, Q = k W in all, 2 m <= Q <= 4 m, Q not a multiple of m: the first m - Q % m tiles
+          in P = Q // m parts, the others in P + 1; time = the most loaded of W level bins when the parts, the larger
+          ones first, each go to the least loaded bin.
+    The smallest time wins (in this order on ties) and must be below 9 cost // 10."""
+    import heapq
     W = n_workgroups
     cls = K = None
     n = 0
@@ -261,22 +267,37 @@ def panel_split(groups, classes, n_stream_classes, n_workgroups):
         c = pick_class(M, classes)
         cl = classes[c]
         if c < n_stream_classes or (len(g) > 3 and g[3]):
-            return 0, 1
+            return 0, 1, 0
         if cls is not None and (c != cls or Kg != K):
-            return 0, 1
+            return 0, 1, 0
         if len(cl) < 4 or cl[3] <= 0 or Kg < cl[3]:
-            return 0, 1
+            return 0, 1, 0
         cls, K = c, Kg
         n += -(-M // cl[1]) * -(-N // cl[2])
     if cls is None or n % W == 0:
-        return 0, 1
+        return 0, 1, 0
     m, cost = n % W, 2040 * K
-    best, parts = cost * 9 // 10, 1
+    best, parts, more = cost * 9 // 10, 1, 0
     for P in (2, 3, 4):
         t = -(-m * P // W) * (cost // P + 1020000)
         if t < best:
-            best, parts = t, P
-    return (m, parts) if parts > 1 else (0, 1)
+            best, parts, more = t, P, 0
+    for k in (1, 2, 3, 4):
+        Q = k * W
+        if Q < 2 * m or Q > 4 * m or Q % m == 0:
+            continue
+        base, extra = divmod(Q, m)
+        bins = [0] * W
+        heapq.heapify(bins)
+        t = 0
+        for i in range(Q):
+            item = cost // base + 1020000 if i < (m - extra) * base else cost // (base + 1) + 1020000
+            load = heapq.heappop(bins) + item
+            heapq.heappush(bins, load)
+            t = max(t, load)
+        if t < best:
+            best, parts, more = t, base, extra
+    return (m, parts, more) if parts > 1 else (0, 1, 0)
 
 
 def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd, panel_m, panel_n):
@@ -298,7 +319,8 @@ def schedule_tiles(groups, classes, n_stream_classes, tiles, n_workgroups, n_xcd
        together on one die are consecutive in the sequence; a workgroup that got a long-K tile gets fewer
        of the short ones.  In a single launch the last m tiles of the table may be left out of this sequence
        and visited in P parts of K instead (panel_split): their parts follow, tile by tile and part by part,
-       each an item of cost 2040 * K // P + 1020000 under the same rule, entry tile | part << 24 | (P - 1) << 28.
+       each an item of cost 2040 * K // P + 1020000 (P: that tile's number of parts) under the same rule, entry
+       tile | part << 24 | (P - 1) << 28.
     2. Streaming tiles, longest first.  cost = K * (6 * cols * (2 if gated) + (2 * BM if BM >= 32 else 0))
        for a streaming tile (weight columns streamed from HBM, plus the activation rows re-read from L2
        at a third of that price, free for the 16-row class), 2040 * K for a panel tile.  In a single launch a
@@ -327,7 +349,7 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
     load = [0] * W
     rank_heap = [(0, r) for r in range(W)]                   # (load, die-major rank); rank r = workgroup (r mod per) * X + r div per
     stream = []
-    n_panel_split, panel_parts = panel_split(*phases[0][:3], W) if len(phases) == 1 else (0, 1)
+    n_panel_split, panel_parts, panel_more = panel_split(*phases[0][:3], W) if len(phases) == 1 else (0, 1, 0)
     for p, (groups, classes, n_stream_classes, tiles) in enumerate(phases):
         if not 0 <= n_stream_classes <= len(classes):
             raise ValueError("bad number of streaming classes")
@@ -355,12 +377,13 @@ def schedule_chain(phases, n_workgroups, n_xcd, panel_m, panel_n):
                                 load[b] += 2040 * K
                                 heapq.heappush(rank_heap, (load[b], r))
         for t in range(len(tiles) - n_panel_split, len(tiles)):    # the parts: tile by tile, part by part, same rule
-            each = 2040 * groups[tiles[t][0]][1] // panel_parts + 1020000
-            for j in range(panel_parts):
+            parts_t = panel_parts + (1 if t >= len(tiles) - panel_more else 0)      # the last panel_more tiles: one part more
+            each = 2040 * groups[tiles[t][0]][1] // parts_t + 1020000
+            for j in range(parts_t):
                 _, r = heapq.heappop(rank_heap)
                 x, i = divmod(r, per)
                 b = i * X + x
-                lists[p][b].append(order_entry(t, j, panel_parts))
+                lists[p][b].append(order_entry(t, j, parts_t))
                 load[b] += each
                 heapq.heappush(rank_heap, (load[b], r))
         for t, tile in enumerate(tiles):

@@ -157,7 +157,7 @@ def lib():
         L.epara_workspace_bytes.restype = i64
         L.epara_split_workspace_bytes.argtypes = [i32, i32]
         L.epara_split_workspace_bytes.restype = i64
-        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp]
         L.epara_panel_split.restype = i32
         L.epara_simulate.argtypes = [vp, vp, i32, vp, i64, vp, vp]
         L.epara_simulate.restype = i32
@@ -181,7 +181,7 @@ def lib():
         L.epara_workspace_bytes.restype = i64
         L.epara_split_workspace_bytes.argtypes = [i32, i32]
         L.epara_split_workspace_bytes.restype = i64
-        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp]
+        L.epara_panel_split.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp]
         L.epara_panel_split.restype = i32
         L.epara_plan_launch.restype = i32
         L.epara_plan_chain.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp]
@@ -405,13 +405,14 @@ def epara_split_workspace_bytes(n_split_tiles, n_panel_split_tiles):
 
 
 def epara_panel_split(groups, classes, n_stream_classes, n_workgroups):
-    """-> (number of panel tiles, the last of the tile table, visited in parts of K; parts)."""
+    """-> (m, P, n_more): the last m panel tiles of the tile table are visited in parts of K, the first m - n_more of
+    them in P parts, the others in P + 1."""
     groups = np.ascontiguousarray(groups, dtype=GROUP_DESC)
     classes = np.ascontiguousarray(classes, dtype=TILE_CLASS)
-    n, parts = ctypes.c_int32(0), ctypes.c_int32(0)
+    n, parts, more = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
     _check(lib().epara_panel_split(_ptr(groups) if len(groups) else None, len(groups), _ptr(classes), len(classes), int(n_stream_classes),
-                                   int(n_workgroups), ctypes.byref(n), ctypes.byref(parts)), "epara_panel_split")
-    return int(n.value), int(parts.value)
+                                   int(n_workgroups), ctypes.byref(n), ctypes.byref(parts), ctypes.byref(more)), "epara_panel_split")
+    return int(n.value), int(parts.value), int(more.value)
 
 
 def epara_workspace_init(d_workspace, nbytes, stream=0):

@@ -29,18 +29,40 @@ inline int64_t tile_cost(const epara_group_desc& d, const epara_tile& tl, const 
     return units * d.K;
 }
 
-// Whether the last round of a launch of equal panel tiles is worth cutting along K, and into how many parts
-// (see "Splitting K" in the header).  n_panel: all tiles of the launch, every one a panel tile of cost `cost`
-// (the class's split_K keeps K long enough for every part to hold whole units of four K stages).  Returns the number of tiles to split (0: none) and the parts.
-inline int32_t panel_split_choice(int64_t n_panel, int64_t W, int64_t cost, int32_t* parts)
+// Whether the last round of a launch of equal panel tiles is worth cutting along K, and how (see "Splitting K" in
+// the header).  n_panel: all tiles of the launch, every one a panel tile of cost `cost` (the class's split_K keeps K
+// long enough for every part to hold whole units of four K stages).  Returns the number m of tiles to split (0: none);
+// the first m - *n_more of them get *parts parts, the last *n_more one part more.
+inline int32_t panel_split_choice(int64_t n_panel, int64_t W, int64_t cost, int32_t* parts, int32_t* n_more)
 {
     *parts = 1;
+    *n_more = 0;
     const int64_t m = n_panel % W;
     if (n_panel == 0 || m == 0) return 0;
     int64_t best = cost * 9 / 10;                                // must beat 0.9 of a whole tile
+    // every tile in P parts
     for (int32_t P = 2; P <= EPARA_SPLIT_MAX_PARTS; ++P) {
         const int64_t t = ((m * P + W - 1) / W) * (cost / P + EPARA_COST_PANEL_PARTIAL);
-        if (t < best) { best = t; *parts = P; }
+        if (t < best) { best = t; *parts = P; *n_more = 0; }
+    }
+    // k parts per workgroup on average: Q = k W parts dealt to the m tiles as evenly as whole numbers allow
+    for (int64_t k = 1; k <= EPARA_SPLIT_MAX_PARTS; ++k) {
+        const int64_t Q = k * W;
+        if (Q < 2 * m || Q > EPARA_SPLIT_MAX_PARTS * m) continue;
+        const int64_t base = Q / m, more = Q % m;
+        if (more == 0) continue;                                 // the same as every tile in `base` parts
+        // the larger parts first, each to the least loaded workgroup (all start level: the whole tiles fill whole rounds)
+        std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> bins;
+        for (int64_t b = 0; b < W; ++b) bins.push(0);
+        int64_t t = 0;
+        for (int64_t i = 0; i < Q; ++i) {
+            const int64_t item = i < (m - more) * base ? cost / base + EPARA_COST_PANEL_PARTIAL : cost / (base + 1) + EPARA_COST_PANEL_PARTIAL;
+            const int64_t load = bins.top() + item;
+            bins.pop();
+            bins.push(load);
+            t = std::max(t, load);
+        }
+        if (t < best) { best = t; *parts = static_cast<int32_t>(base); *n_more = static_cast<int32_t>(more); }
     }
     return *parts > 1 ? static_cast<int32_t>(m) : 0;
 }
@@ -65,9 +87,10 @@ int32_t class_of(int32_t M, const epara_tile_class* classes, int32_t n_classes)
 
 // The panel split of a launch (validated groups and classes): tiles to split, parts.
 int32_t panel_split_of(const epara_group_desc* groups, int32_t G, const epara_tile_class* classes, int32_t n_classes,
-                       int32_t n_stream_classes, int64_t W, int32_t* parts)
+                       int32_t n_stream_classes, int64_t W, int32_t* parts, int32_t* n_more)
 {
     *parts = 1;
+    *n_more = 0;
     int32_t cls = -1, K = 0;
     int64_t n = 0;
     for (int32_t g = 0; g < G; ++g) {
@@ -81,7 +104,7 @@ int32_t panel_split_of(const epara_group_desc* groups, int32_t G, const epara_ti
         n += ceil_div(d.M, classes[c].BM) * ceil_div(d.N, classes[c].BN);
     }
     if (cls < 0 || n > 0xFFFFFF) return 0;
-    return panel_split_choice(n, W, static_cast<int64_t>(EPARA_COST_PANEL) * K, parts);
+    return panel_split_choice(n, W, static_cast<int64_t>(EPARA_COST_PANEL) * K, parts, n_more);
 }
 
 int32_t gated_of(const epara_group_desc* groups, int32_t G, int32_t* gated)
@@ -547,9 +570,9 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
     for (int64_t r = 0; r < W; ++r) panel_heap.push({0, r});
     std::vector<int32_t> class_order, members;
     // a single launch of equal panel tiles may visit the tiles of its last round in parts of K
-    int32_t panel_parts = 1;
+    int32_t panel_parts = 1, panel_more = 0;
     const int64_t n_panel_split = n_phases == 1 ? panel_split_of(phases[0].groups, phases[0].G, phases[0].classes, phases[0].n_classes,
-                                                                 phases[0].n_stream_classes, W, &panel_parts) : 0;
+                                                                 phases[0].n_stream_classes, W, &panel_parts, &panel_more) : 0;
     for (int32_t p = 0; p < n_phases; ++p) {
         const epara_phase_schedule& ph = phases[p];
         class_order.clear();
@@ -586,12 +609,13 @@ int32_t epara_schedule_chain(epara_phase_schedule* phases, int32_t n_phases,
     if (n_panel_split > 0) {                                     // the parts: tile by tile, part by part, same rule
         const epara_phase_schedule& ph = phases[0];
         for (int64_t tile = ph.n_tiles - n_panel_split; tile < ph.n_tiles; ++tile) {
-            const int64_t each = static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[ph.tiles[tile].group].K / panel_parts + EPARA_COST_PANEL_PARTIAL;
-            for (int32_t j = 0; j < panel_parts; ++j) {
+            const int32_t P = panel_parts + (tile >= ph.n_tiles - panel_more ? 1 : 0);       // the last panel_more tiles: one part more
+            const int64_t each = static_cast<int64_t>(EPARA_COST_PANEL) * ph.groups[ph.tiles[tile].group].K / P + EPARA_COST_PANEL_PARTIAL;
+            for (int32_t j = 0; j < P; ++j) {
                 const ranked top = panel_heap.top();
                 panel_heap.pop();
                 const int64_t x = top.second / per_die, i = top.second % per_die, b = i * X + x;
-                lists[0][b].push_back(EPARA_ORDER_ENTRY(static_cast<int32_t>(tile), j, panel_parts));
+                lists[0][b].push_back(EPARA_ORDER_ENTRY(static_cast<int32_t>(tile), j, P));
                 load[b] += each;
                 panel_heap.push({load[b], top.second});
             }
@@ -821,8 +845,8 @@ int32_t epara_plan_launch(const epara_group_desc* groups, int32_t G, int32_t in_
     *plan = ph.plan;
     if (int32_t s3 = epara_split_layout(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, split_base,
                                         &plan->n_split_tiles, &plan->workspace_bytes)) return s3;
-    int32_t panel_parts = 1;
-    plan->n_panel_split_tiles = panel_split_of(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, n_workgroups, &panel_parts);
+    int32_t panel_parts = 1, panel_more = 0;
+    plan->n_panel_split_tiles = panel_split_of(groups, G, plan->classes, plan->n_classes, plan->n_stream_classes, n_workgroups, &panel_parts, &panel_more);
     plan->workspace_bytes = epara_split_workspace_bytes(plan->n_split_tiles, plan->n_panel_split_tiles);
     if (row_off || x_off || y_off) {
         int64_t n = 0;
@@ -893,17 +917,17 @@ int64_t epara_split_workspace_bytes(int32_t n_split_tiles, int32_t n_panel_split
 
 int32_t epara_panel_split(const epara_group_desc* groups, int32_t G,
                           const epara_tile_class* classes, int32_t n_classes, int32_t n_stream_classes,
-                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts)
+                          int32_t n_workgroups, int32_t* n_panel_split_tiles, int32_t* parts, int32_t* n_more)
 {
     if (G < 0 || n_workgroups <= 0) return EPARA_ERR_SHAPE;
-    if (!n_panel_split_tiles || !parts || (G > 0 && !groups)) return EPARA_ERR_NULL;
+    if (!n_panel_split_tiles || !parts || !n_more || (G > 0 && !groups)) return EPARA_ERR_NULL;
     if (int32_t st = check_classes(classes, n_classes)) return st;
     if (n_stream_classes < 0 || n_stream_classes > n_classes) return EPARA_ERR_SHAPE;
     for (int32_t g = 0; g < G; ++g) {
         if (groups[g].M < 0 || groups[g].K <= 0 || groups[g].N <= 0) return EPARA_ERR_SHAPE;
         if (groups[g].M > 0 && class_of(groups[g].M, classes, n_classes) < 0) return EPARA_ERR_SHAPE;
     }
-    *n_panel_split_tiles = panel_split_of(groups, G, classes, n_classes, n_stream_classes, n_workgroups, parts);
+    *n_panel_split_tiles = panel_split_of(groups, G, classes, n_classes, n_stream_classes, n_workgroups, parts, n_more);
     return EPARA_OK;
 }
 
@@ -921,8 +945,8 @@ int64_t epara_workspace_bytes(const epara_group_desc* groups, int32_t G, int32_t
         int64_t bytes = 0;
         if (epara_kernel_classes(in_dtype, gated, narrow, classes, 4, &nc, &ns) != EPARA_OK) return -1;
         if (epara_split_layout(groups, G, classes, nc, ns, nullptr, &n_split, &bytes) != EPARA_OK) return -1;
-        int32_t parts = 1;
-        const int32_t n_panel = panel_split_of(groups, G, classes, nc, ns, n_workgroups, &parts);
+        int32_t parts = 1, more = 0;
+        const int32_t n_panel = panel_split_of(groups, G, classes, nc, ns, n_workgroups, &parts, &more);
         worst = std::max(worst, epara_split_workspace_bytes(n_split, n_panel));
     }
     return worst;

@@ -92,14 +92,14 @@ int32_t validate_launch(const epara_launch* L, int32_t in_dtype, int32_t out_dty
         for (int32_t g = 0; g < L->G; ++g)
             if (L->h_args[g].M > 0 && L->h_args[g].act == EPARA_ACT_SWIGLU) gated = 1;
         epara_tile_class cls[4];
-        int32_t ncls = 0, nstream = 0, n_split = 0, n_panel = 0, parts = 1;
+        int32_t ncls = 0, nstream = 0, n_split = 0, n_panel = 0, parts = 1, more = 0;
         int64_t bytes = 0;
         epara_kernel_classes(in_dtype, gated, narrow, cls, 4, &ncls, &nstream);
         std::vector<epara_group_desc> d(static_cast<size_t>(L->G));
         std::vector<int32_t> base(static_cast<size_t>(L->G));
         for (int32_t g = 0; g < L->G; ++g) d[g] = {L->h_args[g].M, L->h_args[g].K, L->h_args[g].N, L->h_args[g].act, 0, 0};
         if (int32_t st = epara_split_layout(d.data(), L->G, cls, ncls, nstream, base.data(), &n_split, &bytes)) return st;
-        if (int32_t st = epara_panel_split(d.data(), L->G, cls, ncls, nstream, L->n_workgroups, &n_panel, &parts)) return st;
+        if (int32_t st = epara_panel_split(d.data(), L->G, cls, ncls, nstream, L->n_workgroups, &n_panel, &parts, &more)) return st;
         if (n_split != L->n_split_tiles || n_panel != L->n_panel_split_tiles) return EPARA_ERR_SHAPE;
         for (int32_t g = 0; g < L->G; ++g)
             if (base[g] >= 0 && L->h_args[g].reserved != base[g]) return EPARA_ERR_SHAPE;

@@ -109,19 +109,20 @@ int main()
                     CHECK(static_cast<size_t>(t) < tiles.size() && j < n && !(seen[t] >> j & 1) && (parts[t] == 0 || parts[t] == n));
                     seen[t] |= 1 << j; parts[t] = n;
                 }
-                int32_t n_split = 0, n_panel = 0, panel_parts = 1;
-                CHECK(epara_panel_split(groups.data(), G, plan.classes, plan.n_classes, plan.n_stream_classes, 256, &n_panel, &panel_parts) == EPARA_OK);
+                int32_t n_split = 0, n_panel = 0, panel_parts = 1, panel_more = 0;
+                CHECK(epara_panel_split(groups.data(), G, plan.classes, plan.n_classes, plan.n_stream_classes, 256, &n_panel, &panel_parts, &panel_more) == EPARA_OK);
                 for (size_t t = 0; t < tiles.size(); ++t) {
                     const epara_tile_class& c = plan.classes[tiles[t].cls];
                     int32_t want = tiles[t].cls < plan.n_stream_classes && c.split_K > 0 && groups[tiles[t].group].K >= c.split_K ? EPARA_SPLIT_PARTS : 1;
-                    if (tiles[t].cls >= plan.n_stream_classes && static_cast<int64_t>(t) >= plan.n_tiles - plan.n_panel_split_tiles) want = panel_parts;
+                    if (tiles[t].cls >= plan.n_stream_classes && static_cast<int64_t>(t) >= plan.n_tiles - plan.n_panel_split_tiles)
+                        want = panel_parts + (static_cast<int64_t>(t) >= plan.n_tiles - panel_more ? 1 : 0);
                     CHECK(parts[t] == want && seen[t] == (1 << want) - 1);
                     n_split += want > 1 && tiles[t].cls < plan.n_stream_classes;
                 }
                 CHECK(plan.n_split_tiles == n_split && plan.n_panel_split_tiles == n_panel);
                 CHECK(plan.workspace_bytes == epara_split_workspace_bytes(n_split, n_panel));
                 CHECK(epara_workspace_bytes(groups.data(), G, EPARA_BF16, 256) >= plan.workspace_bytes);
-                if (mix == 5 && which == 1) CHECK(n_panel == 148 && panel_parts == 3);
+                if (mix == 5 && which == 1) CHECK(n_panel == 148 && panel_parts == 3 && panel_more == 68);
             }
             const int32_t producer[4] = {0, 1, 2, 3};
             epara_chain_plan_phase ph[2];

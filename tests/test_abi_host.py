@@ -461,7 +461,7 @@ def _ref_cost(group, tile, classes, n_stream, gated, parts=1):
 
 def _visits(order, tiles, groups, classes, n_stream, W=256, gated=False):
     """Checks that a visit order holds every tile the right number of times, each part once."""
-    n_panel, panel_parts = P.panel_split([g + (gated,) for g in groups], classes, n_stream, W)
+    n_panel, panel_parts, panel_more = P.panel_split([g + (gated,) for g in groups], classes, n_stream, W)
     seen = {}
     for e in order:
         if e >= 0:
@@ -470,7 +470,8 @@ def _visits(order, tiles, groups, classes, n_stream, W=256, gated=False):
     assert sorted(seen) == list(range(len(tiles)))
     for t, v in seen.items():
         tile = tiles[t]
-        want = P.split_parts(groups[tile[0]][1], classes[tile[5]]) if tile[5] < n_stream else (panel_parts if t >= len(tiles) - n_panel else 1)
+        want = P.split_parts(groups[tile[0]][1], classes[tile[5]]) if tile[5] < n_stream else (
+            1 if t < len(tiles) - n_panel else panel_parts + (1 if t >= len(tiles) - panel_more else 0))
         assert sorted(v) == [(j, want) for j in range(want)]
 
 
@@ -492,12 +493,13 @@ def test_plan_launch_is_a_valid_plan_and_makes_the_choice_the_header_states(inde
         o = order.reshape(-1, W)
         _visits(order.tolist(), [tuple(int(v) for v in t) for t in tiles], groups, classes, info.n_stream_classes, W, gated)
         ref_base, ref_n, _ = P.split_layout(groups, classes, info.n_stream_classes)
-        ref_panel, ref_parts = P.panel_split([g + (gated,) for g in groups], classes, info.n_stream_classes, W)
+        ref_panel, ref_parts, ref_more = P.panel_split([g + (gated,) for g in groups], classes, info.n_stream_classes, W)
         assert (split_base.tolist(), info.n_split_tiles, info.n_panel_split_tiles) == (ref_base, ref_n, ref_panel)
         assert info.workspace_bytes == P.split_workspace_bytes(ref_n, ref_panel) == B.epara_split_workspace_bytes(ref_n, ref_panel)
-        assert B.epara_panel_split(_desc(groups, 5 if gated else 0), _classes(classes), info.n_stream_classes, W) == (ref_panel, ref_parts)
+        assert B.epara_panel_split(_desc(groups, 5 if gated else 0), _classes(classes), info.n_stream_classes, W) == (ref_panel, ref_parts, ref_more)
         if index == 5 and not gated and dtype == B.EPARA_BF16:
-            assert (ref_panel, ref_parts) == (148, 3)            # 660 tiles on 256 workgroups: the last 148 in three parts
+            # 660 tiles on 256 workgroups: the last 148 in 512 parts, two per workgroup: 80 tiles in three, 68 in four
+            assert (ref_panel, ref_parts, ref_more) == (148, 3, 68)
         for b in range(W):
             col = o[:, b]
             assert np.all(col[: int((col >= 0).sum())] >= 0)
@@ -630,14 +632,15 @@ def test_panel_split_decision_and_its_error_paths():
         for W in (256, 8, 24, 1):
             assert B.epara_panel_split(_desc(groups), cls, ns, W) == P.panel_split(groups, table, ns, W), (groups, W)
     gcls, gns = B.epara_kernel_classes(B.EPARA_BF16, 1)
-    assert B.epara_panel_split(_desc([(4692, 13824, 5120)], 5), gcls, gns, 256) == (0, 1)          # gated groups are not split
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120)], 5), gcls, gns, 256) == (0, 1, 0)       # gated groups are not split
     fcls, fns = B.epara_kernel_classes(B.EPARA_FP8_E4M3, 0)
-    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), fcls, fns, 256) == (0, 1)   # nor fp8 ones
-    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), cls, ns, 256) == (148, 3)
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), fcls, fns, 256) == (0, 1, 0)   # nor fp8 ones
+    assert B.epara_panel_split(_desc([(4692, 13824, 5120), (3500, 13824, 5120)]), cls, ns, 256) == (148, 3, 68)
     g = _desc([(300, 4096, 300)])
     assert status_of(B.epara_panel_split, g, cls, ns, 0) == B.EPARA_ERR_SHAPE
     assert status_of(B.epara_panel_split, g, cls, 9, 8) == B.EPARA_ERR_SHAPE
     assert status_of(B.epara_panel_split, _desc([(300, 0, 300)]), cls, ns, 8) == B.EPARA_ERR_SHAPE
-    n, parts = ctypes.c_int32(0), ctypes.c_int32(0)
-    assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, None, ctypes.byref(parts)) == B.EPARA_ERR_NULL
-    assert B.lib().epara_panel_split(None, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts)) == B.EPARA_ERR_NULL
+    n, parts, more = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, None, ctypes.byref(parts), ctypes.byref(more)) == B.EPARA_ERR_NULL
+    assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts), None) == B.EPARA_ERR_NULL
+    assert B.lib().epara_panel_split(None, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts), ctypes.byref(more)) == B.EPARA_ERR_NULL

@@ -156,6 +156,20 @@ def test_last_round_panel_tiles_visited_in_parts(dtype_name="bf16"):
             for (M, K, N), y, yref in zip(shapes, G.run(), want):
                 assert np.array_equal(y, yref), ("rescaled", W_, M, K, N, np.argwhere(y != yref)[:5])
     assert seen == {1, 2, 4}
+    # tiles of one launch in three and in four parts (two parts per workgroup on average)
+    shapes = [(900, 4112, 300), (600, 4112, 300)]
+    specs = []
+    for M, K, N in shapes:
+        X = rng.integers(-3, 4, (M, K)).astype(np.float32)
+        W = rng.integers(-3, 4, (K, N)).astype(np.float32)
+        specs.append({"X": X, "W": W, "b": rng.integers(-8, 9, N).astype(np.float32), "act": "none", "s_x": 0.125, "s_w": 0.25})
+    G = U.Groups(specs, dtype_name, n_workgroups=24)
+    assert G.plan.n_panel_split_tiles == 14 and {int(e >> 28) + 1 for e in G.plan.order if e >= 0} == {3, 4}
+    want = [ref.bf16_decode(ref.bf16_encode(y)) for y in G.expected()]
+    for rep in range(2):
+        for (M, K, N), y, yref in zip(shapes, G.run(), want):
+            assert np.array_equal(y, yref), ("mixed parts", rep, M, K, N, np.argwhere(y != yref)[:5])
+    shapes = [(300, 2064, 500), (600, 2064, 300)]
     specs = [U.rand_spec(rng, M, K, N, act, bias=True) for (M, K, N), act in zip(shapes, ["gelu_erf", "silu"])]
     G = U.Groups(specs, dtype_name, n_workgroups=8)
     for (M, K, N), y, yref in zip(shapes, G.run(), G.expected()):
