@@ -488,20 +488,19 @@ __device__ __forceinline__ long panel_run(const epara_group_args* __restrict__ a
     return s;
 }
 
-// The visit that counted last at a split panel tile: adds the parts (row-major 256 x 256 fp32 each) in index
+// The visit that counted last at a split panel tile: adds the NP parts (row-major 256 x 256 fp32 each) in index
 // order, whoever wrote them last, and runs the plain epilogue.  Lane l of wave w takes columns 4 l .. 4 l + 3 of the
-// rows w, w + 4, w + 8, ...; the parts come in batches of four rows per wave straight into the LDS (device-scope
-// direct loads, two buffers: the next batch is in flight while this one is added and stored; a wave reads only
-// what it fetched itself, so there is no barrier).
-template <int DT>
-__device__ __forceinline__ void panel_split_finish(const epara_group_args& ga, const epara_tile& tl, int out_dtype, int pslot, int nparts,
-                                                   int tid, const split_ctx* sp, char* lds)
+// rows w, w + 4, w + 8, ...; eight rows at a time: all their parts are asked for first (16-byte device-scope loads
+// into registers), then added and stored, so a batch costs one trip to memory.
+template <int DT, int NP>
+__device__ __forceinline__ void panel_split_finish_n(const epara_group_args& ga, const epara_tile& tl, int out_dtype, int pslot,
+                                                     int tid, const split_ctx* sp)
 {
+    constexpr int R = 8;                                         // rows per lane and batch
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c4 = 4 * lane;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         panel_partials(*sp) + static_cast<size_t>(pslot) * SPLIT_MAX_PARTS * PANEL_SPLIT_STRIDE, 0, -1, 0x00020000);
-    ldsptr mine = (ldsptr)lds + wave * 16384;                    // two buffers of 64 KiB, 16 KiB per wave in each
     const bool vec_ok = (ga.N & 3) == 0;
     float b4[4] = {0.f, 0.f, 0.f, 0.f};
     if (ga.bias) {
@@ -509,34 +508,23 @@ __device__ __forceinline__ void panel_split_finish(const epara_group_args& ga, c
         for (int i = 0; i < 4; ++i) if (c4 + i < tl.cols) b4[i] = as_global<float>(ga.bias)[tl.n0 + c4 + i];
     }
     const float sg = ga.scale, inv = ga.out_inv_scale;
-    const int n_batches = (tl.rows + 15) >> 4;
-    auto issue = [&](int b) {                                    // 4 rows x nparts loads of 1 KiB
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int row = min(16 * b + 4 * k + wave, tl.rows - 1);
-            for (int pt = 0; pt < nparts; ++pt)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(mine + (b & 1) * 65536 + ((k * SPLIT_MAX_PARTS + pt) << 10)),
-                                                         16, lane * 16, pt * PANEL_SPLIT_STRIDE + row * 1024, 0, 16);   // 16: device scope (sc1)
-        }
-    };
     auto run = [&](auto act) {
         constexpr int ACT = decltype(act)::value;
-        issue(0);
-        for (int b = 0; b < n_batches; ++b) {
-            if (b + 1 < n_batches) {
-                issue(b + 1);
-                // everything but the batch just asked for has landed (and the stores before it have left)
-                if (nparts == 2) wait_vmcnt<8>(); else if (nparts == 3) wait_vmcnt<12>(); else wait_vmcnt<16>();
-            } else {
-                wait_vmcnt<0>();
-            }
-            asm volatile("" ::: "memory");
+        for (int rb = wave; rb < tl.rows; rb += 4 * R) {
+            v4i in[R][NP];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int row = 16 * b + 4 * k + wave;
+            for (int k = 0; k < R; ++k) {
+                const int row = min(rb + 4 * k, tl.rows - 1);
+#pragma unroll
+                for (int pt = 0; pt < NP; ++pt)
+                    in[k][pt] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, pt * PANEL_SPLIT_STRIDE + row * 1024, 16);   // 16: device scope (sc1)
+            }
+#pragma unroll
+            for (int k = 0; k < R; ++k) {
+                const int row = rb + 4 * k;
                 v4f sum = {0.f, 0.f, 0.f, 0.f};
-                for (int pt = 0; pt < nparts; ++pt)
-                    sum += *reinterpret_cast<const __attribute__((address_space(3))) v4f*>(mine + (b & 1) * 65536 + ((k * SPLIT_MAX_PARTS + pt) << 10) + lane * 16);
+#pragma unroll
+                for (int pt = 0; pt < NP; ++pt) sum += __builtin_bit_cast(v4f, in[k][pt]);
                 if (row < tl.rows && c4 < tl.cols) {
                     float v[4];
 #pragma unroll
@@ -544,10 +532,18 @@ __device__ __forceinline__ void panel_split_finish(const epara_group_args& ga, c
                     store4<false>(ga.Y, out_dtype, static_cast<size_t>(tl.m0 + row), tl.n0 + c4, ga.N, v, tl.cols - c4, vec_ok);
                 }
             }
-            wait_lgkmcnt0();                                     // the sums are in registers before the buffer is filled again
         }
     };
     with_act(ga.act, run);
+}
+
+template <int DT>
+__device__ __forceinline__ void panel_split_finish(const epara_group_args& ga, const epara_tile& tl, int out_dtype, int pslot, int nparts,
+                                                   int tid, const split_ctx* sp, char*)
+{
+    if (nparts == 2)      panel_split_finish_n<DT, 2>(ga, tl, out_dtype, pslot, tid, sp);
+    else if (nparts == 3) panel_split_finish_n<DT, 3>(ga, tl, out_dtype, pslot, tid, sp);
+    else                  panel_split_finish_n<DT, 4>(ga, tl, out_dtype, pslot, tid, sp);
 }
 
 }  // namespace
