@@ -684,6 +684,62 @@ int32_t epara_quantize_segments_e4m3(const epara_segment* h_segments, const epar
 int32_t epara_patch_scales(epara_group_args* d_args, int32_t G, const float* d_sx, const float* d_sw,
                            const float* d_sw2, const float* d_sout, void* stream);
 
+/* ---- device side: between the dense layers of a vision-transformer block ------------------ */
+
+/* The co-located ViT services (Sec. 3.1 MT; the ViT-B/16 mix) run, per encoder block, QKV projection ->
+ * attention -> output projection -> FFN; the projections and the FFN are grouped dense forwards, and the two
+ * calls below are what lies between them, each for all services in one launch (bf16 in and out, fp32
+ * arithmetic).  Neither allocates nor synchronises. */
+
+/* Rows of one service through a residual connection and a layer normalisation (Ba et al. 2016; the pre-norm
+ * block of Dosovitskiy et al. 2021): s = x + r per element (r absent: s = x), then per row of d values
+ * mu = mean(s), var = mean((s - mu)^2), y = (s - mu) / sqrt(var + eps) * gamma + beta.  The statistics and y
+ * come from the unrounded fp32 sum; S receives the sum rounded to bf16.  64 bytes, the same on host and device. */
+typedef struct {
+    const void*  X;          /* device, bf16 [M, d] row-major, 16-byte aligned */
+    const void*  R;          /* device, bf16 [M, d], or NULL */
+    const float* gamma;      /* device, fp32 [d], 16-byte aligned */
+    const float* beta;       /* device, fp32 [d], 16-byte aligned */
+    void*        S;          /* device, bf16 [M, d], or NULL (the sum is not kept); may be the same buffer as X or R */
+    void*        Y;          /* device, bf16 [M, d]; may be the same buffer as X or R when S is not */
+    int32_t      M, d;       /* M >= 0; d a multiple of 8, 8 <= d <= EPARA_NORM_MAX_D */
+    float        eps;        /* >= 0 */
+    int32_t      first_row;  /* rows of all earlier groups: the running sum of M */
+} epara_norm_args;
+#define EPARA_NORM_MAX_D 8192
+
+/* One kernel on `stream`: a wave per row (the row stays in registers between the two passes over it), rows of all
+ * groups in one grid; a row finds its group by bisection over first_row.  G = 0 or no rows enqueues nothing.
+ * Errors (from h_args): ERR_NULL (an array missing; X, gamma, beta or Y NULL in a group with rows), ERR_SHAPE
+ * (M < 0, d out of range or not a multiple of 8, eps negative or not finite, first_row not the running sum, more
+ * than 2^31 - 1 rows in all), ERR_ALIGN (X, R, S, Y, gamma or beta not 16-byte aligned). */
+int32_t epara_add_layernorm(const epara_norm_args* h_args, const epara_norm_args* d_args, int32_t G, void* stream);
+
+/* Scaled dot-product attention (Vaswani et al. 2017) of one service: its M = images * tokens rows are the output
+ * of the QKV projection, a row = [Q | K | V] with each third d = heads * head_dim wide; per image and head,
+ * S = Q K^T / sqrt(head_dim), P = softmax over the keys of every query row, O = P V, heads side by side in O.
+ * The products run on the matrix cores (bf16 operands, fp32 sums); the softmax is fp32 with the row maximum
+ * taken out; P is rounded to bf16 for the second product and the row sums divide its result.
+ * 40 bytes, the same on host and device. */
+typedef struct {
+    const void* QKV;         /* device, bf16 [M, 3 * heads * head_dim] row-major, 16-byte aligned */
+    void*       O;           /* device, bf16 [M, heads * head_dim], 16-byte aligned; not QKV */
+    int32_t     M;           /* >= 0, a multiple of tokens */
+    int32_t     tokens;      /* 1 .. EPARA_ATTN_MAX_TOKENS */
+    int32_t     heads;       /* >= 1 */
+    int32_t     head_dim;    /* EPARA_ATTN_HEAD_DIM */
+    int32_t     first_item;  /* (image, head) pairs of all earlier groups: the running sum of (M / tokens) * heads */
+    int32_t     reserved;
+} epara_attn_args;
+#define EPARA_ATTN_MAX_TOKENS 224
+#define EPARA_ATTN_HEAD_DIM 64
+
+/* One kernel on `stream`: a workgroup per (image, head) keeps that head's keys and (transposed) values in the LDS;
+ * its four waves take the query rows in blocks of 16.  G = 0 or no rows enqueues nothing.
+ * Errors (from h_args): ERR_NULL; ERR_SHAPE (M < 0 or not a multiple of tokens, tokens or head_dim out of range,
+ * heads < 1, first_item not the running sum, more than 2^31 - 1 items); ERR_ALIGN (QKV or O not 16-byte aligned). */
+int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_args, int32_t G, void* stream);
+
 const char* epara_status_string(int32_t status);
 
 #ifdef __cplusplus

@@ -33,6 +33,12 @@ FFN_DESC = np.dtype([("X", "<u8"), ("Wgate", "<u8"), ("Wup", "<u8"), ("Wdown", "
                      ("s_x", "<f4"), ("s_wgate", "<f4"), ("s_wup", "<f4"), ("s_h", "<f4"), ("s_wdown", "<f4")])
 SEGMENT = np.dtype([("src", "<u8"), ("dst", "<u8"), ("bytes", "<i8"), ("first_chunk", "<i8"), ("group", "<i4"), ("reserved", "<i4")])
 CHAIN_WAIT = np.dtype([("counter", "<i4"), ("need", "<i4")])
+NORM_ARGS = np.dtype([("X", "<u8"), ("R", "<u8"), ("gamma", "<u8"), ("beta", "<u8"), ("S", "<u8"), ("Y", "<u8"),
+                      ("M", "<i4"), ("d", "<i4"), ("eps", "<f4"), ("first_row", "<i4")])
+ATTN_ARGS = np.dtype([("QKV", "<u8"), ("O", "<u8"), ("M", "<i4"), ("tokens", "<i4"), ("heads", "<i4"), ("head_dim", "<i4"),
+                      ("first_item", "<i4"), ("reserved", "<i4")])
+assert NORM_ARGS.itemsize == 64 and ATTN_ARGS.itemsize == 40
+EPARA_NORM_MAX_D, EPARA_ATTN_MAX_TOKENS, EPARA_ATTN_HEAD_DIM = 8192, 224, 64
 SIM_REQUEST = np.dtype([("arrival_us", "<i8"), ("slo_us", "<i8"), ("service", "<i4"), ("origin", "<i4"), ("frames", "<i4"), ("fps_milli", "<i4")])
 assert SIM_REQUEST.itemsize == 32
 EPARA_MAX_CHAIN_PHASES = 4
@@ -198,6 +204,10 @@ def lib():
         L.epara_copy_segments.argtypes = [vp, vp, i64, i64, vp]
         L.epara_quantize_segments_e4m3.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp]
         L.epara_patch_scales.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+        L.epara_add_layernorm.argtypes = [vp, vp, i32, vp]
+        L.epara_add_layernorm.restype = i32
+        L.epara_attention.argtypes = [vp, vp, i32, vp]
+        L.epara_attention.restype = i32
         for name in ("epara_batch_rows", "epara_plan_groups", "epara_schedule_tiles", "epara_kernel_classes",
                      "epara_ffn_swiglu_args", "epara_pack_weights", "epara_grouped_forward", "epara_grouped_ffn_swiglu",
                      "epara_request_segments", "epara_copy_segments", "epara_quantize_segments_e4m3", "epara_patch_scales"):
@@ -263,6 +273,20 @@ def epara_quantize_segments_e4m3(h_segments, d_segments, n_chunks, G, src_dtype,
 def epara_patch_scales(d_args, G, d_sx, d_sw, d_sw2=0, d_sout=0, stream=0):
     _check(lib().epara_patch_scales(int(d_args) or None, int(G), int(d_sx) or None, int(d_sw) or None, int(d_sw2) or None,
                                     int(d_sout) or None, int(stream) or None), "epara_patch_scales")
+
+
+def epara_add_layernorm(h_args, d_args, stream=0):
+    """h_args: NORM_ARGS[G] (host copy, validated); d_args: device address of the same bytes."""
+    h_args = np.ascontiguousarray(h_args, dtype=NORM_ARGS)
+    _check(lib().epara_add_layernorm(_ptr(h_args) if len(h_args) else None, int(d_args) or None, len(h_args), int(stream) or None),
+           "epara_add_layernorm")
+
+
+def epara_attention(h_args, d_args, stream=0):
+    """h_args: ATTN_ARGS[G] (host copy, validated); d_args: device address of the same bytes."""
+    h_args = np.ascontiguousarray(h_args, dtype=ATTN_ARGS)
+    _check(lib().epara_attention(_ptr(h_args) if len(h_args) else None, int(d_args) or None, len(h_args), int(stream) or None),
+           "epara_attention")
 
 
 def epara_dp_group_count(rate_required, rate_of_one_group):

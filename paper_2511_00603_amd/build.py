@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 UNITS = ["epara_k_bf16_plain.hip", "epara_k_bf16_gated.hip", "epara_k_fp8_plain.hip", "epara_k_fp8_gated.hip",
          "epara_c_bf16_plain.hip", "epara_c_bf16_ffn.hip", "epara_c_fp8_plain.hip", "epara_c_fp8_ffn.hip",
-         "epara_k_f32.hip", "epara_launch.hip", "epara_rows.hip", "epara_host.cpp"]
+         "epara_k_f32.hip", "epara_launch.hip", "epara_rows.hip", "epara_block.hip", "epara_host.cpp"]
 SOURCES = [os.path.join(CSRC, u) for u in UNITS]
 HEADERS = [os.path.join(ROOT, "include", "epara.h")] + [os.path.join(CSRC, h) for h in (
     "epara_cast.h", "epara_device.h", "epara_internal.h", "epara_panel.h", "epara_stream.h", "epara_f32.h", "epara_grouped.h")]

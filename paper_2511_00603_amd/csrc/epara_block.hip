@@ -1,0 +1,334 @@
+// libepara: what lies between the dense layers of a vision-transformer encoder block (the ViT services of
+// the paper's co-located setting, Sec. 3.1 MT): residual + layer normalisation, and attention.
+//
+//   epara_add_layernorm   s = x + r, y = LN(s) * gamma + beta, a wave per row        (bound by HBM traffic)
+//   epara_attention       softmax(Q K^T / sqrt(d_h)) V per image and head, MFMA 16x16x32 bf16
+//
+// Attention at ViT sizes (197 tokens, d_h = 64) is small: a head's keys and values are 25 KB each, so a
+// workgroup holds them in the LDS and forms every score of a block of 16 queries at once: no running maximum,
+// no rescaling.  Both matrix products are written "transposed" so that a lane's accumulator quad already is
+// the next operand:
+//   S^T = K Q^T   A = 16 keys x 32 dims (LDS), B = 32 dims x 16 queries (registers, from global memory);
+//                 lane (j = lane % 16, g = lane / 16) then holds the scores of query j against keys
+//                 4 g .. 4 g + 3 of every block of 16 keys: a row of S is spread over the four lanes
+//                 j, j + 16, j + 32, j + 48 and their registers (max and sum: registers, then two shuffles);
+//   O^T = V^T P^T A = 16 dims x 32 keys (LDS, values stored transposed), B = 32 keys x 16 queries = the
+//                 exponentials of two key blocks, packed to bf16 in place.  Only the pairing of A and B
+//                 along the contraction matters, so "key slot 8 g + e" means key 4 g + e of the first block
+//                 (e < 4) or key 4 g + e - 4 of the second in both operands.  A lane ends with four
+//                 consecutive output columns of its query: an 8-byte store.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "epara.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+#define EPARA_GLOBAL __attribute__((address_space(1)))
+
+constexpr int NT = 256;
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+// two fp32 -> two bf16 (round to nearest even, in hardware), low half first
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f{a, b}), v2bf));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+    return v;
+}
+
+// ---- residual + layer normalisation ---------------------------------------------------------------------
+
+// Group of row `row`: the last one whose first_row is <= row (groups without rows are skipped by the rule itself).
+__device__ __forceinline__ int find_norm_group(const epara_norm_args* __restrict__ args, int G, int row)
+{
+    int lo = 0, hi = G - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args[mid].first_row <= row) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// CH 16-byte chunks (8 values) per lane: lane l holds chunks l, l + 64, ... of its row.
+template <int CH>
+__device__ __forceinline__ void norm_row(const epara_norm_args& a, int row, int lane)
+{
+    const int d = a.d, n_chunks = d >> 3;
+    const size_t base = static_cast<size_t>(row) * d * 2;
+    const EPARA_GLOBAL char* x = (const EPARA_GLOBAL char*)a.X + base;
+    const EPARA_GLOBAL char* r = a.R ? (const EPARA_GLOBAL char*)a.R + base : nullptr;
+    float s[CH][8];
+    v4i xv[CH], rv[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int chunk = c * 64 + lane;
+        xv[c] = v4i{0, 0, 0, 0};
+        rv[c] = v4i{0, 0, 0, 0};
+        if (chunk < n_chunks) {
+            xv[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(x + chunk * 16);
+            if (r) rv[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(r + chunk * 16);
+        }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t xu = static_cast<uint32_t>(xv[c][j]), ru = static_cast<uint32_t>(rv[c][j]);
+            s[c][2 * j] = bf16_lo(xu) + bf16_lo(ru);          // chunks past the row hold zeros and add nothing
+            s[c][2 * j + 1] = bf16_hi(xu) + bf16_hi(ru);
+            sum += s[c][2 * j] + s[c][2 * j + 1];
+        }
+    const float fd = static_cast<float>(d);
+    const float mu = wave_sum(sum) / fd;                  // a division: a constant row gives exactly its value, and y = beta
+    float sq = 0.f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+        if (c * 64 + lane < n_chunks) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) { const float t = s[c][j] - mu; sq += t * t; }
+        }
+    const float var = wave_sum(sq) / fd;
+    const float rstd = 1.f / sqrtf(var + a.eps);
+    EPARA_GLOBAL char* so = a.S ? (EPARA_GLOBAL char*)a.S + base : nullptr;
+    EPARA_GLOBAL char* yo = (EPARA_GLOBAL char*)a.Y + base;
+    const EPARA_GLOBAL float* gamma = (const EPARA_GLOBAL float*)a.gamma;
+    const EPARA_GLOBAL float* beta = (const EPARA_GLOBAL float*)a.beta;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int chunk = c * 64 + lane;
+        if (chunk >= n_chunks) continue;
+        const v4f g0 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8), g1 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8 + 4);
+        const v4f b0 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8), b1 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8 + 4);
+        float y[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            y[j] = (s[c][j] - mu) * rstd * g0[j] + b0[j];
+            y[4 + j] = (s[c][4 + j] - mu) * rstd * g1[j] + b1[j];
+        }
+        v4i out;
+        if (so) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) out[j] = static_cast<int>(pack_bf16(s[c][2 * j], s[c][2 * j + 1]));
+            *reinterpret_cast<EPARA_GLOBAL v4i*>(so + chunk * 16) = out;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = static_cast<int>(pack_bf16(y[2 * j], y[2 * j + 1]));
+        *reinterpret_cast<EPARA_GLOBAL v4i*>(yo + chunk * 16) = out;
+    }
+}
+
+// CH = chunks per lane that the widest group of the launch needs (narrower rows leave chunks empty): one kernel per
+// CH, so that the common narrow rows do not pay for the registers of the widest case in waves per unit.
+template <int CH>
+__global__ __launch_bounds__(NT) void add_layernorm_kernel(const epara_norm_args* __restrict__ args, int G, int n_rows)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int row = blockIdx.x * (NT / 64) + wave; row < n_rows; row += gridDim.x * (NT / 64)) {
+        const epara_norm_args a = args[find_norm_group(args, G, row)];
+        norm_row<CH>(a, row - a.first_row, lane);
+    }
+}
+
+// ---- attention --------------------------------------------------------------------------------------------
+
+constexpr int DH = EPARA_ATTN_HEAD_DIM;                   // 64: two MFMA steps of 32 along the head dimension
+constexpr int MAX_KB = EPARA_ATTN_MAX_TOKENS / 16;        // key blocks of 16
+constexpr int K_ROW = DH * 2;                             // bytes of a key row in the LDS: 8 chunks of 16, chunk c at c ^ (key % 8)
+constexpr int VT_ROW = EPARA_ATTN_MAX_TOKENS * 2 + 8;     // bytes of a row of V^T (one head dimension, all keys) + 8: rows fall on different banks
+static_assert(MAX_KB % 2 == 0, "the second product takes key blocks in pairs");
+
+__device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict__ args, int G, int item)
+{
+    int lo = 0, hi = G - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args[mid].first_item <= item) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(NT) void attention_kernel(const epara_attn_args* __restrict__ args, int G)
+{
+    __shared__ __attribute__((aligned(16))) char k_lds[EPARA_ATTN_MAX_TOKENS * K_ROW];
+    __shared__ __attribute__((aligned(16))) char vt_lds[DH * VT_ROW];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int item = blockIdx.x;
+    const epara_attn_args a = args[find_attn_group(args, G, item)];
+    const int local = item - a.first_item, image = local / a.heads, head = local - image * a.heads;
+    const int T = a.tokens, d = a.heads * DH;
+    const int n_kb = (T + 15) >> 4, n_pairs = (n_kb + 1) >> 1;
+    const size_t row_bytes = static_cast<size_t>(3 * d) * 2;
+    const EPARA_GLOBAL char* qkv = (const EPARA_GLOBAL char*)a.QKV + static_cast<size_t>(image) * T * row_bytes + static_cast<size_t>(head) * DH * 2;
+
+    // ---- keys (row-major, swizzled) and values (transposed) of this head into the LDS; rows past the
+    // image are zeros: masked scores never see them, and 0 * 0 is what the second product needs there
+    for (int idx = tid; idx < 2 * n_pairs * 16 * 8; idx += NT) {
+        const int key = idx >> 3, chunk = idx & 7;
+        v4i kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+        if (key < T) {
+            const EPARA_GLOBAL char* src = qkv + key * row_bytes + chunk * 16;
+            kv = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 2);
+            vv = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 4);
+        }
+        *reinterpret_cast<v4i*>(k_lds + key * K_ROW + ((chunk ^ (key & 7)) << 4)) = kv;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t u = static_cast<uint32_t>(vv[e >> 1]);
+            *reinterpret_cast<uint16_t*>(vt_lds + (chunk * 8 + e) * VT_ROW + key * 2) = static_cast<uint16_t>(e & 1 ? u >> 16 : u & 0xffffu);
+        }
+    }
+    __syncthreads();
+
+    const int j = lane & 15, g = lane >> 4;
+    const float scale = 1.4426950408889634f * rsqrtf(static_cast<float>(DH));      // scores in units of log 2: exp2 below
+    EPARA_GLOBAL char* out = (EPARA_GLOBAL char*)a.O + static_cast<size_t>(image) * T * d * 2 + static_cast<size_t>(head) * DH * 2;
+    for (int qb = wave; qb < n_kb; qb += NT / 64) {
+        // ---- my query's two operand chunks: dims 8 g .. 8 g + 7 and 32 + 8 g .. (a row past the image repeats the last one)
+        const int q = min(qb * 16 + j, T - 1);
+        const v4i q0 = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + g * 16);
+        const v4i q1 = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + 64 + g * 16);
+        // ---- S^T, block by block of 16 keys
+        v4f s[MAX_KB];
+#pragma unroll
+        for (int b = 0; b < MAX_KB; ++b) {
+            s[b] = v4f{0.f, 0.f, 0.f, 0.f};
+            if (b < n_kb) {
+                const int key = b * 16 + j;
+                const v4i k0 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + ((g ^ (key & 7)) << 4));
+                const v4i k1 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + (((4 + g) ^ (key & 7)) << 4));
+                s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0), __builtin_bit_cast(bf16x8, q0), s[b], 0, 0, 0);
+                s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1), __builtin_bit_cast(bf16x8, q1), s[b], 0, 0, 0);
+            }
+        }
+        // ---- softmax over the keys of my query: my 4 keys per block, then the lanes j, j + 16, j + 32, j + 48
+        float m = -INFINITY;
+#pragma unroll
+        for (int b = 0; b < MAX_KB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool valid = b * 16 + g * 4 + r < T;
+                s[b][r] = valid ? s[b][r] * scale : -INFINITY;
+                m = fmaxf(m, s[b][r]);
+            }
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));                         // finite: key 0 exists
+        float l = 0.f;
+#pragma unroll
+        for (int b = 0; b < MAX_KB; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[b][r] = exp2f(s[b][r] - m);
+                l += s[b][r];
+            }
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        // ---- O^T = V^T P^T, two key blocks per step
+        v4f o[DH / 16];
+#pragma unroll
+        for (int db = 0; db < DH / 16; ++db) o[db] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int p = 0; p < MAX_KB / 2; ++p) {
+            if (p < n_pairs) {
+                v4i pb;
+                pb[0] = static_cast<int>(pack_bf16(s[2 * p][0], s[2 * p][1]));
+                pb[1] = static_cast<int>(pack_bf16(s[2 * p][2], s[2 * p][3]));
+                pb[2] = static_cast<int>(pack_bf16(s[2 * p + 1][0], s[2 * p + 1][1]));
+                pb[3] = static_cast<int>(pack_bf16(s[2 * p + 1][2], s[2 * p + 1][3]));
+#pragma unroll
+                for (int db = 0; db < DH / 16; ++db) {
+                    const char* vrow = vt_lds + (db * 16 + j) * VT_ROW + (p * 32 + g * 4) * 2;
+                    const v2u lo = *reinterpret_cast<const v2u*>(vrow), hi = *reinterpret_cast<const v2u*>(vrow + 32);
+                    const v4i va = {static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(hi[0]), static_cast<int>(hi[1])};
+                    o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pb), o[db], 0, 0, 0);
+                }
+            }
+        }
+        // ---- my query's columns 16 db + 4 g .. + 3 of this head
+        if (qb * 16 + j < T) {
+            const float inv = 1.f / l;
+            EPARA_GLOBAL char* dst = out + static_cast<size_t>(qb * 16 + j) * d * 2 + g * 8;
+#pragma unroll
+            for (int db = 0; db < DH / 16; ++db) {
+                v2u pk;
+                pk[0] = pack_bf16(o[db][0] * inv, o[db][1] * inv);
+                pk[1] = pack_bf16(o[db][2] * inv, o[db][3] * inv);
+                *reinterpret_cast<EPARA_GLOBAL v2u*>(dst + db * 32) = pk;
+            }
+        }
+    }
+}
+
+inline bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t epara_add_layernorm(const epara_norm_args* h_args, const epara_norm_args* d_args, int32_t G, void* stream)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (G == 0) return EPARA_OK;
+    if (!h_args || !d_args) return EPARA_ERR_NULL;
+    int64_t rows = 0;
+    int32_t widest = 8;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_norm_args& a = h_args[g];
+        if (a.M < 0 || a.d < 8 || a.d > EPARA_NORM_MAX_D || (a.d & 7) || !(a.eps >= 0.f) || !(a.eps < INFINITY)) return EPARA_ERR_SHAPE;
+        if (a.first_row != rows) return EPARA_ERR_SHAPE;
+        if (a.M > 0 && (!a.X || !a.gamma || !a.beta || !a.Y)) return EPARA_ERR_NULL;
+        if (misaligned(a.X, 16) || misaligned(a.R, 16) || misaligned(a.S, 16) || misaligned(a.Y, 16) ||
+            misaligned(a.gamma, 16) || misaligned(a.beta, 16)) return EPARA_ERR_ALIGN;
+        rows += a.M;
+        if (a.M > 0 && a.d > widest) widest = a.d;
+        if (rows > INT32_MAX) return EPARA_ERR_SHAPE;
+    }
+    if (rows == 0) return EPARA_OK;
+    const int64_t groups_of_rows = (rows + NT / 64 - 1) / (NT / 64);
+    const int grid = static_cast<int>(groups_of_rows < 65536 ? groups_of_rows : 65536);
+    const int per_lane = (widest + 511) >> 9;                    // 16-byte chunks per lane of the widest row
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (per_lane <= 2)      hipLaunchKernelGGL(add_layernorm_kernel<2>, dim3(grid), dim3(NT), 0, s, d_args, G, static_cast<int>(rows));
+    else if (per_lane <= 4) hipLaunchKernelGGL(add_layernorm_kernel<4>, dim3(grid), dim3(NT), 0, s, d_args, G, static_cast<int>(rows));
+    else if (per_lane <= 8) hipLaunchKernelGGL(add_layernorm_kernel<8>, dim3(grid), dim3(NT), 0, s, d_args, G, static_cast<int>(rows));
+    else                    hipLaunchKernelGGL(add_layernorm_kernel<16>, dim3(grid), dim3(NT), 0, s, d_args, G, static_cast<int>(rows));
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_args, int32_t G, void* stream)
+{
+    if (G < 0) return EPARA_ERR_SHAPE;
+    if (G == 0) return EPARA_OK;
+    if (!h_args || !d_args) return EPARA_ERR_NULL;
+    int64_t items = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        const epara_attn_args& a = h_args[g];
+        if (a.M < 0 || a.tokens < 1 || a.tokens > EPARA_ATTN_MAX_TOKENS || a.heads < 1 || a.head_dim != EPARA_ATTN_HEAD_DIM ||
+            a.M % a.tokens != 0 || a.heads > INT32_MAX / (3 * EPARA_ATTN_HEAD_DIM)) return EPARA_ERR_SHAPE;
+        if (a.first_item != items) return EPARA_ERR_SHAPE;
+        if (a.M > 0 && (!a.QKV || !a.O)) return EPARA_ERR_NULL;
+        if (a.M > 0 && a.QKV == a.O) return EPARA_ERR_SHAPE;
+        if (misaligned(a.QKV, 16) || misaligned(a.O, 16)) return EPARA_ERR_ALIGN;
+        items += static_cast<int64_t>(a.M / a.tokens) * a.heads;
+        if (items > INT32_MAX) return EPARA_ERR_SHAPE;
+    }
+    if (items == 0) return EPARA_OK;
+    hipLaunchKernelGGL(attention_kernel, dim3(static_cast<unsigned>(items)), dim3(NT), 0, static_cast<hipStream_t>(stream), d_args, G);
+    return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
+}
+
+}  // extern "C"

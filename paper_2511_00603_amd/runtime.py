@@ -230,3 +230,48 @@ def patch_scales(launch_plan, d_sx, d_sw, d_sw2=None, d_sout=None, stream=None):
     ptr = lambda t: 0 if t is None else t.data_ptr()
     B.epara_patch_scales(launch_plan.d_args.data_ptr(), len(launch_plan.args), ptr(d_sx), ptr(d_sw), ptr(d_sw2), ptr(d_sout),
                          current_stream_handle() if stream is None else stream)
+
+
+class NormPlan:
+    """Arguments of one epara_add_layernorm launch, host copy + device copy.  groups: per service a dict with the
+    device tensors X [M, d] (bf16), gamma, beta (float32 [d]), Y [M, d], optionally R and S [M, d], and eps."""
+
+    def __init__(self, groups, device):
+        _require_gpu()
+        ptr = lambda t: 0 if t is None else t.data_ptr()
+        self.args = np.zeros(len(groups), dtype=B.NORM_ARGS)
+        rows = 0
+        for i, g in enumerate(groups):
+            M, d = (int(v) for v in g["X"].shape)
+            live = M > 0
+            self.args[i] = (ptr(g["X"]) if live else 0, ptr(g.get("R")) if live else 0, ptr(g["gamma"]), ptr(g["beta"]),
+                            ptr(g.get("S")) if live else 0, ptr(g["Y"]) if live else 0, M, d, float(g.get("eps", 1e-6)), rows)
+            rows += M
+        self.rows = rows
+        self.d_args = _upload(self.args, device)
+
+
+def add_layernorm(plan, stream=None):
+    B.epara_add_layernorm(plan.args, plan.d_args.data_ptr(), current_stream_handle() if stream is None else stream)
+
+
+class AttnPlan:
+    """Arguments of one epara_attention launch.  groups: per service a dict with the device tensors QKV [M, 3 d] and
+    O [M, d] (bf16), tokens (rows per image) and heads (d = heads * 64)."""
+
+    def __init__(self, groups, device):
+        _require_gpu()
+        self.args = np.zeros(len(groups), dtype=B.ATTN_ARGS)
+        items = 0
+        for i, g in enumerate(groups):
+            M = int(g["QKV"].shape[0])
+            live = M > 0
+            self.args[i] = (g["QKV"].data_ptr() if live else 0, g["O"].data_ptr() if live else 0, M, int(g["tokens"]), int(g["heads"]),
+                            B.EPARA_ATTN_HEAD_DIM, items, 0)
+            items += (M // int(g["tokens"])) * int(g["heads"])
+        self.items = items
+        self.d_args = _upload(self.args, device)
+
+
+def attention(plan, stream=None):
+    B.epara_attention(plan.args, plan.d_args.data_ptr(), current_stream_handle() if stream is None else stream)

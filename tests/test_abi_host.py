@@ -644,3 +644,67 @@ def test_panel_split_decision_and_its_error_paths():
     assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, None, ctypes.byref(parts), ctypes.byref(more)) == B.EPARA_ERR_NULL
     assert B.lib().epara_panel_split(g.ctypes.data, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts), None) == B.EPARA_ERR_NULL
     assert B.lib().epara_panel_split(None, 1, cls.ctypes.data, len(cls), ns, 8, ctypes.byref(n), ctypes.byref(parts), ctypes.byref(more)) == B.EPARA_ERR_NULL
+
+
+def test_block_pieces_argument_checks():
+    """epara_add_layernorm and epara_attention validate the host copy of their arguments before anything is enqueued
+    (every case here returns before a launch: an error, or no rows at all)."""
+    L = B.lib()
+    D = 0x7000000                                    # a pretend device address: never dereferenced on these paths
+
+    def norm(**kw):
+        a = np.zeros(1, dtype=B.NORM_ARGS)
+        a[0] = (D, D + 0x10000, D + 0x20000, D + 0x30000, D + 0x40000, D + 0x50000, 4, 768, 1e-6, 0)
+        for k, v in kw.items():
+            a[0][k] = v
+        return L.epara_add_layernorm(a.ctypes.data, ctypes.c_void_p(D + 0x60000), 1, None)
+
+    assert struct_bytes(B.NORM_ARGS) == 64 and struct_bytes(B.ATTN_ARGS) == 40
+    assert L.epara_add_layernorm(None, None, 0, None) == B.EPARA_OK
+    assert L.epara_add_layernorm(None, None, -1, None) == B.EPARA_ERR_SHAPE
+    assert L.epara_add_layernorm(None, ctypes.c_void_p(D), 1, None) == B.EPARA_ERR_NULL
+    a = np.zeros(1, dtype=B.NORM_ARGS)
+    assert L.epara_add_layernorm(a.ctypes.data, None, 1, None) == B.EPARA_ERR_NULL
+    assert norm(M=0) == B.EPARA_OK                                      # no rows: nothing to enqueue
+    assert norm(M=0, X=0, Y=0, gamma=0, beta=0) == B.EPARA_OK           # and nothing to point to
+    for bad in (dict(M=-1), dict(d=0), dict(d=4), dict(d=12), dict(d=B.EPARA_NORM_MAX_D + 8), dict(eps=-1.0), dict(eps=np.inf),
+                dict(eps=np.nan), dict(first_row=1)):
+        assert norm(**bad) == B.EPARA_ERR_SHAPE, bad
+    for missing in ("X", "gamma", "beta", "Y"):
+        assert norm(**{missing: 0}) == B.EPARA_ERR_NULL, missing
+    for field in ("X", "R", "S", "Y", "gamma", "beta"):
+        assert norm(**{field: D + 8}) == B.EPARA_ERR_ALIGN, field
+    # first_row is the running sum over the groups
+    two = np.zeros(2, dtype=B.NORM_ARGS)
+    two[0] = (D, 0, D + 0x20000, D + 0x30000, 0, D + 0x50000, 0, 768, 1e-6, 0)
+    two[1] = (D, 0, D + 0x20000, D + 0x30000, 0, D + 0x50000, 0, 64, 0.0, 0)
+    assert L.epara_add_layernorm(two.ctypes.data, ctypes.c_void_p(D), 2, None) == B.EPARA_OK
+    two[1]["first_row"] = 5
+    assert L.epara_add_layernorm(two.ctypes.data, ctypes.c_void_p(D), 2, None) == B.EPARA_ERR_SHAPE
+
+    def attn(**kw):
+        a = np.zeros(1, dtype=B.ATTN_ARGS)
+        a[0] = (D, D + 0x100000, 2 * 197, 197, 12, 64, 0, 0)
+        for k, v in kw.items():
+            a[0][k] = v
+        return L.epara_attention(a.ctypes.data, ctypes.c_void_p(D + 0x200000), 1, None)
+
+    assert L.epara_attention(None, None, 0, None) == B.EPARA_OK
+    assert L.epara_attention(None, None, -1, None) == B.EPARA_ERR_SHAPE
+    assert L.epara_attention(None, ctypes.c_void_p(D), 1, None) == B.EPARA_ERR_NULL
+    assert attn(M=0) == B.EPARA_OK and attn(M=0, QKV=0, O=0) == B.EPARA_OK
+    for bad in (dict(M=-197), dict(M=198), dict(tokens=0), dict(tokens=B.EPARA_ATTN_MAX_TOKENS + 1, M=B.EPARA_ATTN_MAX_TOKENS + 1),
+                dict(heads=0), dict(head_dim=32), dict(head_dim=128), dict(first_item=1), dict(O=D)):
+        assert attn(**bad) == B.EPARA_ERR_SHAPE, bad
+    assert attn(QKV=0) == B.EPARA_ERR_NULL and attn(O=0) == B.EPARA_ERR_NULL
+    assert attn(QKV=D + 8) == B.EPARA_ERR_ALIGN and attn(O=D + 0x100008) == B.EPARA_ERR_ALIGN
+    two = np.zeros(2, dtype=B.ATTN_ARGS)
+    two[0] = (D, D + 0x100000, 0, 197, 12, 64, 0, 0)
+    two[1] = (D, D + 0x100000, 0, 50, 3, 64, 0, 0)
+    assert L.epara_attention(two.ctypes.data, ctypes.c_void_p(D), 2, None) == B.EPARA_OK
+    two[1]["first_item"] = 24
+    assert L.epara_attention(two.ctypes.data, ctypes.c_void_p(D), 2, None) == B.EPARA_ERR_SHAPE
+
+
+def struct_bytes(dtype):
+    return dtype.itemsize
