@@ -150,6 +150,9 @@ constexpr int MAX_KB = EPARA_ATTN_MAX_TOKENS / 16;        // key blocks of 16
 constexpr int K_ROW = DH * 2;                             // bytes of a key row in the LDS: 8 chunks of 16, chunk c at c ^ (key % 8)
 constexpr int VT_ROW = EPARA_ATTN_MAX_TOKENS * 2 + 8;     // bytes of a row of V^T (one head dimension, all keys) + 8: rows fall on different banks
 static_assert(MAX_KB % 2 == 0, "the second product takes key blocks in pairs");
+constexpr int NT_ATTN = 512, ATTN_WAVES = NT_ATTN / 64;  // eight waves share a head's keys and values: two or one query block each at ViT sizes
+constexpr int MAX_QB = (MAX_KB + ATTN_WAVES - 1) / ATTN_WAVES;   // query blocks of 16 per wave
+constexpr int STAGE_STEPS = (EPARA_ATTN_MAX_TOKENS / 2 * 8 + NT_ATTN - 1) / NT_ATTN;   // (pairs of keys) x (chunks of a row) over the threads
 
 __device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict__ args, int G, int item)
 {
@@ -161,7 +164,7 @@ __device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict
     return lo;
 }
 
-__global__ __launch_bounds__(NT) void attention_kernel(const epara_attn_args* __restrict__ args, int G)
+__global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_args* __restrict__ args, int G)
 {
     __shared__ __attribute__((aligned(16))) char k_lds[EPARA_ATTN_MAX_TOKENS * K_ROW];
     __shared__ __attribute__((aligned(16))) char vt_lds[DH * VT_ROW];
@@ -175,33 +178,64 @@ __global__ __launch_bounds__(NT) void attention_kernel(const epara_attn_args* __
     const size_t row_bytes = static_cast<size_t>(3 * d) * 2;
     const EPARA_GLOBAL char* qkv = (const EPARA_GLOBAL char*)a.QKV + static_cast<size_t>(image) * T * row_bytes + static_cast<size_t>(head) * DH * 2;
 
-    // ---- keys (row-major, swizzled) and values (transposed) of this head into the LDS; rows past the
-    // image are zeros: masked scores never see them, and 0 * 0 is what the second product needs there
-    for (int idx = tid; idx < 2 * n_pairs * 16 * 8; idx += NT) {
-        const int key = idx >> 3, chunk = idx & 7;
-        v4i kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-        if (key < T) {
-            const EPARA_GLOBAL char* src = qkv + key * row_bytes + chunk * 16;
-            kv = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 2);
-            vv = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 4);
-        }
-        *reinterpret_cast<v4i*>(k_lds + key * K_ROW + ((chunk ^ (key & 7)) << 4)) = kv;
+    const int j = lane & 15, g = lane >> 4;
+    // wave w takes the query blocks first_qb, first_qb + 8, ...; which waves get a block more rotates with the
+    // item, so that two workgroups sharing a compute unit do not put their longer waves on the same SIMDs
+    const int first_qb = (wave + item) & (ATTN_WAVES - 1);
+    // ---- every load of the workgroup first, so that their latencies overlap: the head's keys and values (a thread
+    // takes two neighbouring keys x one 16-byte chunk per step) and this wave's query operands (dims 8 g .. 8 g + 7
+    // and 32 + 8 g ..; a query row past the image repeats the last one)
+    v4i kv[STAGE_STEPS][2], vv[STAGE_STEPS][2];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t u = static_cast<uint32_t>(vv[e >> 1]);
-            *reinterpret_cast<uint16_t*>(vt_lds + (chunk * 8 + e) * VT_ROW + key * 2) = static_cast<uint16_t>(e & 1 ? u >> 16 : u & 0xffffu);
+    for (int it = 0; it < STAGE_STEPS; ++it) {
+        const int idx = it * NT_ATTN + tid, chunk = idx & 7;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int key = 2 * (idx >> 3) + e;
+            kv[it][e] = v4i{0, 0, 0, 0};
+            vv[it][e] = v4i{0, 0, 0, 0};
+            if (key < T) {
+                const EPARA_GLOBAL char* src = qkv + key * row_bytes + chunk * 16;
+                kv[it][e] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 2);
+                vv[it][e] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(src + static_cast<size_t>(d) * 4);
+            }
+        }
+    }
+    v4i qf[MAX_QB][2];
+#pragma unroll
+    for (int i = 0; i < MAX_QB; ++i) {
+        const int q = min((first_qb + ATTN_WAVES * i) * 16 + j, T - 1);
+        qf[i][0] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + g * 16);
+        qf[i][1] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + 64 + g * 16);
+    }
+    // ---- keys row-major (swizzled), values transposed (two keys = one 32-bit word per head dimension); rows past
+    // the image are zeros: masked scores never see them, and 0 * 0 is what the second product needs there
+#pragma unroll
+    for (int it = 0; it < STAGE_STEPS; ++it) {
+        const int idx = it * NT_ATTN + tid, pair = idx >> 3, chunk = idx & 7;
+        if (pair < n_pairs * 16) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int key = 2 * pair + e;
+                *reinterpret_cast<v4i*>(k_lds + key * K_ROW + ((chunk ^ (key & 7)) << 4)) = kv[it][e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t x0 = static_cast<uint32_t>(vv[it][0][e >> 1]), x1 = static_cast<uint32_t>(vv[it][1][e >> 1]);
+                const uint32_t w = e & 1 ? (x0 >> 16) | (x1 & 0xffff0000u) : (x0 & 0xffffu) | (x1 << 16);
+                *reinterpret_cast<uint32_t*>(vt_lds + (chunk * 8 + e) * VT_ROW + pair * 4) = w;
+            }
         }
     }
     __syncthreads();
 
-    const int j = lane & 15, g = lane >> 4;
     const float scale = 1.4426950408889634f * rsqrtf(static_cast<float>(DH));      // scores in units of log 2: exp2 below
     EPARA_GLOBAL char* out = (EPARA_GLOBAL char*)a.O + static_cast<size_t>(image) * T * d * 2 + static_cast<size_t>(head) * DH * 2;
-    for (int qb = wave; qb < n_kb; qb += NT / 64) {
-        // ---- my query's two operand chunks: dims 8 g .. 8 g + 7 and 32 + 8 g .. (a row past the image repeats the last one)
-        const int q = min(qb * 16 + j, T - 1);
-        const v4i q0 = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + g * 16);
-        const v4i q1 = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + 64 + g * 16);
+#pragma unroll
+    for (int i = 0; i < MAX_QB; ++i) {
+        const int qb = first_qb + ATTN_WAVES * i;
+        if (qb >= n_kb) break;
+        const v4i q0 = qf[i][0], q1 = qf[i][1];
         // ---- S^T, block by block of 16 keys
         v4f s[MAX_KB];
 #pragma unroll
@@ -215,26 +249,35 @@ __global__ __launch_bounds__(NT) void attention_kernel(const epara_attn_args* __
                 s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1), __builtin_bit_cast(bf16x8, q1), s[b], 0, 0, 0);
             }
         }
-        // ---- softmax over the keys of my query: my 4 keys per block, then the lanes j, j + 16, j + 32, j + 48
+        // ---- softmax over the keys of my query: my 4 keys per block, then the lanes j, j + 16, j + 32, j + 48.
+        // The maximum is taken over the raw scores (the scale is positive); only a block that reaches past the
+        // image has keys to mask; a block past the last one (the pad of an odd count) keeps its zeros as weights.
         float m = -INFINITY;
 #pragma unroll
-        for (int b = 0; b < MAX_KB; ++b)
+        for (int b = 0; b < MAX_KB; ++b) {
+            if (b < n_kb) {
+                if ((b + 1) * 16 > T) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const bool valid = b * 16 + g * 4 + r < T;
-                s[b][r] = valid ? s[b][r] * scale : -INFINITY;
-                m = fmaxf(m, s[b][r]);
+                    for (int r = 0; r < 4; ++r)
+                        if (b * 16 + g * 4 + r >= T) s[b][r] = -INFINITY;
+                }
+                m = fmaxf(fmaxf(m, fmaxf(s[b][0], s[b][1])), fmaxf(s[b][2], s[b][3]));
             }
+        }
         m = fmaxf(m, __shfl_xor(m, 16));
         m = fmaxf(m, __shfl_xor(m, 32));                         // finite: key 0 exists
+        const float ms = m * scale;
         float l = 0.f;
 #pragma unroll
-        for (int b = 0; b < MAX_KB; ++b)
+        for (int b = 0; b < MAX_KB; ++b) {
+            if (b < n_kb) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                s[b][r] = exp2f(s[b][r] - m);
-                l += s[b][r];
+                for (int r = 0; r < 4; ++r) {
+                    s[b][r] = __builtin_amdgcn_exp2f(fmaf(s[b][r], scale, -ms));      // 2^(scale (s - m)) in (0, 1]; 0 for masked keys
+                    l += s[b][r];
+                }
             }
+        }
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         // ---- O^T = V^T P^T, two key blocks per step
@@ -327,7 +370,7 @@ int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_
         if (items > INT32_MAX) return EPARA_ERR_SHAPE;
     }
     if (items == 0) return EPARA_OK;
-    hipLaunchKernelGGL(attention_kernel, dim3(static_cast<unsigned>(items)), dim3(NT), 0, static_cast<hipStream_t>(stream), d_args, G);
+    hipLaunchKernelGGL(attention_kernel, dim3(static_cast<unsigned>(items)), dim3(NT_ATTN), 0, static_cast<hipStream_t>(stream), d_args, G);
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 
