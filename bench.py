@@ -346,6 +346,61 @@ def time_batch_forming(mix, steps, warmup):
     return out
 
 
+def time_vit_block_pieces(mix, steps, warmup):
+    """What lies between the dense layers of a ViT encoder block, on the ViT mix's own tensors: attention over the QKV
+    projection's output of every service (one launch), and the residual + layer normalisation that follows a block
+    (FFN output + block input; one launch).  Both are bound by HBM traffic at these sizes: bytes = inputs once +
+    outputs once.  Six copies of the tensors are rotated so that no pass finds its data in the last-level cache."""
+    import torch
+    from paper_2511_00603_amd import runtime as R
+    from paper_2511_00603_amd.mixrun import StagedMix
+    dev = "cuda:0"
+    st = StagedMix(mix, "bf16", dev)
+    st.run()
+    torch.cuda.synchronize()
+    by_label = {}
+    for launch in st.outputs[0]:
+        for g, label, t in launch:
+            by_label[(g, label)] = t
+    tokens = mix.services[0].request_rows[0]
+    d = mix.services[0].X.shape[1]
+    heads = d // 64
+    copies = 6
+    attn, norm = [], []
+    for _ in range(copies):
+        ga, gn = [], []
+        for g, svc in enumerate(mix.services):
+            qkv = by_label[(g, "L0")].clone()
+            ga.append({"QKV": qkv, "O": torch.empty((svc.M, d), dtype=torch.bfloat16, device=dev), "tokens": tokens, "heads": heads})
+            gn.append({"X": by_label[(g, "L2")].clone(), "R": st.inputs[0][g].clone(),
+                       "gamma": torch.ones(d, dtype=torch.float32, device=dev), "beta": torch.zeros(d, dtype=torch.float32, device=dev),
+                       "S": torch.empty((svc.M, d), dtype=torch.bfloat16, device=dev),
+                       "Y": torch.empty((svc.M, d), dtype=torch.bfloat16, device=dev), "eps": 1e-6})
+        attn.append(R.AttnPlan(ga, dev))
+        norm.append(R.NormPlan(gn, dev))
+    M = int(mix.rows)
+    images = M // tokens
+    cases = {"attention": (attn, R.attention, M * 4 * d * 2, 4 * images * heads * tokens * tokens * 64),
+             "add_layernorm": (norm, R.add_layernorm, M * 4 * d * 2, 0)}
+    out = {"rows": M, "images": images, "tokens": tokens, "heads": heads, "d": d, "copies": copies}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for name, (plans, fn, nbytes, flops) in cases.items():
+        for i in range(max(warmup, copies)):
+            fn(plans[i % copies])
+        e0.record()
+        for i in range(steps):
+            fn(plans[i % copies])
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / steps * 1e3
+        out[name] = {"us": us, "bytes": int(nbytes), "GBs": nbytes / us / 1e3, "frac_hbm": nbytes / us / 1e3 / HBM_PEAK_GBS}
+        if flops:
+            out[name]["TFLOPs"] = flops / us / 1e6
+    del st
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(mix, budget_s=15.0):
     """The oracle as it stands on the host cores, on a few rows of service 0 of the prefill mix (fp64)."""
     from oracle import reference as ref
@@ -389,7 +444,7 @@ def main():
         sys.exit(2)
 
     peaks = None if a.no_peaks else measure_peaks()
-    results, cache, cpu, forming = [], {}, None, None
+    results, cache, cpu, forming, pieces = [], {}, None, None, None
     for tag in a.mixes.split(","):
         idx = int(tag[0])
         dtype_name = "fp8" if tag.endswith("fp8") else None
@@ -412,6 +467,11 @@ def main():
             cpu = cpu_baseline(mix)
         if idx == 5 and forming is None:
             forming = time_batch_forming(mix, a.steps, a.warmup)
+        if idx == 3 and dtype_name == "bf16" and pieces is None:
+            pieces = time_vit_block_pieces(mix, a.steps, a.warmup)
+            print("# between the dense layers of a ViT block: attention %.1f us (%.0f GB/s, %.1f TFLOP/s), residual + layer norm %.1f us (%.0f GB/s)" % (
+                pieces["attention"]["us"], pieces["attention"]["GBs"], pieces["attention"]["TFLOPs"], pieces["add_layernorm"]["us"],
+                pieces["add_layernorm"]["GBs"]), file=sys.stderr, flush=True)
         r = results[-1]
         print("# %s %s: %.3f ms/step (median %.3f, min %.3f), %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%% (whole pass %.1f%%); graph replay %.3f ms; passes on two streams %.3f ms%s" % (
             mix.name, dtype_name, r["ms_per_step"], r["ms_per_step_median"], r["ms_per_step_min"], r["tflops"], r["requests_per_s"],
@@ -428,7 +488,7 @@ def main():
             "config": {"workload": "%s (%s): %d rows, %d requests per pass, %d launches" % (
                 head["name"], head["dtype"], head["rows"], head["requests"], head["launches"])},
             "requests_per_s": head["requests_per_s"], "measured_peaks": peaks,
-            "roofline": head["roofline"], "cpu_baseline": cpu, "pass_roofline": head["pass_roofline"], "batch_forming": forming,
+            "roofline": head["roofline"], "cpu_baseline": cpu, "pass_roofline": head["pass_roofline"], "batch_forming": forming, "vit_block_pieces": pieces,
             "mixes": {("%s_%s" % (r["name"], r["dtype"])): r for r in results}}
     print(json.dumps(line))
 
