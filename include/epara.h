@@ -708,8 +708,8 @@ typedef struct {
 } epara_norm_args;
 #define EPARA_NORM_MAX_D 8192
 
-/* One kernel on `stream`: a wave per row (the row stays in registers between the two passes over it), rows of all
- * groups in one grid; a row finds its group by bisection over first_row.  G = 0 or no rows enqueues nothing.
+/* One kernel on `stream`: a wave per row (the row stays in registers between the two passes over it, the next row's
+ * loads are in flight meanwhile), rows of all groups in one grid; a row finds its group by bisection over first_row.  G = 0 or no rows enqueues nothing.
  * Errors (from h_args): ERR_NULL (an array missing; X, gamma, beta or Y NULL in a group with rows), ERR_SHAPE
  * (M < 0, d out of range or not a multiple of 8, eps negative or not finite, first_row not the running sum, more
  * than 2^31 - 1 rows in all), ERR_ALIGN (X, R, S, Y, gamma or beta not 16-byte aligned). */

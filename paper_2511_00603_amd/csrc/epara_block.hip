@@ -33,6 +33,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 #define EPARA_GLOBAL __attribute__((address_space(1)))
 
 constexpr int NT = 256;
+constexpr int NORM_GRID = 1024;          // workgroups of the normalisation kernel: four per compute unit, a few rows per wave
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
@@ -61,32 +62,64 @@ __device__ __forceinline__ int find_norm_group(const epara_norm_args* __restrict
     return lo;
 }
 
-// CH 16-byte chunks (8 values) per lane: lane l holds chunks l, l + 64, ... of its row.
+// A row on its way through a wave: CH 16-byte chunks (8 values) per lane, lane l holds chunks l, l + 64, ... of it.
 template <int CH>
-__device__ __forceinline__ void norm_row(const epara_norm_args& a, int row, int lane)
+struct norm_row_regs {
+    epara_norm_args a;     // the row's group (the same for all lanes)
+    int row;               // its index inside the group
+    v4i x[CH], r[CH];
+};
+
+template <int CH>
+__device__ __forceinline__ void norm_load(const epara_norm_args* __restrict__ args, int G, int global_row, int lane, norm_row_regs<CH>& q)
 {
-    const int d = a.d, n_chunks = d >> 3;
-    const size_t base = static_cast<size_t>(row) * d * 2;
-    const EPARA_GLOBAL char* x = (const EPARA_GLOBAL char*)a.X + base;
-    const EPARA_GLOBAL char* r = a.R ? (const EPARA_GLOBAL char*)a.R + base : nullptr;
-    float s[CH][8];
-    v4i xv[CH], rv[CH];
+    q.a = args[find_norm_group(args, G, global_row)];
+    q.row = global_row - q.a.first_row;
+    const int n_chunks = q.a.d >> 3;
+    const size_t base = static_cast<size_t>(q.row) * q.a.d * 2;
+    const EPARA_GLOBAL char* x = (const EPARA_GLOBAL char*)q.a.X + base;
+    const EPARA_GLOBAL char* r = q.a.R ? (const EPARA_GLOBAL char*)q.a.R + base : nullptr;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         const int chunk = c * 64 + lane;
-        xv[c] = v4i{0, 0, 0, 0};
-        rv[c] = v4i{0, 0, 0, 0};
+        q.x[c] = v4i{0, 0, 0, 0};
+        q.r[c] = v4i{0, 0, 0, 0};
         if (chunk < n_chunks) {
-            xv[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(x + chunk * 16);
-            if (r) rv[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(r + chunk * 16);
+            q.x[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(x + chunk * 16);
+            if (r) q.r[c] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(r + chunk * 16);
         }
     }
+}
+
+template <int CH>
+__device__ __forceinline__ void norm_finish(const norm_row_regs<CH>& q, int lane)
+{
+    const epara_norm_args& a = q.a;
+    const int d = a.d, n_chunks = d >> 3;
+    const size_t base = static_cast<size_t>(q.row) * d * 2;
+    // scale and shift of my columns: asked for before the reductions, so that they arrive under them
+    const EPARA_GLOBAL float* gamma = (const EPARA_GLOBAL float*)a.gamma;
+    const EPARA_GLOBAL float* beta = (const EPARA_GLOBAL float*)a.beta;
+    constexpr bool EARLY = CH <= 4;                       // wide rows have no registers to spare for it
+    v4f gm[EARLY ? CH : 1][2], bt[EARLY ? CH : 1][2];
+    auto scale_shift = [&](int c, int chunk) {
+        gm[c][0] = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8);
+        gm[c][1] = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8 + 4);
+        bt[c][0] = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8);
+        bt[c][1] = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8 + 4);
+    };
+    if constexpr (EARLY) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+            if (c * 64 + lane < n_chunks) scale_shift(c, c * 64 + lane);
+    }
+    float s[CH][8];
     float sum = 0.f;
 #pragma unroll
     for (int c = 0; c < CH; ++c)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t xu = static_cast<uint32_t>(xv[c][j]), ru = static_cast<uint32_t>(rv[c][j]);
+            const uint32_t xu = static_cast<uint32_t>(q.x[c][j]), ru = static_cast<uint32_t>(q.r[c][j]);
             s[c][2 * j] = bf16_lo(xu) + bf16_lo(ru);          // chunks past the row hold zeros and add nothing
             s[c][2 * j + 1] = bf16_hi(xu) + bf16_hi(ru);
             sum += s[c][2 * j] + s[c][2 * j + 1];
@@ -104,19 +137,17 @@ __device__ __forceinline__ void norm_row(const epara_norm_args& a, int row, int 
     const float rstd = 1.f / sqrtf(var + a.eps);
     EPARA_GLOBAL char* so = a.S ? (EPARA_GLOBAL char*)a.S + base : nullptr;
     EPARA_GLOBAL char* yo = (EPARA_GLOBAL char*)a.Y + base;
-    const EPARA_GLOBAL float* gamma = (const EPARA_GLOBAL float*)a.gamma;
-    const EPARA_GLOBAL float* beta = (const EPARA_GLOBAL float*)a.beta;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         const int chunk = c * 64 + lane;
         if (chunk >= n_chunks) continue;
-        const v4f g0 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8), g1 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(gamma + chunk * 8 + 4);
-        const v4f b0 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8), b1 = *reinterpret_cast<const EPARA_GLOBAL v4f*>(beta + chunk * 8 + 4);
+        const int gc = EARLY ? c : 0;
+        if constexpr (!EARLY) scale_shift(0, chunk);
         float y[8];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            y[j] = (s[c][j] - mu) * rstd * g0[j] + b0[j];
-            y[4 + j] = (s[c][4 + j] - mu) * rstd * g1[j] + b1[j];
+            y[j] = (s[c][j] - mu) * rstd * gm[gc][0][j] + bt[gc][0][j];
+            y[4 + j] = (s[c][4 + j] - mu) * rstd * gm[gc][1][j] + bt[gc][1][j];
         }
         v4i out;
         if (so) {
@@ -130,16 +161,35 @@ __device__ __forceinline__ void norm_row(const epara_norm_args& a, int row, int 
     }
 }
 
-// CH = chunks per lane that the widest group of the launch needs (narrower rows leave chunks empty): one kernel per
-// CH, so that the common narrow rows do not pay for the registers of the widest case in waves per unit.
+// A wave walks rows wave, wave + (waves of the grid), ... and (narrow rows) has the loads of its next row in flight
+// while it reduces and stores the current one.  CH = chunks per lane that the widest group of the launch needs (narrower rows
+// leave chunks empty): one kernel per CH, so that the common narrow rows do not pay for the registers of the widest.
 template <int CH>
 __global__ __launch_bounds__(NT) void add_layernorm_kernel(const epara_norm_args* __restrict__ args, int G, int n_rows)
 {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int row = blockIdx.x * (NT / 64) + wave; row < n_rows; row += gridDim.x * (NT / 64)) {
-        const epara_norm_args a = args[find_norm_group(args, G, row)];
-        norm_row<CH>(a, row - a.first_row, lane);
+    const int stride = gridDim.x * (NT / 64);
+    int row = blockIdx.x * (NT / 64) + wave;
+    if (row >= n_rows) return;
+    if constexpr (CH <= 4) {
+        norm_row_regs<CH> cur, nxt;
+        norm_load<CH>(args, G, row, lane, cur);
+        for (;;) {
+            const int next = row + stride;
+            const bool more = next < n_rows;
+            if (more) norm_load<CH>(args, G, next, lane, nxt);
+            norm_finish<CH>(cur, lane);
+            if (!more) break;
+            cur = nxt;
+            row = next;
+        }
+    } else {                                              // a wide row alone is 8 KiB or more of loads in flight
+        for (; row < n_rows; row += stride) {
+            norm_row_regs<CH> cur;
+            norm_load<CH>(args, G, row, lane, cur);
+            norm_finish<CH>(cur, lane);
+        }
     }
 }
 
@@ -342,7 +392,7 @@ int32_t epara_add_layernorm(const epara_norm_args* h_args, const epara_norm_args
     }
     if (rows == 0) return EPARA_OK;
     const int64_t groups_of_rows = (rows + NT / 64 - 1) / (NT / 64);
-    const int grid = static_cast<int>(groups_of_rows < 65536 ? groups_of_rows : 65536);
+    const int grid = static_cast<int>(groups_of_rows < NORM_GRID ? groups_of_rows : NORM_GRID);
     const int per_lane = (widest + 511) >> 9;                    // 16-byte chunks per lane of the widest row
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (per_lane <= 2)      hipLaunchKernelGGL(add_layernorm_kernel<2>, dim3(grid), dim3(NT), 0, s, d_args, G, static_cast<int>(rows));
