@@ -267,3 +267,49 @@ def test_vit_encoder_block_end_to_end(d, ffn, tokens, heads, images):
         _qkv, _a, _s2, want_out = _oracle_block(s["x"], p, tokens, heads, eps)
         worst = max(worst, assert_close(fetch(s3[i]), want_out, 2 * TOL["bf16"], "service %d whole block" % i))
     print("whole block, worst relative error over the services: %.2e" % worst)
+
+
+def test_block_pieces_in_a_hip_graph():
+    """Both calls only enqueue a kernel on the caller's stream, so they can be captured; every replay, with eager work
+    and synchronisations in between, must reproduce the eager result bit for bit and follow its inputs."""
+    rng = np.random.default_rng(61)
+    T, H = 197, 3
+    d = H * 64
+    _, X = dev_bf16(rng.standard_normal((2 * T, d)))
+    _, Rt = dev_bf16(rng.standard_normal((2 * T, d)))
+    _, Q = dev_bf16(rng.standard_normal((2 * T, 3 * d)))
+    norm = {"X": X, "R": Rt, "gamma": dev_f32(1.0 + 0.1 * rng.standard_normal(d)), "beta": dev_f32(0.1 * rng.standard_normal(d)),
+            "S": torch.zeros((2 * T, d), dtype=torch.bfloat16, device=DEV), "Y": torch.zeros((2 * T, d), dtype=torch.bfloat16, device=DEV), "eps": 1e-6}
+    attn = {"QKV": Q, "O": torch.zeros((2 * T, d), dtype=torch.bfloat16, device=DEV), "tokens": T, "heads": H}
+    np_, ap = R.NormPlan([norm], DEV), R.AttnPlan([attn], DEV)
+    outs = (norm["S"], norm["Y"], attn["O"])
+
+    def run():
+        R.add_layernorm(np_)
+        R.attention(ap)
+
+    def raw():
+        return [t.cpu().view(torch.uint8).numpy().copy() for t in outs]
+
+    run()
+    torch.cuda.synchronize()
+    want = raw()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.synchronize()
+    for factor in (2.0, 0.5, -1.0):
+        for t in outs:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, raw()):
+            assert np.array_equal(a, b)
+        X.mul_(factor)
+        Q.mul_(factor)
+        run()
+        torch.cuda.synchronize()
+        want = raw()
