@@ -204,8 +204,14 @@ constexpr int NT_ATTN = 512, ATTN_WAVES = NT_ATTN / 64;  // eight waves share a 
 constexpr int MAX_QB = (MAX_KB + ATTN_WAVES - 1) / ATTN_WAVES;   // query blocks of 16 per wave
 constexpr int STAGE_STEPS = (EPARA_ATTN_MAX_TOKENS / 2 * 8 + NT_ATTN - 1) / NT_ATTN;   // (pairs of keys) x (chunks of a row) over the threads
 
-__device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict__ args, int G, int item)
+// Group of item `item`: the last one whose first_item is <= item.  Up to 64 groups: every lane looks at one group
+// and the wave counts (one memory latency); more: bisection.
+__device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict__ args, int G, int item, int lane)
 {
+    if (G <= 64) {
+        const int first = lane < G ? args[lane].first_item : 0x7fffffff;
+        return __builtin_popcountll(__ballot(first <= item)) - 1;        // first_item never decreases, group 0 starts at 0
+    }
     int lo = 0, hi = G - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int item = blockIdx.x;
-    const epara_attn_args a = args[find_attn_group(args, G, item)];
+    const epara_attn_args a = args[__builtin_amdgcn_readfirstlane(find_attn_group(args, G, item, lane))];
     const int local = item - a.first_item, image = local / a.heads, head = local - image * a.heads;
     const int T = a.tokens, d = a.heads * DH;
     const int n_kb = (T + 15) >> 4, n_pairs = (n_kb + 1) >> 1;

@@ -139,6 +139,14 @@ def test_attention_token_counts_around_the_block_edges():
     check_attn(groups, want, "edges")
 
 
+def test_attention_many_services():
+    """More than 64 groups in a launch (the kernel then finds an item's group by bisection), some of them empty."""
+    rng = np.random.default_rng(44)
+    specs = [((i % 3), 3 + (i % 5), 1 + (i % 2)) for i in range(70)]
+    groups, want = attn_case(rng, specs)
+    check_attn(groups, want, "seventy services")
+
+
 def test_attention_vit_b16_service_and_peaked_scores():
     rng = np.random.default_rng(42)
     groups, want = attn_case(rng, [(4, 197, 12), (1, 197, 12)])
