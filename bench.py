@@ -396,7 +396,33 @@ def time_vit_block_pieces(mix, steps, warmup):
         out[name] = {"us": us, "bytes": int(nbytes), "GBs": nbytes / us / 1e3, "frac_hbm": nbytes / us / 1e3 / HBM_PEAK_GBS}
         if flops:
             out[name]["TFLOPs"] = flops / us / 1e6
-    del st
+    del st, attn, norm
+    torch.cuda.empty_cache()
+    # a whole encoder block of every service: the eight launches back to back, then each launch on its own
+    from paper_2511_00603_amd.vitblock import STEPS, VitBlock
+    from workloads import make_vit_block
+    blk = VitBlock(mix, make_vit_block(mix), dev, copies=2)
+    for i in range(warmup):
+        blk.run(i)
+    e0.record()
+    for i in range(steps):
+        blk.run(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    per = {}
+    for k, name in enumerate(STEPS):
+        blk.run_step(k, 0)
+        e0.record()
+        for i in range(steps):
+            blk.run_step(k, i)
+        e1.record()
+        torch.cuda.synchronize()
+        per[name] = e0.elapsed_time(e1) / steps * 1e3
+    out["block"] = {"what": "LN -> QKV -> attention -> projection -> add + LN -> FFN up (GELU) -> FFN down -> add + LN, all services per launch",
+                    "ms_per_step": ms, "launches": len(STEPS), "us_per_launch": per, "flops": blk.flops(),
+                    "tflops": blk.flops() / (ms * 1e-3) / 1e12, "requests_per_s": images / (ms * 1e-3)}
+    del blk
     torch.cuda.empty_cache()
     return out
 
@@ -469,9 +495,10 @@ def main():
             forming = time_batch_forming(mix, a.steps, a.warmup)
         if idx == 3 and dtype_name == "bf16" and pieces is None:
             pieces = time_vit_block_pieces(mix, a.steps, a.warmup)
-            print("# between the dense layers of a ViT block: attention %.1f us (%.0f GB/s, %.1f TFLOP/s), residual + layer norm %.1f us (%.0f GB/s)" % (
+            print("# between the dense layers of a ViT block: attention %.1f us (%.0f GB/s, %.1f TFLOP/s), residual + layer norm %.1f us (%.0f GB/s); a whole encoder block of all services: %.3f ms (%.1f TFLOP/s, %.0f images/s; %s)" % (
                 pieces["attention"]["us"], pieces["attention"]["GBs"], pieces["attention"]["TFLOPs"], pieces["add_layernorm"]["us"],
-                pieces["add_layernorm"]["GBs"]), file=sys.stderr, flush=True)
+                pieces["add_layernorm"]["GBs"], pieces["block"]["ms_per_step"], pieces["block"]["tflops"], pieces["block"]["requests_per_s"],
+                ", ".join("%s %.0f" % kv for kv in pieces["block"]["us_per_launch"].items())), file=sys.stderr, flush=True)
         r = results[-1]
         print("# %s %s: %.3f ms/step (median %.3f, min %.3f), %.1f TFLOP/s, %.0f req/s, roofline %s %.1f%% (whole pass %.1f%%); graph replay %.3f ms; passes on two streams %.3f ms%s" % (
             mix.name, dtype_name, r["ms_per_step"], r["ms_per_step_median"], r["ms_per_step_min"], r["tflops"], r["requests_per_s"],

@@ -181,99 +181,57 @@ def test_attention_closed_forms_on_the_gpu():
 
 # ---- a whole encoder block: the dense layers of the grouped forward with the pieces above between them ----
 
-def _block_params(rng, d, ffn):
-    dense = lambda K, N: ((rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32), (0.01 * rng.standard_normal(N)).astype(np.float32))
-    p = {"qkv": dense(d, 3 * d), "proj": dense(d, d), "up": dense(d, ffn), "down": dense(ffn, d)}
-    for n in ("1", "2"):
-        p["gamma" + n] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float32)
-        p["beta" + n] = (0.1 * rng.standard_normal(d)).astype(np.float32)
-    return p
+def _oracle_block(x, w, b, p):
+    """Pre-norm encoder block (Dosovitskiy et al. 2021) in fp64 on the bf16 values of inputs and weights, never rounding
+    in between."""
+    g = lambda a: a.astype(np.float64)
+    eps = float(np.float32(p.eps))
+    y1 = OB.layer_norm(x, g(p.gamma1), g(p.beta1), eps)
+    a = OB.attention(ref.dense_forward(y1, w["qkv"], b["qkv"], "none"), p.tokens, p.heads)
+    s2, y2 = OB.add_layer_norm(x, ref.dense_forward(a, w["proj"], b["proj"], "none"), g(p.gamma2), g(p.beta2), eps)
+    f = ref.dense_forward(ref.dense_forward(y2, w["up"], b["up"], "gelu_erf"), w["down"], b["down"], "none")
+    return s2 + f
 
 
-def _oracle_block(x, p, tokens, heads, eps):
-    """Pre-norm encoder block (Dosovitskiy et al. 2021) in fp64 on the bf16 values of inputs and weights."""
-    w = lambda name: ref.bf16_decode(casts.bf16_bits(p[name][0]))
-    b = lambda name: p[name][1].astype(np.float64)
-    y1 = OB.layer_norm(x, p["gamma1"].astype(np.float64), p["beta1"].astype(np.float64), eps)
-    qkv = ref.dense_forward(y1, w("qkv"), b("qkv"), "none")
-    a = OB.attention(qkv, tokens, heads)
-    s2, y2 = OB.add_layer_norm(x, ref.dense_forward(a, w("proj"), b("proj"), "none"), p["gamma2"].astype(np.float64), p["beta2"].astype(np.float64), eps)
-    f = ref.dense_forward(ref.dense_forward(y2, w("up"), b("up"), "gelu_erf"), w("down"), b("down"), "none")
-    return qkv, a, s2, s2 + f
-
-
-@pytest.mark.parametrize("d,ffn,tokens,heads,images", [(128, 512, 50, 2, [2, 1, 3]), (768, 3072, 197, 12, [2, 1])])
-def test_vit_encoder_block_end_to_end(d, ffn, tokens, heads, images):
-    """x -> LN -> QKV -> attention -> projection -> (+ x) -> LN -> FFN (GELU) -> (+): every service of the launch with
-    its own weights and image count; four grouped forwards, one attention and three normalisation launches."""
-    from paper_2511_00603_amd import binding as B
-    rng = np.random.default_rng([51, d])
-    eps = float(np.float32(1e-6))
-    svcs = []
-    for n in images:
-        x, X = dev_bf16(rng.standard_normal((n * tokens, d)))
-        svcs.append({"x": x, "X": X, "p": _block_params(rng, d, ffn), "M": n * tokens})
-    empty = lambda M, N: torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
-    keep = []
-
-    def forward(layer, inputs, N, act):
-        args, outs = [], []
-        for s, Xin in zip(svcs, inputs):
-            W, b = s["p"][layer]
-            K = W.shape[0]
-            Wd = R.pack_weights(R.device_tensor_from_bits(casts.bf16_bits(W), B.EPARA_BF16, DEV), B.EPARA_BF16)
-            bd = dev_f32(b)
-            Y = empty(s["M"], N)
-            keep.extend([Wd, bd])
-            args.append(R.group_args(Xin, Wd, Y, s["M"], K, N, act, bias=bd))
-            outs.append(Y)
-        plan = R.LaunchPlan(np.array(args, dtype=B.GROUP_ARGS), B.EPARA_BF16, DEV)
-        keep.append(plan)
-        R.grouped_forward(plan, B.EPARA_BF16)
-        return outs
-
-    def norm(xs, rs, which, keep_sum):
-        groups = []
-        for i, s in enumerate(svcs):
-            groups.append({"X": xs[i], "R": None if rs is None else rs[i], "gamma": dev_f32(s["p"]["gamma" + which]), "beta": dev_f32(s["p"]["beta" + which]),
-                           "S": empty(s["M"], d) if keep_sum else None, "Y": empty(s["M"], d), "eps": eps})
-        plan = R.NormPlan(groups, DEV)
-        keep.extend([plan, groups])
-        R.add_layernorm(plan)
-        return [g["S"] for g in groups], [g["Y"] for g in groups]
-
-    X = [s["X"] for s in svcs]
-    _, y1 = norm(X, None, "1", False)
-    qkv = forward("qkv", y1, 3 * d, "none")
-    attn = [{"QKV": q, "O": empty(s["M"], d), "tokens": tokens, "heads": heads} for q, s in zip(qkv, svcs)]
-    R.attention(R.AttnPlan(attn, DEV))
-    proj = forward("proj", [g["O"] for g in attn], d, "none")
-    s2, y2 = norm(X, proj, "2", True)
-    f = forward("down", forward("up", y2, ffn, "gelu_erf"), d, "none")
-    s3, _ = norm(s2, f, "1", True)                   # the sum that enters the next block (its first normalisation comes with it)
+@pytest.mark.parametrize("shrink", [dict(d=128, ffn=512, tokens=50, images=[2, 1, 3], n_services=3),
+                                    dict(images=[2, 1], n_services=2)])
+def test_vit_encoder_block_end_to_end(shrink):
+    """x -> LN -> QKV -> attention -> projection -> (+ x) -> LN -> FFN (GELU) -> (+) -> LN: every service of the launch
+    with its own weights and image count; four grouped forwards, one attention and three normalisation launches
+    (a small block and ViT-B/16 itself)."""
+    from paper_2511_00603_amd.vitblock import VitBlock
+    from workloads import make_mix, make_vit_block
+    mix = make_mix(3, **shrink)
+    params = make_vit_block(mix)
+    blk = VitBlock(mix, params, DEV)
+    blk.run()
     torch.cuda.synchronize()
     worst = 0.0
-    for i, s in enumerate(svcs):
-        p = s["p"]
-        w = lambda name: ref.bf16_decode(casts.bf16_bits(p[name][0]))
-        b = lambda name: p[name][1].astype(np.float64)
-        g64 = lambda name: p[name].astype(np.float64)
+    for i, (p, hb, t) in enumerate(zip(params, blk.bits, blk.tensors[0])):
+        x = ref.bf16_decode(hb["X"])
+        w = {n: ref.bf16_decode(v) for n, v in hb["W"].items()}
+        b = {n: v.astype(np.float64) for n, v in hb["b"].items()}
+        g64 = lambda a: a.astype(np.float64)
+        eps = float(np.float32(p.eps))
+        got = {n: fetch(t[n]) for n in ("y1", "qkv", "attn", "proj", "s2", "y2", "h", "f", "s3", "y3")}
         # stage by stage, each against the reference on the very (bf16) tensors the stage read on the GPU: this isolates
         # the stage's own error from what the roundings before it did to its input
-        assert_close(fetch(y1[i]), OB.layer_norm(s["x"], g64("gamma1"), g64("beta1"), eps), TOL_NORM, "service %d first normalisation" % i)
-        assert_close(fetch(qkv[i]), ref.dense_forward(fetch(y1[i]), w("qkv"), b("qkv"), "none"), TOL["bf16"], "service %d QKV" % i)
-        assert_close(fetch(attn[i]["O"]), OB.attention(fetch(qkv[i]), tokens, heads), TOL_ATTN, "service %d attention" % i)
-        assert_close(fetch(proj[i]), ref.dense_forward(fetch(attn[i]["O"]), w("proj"), b("proj"), "none"), TOL["bf16"], "service %d projection" % i)
-        want_s2, want_y2 = OB.add_layer_norm(s["x"], fetch(proj[i]), g64("gamma2"), g64("beta2"), eps)
-        assert_close(fetch(s2[i]), want_s2, TOL_NORM, "service %d sum after attention" % i)
-        assert_close(fetch(y2[i]), want_y2, TOL_NORM, "service %d second normalisation" % i)
-        want_f = ref.dense_forward(ref.dense_forward(fetch(y2[i]), w("up"), b("up"), "gelu_erf"), w("down"), b("down"), "none")
-        assert_close(fetch(f[i]), want_f, TOL["bf16"], "service %d FFN" % i)
-        assert_close(fetch(s3[i]), fetch(s2[i]) + fetch(f[i]), TOL_NORM, "service %d block output" % i)
+        assert_close(got["y1"], OB.layer_norm(x, g64(p.gamma1), g64(p.beta1), eps), TOL_NORM, "service %d first normalisation" % i)
+        assert_close(got["qkv"], ref.dense_forward(got["y1"], w["qkv"], b["qkv"], "none"), TOL["bf16"], "service %d QKV" % i)
+        assert_close(got["attn"], OB.attention(got["qkv"], p.tokens, p.heads), TOL_ATTN, "service %d attention" % i)
+        assert_close(got["proj"], ref.dense_forward(got["attn"], w["proj"], b["proj"], "none"), TOL["bf16"], "service %d projection" % i)
+        want_s2, want_y2 = OB.add_layer_norm(x, got["proj"], g64(p.gamma2), g64(p.beta2), eps)
+        assert_close(got["s2"], want_s2, TOL_NORM, "service %d sum after attention" % i)
+        assert_close(got["y2"], want_y2, TOL_NORM, "service %d second normalisation" % i)
+        assert_close(got["h"], ref.dense_forward(got["y2"], w["up"], b["up"], "gelu_erf"), TOL["bf16"], "service %d FFN up" % i)
+        assert_close(got["f"], ref.dense_forward(got["h"], w["down"], b["down"], "none"), TOL["bf16"], "service %d FFN down" % i)
+        want_s3, want_y3 = OB.add_layer_norm(got["s2"], got["f"], g64(p.gamma1), g64(p.beta1), eps)
+        assert_close(got["s3"], want_s3, TOL_NORM, "service %d block output" % i)
+        assert_close(got["y3"], want_y3, TOL_NORM, "service %d block output, normalised" % i)
         # and the whole block against the reference that never rounds in between: nine tensors are rounded to bf16 on
-        # the way (2^-9 each, and a score error d changes an attention weight by e^d), so twice the single-stage bound
-        _qkv, _a, _s2, want_out = _oracle_block(s["x"], p, tokens, heads, eps)
-        worst = max(worst, assert_close(fetch(s3[i]), want_out, 2 * TOL["bf16"], "service %d whole block" % i))
+        # the way (2^-9 each, and a score error e changes an attention weight by a factor exp(e)), so twice the
+        # single-stage bound
+        worst = max(worst, assert_close(got["s3"], _oracle_block(x, w, b, p), 2 * TOL["bf16"], "service %d whole block" % i))
     print("whole block, worst relative error over the services: %.2e" % worst)
 
 

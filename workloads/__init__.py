@@ -1,2 +1,2 @@
 """Seeded synthetic inputs shared by the tests, the smoke check and the benchmark."""
-from .mixes import SEED, Layer, Mix, Service, make_mix  # noqa: F401
+from .mixes import SEED, BlockParams, Layer, Mix, Service, make_mix, make_vit_block  # noqa: F401

@@ -47,6 +47,19 @@ class Service:
 
 
 @dataclass
+class BlockParams:
+    """What a ViT service needs besides its QKV and FFN layers to run a whole pre-norm encoder block."""
+    proj: Layer                   # attention output projection [d, d]
+    gamma1: np.ndarray            # fp32 [d]: scale / shift of the normalisation before attention ...
+    beta1: np.ndarray
+    gamma2: np.ndarray            # ... and of the one before the FFN
+    beta2: np.ndarray
+    heads: int
+    tokens: int                   # rows per image
+    eps: float
+
+
+@dataclass
 class Mix:
     index: int
     name: str
@@ -162,3 +175,18 @@ def make_mix(index, seed=SEED, **shrink):
             svcs.append(Service(X, per[s], "swiglu", Wgate=Wg, Wup=Wu, Wdown=Wd))
         return Mix(5, "llm_prefill", "bf16", svcs)
     raise ValueError("mix index must be 1..5")
+
+
+def make_vit_block(mix, seed=SEED, eps=1e-6):
+    """Per service of a ViT mix (index 3, any size): the rest of an encoder block's parameters, from a generator of
+    their own (the mix's draws stay what they are): projection W ~ N(0, 1/d) and b ~ N(0, 0.01) like the other layers,
+    scales 1 + N(0, 0.1), shifts N(0, 0.1); heads of 64 columns."""
+    rng = np.random.default_rng([seed, mix.index, 1])
+    out = []
+    for svc in mix.services:
+        d = svc.X.shape[1]
+        proj = _dense(rng, d, d, "none")
+        g1, b1 = (1.0 + _normal(rng, (d,), 0.1)).astype(np.float32), _normal(rng, (d,), 0.1)
+        g2, b2 = (1.0 + _normal(rng, (d,), 0.1)).astype(np.float32), _normal(rng, (d,), 0.1)
+        out.append(BlockParams(proj, g1, b1, g2, b2, d // 64, svc.request_rows[0], eps))
+    return out
