@@ -198,11 +198,8 @@ __global__ __launch_bounds__(NT) void add_layernorm_kernel(const epara_norm_args
 constexpr int DH = EPARA_ATTN_HEAD_DIM;                   // 64: two MFMA steps of 32 along the head dimension
 constexpr int MAX_KB = EPARA_ATTN_MAX_TOKENS / 16;        // key blocks of 16
 constexpr int K_ROW = DH * 2;                             // bytes of a key row in the LDS: 8 chunks of 16, chunk c at c ^ (key % 8)
-constexpr int VT_ROW = EPARA_ATTN_MAX_TOKENS * 2 + 8;     // bytes of a row of V^T (one head dimension, all keys) + 8: rows fall on different banks
 static_assert(MAX_KB % 2 == 0, "the second product takes key blocks in pairs");
 constexpr int NT_ATTN = 512, ATTN_WAVES = NT_ATTN / 64;  // eight waves share a head's keys and values: two or one query block each at ViT sizes
-constexpr int MAX_QB = (MAX_KB + ATTN_WAVES - 1) / ATTN_WAVES;   // query blocks of 16 per wave
-constexpr int STAGE_STEPS = (EPARA_ATTN_MAX_TOKENS / 2 * 8 + NT_ATTN - 1) / NT_ATTN;   // (pairs of keys) x (chunks of a row) over the threads
 
 // Group of item `item`: the last one whose first_item is <= item.  Up to 64 groups: every lane looks at one group
 // and the wave counts (one memory latency); more: bisection.
@@ -220,9 +217,17 @@ __device__ __forceinline__ int find_attn_group(const epara_attn_args* __restrict
     return lo;
 }
 
+// KB = key blocks of 16 that the kernel multiplies for every image (even; the host takes the smallest instance that
+// holds the longest image of the launch): the loops over key blocks have no conditions in them, so the LDS reads
+// of a block run ahead of the products of the one before.  Keys past an image are zero rows whose scores are masked.
+template <int KB>
 __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_args* __restrict__ args, int G)
 {
-    __shared__ __attribute__((aligned(16))) char k_lds[EPARA_ATTN_MAX_TOKENS * K_ROW];
+    constexpr int KEYS = KB * 16;
+    constexpr int VT_ROW = KEYS * 2 + 8;                  // bytes of a row of V^T (one head dimension, all keys) + 8: rows fall on different banks
+    constexpr int MAX_QB = (KB + ATTN_WAVES - 1) / ATTN_WAVES;                       // query blocks of 16 per wave
+    constexpr int STAGE_STEPS = (KEYS / 2 * 8 + NT_ATTN - 1) / NT_ATTN;              // (pairs of keys) x (chunks of a row) over the threads
+    __shared__ __attribute__((aligned(16))) char k_lds[KEYS * K_ROW];
     __shared__ __attribute__((aligned(16))) char vt_lds[DH * VT_ROW];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -230,7 +235,7 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
     const epara_attn_args a = args[__builtin_amdgcn_readfirstlane(find_attn_group(args, G, item, lane))];
     const int local = item - a.first_item, image = local / a.heads, head = local - image * a.heads;
     const int T = a.tokens, d = a.heads * DH;
-    const int n_kb = (T + 15) >> 4, n_pairs = (n_kb + 1) >> 1;
+    const int n_qb = (T + 15) >> 4;
     const size_t row_bytes = static_cast<size_t>(3 * d) * 2;
     const EPARA_GLOBAL char* qkv = (const EPARA_GLOBAL char*)a.QKV + static_cast<size_t>(image) * T * row_bytes + static_cast<size_t>(head) * DH * 2;
 
@@ -265,11 +270,13 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
         qf[i][1] = *reinterpret_cast<const EPARA_GLOBAL v4i*>(qkv + q * row_bytes + 64 + g * 16);
     }
     // ---- keys row-major (swizzled), values transposed (two keys = one 32-bit word per head dimension); rows past
-    // the image are zeros: masked scores never see them, and 0 * 0 is what the second product needs there
+    // the image are zeros: their scores are masked, and 0 * 0 is what the second product needs there.  V^T keeps
+    // head dimension 16 a + 4 b + r (a, b, r < 4) in row 16 b + 4 a + r: block b of the second product then leaves
+    // lane (query, g) with dimensions 16 g + 4 b .. + 3, i.e. 16 consecutive ones over its four blocks.
 #pragma unroll
     for (int it = 0; it < STAGE_STEPS; ++it) {
         const int idx = it * NT_ATTN + tid, pair = idx >> 3, chunk = idx & 7;
-        if (pair < n_pairs * 16) {
+        if (pair < KEYS / 2) {
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int key = 2 * pair + e;
@@ -279,7 +286,8 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
             for (int e = 0; e < 8; ++e) {
                 const uint32_t x0 = static_cast<uint32_t>(vv[it][0][e >> 1]), x1 = static_cast<uint32_t>(vv[it][1][e >> 1]);
                 const uint32_t w = e & 1 ? (x0 >> 16) | (x1 & 0xffff0000u) : (x0 & 0xffffu) | (x1 << 16);
-                *reinterpret_cast<uint32_t*>(vt_lds + (chunk * 8 + e) * VT_ROW + pair * 4) = w;
+                const int row = ((((chunk & 1) << 1) | (e >> 2)) << 4) + ((chunk >> 1) << 2) + (e & 3);     // of dimension 8 chunk + e
+                *reinterpret_cast<uint32_t*>(vt_lds + row * VT_ROW + pair * 4) = w;
             }
         }
     }
@@ -290,50 +298,40 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
 #pragma unroll
     for (int i = 0; i < MAX_QB; ++i) {
         const int qb = first_qb + ATTN_WAVES * i;
-        if (qb >= n_kb) break;
+        if (qb >= n_qb) break;
         const v4i q0 = qf[i][0], q1 = qf[i][1];
         // ---- S^T, block by block of 16 keys
-        v4f s[MAX_KB];
+        v4f s[KB];
 #pragma unroll
-        for (int b = 0; b < MAX_KB; ++b) {
-            s[b] = v4f{0.f, 0.f, 0.f, 0.f};
-            if (b < n_kb) {
-                const int key = b * 16 + j;
-                const v4i k0 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + ((g ^ (key & 7)) << 4));
-                const v4i k1 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + (((4 + g) ^ (key & 7)) << 4));
-                s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0), __builtin_bit_cast(bf16x8, q0), s[b], 0, 0, 0);
-                s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1), __builtin_bit_cast(bf16x8, q1), s[b], 0, 0, 0);
-            }
+        for (int b = 0; b < KB; ++b) {
+            const int key = b * 16 + j;
+            const v4i k0 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + ((g ^ (key & 7)) << 4));
+            const v4i k1 = *reinterpret_cast<const v4i*>(k_lds + key * K_ROW + (((4 + g) ^ (key & 7)) << 4));
+            s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k0), __builtin_bit_cast(bf16x8, q0), v4f{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k1), __builtin_bit_cast(bf16x8, q1), s[b], 0, 0, 0);
         }
         // ---- softmax over the keys of my query: my 4 keys per block, then the lanes j, j + 16, j + 32, j + 48.
-        // The maximum is taken over the raw scores (the scale is positive); only a block that reaches past the
-        // image has keys to mask; a block past the last one (the pad of an odd count) keeps its zeros as weights.
+        // Keys past the image are masked; the maximum is taken over the raw scores (the scale is positive).
+        const int my_keys = T - g * 4;                           // key b * 16 + g * 4 + r exists iff b * 16 + r < my_keys
         float m = -INFINITY;
 #pragma unroll
-        for (int b = 0; b < MAX_KB; ++b) {
-            if (b < n_kb) {
-                if ((b + 1) * 16 > T) {
+        for (int b = 0; b < KB; ++b) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (b * 16 + g * 4 + r >= T) s[b][r] = -INFINITY;
-                }
-                m = fmaxf(fmaxf(m, fmaxf(s[b][0], s[b][1])), fmaxf(s[b][2], s[b][3]));
-            }
+            for (int r = 0; r < 4; ++r)
+                if (b * 16 + r >= my_keys) s[b][r] = -INFINITY;
+            m = fmaxf(fmaxf(m, fmaxf(s[b][0], s[b][1])), fmaxf(s[b][2], s[b][3]));
         }
         m = fmaxf(m, __shfl_xor(m, 16));
         m = fmaxf(m, __shfl_xor(m, 32));                         // finite: key 0 exists
         const float ms = m * scale;
         float l = 0.f;
 #pragma unroll
-        for (int b = 0; b < MAX_KB; ++b) {
-            if (b < n_kb) {
+        for (int b = 0; b < KB; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    s[b][r] = __builtin_amdgcn_exp2f(fmaf(s[b][r], scale, -ms));      // 2^(scale (s - m)) in (0, 1]; 0 for masked keys
-                    l += s[b][r];
-                }
+            for (int r = 0; r < 4; ++r) {
+                s[b][r] = __builtin_amdgcn_exp2f(fmaf(s[b][r], scale, -ms));          // 2^(scale (s - m)) in (0, 1]; 0 for masked keys
+                l += s[b][r];
             }
-        }
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
         // ---- O^T = V^T P^T, two key blocks per step
@@ -341,32 +339,33 @@ __global__ __launch_bounds__(NT_ATTN, 4) void attention_kernel(const epara_attn_
 #pragma unroll
         for (int db = 0; db < DH / 16; ++db) o[db] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int p = 0; p < MAX_KB / 2; ++p) {
-            if (p < n_pairs) {
-                v4i pb;
-                pb[0] = static_cast<int>(pack_bf16(s[2 * p][0], s[2 * p][1]));
-                pb[1] = static_cast<int>(pack_bf16(s[2 * p][2], s[2 * p][3]));
-                pb[2] = static_cast<int>(pack_bf16(s[2 * p + 1][0], s[2 * p + 1][1]));
-                pb[3] = static_cast<int>(pack_bf16(s[2 * p + 1][2], s[2 * p + 1][3]));
-#pragma unroll
-                for (int db = 0; db < DH / 16; ++db) {
-                    const char* vrow = vt_lds + (db * 16 + j) * VT_ROW + (p * 32 + g * 4) * 2;
-                    const v2u lo = *reinterpret_cast<const v2u*>(vrow), hi = *reinterpret_cast<const v2u*>(vrow + 32);
-                    const v4i va = {static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(hi[0]), static_cast<int>(hi[1])};
-                    o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pb), o[db], 0, 0, 0);
-                }
-            }
-        }
-        // ---- my query's columns 16 db + 4 g .. + 3 of this head
-        if (qb * 16 + j < T) {
-            const float inv = 1.f / l;
-            EPARA_GLOBAL char* dst = out + static_cast<size_t>(qb * 16 + j) * d * 2 + g * 8;
+        for (int p = 0; p < KB / 2; ++p) {
+            v4i pb;
+            pb[0] = static_cast<int>(pack_bf16(s[2 * p][0], s[2 * p][1]));
+            pb[1] = static_cast<int>(pack_bf16(s[2 * p][2], s[2 * p][3]));
+            pb[2] = static_cast<int>(pack_bf16(s[2 * p + 1][0], s[2 * p + 1][1]));
+            pb[3] = static_cast<int>(pack_bf16(s[2 * p + 1][2], s[2 * p + 1][3]));
 #pragma unroll
             for (int db = 0; db < DH / 16; ++db) {
-                v2u pk;
-                pk[0] = pack_bf16(o[db][0] * inv, o[db][1] * inv);
-                pk[1] = pack_bf16(o[db][2] * inv, o[db][3] * inv);
-                *reinterpret_cast<EPARA_GLOBAL v2u*>(dst + db * 32) = pk;
+                const char* vrow = vt_lds + (db * 16 + j) * VT_ROW + (p * 32 + g * 4) * 2;
+                const v2u lo = *reinterpret_cast<const v2u*>(vrow), hi = *reinterpret_cast<const v2u*>(vrow + 32);
+                const v4i va = {static_cast<int>(lo[0]), static_cast<int>(lo[1]), static_cast<int>(hi[0]), static_cast<int>(hi[1])};
+                o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pb), o[db], 0, 0, 0);
+            }
+        }
+        // ---- my query's columns 16 g .. 16 g + 15 of this head (block db holds 16 g + 4 db .. + 3): 32 bytes in a row
+        if (qb * 16 + j < T) {
+            const float inv = 1.f / l;
+            EPARA_GLOBAL char* dst = out + static_cast<size_t>(qb * 16 + j) * d * 2 + g * 32;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                v4i pk;
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    pk[2 * k] = static_cast<int>(pack_bf16(o[2 * h + k][0] * inv, o[2 * h + k][1] * inv));
+                    pk[2 * k + 1] = static_cast<int>(pack_bf16(o[2 * h + k][2] * inv, o[2 * h + k][3] * inv));
+                }
+                *reinterpret_cast<EPARA_GLOBAL v4i*>(dst + h * 16) = pk;
             }
         }
     }
@@ -414,6 +413,7 @@ int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_
     if (G == 0) return EPARA_OK;
     if (!h_args || !d_args) return EPARA_ERR_NULL;
     int64_t items = 0;
+    int32_t longest = 1;
     for (int32_t g = 0; g < G; ++g) {
         const epara_attn_args& a = h_args[g];
         if (a.M < 0 || a.tokens < 1 || a.tokens > EPARA_ATTN_MAX_TOKENS || a.heads < 1 || a.head_dim != EPARA_ATTN_HEAD_DIM ||
@@ -423,10 +423,17 @@ int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_
         if (a.M > 0 && a.QKV == a.O) return EPARA_ERR_SHAPE;
         if (misaligned(a.QKV, 16) || misaligned(a.O, 16)) return EPARA_ERR_ALIGN;
         items += static_cast<int64_t>(a.M / a.tokens) * a.heads;
+        if (a.M > 0 && a.tokens > longest) longest = a.tokens;
         if (items > INT32_MAX) return EPARA_ERR_SHAPE;
     }
     if (items == 0) return EPARA_OK;
-    hipLaunchKernelGGL(attention_kernel, dim3(static_cast<unsigned>(items)), dim3(NT_ATTN), 0, static_cast<hipStream_t>(stream), d_args, G);
+    const int blocks = (longest + 15) / 16;                      // key blocks of the longest image
+    const dim3 grid(static_cast<unsigned>(items)), wg(NT_ATTN);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (blocks <= 2)      hipLaunchKernelGGL(attention_kernel<2>, grid, wg, 0, s, d_args, G);
+    else if (blocks <= 4) hipLaunchKernelGGL(attention_kernel<4>, grid, wg, 0, s, d_args, G);
+    else if (blocks <= 8) hipLaunchKernelGGL(attention_kernel<8>, grid, wg, 0, s, d_args, G);
+    else                  hipLaunchKernelGGL(attention_kernel<MAX_KB>, grid, wg, 0, s, d_args, G);
     return hipGetLastError() == hipSuccess ? EPARA_OK : EPARA_ERR_HIP;
 }
 

@@ -154,6 +154,10 @@ def test_attention_vit_b16_service_and_peaked_scores():
     # larger projections: scores of +-30 and more, rows dominated by one or two keys (the maximum is taken out first)
     groups, want = attn_case(rng, [(2, 197, 2), (1, 50, 1)], spread=4.0)
     check_attn(groups, want, "peaked")
+    # launches whose longest image needs 8, 4 and 2 key blocks (the kernel is compiled per number of blocks)
+    for tokens in (100, 128, 65, 64, 33, 20):
+        groups, want = attn_case(rng, [(2, tokens, 2), (1, max(1, tokens // 3), 1)])
+        check_attn(groups, want, "%d tokens" % tokens)
 
 
 def test_attention_closed_forms_on_the_gpu():
