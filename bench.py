@@ -396,6 +396,25 @@ def time_vit_block_pieces(mix, steps, warmup):
         out[name] = {"us": us, "bytes": int(nbytes), "GBs": nbytes / us / 1e3, "frac_hbm": nbytes / us / 1e3 / HBM_PEAK_GBS}
         if flops:
             out[name]["TFLOPs"] = flops / us / 1e6
+    # the fp64 reference on the host for the same two steps, on a bounded sample (the images of the smallest services)
+    import numpy as np
+    from oracle import block as OB
+    small = sorted(range(len(mix.services)), key=lambda g: mix.services[g].M)[:3]
+    t0 = time.perf_counter()
+    n_img = 0
+    for g in small:
+        OB.attention(by_label[(g, "L0")].float().cpu().numpy().astype(np.float64), tokens, heads)
+        n_img += mix.services[g].M // tokens
+    t_attn = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    n_rows = 0
+    for g in small:
+        OB.add_layer_norm(by_label[(g, "L2")].float().cpu().numpy().astype(np.float64), st.inputs[0][g].float().cpu().numpy().astype(np.float64),
+                          np.ones(d), np.zeros(d), 1e-6)
+        n_rows += mix.services[g].M
+    t_norm = time.perf_counter() - t0
+    out["cpu_reference"] = {"kind": "oracle", "attention_images_per_s": n_img / t_attn, "add_layernorm_rows_per_s": n_rows / t_norm,
+                            "sample": "%d images / %d rows of the three smallest services, numpy fp64, %.2f s + %.2f s" % (n_img, n_rows, t_attn, t_norm)}
     del st, attn, norm
     torch.cuda.empty_cache()
     # a whole encoder block of every service: the eight launches back to back, then each launch on its own
