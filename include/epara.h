@@ -738,7 +738,8 @@ typedef struct {
  * a workgroup per (image, head) keeps that head's keys and (transposed) values in the LDS; its eight waves take the
  * query rows in blocks of 16.  G = 0 or no rows enqueues nothing.
  * Errors (from h_args): ERR_NULL; ERR_SHAPE (M < 0 or not a multiple of tokens, tokens or head_dim out of range,
- * heads < 1, first_item not the running sum, more than 2^31 - 1 items); ERR_ALIGN (QKV or O not 16-byte aligned). */
+ * heads < 1, O the same buffer as QKV, first_item not the running sum, more than 2^31 - 1 items); ERR_ALIGN (QKV or O
+ * not 16-byte aligned). */
 int32_t epara_attention(const epara_attn_args* h_args, const epara_attn_args* d_args, int32_t G, void* stream);
 
 const char* epara_status_string(int32_t status);
