@@ -15,8 +15,8 @@
 //   O^T = V^T P^T A = 16 dims x 32 keys (LDS, values stored transposed), B = 32 keys x 16 queries = the
 //                 exponentials of two key blocks, packed to bf16 in place.  Only the pairing of A and B
 //                 along the contraction matters, so "key slot 8 g + e" means key 4 g + e of the first block
-//                 (e < 4) or key 4 g + e - 4 of the second in both operands.  A lane ends with four
-//                 consecutive output columns of its query: an 8-byte store.
+//                 (e < 4) or key 4 g + e - 4 of the second in both operands.  The same freedom orders the rows of
+//                 V^T so that a lane ends with 16 consecutive output columns of its query: two 16-byte stores.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
