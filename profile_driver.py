@@ -3,6 +3,7 @@ of known size whose HBM traffic calibrates the byte counters.
 
     rocprofv3 --kernel-trace --stats --output-format csv -d OUT -o run -- python3 profile_driver.py 5 bf16 6
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 profile_driver.py 5 bf16 3
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 profile_driver.py 3 block 6
 """
 import sys
 
@@ -47,6 +48,33 @@ def batch_forming(mix, steps):
     print("profile_driver: batch forming of mix %d, %d passes, %d source bytes per pass" % (mix.index, steps, gather.bytes))
 
 
+def block_pieces(mix, steps):
+    """Attention and residual + layer normalisation over the ViT mix's services (tensors of the mix's shapes with
+    N(0, 1) values), `steps` times each, then the copy probe."""
+    from paper_2511_00603_amd import runtime as R
+    dev = "cuda:0"
+    d = mix.services[0].X.shape[1]
+    tokens, heads = mix.services[0].request_rows[0], d // 64
+    bf = lambda M, N: torch.randn((M, N), device=dev).to(torch.bfloat16)
+    attn = R.AttnPlan([{"QKV": bf(s.M, 3 * d), "O": bf(s.M, d), "tokens": tokens, "heads": heads} for s in mix.services], dev)
+    norm = R.NormPlan([{"X": bf(s.M, d), "R": bf(s.M, d), "gamma": torch.ones(d, device=dev), "beta": torch.zeros(d, device=dev),
+                        "S": bf(s.M, d), "Y": bf(s.M, d), "eps": 1e-6} for s in mix.services], dev)
+    for _ in range(steps):
+        R.attention(attn)
+        R.add_layernorm(norm)
+    torch.cuda.synchronize()
+    copy_probe()
+    print("profile_driver: attention and add + layer norm over mix %d, %d launches each, %d rows" % (mix.index, steps, mix.rows))
+
+
+def copy_probe():
+    src = torch.ones(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):
+        P.probe_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+
+
 def main():
     idx = int(sys.argv[1])
     dtype = sys.argv[2] if len(sys.argv) > 2 else None
@@ -54,6 +82,8 @@ def main():
     mix = make_mix(idx)
     if dtype == "rows":          # batch forming of the mix's requests instead of its forward pass
         return batch_forming(mix, steps)
+    if dtype == "block":         # the pieces between a ViT block's dense layers
+        return block_pieces(mix, steps)
     s_h = None
     if dtype == "fp8":
         cal = StagedMix(mix, "bf16", "cuda:0")
@@ -65,11 +95,7 @@ def main():
     for _ in range(steps):
         staged.run()
     torch.cuda.synchronize()
-    src = torch.ones(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
-    dst = torch.zeros(COPY_BYTES, dtype=torch.uint8, device="cuda:0")
-    for _ in range(2):
-        P.probe_copy(src.data_ptr(), dst.data_ptr(), COPY_BYTES, torch.cuda.current_stream().cuda_stream)
-    torch.cuda.synchronize()
+    copy_probe()
     print("profile_driver: mix %d %s, %d passes, copy probe %d bytes" % (idx, dtype or mix.dtype, steps, COPY_BYTES))
 
 

@@ -5,6 +5,7 @@ short text summaries kept under profiles/ and into profiles/traffic.txt.
     python profile_summary.py traffic OUT/fetch_counter_collection.csv OUT/write_counter_collection.csv WORKLOAD
     python profile_summary.py report OUT WORKLOAD MIX DTYPE      (both, from OUT/{run,fetch,write}_*.csv)
     python profile_summary.py counters OUT WORKLOAD MIX DTYPE    (OUT/{sq,tcc}_counter_collection.csv)
+    python profile_summary.py pieces OUT ROWS D                  (OUT/{fetch,write}_counter_collection.csv of `profile_driver.py 3 block N`)
 
 Per-launch figures: the launches of one pass alternate (launch 0, launch 1, ...), so dispatch i of
 grouped_kernel belongs to launch i mod L.  HBM traffic of a launch = counter value (KiB) x 1024 x
@@ -103,6 +104,50 @@ def traffic(fetch_csv, write_csv, workload, launches_per_pass):
     print(json.dumps(out, indent=1))
 
 
+def pieces(out_dir, rows, d):
+    """profiles/counters_vit_block_pieces.txt: HBM-side bytes per launch of the attention and normalisation kernels."""
+    def per_kernel(path, counter):
+        vals = {}
+        for r in _rows(path):
+            if r["Counter_Name"] == counter:
+                key = (int(r["Dispatch_Id"]), r["Kernel_Name"])
+                vals[key] = vals.get(key, 0.0) + float(r["Counter_Value"])
+        pick = lambda name: [v for (i, k), v in sorted(vals.items()) if name in k]
+        return pick("attention_kernel"), pick("add_layernorm_kernel"), pick("copy_kernel")
+    fa, fn, fc = per_kernel(os.path.join(out_dir, "fetch_counter_collection.csv"), "FETCH_SIZE")
+    wa, wn, wc = per_kernel(os.path.join(out_dir, "write_counter_collection.csv"), "WRITE_SIZE")
+    f_scale, w_scale = COPY_BYTES / (fc[-1] * 1024.0), COPY_BYTES / (wc[-1] * 1024.0)
+    alg = rows * d * 2
+    L = ["rocprofv3 counter summary of the kernels between a ViT block's dense layers (medians over the launches, first skipped)",
+         "commands: rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -o fetch -- python3 profile_driver.py 3 block 6",
+         "          rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT -o write -- python3 profile_driver.py 3 block 6",
+         "counter values (KiB per dispatch) scaled by what the same counter reads for a copy kernel of %d bytes: x %.3f (fetch), x %.3f (write)" % (COPY_BYTES, f_scale, w_scale), ""]
+    for name, f, w, rd, wr in (("attention_kernel", fa, wa, 3 * alg, alg), ("add_layernorm_kernel", fn, wn, 2 * alg, 2 * alg)):
+        fb, wb = statistics.median(f[1:]) * 1024 * f_scale, statistics.median(w[1:]) * 1024 * w_scale
+        L.append("%-22s fetched %7.1f MB (algorithmic %6.1f MB)   written %6.1f MB (algorithmic %6.1f MB)   together %.2f x the algorithmic bytes"
+                 % (name, fb / 1e6, rd / 1e6, wb / 1e6, wr / 1e6, (fb + wb) / (rd + wr)))
+    sq = os.path.join(out_dir, "sq_counter_collection.csv")
+    if os.path.exists(sq):
+        L += ["", "          rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_WAIT_INST_LDS SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE --output-format csv -d OUT -o sq -- python3 profile_driver.py 3 block 6",
+              "(sums over the chip: GRBM_GUI_ACTIVE over 8 dies, SQ_VALU_MFMA_BUSY_CYCLES over 1024 SIMDs)"]
+        vals = {}
+        for r in _rows(sq):
+            name = "attention_kernel" if "attention_kernel" in r["Kernel_Name"] else ("add_layernorm_kernel" if "add_layernorm" in r["Kernel_Name"] else None)
+            if name:
+                d = vals.setdefault(name, {}).setdefault(int(r["Dispatch_Id"]), {})
+                d[r["Counter_Name"]] = d.get(r["Counter_Name"], 0.0) + float(r["Counter_Value"])
+        for name, per in vals.items():
+            med = lambda c: statistics.median([v[c] for v in list(per.values())[1:]])
+            active = med("GRBM_GUI_ACTIVE") / 8
+            L.append("%-22s active cycles per die %8.0f   matrix cores busy %5.1f %%   LDS bank conflict cycles %4.1f %% of LDS active   wave cycles waiting on LDS / any %4.1f %% / %4.1f %%"
+                     % (name, active, 100 * med("SQ_VALU_MFMA_BUSY_CYCLES") / 1024 / active,
+                        100 * med("SQ_LDS_BANK_CONFLICT") / max(med("SQ_LDS_IDX_ACTIVE"), 1.0),
+                        100 * med("SQ_WAIT_INST_LDS") / med("SQ_WAVE_CYCLES"), 100 * med("SQ_WAIT_INST_ANY") / med("SQ_WAVE_CYCLES")))
+    out = os.path.join(ROOT, "profiles", "counters_vit_block_pieces.txt")
+    open(out, "w").write("\n".join(L) + "\n")
+    print("\n".join(L))
+
+
 def lookup_traffic(workload, launch):
     """HBM bytes (fetch + write) per launch from the last counter runs, or None if absent / the kernel source changed since."""
     if not os.path.exists(TRAFFIC_JSON):
@@ -195,5 +240,7 @@ if __name__ == "__main__":
     elif sys.argv[1] == "kernels":
         kernels(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2,
                 int(sys.argv[6]) if len(sys.argv) > 6 else 0, int(sys.argv[7]) if len(sys.argv) > 7 else None)
+    elif sys.argv[1] == "pieces":
+        pieces(sys.argv[2], int(sys.argv[3]), int(sys.argv[4]))
     elif sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4], int(sys.argv[5]) if len(sys.argv) > 5 else 2)
